@@ -1,0 +1,227 @@
+"""Python face of the CPU oracle (oracle/slim_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+CPU-baseline leg of the benchmark.  It imports nothing from the product
+package and the product package imports nothing from here.
+
+All arrays are numpy, on the host.  fp16 inputs (X, L, R) are widened to
+float64 (exact) before they reach the C code.  Orientation is nn.Linear's:
+W [n][k], L [n][r], R [r][k], X [m][k], Y [m][n]; the paper's
+``Y = X W^C + (X L) R`` (Sec. 3.2) with every matrix transposed.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "slim_oracle.c")
+_LIB = os.path.join(_HERE, "libslim_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile slim_oracle.c with gcc (IEEE semantics, OpenMP over rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fno-fast-math", "-ffp-contract=off", "-fopenmp", "-fPIC",
+               "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i64, p = ctypes.c_int64, ctypes.c_void_p
+        lib.slim_oracle_threads.restype = ctypes.c_int
+        for name, args in {
+            "slim_oracle_mask": [p, i64, i64, p],
+            "slim_oracle_scale": [p, i64, i64, p],
+            "slim_oracle_quantize": [p, p, p, i64, i64, p],
+            "slim_oracle_pack": [p, p, i64, i64, p, p],
+            "slim_oracle_unpack": [p, p, i64, i64, p, p],
+            "slim_oracle_dequant": [p, p, p, i64, i64, p],
+            "slim_oracle_xr": [p, p, i64, i64, i64, p],
+            "slim_oracle_forward": [p, p, p, p, p, p, i64, i64, i64, i64, p, i64, p],
+        }.items():
+            fn = getattr(lib, name)
+            fn.argtypes = args
+            fn.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    return int(_load().slim_oracle_threads())
+
+
+def _c(a: np.ndarray, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"{what} failed with code {rc}")
+
+
+# ---- steps 1-3 ---------------------------------------------------------------
+
+def mask_2of4(W: np.ndarray) -> np.ndarray:
+    """2:4 magnitude mask of W [n][k] (float32): uint8, 1 = kept."""
+    W = _c(W, np.float32)
+    n, k = W.shape
+    mask = np.empty((n, k), np.uint8)
+    _check(_load().slim_oracle_mask(_ptr(W), n, k, _ptr(mask)), "mask")
+    return mask
+
+
+def row_scale(W: np.ndarray) -> np.ndarray:
+    """Per-row AbsMax scale max|w| / 7 in binary32 (1.0 for an all-zero row)."""
+    W = _c(W, np.float32)
+    n, k = W.shape
+    s = np.empty((n,), np.float32)
+    _check(_load().slim_oracle_scale(_ptr(W), n, k, _ptr(s)), "scale")
+    return s
+
+
+def quantize(W: np.ndarray, mask: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """int8 codes in [-8, 7] at kept positions, 0 elsewhere (Sec. 3.1 Eq. 2)."""
+    W = _c(W, np.float32)
+    mask = _c(mask, np.uint8)
+    scale = _c(scale, np.float32)
+    n, k = W.shape
+    assert mask.shape == (n, k) and scale.shape == (n,)
+    codes = np.empty((n, k), np.int8)
+    _check(_load().slim_oracle_quantize(_ptr(W), _ptr(mask), _ptr(scale), n, k, _ptr(codes)),
+           "quantize")
+    return codes
+
+
+# ---- steps 4-5 ---------------------------------------------------------------
+
+def pack(codes: np.ndarray, mask: np.ndarray):
+    """Canonical bytes: qvals [n][k/4], meta [n][k/8]."""
+    codes = _c(codes, np.int8)
+    mask = _c(mask, np.uint8)
+    n, k = codes.shape
+    assert mask.shape == (n, k)
+    qvals = np.empty((n, k // 4), np.uint8)
+    meta = np.empty((n, k // 8), np.uint8)
+    _check(_load().slim_oracle_pack(_ptr(codes), _ptr(mask), n, k, _ptr(qvals), _ptr(meta)), "pack")
+    return qvals, meta
+
+
+def unpack(qvals: np.ndarray, meta: np.ndarray):
+    """Inverse of pack: (codes int8 [n][k], mask uint8 [n][k])."""
+    qvals = _c(qvals, np.uint8)
+    meta = _c(meta, np.uint8)
+    n, kq = qvals.shape
+    k = kq * 4
+    assert meta.shape == (n, k // 8)
+    codes = np.empty((n, k), np.int8)
+    mask = np.empty((n, k), np.uint8)
+    _check(_load().slim_oracle_unpack(_ptr(qvals), _ptr(meta), n, k, _ptr(codes), _ptr(mask)),
+           "unpack")
+    return codes, mask
+
+
+def dequant(qvals: np.ndarray, meta: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """Dense dequantized weights Wd [n][k] in float64."""
+    qvals = _c(qvals, np.uint8)
+    meta = _c(meta, np.uint8)
+    scale = _c(scale, np.float32)
+    n, kq = qvals.shape
+    k = kq * 4
+    Wd = np.empty((n, k), np.float64)
+    _check(_load().slim_oracle_dequant(_ptr(qvals), _ptr(meta), _ptr(scale), n, k, _ptr(Wd)),
+           "dequant")
+    return Wd
+
+
+@dataclass
+class PackedLayer:
+    qvals: np.ndarray   # uint8 [n][k/4]
+    meta: np.ndarray    # uint8 [n][k/8]
+    scale: np.ndarray   # float32 [n]
+
+    @property
+    def n(self):
+        return self.qvals.shape[0]
+
+    @property
+    def k(self):
+        return self.qvals.shape[1] * 4
+
+
+def compress(W: np.ndarray) -> PackedLayer:
+    """Steps 1-4 in order: mask on the fp32 magnitudes, scale, quantize, pack."""
+    mask = mask_2of4(W)
+    scale = row_scale(W)
+    codes = quantize(W, mask, scale)
+    qvals, meta = pack(codes, mask)
+    return PackedLayer(qvals, meta, scale)
+
+
+# ---- step 6 --------------------------------------------------------------------
+
+def xr(X: np.ndarray, R: np.ndarray) -> np.ndarray:
+    """T = X R^T in float64, plain loops."""
+    X = _c(X, np.float64)
+    R = _c(R, np.float64)
+    m, k = X.shape
+    r = R.shape[0]
+    assert R.shape == (r, k)
+    T = np.empty((m, r), np.float64)
+    _check(_load().slim_oracle_xr(_ptr(X), _ptr(R), m, k, r, _ptr(T)), "xr")
+    return T
+
+
+def forward(layer: PackedLayer, L, R, X, rows=None) -> np.ndarray:
+    """Route (i): Y from the packed bytes, float64, [m][n] (or [m][len(rows)])."""
+    X = _c(X, np.float64)
+    m, k = X.shape
+    n = layer.n
+    assert k == layer.k
+    r = 0
+    if L is not None:
+        L = _c(L, np.float64)
+        R = _c(R, np.float64)
+        r = L.shape[1]
+        assert L.shape == (n, r) and R.shape == (r, k)
+        if r == 0:
+            L = R = None
+    rows_arr = None
+    nrows = n
+    if rows is not None:
+        rows_arr = _c(np.asarray(rows), np.int64)
+        nrows = rows_arr.shape[0]
+    Y = np.empty((m, nrows), np.float64)
+    qv, me, sc = _c(layer.qvals, np.uint8), _c(layer.meta, np.uint8), _c(layer.scale, np.float32)
+    _check(_load().slim_oracle_forward(_ptr(qv), _ptr(me), _ptr(sc), _ptr(L), _ptr(R), _ptr(X),
+                                       n, k, r, m, _ptr(rows_arr), nrows, _ptr(Y)), "forward")
+    return Y
+
+
+def forward_explicit_dense(W: np.ndarray, L, R, X) -> np.ndarray:
+    """Route (ii): never packs.  Builds Wd = mask * codes * scale directly from
+    steps 1-3, forms the dense n x k product L R, and multiplies once:
+    Y = X (Wd + L R)^T.  For tiny shapes (it materialises n x k matrices)."""
+    mask = mask_2of4(W)
+    scale = row_scale(W)
+    codes = quantize(W, mask, scale)
+    Wd = mask.astype(np.float64) * codes.astype(np.float64) * scale.astype(np.float64)[:, None]
+    X = np.asarray(X, np.float64)
+    if L is not None and np.asarray(L).shape[1] > 0:
+        Wd = Wd + np.asarray(L, np.float64) @ np.asarray(R, np.float64)
+    return X @ Wd.T
