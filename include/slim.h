@@ -1,0 +1,158 @@
+/*
+ * libslim -- forward pass of one SLiM-compressed linear layer on MI355X (gfx950).
+ *
+ *     Y = X . dequant(Wq (.) M_2:4)^T + (X . R^T) . L^T
+ *
+ * Wq: symmetric 4-bit codes under a 2:4 semi-structured mask, one fp32 scale
+ * per output row; L, R: fp16 low-rank adapters.  This is the inference form
+ * of the paper's decomposition W ~= W^C + L R (arXiv 2410.09615, Sec. 3.2),
+ * written in nn.Linear orientation: W is [n][k] = d_out x d_in, L is [n][rank],
+ * R is [rank][k], X is [m][k], Y is [m][n].  (The paper stores W as
+ * d_in x d_out and names the d_in-side factor L: its L is R^T here and its R
+ * is L^T here.)
+ *
+ * Conventions for every entry point
+ *   - returns 0 (SLIM_OK) or a negative slim_status; never throws, never exits;
+ *   - every pointer is a DEVICE pointer owned by the caller (except the
+ *     out-parameters of the size queries, which are host pointers);
+ *   - matrices are row-major, contiguous, 16-byte aligned;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream);
+ *     all work is enqueued on it and the call returns without synchronizing;
+ *   - the library allocates nothing and keeps no state between calls;
+ *   - arguments are validated on the host before anything is launched; on an
+ *     error nothing has been enqueued.
+ * fp16 values are IEEE binary16 bit patterns (`slim_half`).
+ *
+ * Canonical packed format (written by slim_pack, read by every kernel):
+ *   group g of row o = inputs 4g .. 4g+3; i0 < i1 are its two kept positions
+ *   qvals[o][g]  = (code(i0) & 15) | ((code(i1) & 15) << 4)   two's-complement nibbles
+ *   meta[o][g/2] = m4(2*(g/2)) | (m4(2*(g/2)+1) << 4),  m4(g) = i0 | (i1 << 2)
+ *   scale[o]     = fp32
+ * 3 bits per original weight.
+ */
+#ifndef SLIM_H
+#define SLIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t slim_half;
+
+typedef enum {
+    SLIM_OK = 0,
+    SLIM_ERR_NULL = -1,       /* a required pointer is NULL                          */
+    SLIM_ERR_SHAPE = -2,      /* a dimension is out of the documented range           */
+    SLIM_ERR_ALIGN = -3,      /* a pointer is not 16-byte aligned                     */
+    SLIM_ERR_WORKSPACE = -4,  /* workspace missing or smaller than slim_workspace_bytes */
+    SLIM_ERR_HIP = -5         /* a HIP runtime call failed (launch error)             */
+} slim_status;
+
+/* d_out, d_in and the true adapter rank (0 = layer without adapters). */
+typedef struct {
+    int32_t n, k, rank;
+} slim_shape;
+
+/* One compressed layer: device pointers to caller-owned buffers. */
+typedef struct {
+    slim_shape shape;
+    const uint8_t *qvals;   /* [n][k/4]                                              */
+    const uint8_t *meta;    /* [n][k/8]                                              */
+    const float *scale;     /* [n]                                                   */
+    const slim_half *L;     /* [n][rank_pad], columns >= rank are zero (NULL if rank == 0) */
+    const slim_half *R;     /* [rank_pad][k], rows >= rank are zero    (NULL if rank == 0) */
+    int32_t rank_pad;       /* slim_rank_pad(rank)                                   */
+} slim_layer;
+
+/* Text for a status code; a static string, never NULL. */
+const char *slim_status_string(int status);
+
+/* Padded rank the kernels work with: rank rounded up to a multiple of 32
+ * (the k-extent of one matrix-core instruction); 0 stays 0. */
+int32_t slim_rank_pad(int32_t rank);
+
+/*
+ * Buffer sizes, in bytes, of the packed layer for a given shape.  All
+ * out-pointers are HOST pointers and may be NULL individually.
+ * Errors: SLIM_ERR_SHAPE unless n >= 1, k >= 8, k % 8 == 0, rank >= 0.
+ */
+int slim_packed_sizes(slim_shape shape, size_t *qvals_bytes, size_t *meta_bytes,
+                      size_t *scale_bytes, int32_t *rank_pad, size_t *L_bytes, size_t *R_bytes);
+
+/*
+ * slim_pack -- dense weights in, compressed layer out.
+ *   mask   2:4 magnitude pruning: of every 4 consecutive inputs keep the two of
+ *          largest |w| (ties: lower position first);
+ *   scale  AbsMax per output row (Sec. 2): scale[o] = max_k |W[o][k]| / 7 as one
+ *          binary32 division (1.0 for an all-zero row);
+ *   codes  symmetric uniform 4-bit quantization (Sec. 2; Sec. 3.1 Eq. 2):
+ *          round-half-even(W / scale) in binary32, clamped to [-8, 7];
+ *   bytes  the canonical format above.
+ * W [n][k] fp32 in; qvals [n][k/4], meta [n][k/8], scale [n] out.
+ * W must be finite.  Errors: NULL, SHAPE (k % 8 != 0, n < 1), ALIGN, HIP.
+ */
+int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8_t *meta, float *scale,
+              void *stream);
+
+/*
+ * slim_pack_adapters -- lay the fp16 adapters out for the kernels: copy
+ * L [n][rank] into L_pad [n][rank_pad] and R [rank][k] into R_pad [rank_pad][k],
+ * zero-filling the padding.  No arithmetic.  rank must be >= 1.
+ */
+int slim_pack_adapters(const slim_half *L, const slim_half *R, slim_shape shape,
+                       slim_half *L_pad, slim_half *R_pad, void *stream);
+
+/*
+ * slim_unpack -- inverse of the canonical format, for tests and inspection:
+ * codes [n][k] int8 (0 where dropped) and mask [n][k] uint8 (1 where kept).
+ */
+int slim_unpack(const uint8_t *qvals, const uint8_t *meta, slim_shape shape, int8_t *codes,
+                uint8_t *mask, void *stream);
+
+/*
+ * Scratch the forward calls need for a layer at m tokens (a HOST out-pointer).
+ * The same size covers slim_linear_gemv (m <= 16), slim_linear_gemm and
+ * slim_lowrank.  The workspace needs no initialisation and carries nothing
+ * between calls; two calls that overlap in time need two workspaces.
+ */
+int slim_workspace_bytes(const slim_layer *layer, int32_t m, size_t *bytes);
+
+/*
+ * slim_linear_gemv -- decode-shaped forward, 1 <= m <= 16 tokens (the paper's
+ * "small batch sizes during decoding", Sec. 4 "Speedup").  Streams the packed
+ * rows and the adapters once; fp16 inputs, fp32 accumulation, Y rounded once
+ * to fp16.  X [m][k] fp16 in, Y [m][n] fp16 out.
+ * Requires k % 128 == 0.  Errors: NULL, SHAPE (m out of range, k), ALIGN,
+ * WORKSPACE, HIP.
+ */
+int slim_linear_gemv(const slim_layer *layer, const slim_half *X, int32_t m, slim_half *Y,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * slim_linear_gemm -- prefill-shaped forward, any m >= 1 (meant for m >= 64):
+ * matrix-core GEMM over the compressed weights with the adapter product
+ * T = X R^T (rounded once to fp16) folded in as extra k-steps, row scale
+ * applied to the fp32 accumulators, Y rounded once to fp16.
+ * Requires k % 128 == 0.  Errors as slim_linear_gemv.
+ */
+int slim_linear_gemm(const slim_layer *layer, const slim_half *X, int32_t m, slim_half *Y,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * slim_lowrank -- the adapter term alone (Sec. 3.2; cost O(2 b r d^2), App.
+ * "Rank Analysis"):  Y = (X R^T) L^T  or, with accumulate != 0,  Y += ...
+ * L [n][rank_pad], R [rank_pad][k] as in slim_layer; shape.rank >= 1;
+ * k % 128 == 0.  In accumulate mode Y is read as fp16, added to in fp32 and
+ * rounded back once.
+ */
+int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, const slim_half *L,
+                 slim_shape shape, int32_t rank_pad, slim_half *Y, int accumulate,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIM_H */

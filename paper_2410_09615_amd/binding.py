@@ -1,0 +1,235 @@
+"""ctypes binding of libslim (include/slim.h): argument marshalling only.
+
+Every function here has the name and meaning of the C entry point it calls;
+torch owns the device memory and the stream, the library does all the work.
+There is no fallback: if libslim.so is not built, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libslim.so")
+_lib = None
+
+
+class SlimError(RuntimeError):
+    def __init__(self, fn: str, status: int, text: str):
+        super().__init__(f"{fn}: {text} (status {status})")
+        self.status = status
+
+
+class slim_shape(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int32), ("k", ctypes.c_int32), ("rank", ctypes.c_int32)]
+
+
+class slim_layer(ctypes.Structure):
+    _fields_ = [("shape", slim_shape), ("qvals", ctypes.c_void_p), ("meta", ctypes.c_void_p),
+                ("scale", ctypes.c_void_p), ("L", ctypes.c_void_p), ("R", ctypes.c_void_p),
+                ("rank_pad", ctypes.c_int32)]
+
+
+SLIM_OK, SLIM_ERR_NULL, SLIM_ERR_SHAPE, SLIM_ERR_ALIGN, SLIM_ERR_WORKSPACE, SLIM_ERR_HIP = 0, -1, -2, -3, -4, -5
+
+EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pack", "slim_pack_adapters",
+           "slim_unpack", "slim_workspace_bytes", "slim_linear_gemv", "slim_linear_gemm", "slim_lowrank"]
+
+
+def lib():
+    """Load libslim.so once; raise if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2410_09615_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        psz, pi32 = ctypes.POINTER(sz), ctypes.POINTER(i32)
+        L.slim_status_string.argtypes = [ctypes.c_int]
+        L.slim_status_string.restype = ctypes.c_char_p
+        L.slim_rank_pad.argtypes = [i32]
+        L.slim_rank_pad.restype = i32
+        L.slim_packed_sizes.argtypes = [slim_shape, psz, psz, psz, pi32, psz, psz]
+        L.slim_pack.argtypes = [vp, slim_shape, vp, vp, vp, vp]
+        L.slim_pack_adapters.argtypes = [vp, vp, slim_shape, vp, vp, vp]
+        L.slim_unpack.argtypes = [vp, vp, slim_shape, vp, vp, vp]
+        L.slim_workspace_bytes.argtypes = [ctypes.POINTER(slim_layer), i32, psz]
+        L.slim_linear_gemv.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp, sz, vp]
+        L.slim_linear_gemm.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp, sz, vp]
+        L.slim_lowrank.argtypes = [vp, i32, vp, vp, slim_shape, i32, vp, ctypes.c_int, vp, sz, vp]
+        for name in EXPORTS[2:]:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(fn: str, status: int):
+    if status != SLIM_OK:
+        raise SlimError(fn, status, lib().slim_status_string(status).decode())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(t: torch.Tensor):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous {dtype}")
+    return t
+
+
+def slim_status_string(status: int) -> str:
+    return lib().slim_status_string(status).decode()
+
+
+def slim_rank_pad(rank: int) -> int:
+    return int(lib().slim_rank_pad(rank))
+
+
+def slim_packed_sizes(n: int, k: int, rank: int) -> dict:
+    q, me, sc, lb, rb = (ctypes.c_size_t() for _ in range(5))
+    rp = ctypes.c_int32()
+    _check("slim_packed_sizes", lib().slim_packed_sizes(slim_shape(n, k, rank), q, me, sc, rp, lb, rb))
+    return {"qvals": q.value, "meta": me.value, "scale": sc.value, "rank_pad": rp.value,
+            "L": lb.value, "R": rb.value}
+
+
+@dataclass
+class SlimLayer:
+    """Device buffers of one compressed layer (what `slim_layer` points at)."""
+    n: int
+    k: int
+    rank: int
+    rank_pad: int
+    qvals: torch.Tensor            # uint8 [n][k/4]
+    meta: torch.Tensor             # uint8 [n][k/8]
+    scale: torch.Tensor            # float32 [n]
+    L: torch.Tensor | None         # float16 [n][rank_pad]
+    R: torch.Tensor | None         # float16 [rank_pad][k]
+
+    def c_struct(self) -> slim_layer:
+        return slim_layer(slim_shape(self.n, self.k, self.rank), self.qvals.data_ptr(), self.meta.data_ptr(),
+                          self.scale.data_ptr(), self.L.data_ptr() if self.L is not None else None,
+                          self.R.data_ptr() if self.R is not None else None, self.rank_pad)
+
+
+def slim_pack(W: torch.Tensor, qvals=None, meta=None, scale=None):
+    """W fp32 [n][k] on the device -> (qvals, meta, scale) device tensors."""
+    _dev(W, torch.float32, "W")
+    n, k = W.shape
+    sizes = slim_packed_sizes(n, k, 0)
+    if qvals is None:
+        qvals = torch.empty(sizes["qvals"], dtype=torch.uint8, device=W.device).view(n, k // 4)
+        meta = torch.empty(sizes["meta"], dtype=torch.uint8, device=W.device).view(n, k // 8)
+        scale = torch.empty(n, dtype=torch.float32, device=W.device)
+    _check("slim_pack", lib().slim_pack(_ptr(W), slim_shape(n, k, 0), _ptr(qvals), _ptr(meta), _ptr(scale),
+                                        _stream(W)))
+    return qvals, meta, scale
+
+
+def slim_pack_adapters(L: torch.Tensor, R: torch.Tensor):
+    """L fp16 [n][rank], R fp16 [rank][k] -> zero-padded (L_pad, R_pad)."""
+    _dev(L, torch.float16, "L")
+    _dev(R, torch.float16, "R")
+    n, rank = L.shape
+    k = R.shape[1]
+    if R.shape[0] != rank:
+        raise ValueError("L and R disagree on the rank")
+    rp = slim_rank_pad(rank)
+    L_pad = torch.empty(n, rp, dtype=torch.float16, device=L.device)
+    R_pad = torch.empty(rp, k, dtype=torch.float16, device=L.device)
+    _check("slim_pack_adapters", lib().slim_pack_adapters(_ptr(L), _ptr(R), slim_shape(n, k, rank), _ptr(L_pad),
+                                                          _ptr(R_pad), _stream(L)))
+    return L_pad, R_pad
+
+
+def slim_unpack(qvals: torch.Tensor, meta: torch.Tensor):
+    """(codes int8 [n][k], mask uint8 [n][k]) from the canonical bytes."""
+    _dev(qvals, torch.uint8, "qvals")
+    _dev(meta, torch.uint8, "meta")
+    n, kq = qvals.shape
+    k = kq * 4
+    codes = torch.empty(n, k, dtype=torch.int8, device=qvals.device)
+    mask = torch.empty(n, k, dtype=torch.uint8, device=qvals.device)
+    _check("slim_unpack", lib().slim_unpack(_ptr(qvals), _ptr(meta), slim_shape(n, k, 0), _ptr(codes), _ptr(mask),
+                                            _stream(qvals)))
+    return codes, mask
+
+
+def compress(W: torch.Tensor, L: torch.Tensor | None = None, R: torch.Tensor | None = None) -> SlimLayer:
+    """slim_pack (+ slim_pack_adapters) into a SlimLayer."""
+    n, k = W.shape
+    qvals, meta, scale = slim_pack(W)
+    rank, rp, Lp, Rp = 0, 0, None, None
+    if L is not None and L.shape[1] > 0:
+        rank = L.shape[1]
+        Lp, Rp = slim_pack_adapters(L, R)
+        rp = Lp.shape[1]
+    return SlimLayer(n, k, rank, rp, qvals, meta, scale, Lp, Rp)
+
+
+def slim_workspace_bytes(layer: SlimLayer, m: int) -> int:
+    out = ctypes.c_size_t()
+    cs = layer.c_struct()
+    _check("slim_workspace_bytes", lib().slim_workspace_bytes(ctypes.byref(cs), m, out))
+    return out.value
+
+
+def alloc_workspace(layer: SlimLayer, m: int) -> torch.Tensor:
+    return torch.empty(slim_workspace_bytes(layer, m), dtype=torch.uint8, device=layer.qvals.device)
+
+
+def _forward(fn_name: str, layer: SlimLayer, X: torch.Tensor, Y, workspace):
+    _dev(X, torch.float16, "X")
+    m, k = X.shape
+    if k != layer.k:
+        raise ValueError("X has the wrong number of inputs")
+    if Y is None:
+        Y = torch.empty(m, layer.n, dtype=torch.float16, device=X.device)
+    if workspace is None:
+        workspace = alloc_workspace(layer, m)
+    cs = layer.c_struct()
+    fn = getattr(lib(), fn_name)
+    _check(fn_name, fn(ctypes.byref(cs), _ptr(X), m, _ptr(Y), _ptr(workspace), workspace.numel(), _stream(X)))
+    return Y
+
+
+def slim_linear_gemv(layer: SlimLayer, X: torch.Tensor, Y=None, workspace=None) -> torch.Tensor:
+    """Decode-shaped forward, 1 <= m <= 16."""
+    return _forward("slim_linear_gemv", layer, X, Y, workspace)
+
+
+def slim_linear_gemm(layer: SlimLayer, X: torch.Tensor, Y=None, workspace=None) -> torch.Tensor:
+    """Prefill-shaped forward."""
+    return _forward("slim_linear_gemm", layer, X, Y, workspace)
+
+
+def slim_lowrank(X: torch.Tensor, R_pad: torch.Tensor, L_pad: torch.Tensor, rank: int, Y=None,
+                 accumulate: bool = False, workspace=None) -> torch.Tensor:
+    """Y (+)= (X R^T) L^T with padded adapters as produced by slim_pack_adapters."""
+    _dev(X, torch.float16, "X")
+    _dev(R_pad, torch.float16, "R_pad")
+    _dev(L_pad, torch.float16, "L_pad")
+    m, k = X.shape
+    n, rp = L_pad.shape
+    if Y is None:
+        if accumulate:
+            raise ValueError("accumulate needs Y")
+        Y = torch.empty(m, n, dtype=torch.float16, device=X.device)
+    if workspace is None:
+        tmp = SlimLayer(n, k, rank, rp, X, X, X, L_pad, R_pad)
+        workspace = torch.empty(slim_workspace_bytes(tmp, m), dtype=torch.uint8, device=X.device)
+    _check("slim_lowrank", lib().slim_lowrank(_ptr(X), m, _ptr(R_pad), _ptr(L_pad), slim_shape(n, k, rank), rp,
+                                              _ptr(Y), 1 if accumulate else 0, _ptr(workspace), workspace.numel(),
+                                              _stream(X)))
+    return Y

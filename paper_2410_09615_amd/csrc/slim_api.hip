@@ -1,0 +1,68 @@
+// Host-only parts of the boundary: status text, size queries, workspace plan.
+#include "slim_internal.h"
+
+namespace slim {
+
+static size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int gemm_t_splits(int32_t m, int32_t rank_pad, int32_t k);   // slim_gemm.hip
+
+WorkspacePlan plan_workspace(int32_t n, int32_t k, int32_t rank_pad, int32_t m)
+{
+    WorkspacePlan p{};
+    size_t t_gemv = (size_t)16 * rank_pad * sizeof(float);
+    size_t t_gemm = (size_t)m * rank_pad * sizeof(uint16_t);
+    p.t_off = 0;
+    p.t_bytes = round256(t_gemv > t_gemm ? t_gemv : t_gemm);
+    p.acc_off = p.t_off + p.t_bytes;
+    p.acc_bytes = round256((size_t)16 * n * sizeof(float));
+    p.part_off = p.acc_off + p.acc_bytes;
+    p.splits = rank_pad > 0 ? gemm_t_splits(m, rank_pad, k) : 1;
+    p.part_bytes = p.splits > 1 ? round256((size_t)p.splits * m * rank_pad * sizeof(float)) : 0;
+    p.total = p.part_off + p.part_bytes;
+    if (p.total < 256) p.total = 256;
+    return p;
+}
+
+}  // namespace slim
+
+using namespace slim;
+
+extern "C" const char *slim_status_string(int status)
+{
+    switch (status) {
+        case SLIM_OK: return "ok";
+        case SLIM_ERR_NULL: return "a required pointer is NULL";
+        case SLIM_ERR_SHAPE: return "a dimension is outside the supported range";
+        case SLIM_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+        case SLIM_ERR_WORKSPACE: return "workspace is NULL or too small";
+        case SLIM_ERR_HIP: return "a HIP runtime call failed";
+        default: return "unknown status";
+    }
+}
+
+extern "C" int32_t slim_rank_pad(int32_t rank) { return rank <= 0 ? 0 : (rank + 31) / 32 * 32; }
+
+extern "C" int slim_packed_sizes(slim_shape shape, size_t *qvals_bytes, size_t *meta_bytes, size_t *scale_bytes,
+                                 int32_t *rank_pad, size_t *L_bytes, size_t *R_bytes)
+{
+    if (shape.n < 1 || shape.k < 8 || shape.k % 8 || shape.rank < 0) return SLIM_ERR_SHAPE;
+    int32_t rp = slim_rank_pad(shape.rank);
+    if (qvals_bytes) *qvals_bytes = (size_t)shape.n * (shape.k / 4);
+    if (meta_bytes) *meta_bytes = (size_t)shape.n * (shape.k / 8);
+    if (scale_bytes) *scale_bytes = (size_t)shape.n * sizeof(float);
+    if (rank_pad) *rank_pad = rp;
+    if (L_bytes) *L_bytes = (size_t)shape.n * rp * sizeof(slim_half);
+    if (R_bytes) *R_bytes = (size_t)rp * shape.k * sizeof(slim_half);
+    return SLIM_OK;
+}
+
+extern "C" int slim_workspace_bytes(const slim_layer *layer, int32_t m, size_t *bytes)
+{
+    if (!layer || !bytes) return SLIM_ERR_NULL;
+    const slim_shape s = layer->shape;
+    if (s.n < 1 || s.k < 8 || s.k % 8 || s.rank < 0 || m < 1) return SLIM_ERR_SHAPE;
+    if (layer->rank_pad != slim_rank_pad(s.rank)) return SLIM_ERR_SHAPE;
+    *bytes = plan_workspace(s.n, s.k, layer->rank_pad, m).total;
+    return SLIM_OK;
+}

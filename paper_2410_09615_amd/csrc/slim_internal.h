@@ -1,0 +1,58 @@
+// Internal helpers shared by the libslim translation units (device + host).
+// Not part of the public boundary (include/slim.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "slim.h"
+
+namespace slim {
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half16_t __attribute__((ext_vector_type(16)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t uint2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+// Sum over the 64 lanes of a wavefront; every lane gets the total.
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+// Two's-complement nibble -> int in [-8, 7].
+__device__ __forceinline__ int nibble_to_int(uint32_t v) { return (int)(v & 7u) - (int)(v & 8u); }
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? SLIM_OK : SLIM_ERR_HIP; }
+
+// Workspace carve-up used by the forward entry points (offsets in bytes,
+// each a multiple of 256).
+struct WorkspacePlan {
+    size_t t_off, t_bytes;        // T = X R^T: fp32 [16][rank_pad] (gemv) or fp16 [m][rank_pad] (gemm)
+    size_t acc_off, acc_bytes;    // gemv: scaled quantized term, fp32 [m][n]
+    size_t part_off, part_bytes;  // gemm: split-K partials of T, fp32 [splits][m][rank_pad]
+    int splits;                   // split-K factor of the T product
+    size_t total;
+};
+
+WorkspacePlan plan_workspace(int32_t n, int32_t k, int32_t rank_pad, int32_t m);
+
+}  // namespace slim

@@ -1,0 +1,205 @@
+// slim_pack / slim_unpack / slim_pack_adapters: the encoding side of the layer.
+//
+// slim_pack is a streaming kernel bound by HBM: it reads 4 bytes per weight
+// and writes 3 bits per weight.  One workgroup owns one output row: it keeps
+// the row in registers while the row maximum is reduced (so W is read from
+// memory once), then each lane encodes the groups of 4 it holds.
+#include "slim_internal.h"
+
+namespace slim {
+
+constexpr int kPackThreads = 256;
+constexpr int kPackCached = 12;   // float4 groups a lane keeps: rows up to 4*256*12 = 12288 inputs
+
+// Kept positions of one group: order by (|w| descending, position ascending),
+// take two, return them as i0 < i1 packed as i0 | (i1 << 2).
+__device__ __forceinline__ uint32_t keep_two(float a0, float a1, float a2, float a3)
+{
+    int first = 0;
+    float best = a0;
+    if (a1 > best) { best = a1; first = 1; }
+    if (a2 > best) { best = a2; first = 2; }
+    if (a3 > best) { best = a3; first = 3; }
+    int second = -1;
+    float sb = -1.0f;
+    if (first != 0 && a0 > sb) { sb = a0; second = 0; }
+    if (first != 1 && a1 > sb) { sb = a1; second = 1; }
+    if (first != 2 && a2 > sb) { sb = a2; second = 2; }
+    if (first != 3 && a3 > sb) { sb = a3; second = 3; }
+    int i0 = first < second ? first : second;
+    int i1 = first < second ? second : first;
+    return (uint32_t)i0 | ((uint32_t)i1 << 2);
+}
+
+__device__ __forceinline__ uint32_t quantize_code(float w, float s)
+{
+    float q = rintf(w / s);               // IEEE division, round half to even
+    q = fminf(fmaxf(q, -8.0f), 7.0f);
+    return (uint32_t)(int)q & 0xFu;
+}
+
+// Encode one group: returns the qvals byte, *m4 the metadata nibble.
+__device__ __forceinline__ uint32_t encode_group(float4 v, float s, uint32_t *m4)
+{
+    uint32_t sel = keep_two(fabsf(v.x), fabsf(v.y), fabsf(v.z), fabsf(v.w));
+    uint32_t i0 = sel & 3u, i1 = sel >> 2;
+    float w[4] = {v.x, v.y, v.z, v.w};
+    float w0 = i0 == 0 ? w[0] : (i0 == 1 ? w[1] : w[2]);
+    float w1 = i1 == 1 ? w[1] : (i1 == 2 ? w[2] : w[3]);
+    *m4 = sel;
+    return quantize_code(w0, s) | (quantize_code(w1, s) << 4);
+}
+
+template <bool CACHED>
+__global__ __launch_bounds__(kPackThreads) void pack_kernel(const float *__restrict__ W, int n, int k,
+                                                            uint8_t *__restrict__ qvals,
+                                                            uint8_t *__restrict__ meta,
+                                                            float *__restrict__ scale)
+{
+    __shared__ float wave_part[kPackThreads / kWave];
+    const int ngroups = k / 4;
+    const int tid = threadIdx.x;
+    for (int o = blockIdx.x; o < n; o += gridDim.x) {
+        const float4 *row = reinterpret_cast<const float4 *>(W + (size_t)o * k);
+        float4 cache[CACHED ? kPackCached : 1];
+        float a = 0.0f;
+        if (CACHED) {
+#pragma unroll
+            for (int i = 0; i < kPackCached; ++i) {
+                int g = tid + i * kPackThreads;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (g < ngroups) v = row[g];
+                cache[i] = v;
+                a = fmaxf(a, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+            }
+        } else {
+            for (int g = tid; g < ngroups; g += kPackThreads) {
+                float4 v = row[g];
+                a = fmaxf(a, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+            }
+        }
+        a = wave_max(a);
+        __syncthreads();                       // wave_part is reused across rows
+        if ((tid & (kWave - 1)) == 0) wave_part[tid / kWave] = a;
+        __syncthreads();
+        a = fmaxf(fmaxf(wave_part[0], wave_part[1]), fmaxf(wave_part[2], wave_part[3]));
+        const float s = (a == 0.0f) ? 1.0f : a / 7.0f;
+        if (tid == 0) scale[o] = s;
+
+        uint8_t *qrow = qvals + (size_t)o * ngroups;
+        uint8_t *mrow = meta + (size_t)o * (ngroups / 2);
+        // Lanes g and g^1 hold the two groups of one metadata byte; ngroups and
+        // the stride are even, so both are active together.
+        if (CACHED) {
+#pragma unroll
+            for (int i = 0; i < kPackCached; ++i) {
+                int g = tid + i * kPackThreads;
+                if (g < ngroups) {
+                    uint32_t m4;
+                    uint32_t q = encode_group(cache[i], s, &m4);
+                    qrow[g] = (uint8_t)q;
+                    uint32_t other = __shfl_xor(m4, 1, kWave);
+                    if ((g & 1) == 0) mrow[g >> 1] = (uint8_t)(m4 | (other << 4));
+                }
+            }
+        } else {
+            for (int g = tid; g < ngroups; g += kPackThreads) {
+                uint32_t m4;
+                uint32_t q = encode_group(row[g], s, &m4);
+                qrow[g] = (uint8_t)q;
+                uint32_t other = __shfl_xor(m4, 1, kWave);
+                if ((g & 1) == 0) mrow[g >> 1] = (uint8_t)(m4 | (other << 4));
+            }
+        }
+    }
+}
+
+// One lane decodes one group: 4 codes and 4 mask bytes, one dword store each.
+__global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__ qvals,
+                                                     const uint8_t *__restrict__ meta, size_t total_groups,
+                                                     int8_t *__restrict__ codes, uint8_t *__restrict__ mask)
+{
+    for (size_t g = blockIdx.x * (size_t)blockDim.x + threadIdx.x; g < total_groups;
+         g += (size_t)gridDim.x * blockDim.x) {
+        uint32_t q = qvals[g];
+        uint32_t m4 = (meta[g >> 1] >> (4 * (g & 1))) & 0xFu;
+        uint32_t i0 = m4 & 3u, i1 = m4 >> 2;
+        uint32_t c0 = (uint32_t)nibble_to_int(q & 0xFu) & 0xFFu;
+        uint32_t c1 = (uint32_t)nibble_to_int(q >> 4) & 0xFFu;
+        // a malformed nibble with i1 == i0 keeps the later write, as a
+        // sequential decoder would
+        uint32_t cw = (i0 == i1) ? (c1 << (8 * i1)) : ((c0 << (8 * i0)) | (c1 << (8 * i1)));
+        uint32_t mw = (1u << (8 * i0)) | (1u << (8 * i1));
+        reinterpret_cast<uint32_t *>(codes)[g] = cw;
+        reinterpret_cast<uint32_t *>(mask)[g] = mw;
+    }
+}
+
+// dst [rows][dst_cols] <- src [src_rows][src_cols], zero outside the source.
+__global__ __launch_bounds__(256) void pad_copy_kernel(const uint16_t *__restrict__ src, int src_rows,
+                                                       int src_cols, uint16_t *__restrict__ dst, int rows,
+                                                       int dst_cols)
+{
+    size_t total = (size_t)rows * dst_cols;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * blockDim.x) {
+        int r = (int)(i / dst_cols), c = (int)(i % dst_cols);
+        dst[i] = (r < src_rows && c < src_cols) ? src[(size_t)r * src_cols + c] : (uint16_t)0;
+    }
+}
+
+static int grid_for(size_t items, int threads, int cap = 256 * 16)
+{
+    size_t b = (items + threads - 1) / threads;
+    if (b > (size_t)cap) b = cap;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+}  // namespace slim
+
+using namespace slim;
+
+extern "C" int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8_t *meta, float *scale,
+                         void *stream)
+{
+    if (!W || !qvals || !meta || !scale) return SLIM_ERR_NULL;
+    if (shape.n < 1 || shape.k < 8 || shape.k % 8) return SLIM_ERR_SHAPE;
+    if (!aligned16(W) || !aligned16(qvals) || !aligned16(meta) || !aligned16(scale)) return SLIM_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int grid = shape.n < 256 * 8 ? shape.n : 256 * 8;
+    if (shape.k / 4 <= kPackThreads * kPackCached)
+        hipLaunchKernelGGL(pack_kernel<true>, dim3(grid), dim3(kPackThreads), 0, st, W, shape.n, shape.k,
+                           qvals, meta, scale);
+    else
+        hipLaunchKernelGGL(pack_kernel<false>, dim3(grid), dim3(kPackThreads), 0, st, W, shape.n, shape.k,
+                           qvals, meta, scale);
+    return hip_status(hipGetLastError());
+}
+
+extern "C" int slim_unpack(const uint8_t *qvals, const uint8_t *meta, slim_shape shape, int8_t *codes,
+                           uint8_t *mask, void *stream)
+{
+    if (!qvals || !meta || !codes || !mask) return SLIM_ERR_NULL;
+    if (shape.n < 1 || shape.k < 8 || shape.k % 8) return SLIM_ERR_SHAPE;
+    if (!aligned16(qvals) || !aligned16(meta) || !aligned16(codes) || !aligned16(mask)) return SLIM_ERR_ALIGN;
+    size_t groups = (size_t)shape.n * (shape.k / 4);
+    hipLaunchKernelGGL(unpack_kernel, dim3(grid_for(groups, 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), qvals, meta, groups, codes, mask);
+    return hip_status(hipGetLastError());
+}
+
+extern "C" int slim_pack_adapters(const slim_half *L, const slim_half *R, slim_shape shape, slim_half *L_pad,
+                                  slim_half *R_pad, void *stream)
+{
+    if (!L || !R || !L_pad || !R_pad) return SLIM_ERR_NULL;
+    if (shape.n < 1 || shape.k < 8 || shape.k % 8 || shape.rank < 1) return SLIM_ERR_SHAPE;
+    if (!aligned16(L_pad) || !aligned16(R_pad)) return SLIM_ERR_ALIGN;
+    int rp = slim_rank_pad(shape.rank);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(pad_copy_kernel, dim3(grid_for((size_t)shape.n * rp, 256)), dim3(256), 0, st, L,
+                       shape.n, shape.rank, L_pad, shape.n, rp);
+    hipLaunchKernelGGL(pad_copy_kernel, dim3(grid_for((size_t)rp * shape.k, 256)), dim3(256), 0, st, R,
+                       shape.rank, shape.k, R_pad, rp, shape.k);
+    return hip_status(hipGetLastError());
+}

@@ -1,0 +1,189 @@
+"""Parity of the HIP path (through the C-ABI binding) against the CPU oracle.
+
+Packing, metadata and scales must be bit-exact.  Y must be within a relative
+Frobenius error of 2e-3 of the fp64 oracle (fp16 inputs, fp32 accumulation,
+one final rounding to fp16; T = X R^T is rounded once to fp16 on the prefill
+path).  Inputs come from the shared seeded generator.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slim_oracle as O
+from paper_2410_09615_amd import binding as B
+from paper_2410_09615_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL_Y = 2e-3
+DEV = "cuda:0"
+
+
+def _relerr(a, b):
+    return float(np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b))
+
+
+def _shape(n, k, r, outliers=True):
+    return wl.LayerShape(f"t_{n}x{k}_r{r}", n, k, r, outliers)
+
+
+def _gpu_layer(W, L, R):
+    Wd = W.to(DEV)
+    return B.compress(Wd, None if L is None else L.to(DEV), None if R is None else R.to(DEV))
+
+
+def _assert_pack_equal(layer, W):
+    ref = O.compress(W.numpy())
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.scale.cpu().numpy().view(np.uint32), ref.scale.view(np.uint32))
+    assert np.array_equal(layer.qvals.cpu().numpy(), ref.qvals)
+    assert np.array_equal(layer.meta.cpu().numpy(), ref.meta)
+    return ref
+
+
+# ---- slim_pack / slim_unpack / slim_pack_adapters: bit-exact -------------------
+
+@pytest.mark.parametrize("n,k", [(512, 512), (37, 136), (96, 1024), (3, 8), (130, 12800), (1, 4096)])
+def test_pack_bit_exact_small(n, k):
+    W = wl.make_weight(n, k, seed=n + k)
+    if n > 2:
+        W[1] = 0.0                                   # all-zero row
+        W[2, : k // 2] = 0.0                         # zero groups
+    layer = _gpu_layer(W, None, None)
+    ref = _assert_pack_equal(layer, W)
+    codes, mask = B.slim_unpack(layer.qvals, layer.meta)
+    rc, rm = O.unpack(ref.qvals, ref.meta)
+    assert np.array_equal(codes.cpu().numpy(), rc) and np.array_equal(mask.cpu().numpy(), rm)
+
+
+def test_pack_bit_exact_with_ties():
+    g = torch.Generator().manual_seed(5)
+    vals = torch.tensor([0.0, -0.0, 0.25, -0.25, 0.5, -0.5, 1.0, -1.0, 0.75, 0.125])
+    W = vals[torch.randint(0, len(vals), (256, 2048), generator=g)].contiguous()
+    _assert_pack_equal(_gpu_layer(W, None, None), W)
+    # exact halves of the scale (row max 7 -> s = 1): round-half-even cases
+    halves = torch.tensor([0.5, 1.5, 2.5, 3.5, 4.5, 5.5, 6.5, -0.5, -1.5, -2.5, -3.5, -4.5, -5.5, -6.5, 7.0, -7.0])
+    W2 = halves[torch.randint(0, len(halves), (64, 512), generator=g)].contiguous()
+    W2[:, 0] = 7.0
+    _assert_pack_equal(_gpu_layer(W2, None, None), W2)
+
+
+@pytest.mark.parametrize("shape", [wl.L7B_ATTN, wl.L7B_UP, wl.L7B_DOWN, wl.L13B_ATTN, wl.L13B_UP, wl.L70B_ATTN,
+                                   wl.L70B_UP], ids=lambda s: s.name)
+def test_pack_bit_exact_full_size(shape):
+    W = wl.make_weight(shape.n, shape.k)
+    _assert_pack_equal(_gpu_layer(W, None, None), W)
+
+
+def test_pack_adapters_pads_with_zeros():
+    L, R = wl.make_adapters(300, 640, 51)
+    Lp, Rp = B.slim_pack_adapters(L.to(DEV), R.to(DEV))
+    assert Lp.shape == (300, 64) and Rp.shape == (64, 640)
+    assert torch.equal(Lp[:, :51].cpu(), L) and torch.equal(Rp[:51].cpu(), R)
+    assert (Lp[:, 51:] == 0).all() and (Rp[51:] == 0).all()
+
+
+def test_unpack_arbitrary_valid_bytes():
+    rng = np.random.default_rng(3)
+    valid = np.array([0x4, 0x8, 0xC, 0x9, 0xD, 0xE], np.uint8)
+    n, k = 64, 1024
+    q = rng.integers(0, 256, size=(n, k // 4), dtype=np.uint8)
+    me = (valid[rng.integers(0, 6, size=(n, k // 8))] | (valid[rng.integers(0, 6, size=(n, k // 8))] << 4)).astype(np.uint8)
+    codes, mask = B.slim_unpack(torch.from_numpy(q).to(DEV), torch.from_numpy(me).to(DEV))
+    rc, rm = O.unpack(q, me)
+    assert np.array_equal(codes.cpu().numpy(), rc) and np.array_equal(mask.cpu().numpy(), rm)
+
+
+# ---- forward: decode ------------------------------------------------------------
+
+def _forward_case(shape, m, fn, seed=0, rows=None):
+    W, L, R, X = wl.make_layer(shape, m, seed=seed)
+    layer = _gpu_layer(W, L if shape.r > 0 else None, R if shape.r > 0 else None)
+    Y = fn(layer, X.to(DEV))
+    torch.cuda.synchronize()
+    ref_layer = O.compress(W.numpy())
+    Lr, Rr = (L.numpy(), R.numpy()) if shape.r > 0 else (None, None)
+    Yref = O.forward(ref_layer, Lr, Rr, X.numpy(), rows=rows)
+    Yg = Y.cpu().numpy()
+    if rows is not None:
+        Yg = Yg[:, rows]
+    assert np.isfinite(Yg).all()
+    return _relerr(Yg, Yref)
+
+
+@pytest.mark.parametrize("m", [1, 4, 8, 16])
+def test_gemv_tiny_layer(m):
+    assert _forward_case(wl.TINY, m, B.slim_linear_gemv) <= TOL_Y
+
+
+@pytest.mark.parametrize("m", [1, 4, 16])
+def test_gemv_llama7b_attention(m):
+    assert _forward_case(wl.L7B_ATTN, m, B.slim_linear_gemv) <= TOL_Y
+
+
+@pytest.mark.parametrize("n,k,r,m", [(1000, 1280, 37, 3), (17, 128, 1, 5), (2049, 640, 33, 16), (130, 11008, 410, 2)])
+def test_gemv_ragged_shapes(n, k, r, m):
+    assert _forward_case(_shape(n, k, r), m, B.slim_linear_gemv, seed=7) <= TOL_Y
+
+
+def test_gemv_without_adapters():
+    assert _forward_case(_shape(512, 1024, 0), 4, B.slim_linear_gemv, seed=3) <= TOL_Y
+
+
+@pytest.mark.parametrize("shape,m", [(wl.L13B_UP, 1), (wl.L70B_ATTN, 16), (wl.L70B_UP, 1)], ids=lambda v: str(getattr(v, "name", v)))
+def test_gemv_full_size_sampled_rows(shape, m):
+    rows = np.random.default_rng(1).choice(shape.n, size=512, replace=False)
+    rows.sort()
+    assert _forward_case(shape, m, B.slim_linear_gemv, rows=rows) <= TOL_Y
+
+
+# ---- forward: prefill -----------------------------------------------------------
+
+@pytest.mark.parametrize("m", [8, 128, 200])
+def test_gemm_tiny_layer(m):
+    assert _forward_case(wl.TINY, m, B.slim_linear_gemm) <= TOL_Y
+
+
+@pytest.mark.parametrize("n,k,r,m", [(1000, 1280, 37, 200), (130, 256, 5, 77), (384, 640, 64, 129)])
+def test_gemm_ragged_shapes(n, k, r, m):
+    assert _forward_case(_shape(n, k, r), m, B.slim_linear_gemm, seed=11) <= TOL_Y
+
+
+def test_gemm_without_adapters():
+    assert _forward_case(_shape(512, 1024, 0), 256, B.slim_linear_gemm, seed=4) <= TOL_Y
+
+
+@pytest.mark.parametrize("shape,m", [(wl.L7B_UP, 2048), (wl.L7B_DOWN, 2048)], ids=lambda v: str(getattr(v, "name", v)))
+def test_gemm_llama7b_mlp_sampled_rows(shape, m):
+    rows = np.random.default_rng(2).choice(shape.n, size=256, replace=False)
+    rows.sort()
+    assert _forward_case(shape, m, B.slim_linear_gemm, rows=rows) <= TOL_Y
+
+
+def test_gemv_and_gemm_agree():
+    W, L, R, X = wl.make_layer(wl.TINY, 16, seed=2)
+    layer = _gpu_layer(W, L, R)
+    Xd = X.to(DEV)
+    a = B.slim_linear_gemv(layer, Xd).float()
+    b = B.slim_linear_gemm(layer, Xd).float()
+    assert float((a - b).norm() / a.norm()) <= 1e-3
+
+
+# ---- slim_lowrank -----------------------------------------------------------------
+
+@pytest.mark.parametrize("m", [1, 16, 300])
+@pytest.mark.parametrize("accumulate", [False, True])
+def test_lowrank(m, accumulate):
+    n, k, r = 640, 1280, 51
+    L, R = wl.make_adapters(n, k, r, 21, 22)
+    X = wl.make_activations(m, k, True, 23, 24)
+    Lp, Rp = B.slim_pack_adapters(L.to(DEV), R.to(DEV))
+    ref = O.xr(X.numpy(), R.numpy()) @ L.numpy().astype(np.float64).T
+    Y0 = None
+    if accumulate:
+        Y0 = (torch.randn(m, n, generator=torch.Generator().manual_seed(9)) * ref.std()).to(torch.float16)
+        ref = ref + Y0.numpy().astype(np.float64)
+        Y0 = Y0.to(DEV)
+    Y = B.slim_lowrank(X.to(DEV), Rp, Lp, r, Y=Y0, accumulate=accumulate)
+    torch.cuda.synchronize()
+    assert _relerr(Y.cpu().numpy(), ref) <= TOL_Y

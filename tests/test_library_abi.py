@@ -1,0 +1,88 @@
+"""The C-ABI library loads, exports what include/slim.h declares, and its
+host-side logic (size queries, argument validation) behaves as documented.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2410_09615_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "slim.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(slim_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    lib = B.lib()
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings():
+    for code in (0, -1, -2, -3, -4, -5):
+        assert B.slim_status_string(code)
+    assert B.slim_status_string(-99) == "unknown status"
+
+
+def test_rank_pad_and_sizes():
+    assert [B.slim_rank_pad(r) for r in (0, 1, 32, 33, 51, 410, 512, 820)] == [0, 32, 32, 64, 64, 416, 512, 832]
+    s = B.slim_packed_sizes(4096, 4096, 410)
+    assert s == {"qvals": 4096 * 1024, "meta": 4096 * 512, "scale": 4096 * 4, "rank_pad": 416,
+                 "L": 4096 * 416 * 2, "R": 416 * 4096 * 2}
+    for bad in ((0, 512, 1), (8, 4, 0), (8, 12, 0), (8, 16, -1)):
+        with pytest.raises(B.SlimError) as e:
+            B.slim_packed_sizes(*bad)
+        assert e.value.status == B.SLIM_ERR_SHAPE
+
+
+def test_workspace_query():
+    layer = B.slim_layer(B.slim_shape(4096, 4096, 410), None, None, None, None, None, 416)
+    out = ctypes.c_size_t()
+    assert B.lib().slim_workspace_bytes(ctypes.byref(layer), 16, out) == 0
+    # at least T (fp32 [16][416]) and the quantized-term buffer (fp32 [16][4096])
+    assert out.value >= 16 * 416 * 4 + 16 * 4096 * 4
+    big = ctypes.c_size_t()
+    assert B.lib().slim_workspace_bytes(ctypes.byref(layer), 2048, big) == 0
+    assert big.value >= 2048 * 416 * 2
+    layer.rank_pad = 410                                # not slim_rank_pad(rank)
+    assert B.lib().slim_workspace_bytes(ctypes.byref(layer), 16, out) == B.SLIM_ERR_SHAPE
+    assert B.lib().slim_workspace_bytes(None, 16, out) == B.SLIM_ERR_NULL
+
+
+def test_argument_validation_returns_codes_before_any_launch():
+    lib = B.lib()
+    shape = B.slim_shape(128, 256, 0)
+    a = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    assert lib.slim_pack(None, shape, a, a, a, None) == B.SLIM_ERR_NULL
+    assert lib.slim_pack(a, B.slim_shape(128, 12, 0), a, a, a, None) == B.SLIM_ERR_SHAPE
+    assert lib.slim_pack(ctypes.c_void_p(0x1004), shape, a, a, a, None) == B.SLIM_ERR_ALIGN
+    assert lib.slim_unpack(a, None, shape, a, a, None) == B.SLIM_ERR_NULL
+    assert lib.slim_pack_adapters(a, a, shape, a, a, None) == B.SLIM_ERR_SHAPE      # rank 0
+    layer = B.slim_layer(shape, 0x1000, 0x1000, 0x1000, None, None, 0)
+    for fn in (lib.slim_linear_gemv, lib.slim_linear_gemm):
+        assert fn(None, a, 1, a, a, 1 << 20, None) == B.SLIM_ERR_NULL
+        assert fn(ctypes.byref(layer), a, 0, a, a, 1 << 20, None) == B.SLIM_ERR_SHAPE
+        assert fn(ctypes.byref(layer), a, 1, a, a, 16, None) == B.SLIM_ERR_WORKSPACE
+        assert fn(ctypes.byref(layer), a, 1, a, None, 0, None) == B.SLIM_ERR_WORKSPACE
+    assert lib.slim_linear_gemv(ctypes.byref(layer), a, 17, a, a, 1 << 20, None) == B.SLIM_ERR_SHAPE
+    odd = B.slim_layer(B.slim_shape(128, 192, 0), 0x1000, 0x1000, 0x1000, None, None, 0)
+    assert lib.slim_linear_gemv(ctypes.byref(odd), a, 1, a, a, 1 << 20, None) == B.SLIM_ERR_SHAPE   # k % 128
+    withrank = B.slim_layer(B.slim_shape(128, 256, 8), 0x1000, 0x1000, 0x1000, None, None, 32)
+    assert lib.slim_linear_gemm(ctypes.byref(withrank), a, 4, a, a, 1 << 20, None) == B.SLIM_ERR_NULL
+    assert lib.slim_lowrank(a, 4, a, a, B.slim_shape(128, 256, 0), 0, a, 0, a, 1 << 20, None) == B.SLIM_ERR_SHAPE
+    assert lib.slim_lowrank(a, 4, a, a, B.slim_shape(128, 256, 8), 8, a, 0, a, 1 << 20, None) == B.SLIM_ERR_SHAPE
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libslim.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        B.lib()
