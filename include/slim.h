@@ -115,8 +115,12 @@ int slim_unpack(const uint8_t *qvals, const uint8_t *meta, slim_shape shape, int
 /*
  * Scratch the forward calls need for a layer at m tokens (a HOST out-pointer).
  * The same size covers slim_linear_gemv (m <= 16), slim_linear_gemm and
- * slim_lowrank.  The workspace needs no initialisation and carries nothing
- * between calls; two calls that overlap in time need two workspaces.
+ * slim_lowrank.
+ * The workspace must be ZERO-FILLED ONCE before its first use (hipMemset):
+ * its first bytes hold a small accumulator (T = X R^T of the decode path,
+ * added to with atomics) and a counter that every decode call finds zero and
+ * leaves zero.  Nothing else is carried between calls.  Two calls that
+ * overlap in time need two workspaces.
  */
 int slim_workspace_bytes(const slim_layer *layer, int32_t m, size_t *bytes);
 

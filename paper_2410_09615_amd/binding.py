@@ -186,7 +186,7 @@ def slim_workspace_bytes(layer: SlimLayer, m: int) -> int:
 
 
 def alloc_workspace(layer: SlimLayer, m: int) -> torch.Tensor:
-    return torch.empty(slim_workspace_bytes(layer, m), dtype=torch.uint8, device=layer.qvals.device)
+    return torch.zeros(slim_workspace_bytes(layer, m), dtype=torch.uint8, device=layer.qvals.device)
 
 
 def _forward(fn_name: str, layer: SlimLayer, X: torch.Tensor, Y, workspace):
@@ -228,7 +228,7 @@ def slim_lowrank(X: torch.Tensor, R_pad: torch.Tensor, L_pad: torch.Tensor, rank
         Y = torch.empty(m, n, dtype=torch.float16, device=X.device)
     if workspace is None:
         tmp = SlimLayer(n, k, rank, rp, X, X, X, L_pad, R_pad)
-        workspace = torch.empty(slim_workspace_bytes(tmp, m), dtype=torch.uint8, device=X.device)
+        workspace = torch.zeros(slim_workspace_bytes(tmp, m), dtype=torch.uint8, device=X.device)
     _check("slim_lowrank", lib().slim_lowrank(_ptr(X), m, _ptr(R_pad), _ptr(L_pad), slim_shape(n, k, rank), rp,
                                               _ptr(Y), 1 if accumulate else 0, _ptr(workspace), workspace.numel(),
                                               _stream(X)))

@@ -14,6 +14,7 @@ LIB = os.path.join(PKG, "libslim.so")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-munsafe-fp-atomics",
     "-Wall", "-Wno-unused-function",
 ]
 

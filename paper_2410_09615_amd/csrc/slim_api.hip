@@ -10,12 +10,12 @@ int gemm_t_splits(int32_t m, int32_t rank_pad, int32_t k);   // slim_gemm.hip
 WorkspacePlan plan_workspace(int32_t n, int32_t k, int32_t rank_pad, int32_t m)
 {
     WorkspacePlan p{};
-    size_t t_gemv = (size_t)16 * rank_pad * sizeof(float);
-    size_t t_gemm = (size_t)m * rank_pad * sizeof(uint16_t);
-    p.t_off = 0;
-    p.t_bytes = round256(t_gemv > t_gemm ? t_gemv : t_gemm);
+    p.dec_off = 0;
+    p.dec_bytes = 256 + 2 * round256((size_t)16 * rank_pad * sizeof(float));
+    p.t_off = p.dec_off + p.dec_bytes;
+    p.t_bytes = m > 16 ? round256((size_t)m * rank_pad * sizeof(uint16_t)) : 0;
     p.acc_off = p.t_off + p.t_bytes;
-    p.acc_bytes = round256((size_t)16 * n * sizeof(float));
+    p.acc_bytes = m <= 16 ? round256((size_t)plan_decode(n, k, rank_pad, m).slots * m * n * sizeof(float)) : 0;
     p.part_off = p.acc_off + p.acc_bytes;
     p.splits = rank_pad > 0 ? gemm_t_splits(m, rank_pad, k) : 1;
     p.part_bytes = p.splits > 1 ? round256((size_t)p.splits * m * rank_pad * sizeof(float)) : 0;

@@ -295,7 +295,7 @@ static void launch_t(const half_t *X, int m, const half_t *R, int k, int rank_pa
 }
 
 int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t *L, int n, int k, int rank_pad,
-                          half_t *Y, int accumulate, float *T, hipStream_t st);   // slim_gemv.hip
+                          half_t *Y, int accumulate, float *T, unsigned *counter, hipStream_t st);   // slim_gemv.hip
 
 }  // namespace slim
 
@@ -362,7 +362,8 @@ extern "C" int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, c
     half_t *Yh = reinterpret_cast<half_t *>(Y);
     if (m <= 16)
         return launch_lowrank_decode(Xh, m, Rh, Lh, shape.n, shape.k, rank_pad, Yh, accumulate,
-                                     reinterpret_cast<float *>(ws + p.t_off), st);
+                                     reinterpret_cast<float *>(ws + p.dec_off + 256),
+                                     reinterpret_cast<unsigned *>(ws + p.dec_off), st);
 
     half_t *T = reinterpret_cast<half_t *>(ws + p.t_off);
     launch_t(Xh, m, Rh, shape.k, rank_pad, T, reinterpret_cast<float *>(ws + p.part_off), p.splits, st);

@@ -1,146 +1,558 @@
-// slim_linear_gemv: decode-shaped forward (1 <= m <= 16 tokens).
+// slim_linear_gemv: decode-shaped forward (1 <= m <= 16 tokens), HBM-bound.
 //
-// Two launches.  Kernel 1 treats the adapter factor R as `rank_pad` more
-// output rows of the same X: one wavefront per row streams either a packed
-// weight row (codes + positions, dequantized in registers) or a fp16 row of R,
-// reduces its partial sums across the 64 lanes and writes the scaled
-// quantized term acc[m][o] or T[m][j] = (X R^T)[m][j] in fp32.  Kernel 2
-// streams L and writes Y[m][o] = fp16(acc[m][o] + sum_j T[m][j] L[o][j]).
+// Two launches; the kernel boundary is the only device-wide synchronisation
+// (an in-kernel wait of all blocks on one counter was measured at about 18 us
+// on this eight-die part, a launch boundary costs about 3 us).
+//
+//  part 1  A wavefront owns "units" of 16 rows x a slice of inputs, streams
+//          them with 128-bit loads straight into registers, and feeds the
+//          matrix cores with the tokens as the 16 columns of the B operand.
+//          Rows are the packed weight rows AND the rank_pad rows of R (the
+//          adapter stage T = X R^T is just more output rows of the same X):
+//           - packed rows: the two int4 codes of a group become two fp16
+//             values in registers and go, with the group's 2-bit position
+//             pair as the index operand, into the structured-sparse matrix
+//             instruction (V_SMFMAC_F32_16X16X64_F16), which picks the
+//             matching X values itself: the canonical metadata bytes are
+//             exactly that instruction's index format;
+//           - R rows: dense fp16 matrix instruction.
+//          X (the block's k-chunk of it) sits in LDS in fp16, zero-padded to
+//          whole units and with one extra all-zero row that the lanes of
+//          unused token columns read, so the inner loop has no branches.
+//          A packed-row task writes partial sums to P[slot][token][row]; an R
+//          unit adds its partial sums to T with fp32 atomics.  The loads of
+//          the next unit are in flight while the current one is computed.
+//  part 2  Y[t][o] = fp16(scale[o] * sum_slot P[slot][t][o] + sum_j T[t][j] L[o][j]):
+//          L rows stream through the dense matrix instruction against T held
+//          in LDS as an fp16 hi/lo pair (T keeps fp32 accuracy).
+//
+// Every 128-bit load instruction of a wavefront covers 64 contiguous bytes
+// (R, L, metadata) or 128 bytes at stride 32 (codes) of each of 16 rows.
+//
+// State between calls lives in the head of the workspace: two T buffers used
+// alternately (a call accumulates into one and zeroes the other, which the
+// previous call left dirty) and an epoch word that selects the buffer.  All of
+// it starts as zeros.
 #include "slim_internal.h"
 
 namespace slim {
 
 constexpr int kMaxTokens = 16;
-constexpr int kGemvThreads = 256;
-constexpr int kGemvWaves = kGemvThreads / kWave;
+constexpr int kDecThreads = 256;
+constexpr int kDecWaves = kDecThreads / kWave;
+constexpr int kLdsPad = 8;                 // halves of padding per LDS row (16 B)
+constexpr int kLdsBudget = 72 * 1024;      // bytes of LDS per block: two blocks per CU
+constexpr int kUnitK = 1024;               // inputs per packed-row unit
+constexpr int kUnitR = 256;                // inputs per R unit
 
-__global__ __launch_bounds__(kGemvThreads) void gemv_rows_kernel(
-    const uint8_t *__restrict__ qvals, const uint8_t *__restrict__ meta, const float *__restrict__ scale,
-    const half_t *__restrict__ R, const half_t *__restrict__ X, int n, int k, int rank_pad, int m,
-    float *__restrict__ acc_out, float *__restrict__ T_out)
+struct DecodeArgs {
+    const uint8_t *qvals;
+    const uint8_t *meta;
+    const float *scale;
+    const half_t *R;
+    const half_t *L;
+    const half_t *X;
+    half_t *Y;
+    float *P;            // [slots][m][n]; nullptr: no packed term (slim_lowrank)
+    float *T;            // two buffers of [16][rank_pad] fp32
+    unsigned *ctrl;      // [0] epoch, [1] epoch + 1 while a call is between its two launches
+    int n, k, rank_pad, m;
+    int mp;              // token rows of the LDS tiles (1, 4, 8 or 16) before the zero row
+    int n_packed;        // rows with a packed term in part 1 (n, or 0)
+    int kc;              // inputs per chunk (multiple of kUnitK)
+    int nch;             // number of chunks
+    int sl;              // inputs per packed-row task (multiple of kUnitK)
+    int wsl_full;        // tasks per row tile in a full chunk
+    int slots;           // total partial slots
+    int accumulate;      // slim_lowrank only: add the fp16 value already in Y
+};
+
+// Four packed groups (one dword of code bytes) -> eight fp16 values in
+// matrix-operand order: value 2g is the low nibble of byte g, value 2g+1 its
+// high nibble.
+__device__ __forceinline__ half8_t codes_to_half8(uint32_t q)
 {
+    const uint32_t x = q ^ 0x88888888u;            // two's complement -> offset by 8
+    const half2_t mul = {(half_t)1.0f, (half_t)0.0625f};
+    const half2_t add = {(half_t)-1032.0f, (half_t)-72.0f};
+    half8_t out;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        // bytes [b, 0x64, b, 0x64]: both halves read 1024 + b; keep the low
+        // nibble in the low half and the high nibble (x16) in the high half.
+        // Selector bytes 4..7 pick bytes of the first operand, 0..3 of the second.
+        const uint32_t sel = ((4u + g) << 16) | (4u + g);
+        uint32_t v = __builtin_amdgcn_perm(x, 0x64646464u, sel);
+        v &= 0x64F0640Fu;
+        half2_t h = __builtin_bit_cast(half2_t, v);
+        h = __builtin_elementwise_fma(h, mul, add);  // (1024+n0)-1032, (1024+16 n1)/16-72
+        out[2 * g] = h[0];
+        out[2 * g + 1] = h[1];
+    }
+    return out;
+}
+
+// One unit of part 1: which rows, which inputs, and where its task stands.
+struct Unit {
+    int q;         // task index within this wave's chunk (-1: none)
+    int u;         // unit within the task
+    int tile;      // row tile (16 rows)
+    int k0;        // first input, chunk-relative
+    int k1;        // end of the inputs of this unit, chunk-relative
+    int slot_s;    // packed rows: slice index of the task in the chunk
+    bool is_r;
+    bool last;     // last unit of its task
+};
+
+struct UnitRegs {
+    uint4_t r[8];  // the 8 x 128-bit loads of one unit
+};
+
+// Geometry of part 1 for one block (one k-chunk).
+struct Part1Geom {
+    int kbeg, klen, rsub, n_rtasks, wsl, n_tasks, gstride;
+};
+
+__device__ __forceinline__ Unit describe_unit(const DecodeArgs &a, const Part1Geom &g, int q, int u)
+{
+    Unit d;
+    d.q = q;
+    d.u = u;
+    d.tile = d.k0 = d.k1 = d.slot_s = 0;
+    d.is_r = false;
+    d.last = true;
+    if (q >= g.n_tasks) {
+        d.q = -1;
+    } else if (q < g.n_rtasks) {
+        d.is_r = true;
+        d.tile = q / g.rsub;
+        d.k0 = (q - d.tile * g.rsub) * kUnitR;
+        d.k1 = min(g.klen, d.k0 + kUnitR);
+    } else {
+        const int qq = q - g.n_rtasks;
+        d.tile = qq / g.wsl;
+        d.slot_s = qq - d.tile * g.wsl;
+        const int t0 = d.slot_s * a.sl;
+        const int t1 = min(g.klen, t0 + a.sl);
+        d.k0 = t0 + u * kUnitK;
+        d.k1 = min(t1, d.k0 + kUnitK);
+        d.last = d.k0 + kUnitK >= t1;
+    }
+    return d;
+}
+
+// Loads of one unit: up to 8 x 128 bit per lane.
+//  R unit:      8 inputs of row lx per matrix step (8 steps of 32 inputs)
+//  packed unit: per 512 inputs (two halves per unit): 2 quads of codes, 1 of
+//               positions, for the lane's 128 inputs of row lx
+// Whatever lies beyond the end of the unit's inputs or rows is loaded as zero.
+__device__ __forceinline__ void issue_unit(const DecodeArgs &a, const Part1Geom &g, const Unit &d, int lx, int ly,
+                                           UnitRegs &b)
+{
+    const uint4_t zero = {0u, 0u, 0u, 0u};
+    if (d.q < 0) return;
+    if (d.is_r) {
+        const half_t *p = a.R + (size_t)(16 * d.tile + lx) * a.k + g.kbeg + d.k0 + 8 * ly;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const bool valid = d.k0 + 32 * t < d.k1;
+            b.r[t] = valid ? *reinterpret_cast<const uint4_t *>(p + 32 * t) : zero;
+        }
+    } else {
+        const int o = 16 * d.tile + lx;
+        const bool rowok = o < a.n_packed;
+        const size_t row = rowok ? o : 0;
+        const int kl0 = d.k0 + 128 * ly;
+        const int kl1 = kl0 + 512;
+        const bool valid0 = rowok && kl0 < d.k1;
+        const bool valid1 = rowok && kl1 < d.k1;
+        const int kg0 = g.kbeg + (valid0 ? kl0 : 0);
+        const int kg1 = g.kbeg + (valid1 ? kl1 : 0);
+        const uint4_t *qp0 = reinterpret_cast<const uint4_t *>(a.qvals + row * (a.k / 4) + kg0 / 4);
+        const uint4_t *mp0 = reinterpret_cast<const uint4_t *>(a.meta + row * (a.k / 8) + kg0 / 8);
+        const uint4_t *qp1 = reinterpret_cast<const uint4_t *>(a.qvals + row * (a.k / 4) + kg1 / 4);
+        const uint4_t *mp1 = reinterpret_cast<const uint4_t *>(a.meta + row * (a.k / 8) + kg1 / 8);
+        b.r[0] = valid0 ? qp0[0] : zero;
+        b.r[1] = valid0 ? qp0[1] : zero;
+        b.r[2] = valid0 ? mp0[0] : zero;
+        b.r[3] = valid1 ? qp1[0] : zero;
+        b.r[4] = valid1 ? qp1[1] : zero;
+        b.r[5] = valid1 ? mp1[0] : zero;
+    }
+}
+
+// One half (512 inputs) of a packed unit: 8 sparse matrix instructions.
+// B operand of instruction t: values 0-7 pair with the A lanes of k-block
+// (ly >> 1), values 8-15 with k-block 2 + (ly >> 1); inside the lane's 128
+// inputs they are the 8 inputs at 16 t + 8 (ly & 1).
+template <int H>
+__device__ __forceinline__ void packed_half(const UnitRegs &b, const half_t *xk, float4_t &acc0, float4_t &acc1)
+{
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint32_t qd = t < 4 ? b.r[3 * H][t] : b.r[3 * H + 1][t - 4];
+        const half8_t av = codes_to_half8(qd);
+        const half8_t b1 = *reinterpret_cast<const half8_t *>(xk + 512 * H + 16 * t);
+        const half8_t b2 = *reinterpret_cast<const half8_t *>(xk + 512 * H + 256 + 16 * t);
+        const half16_t bv = __builtin_shufflevector(b1, b2, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+        const int idx = (int)b.r[3 * H + 2][t >> 1];
+        // even t: index bits 15..0, odd t: bits 31..16 of the position dword
+        if (t & 1)
+            acc1 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(av, bv, acc1, idx, 0, 1);
+        else
+            acc0 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(av, bv, acc0, idx, 0, 0);
+    }
+}
+
+// ---- part 1: packed rows -> P, R rows -> T (atomics) ----
+__global__ __launch_bounds__(kDecThreads, 2) void decode_part1_kernel(DecodeArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) half_t lds[];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = blockIdx.x * kGemvWaves + threadIdx.x / kWave;
-    const int nwaves = gridDim.x * kGemvWaves;
-    const int rows = n + rank_pad;
-    for (int row = wave; row < rows; row += nwaves) {
-        float acc[kMaxTokens];
+    const int wave = threadIdx.x / kWave;
+    const int lx = lane & 15;       // A-operand row / B-operand token
+    const int ly = lane >> 4;       // k-block of the lane
+    const int chunk = blockIdx.x % a.nch;
+    const int rp = a.rank_pad;
+    const int ldx = a.kc + kLdsPad;
+
+    Part1Geom g;
+    g.kbeg = chunk * a.kc;
+    g.klen = min(a.k, g.kbeg + a.kc) - g.kbeg;
+    g.rsub = (g.klen + kUnitR - 1) / kUnitR;
+    g.n_rtasks = (rp / 16) * g.rsub;
+    g.wsl = (g.klen + a.sl - 1) / a.sl;
+    g.n_tasks = g.n_rtasks + ((a.n_packed + 15) / 16) * g.wsl;
+    g.gstride = (gridDim.x / a.nch) * kDecWaves;
+
+    // first loads go out before anything else
+    UnitRegs bufA, bufB;
+    Unit cur = describe_unit(a, g, (blockIdx.x / a.nch) * kDecWaves + wave, 0);
+    issue_unit(a, g, cur, lx, ly, bufA);
+
+    // T of this call: the epoch selects one of two buffers.  The other one is
+    // dirty from the previous call and nobody uses it during this call: zero it
+    // here, so that part 2 can simply add the two buffers.  (A vector load: the
+    // wait for it must not sit on the scalar/LDS counter.)
+    // The epoch is first needed when an R unit is finished; the cleaning is
+    // done at the end of the kernel.
+    const unsigned epoch = __builtin_nontemporal_load(a.ctrl);
+    float *Tcur = a.T + (size_t)(epoch & 1u) * kMaxTokens * rp;
+
+    // stage this chunk of X: mp token rows (rows >= m zero), inputs beyond the
+    // chunk zero up to kc, then one all-zero row
+    // (loads are issued in batches of 8 per lane before the LDS stores, so the
+    // copy costs a few memory round trips, not one per element)
+    {
+        const int per_row = a.kc / 8;                       // 128-bit pieces per row
+        const int total = (a.mp + 1) * per_row;
+        for (int e0 = threadIdx.x; e0 < total; e0 += 8 * kDecThreads) {
+            uint4_t v[8];
 #pragma unroll
-        for (int t = 0; t < kMaxTokens; ++t) acc[t] = 0.0f;
-        if (row < n) {
-            const uint8_t *qrow = qvals + (size_t)row * (k / 4);
-            const uint8_t *mrow = meta + (size_t)row * (k / 8);
-            // a lane takes 8 groups (32 inputs) per step
-            for (int g0 = lane * 8; g0 < k / 4; g0 += kWave * 8) {
-                uint2_t q = *reinterpret_cast<const uint2_t *>(qrow + g0);
-                uint32_t me = *reinterpret_cast<const uint32_t *>(mrow + g0 / 2);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    uint32_t b = ((j < 4 ? q.x : q.y) >> (8 * (j & 3))) & 0xFFu;
-                    uint32_t nib = (me >> (4 * j)) & 0xFu;
-                    float c0 = (float)nibble_to_int(b & 0xFu);
-                    float c1 = (float)nibble_to_int(b >> 4);
-                    int k0 = 4 * (g0 + j) + (int)(nib & 3u);
-                    int k1 = 4 * (g0 + j) + (int)(nib >> 2);
-#pragma unroll
-                    for (int t = 0; t < kMaxTokens; ++t)
-                        if (t < m) {
-                            acc[t] = fmaf(c0, (float)X[(size_t)t * k + k0], acc[t]);
-                            acc[t] = fmaf(c1, (float)X[(size_t)t * k + k1], acc[t]);
-                        }
-                }
+            for (int i = 0; i < 8; ++i) {
+                const int e = e0 + i * kDecThreads;
+                const int row = e / per_row, c = e - row * per_row;
+                v[i] = uint4_t{0u, 0u, 0u, 0u};
+                if (e < total && row < a.m && c * 8 < g.klen)
+                    v[i] = *reinterpret_cast<const uint4_t *>(a.X + (size_t)row * a.k + g.kbeg + c * 8);
             }
-            const float s = scale[row];
 #pragma unroll
-            for (int t = 0; t < kMaxTokens; ++t)
-                if (t < m) {
-                    float v = wave_sum(acc[t]);
-                    if (lane == 0) acc_out[(size_t)t * n + row] = s * v;
-                }
+            for (int i = 0; i < 8; ++i) {
+                const int e = e0 + i * kDecThreads;
+                const int row = e / per_row, c = e - row * per_row;
+                if (e < total) *reinterpret_cast<uint4_t *>(lds + row * ldx + c * 8) = v[i];
+            }
+        }
+    }
+    __syncthreads();
+
+    // this lane's B-operand row: its token, or the zero row
+    const half_t *xrow = lds + (lx < a.mp ? lx : a.mp) * ldx;
+    const half_t *xrow_packed = xrow + 128 * (ly >> 1) + 8 * (ly & 1);
+    const half_t *xrow_r = xrow + 8 * ly;
+    float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+    while (cur.q >= 0) {
+        const Unit nxt = cur.last ? describe_unit(a, g, cur.q + g.gstride, 0) : describe_unit(a, g, cur.q, cur.u + 1);
+        issue_unit(a, g, nxt, lx, ly, bufB);
+        if (cur.is_r) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const half8_t bv = *reinterpret_cast<const half8_t *>(xrow_r + cur.k0 + 32 * t);
+                const half8_t av = __builtin_bit_cast(half8_t, bufA.r[t]);
+                if (t & 1)
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
+                else
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
+            }
         } else {
-            const int j = row - n;
-            const half_t *rrow = R + (size_t)j * k;
-            for (int c0 = lane * 8; c0 < k; c0 += kWave * 8) {
-                half8_t rv = *reinterpret_cast<const half8_t *>(rrow + c0);
+            packed_half<0>(bufA, xrow_packed + cur.k0, acc0, acc1);
+            packed_half<1>(bufA, xrow_packed + cur.k0, acc0, acc1);
+        }
+        if (cur.last) {
+            // lane holds token lx, rows 16 tile + 4 ly .. + 3
+            const float4_t acc = acc0 + acc1;
+            acc0 = float4_t{0.f, 0.f, 0.f, 0.f};
+            acc1 = acc0;
+            if (lx < a.m) {
+                if (cur.is_r) {
+                    float *tp = Tcur + (size_t)lx * rp + 16 * cur.tile + 4 * ly;
 #pragma unroll
-                for (int t = 0; t < kMaxTokens; ++t)
-                    if (t < m) {
-                        half8_t xv = *reinterpret_cast<const half8_t *>(X + (size_t)t * k + c0);
+                    for (int v = 0; v < 4; ++v)
+                        __hip_atomic_fetch_add(tp + v, acc[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    const int slot = chunk * a.wsl_full + cur.slot_s;
+                    const int ob = 16 * cur.tile + 4 * ly;
+                    float *pp = a.P + ((size_t)slot * a.m + lx) * a.n + ob;
+                    if (ob + 3 < a.n && (a.n & 3) == 0) {
+                        *reinterpret_cast<float4_t *>(pp) = acc;
+                    } else {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) acc[t] = fmaf((float)rv[e], (float)xv[e], acc[t]);
+                        for (int v = 0; v < 4; ++v)
+                            if (ob + v < a.n) pp[v] = acc[v];
                     }
-            }
-#pragma unroll
-            for (int t = 0; t < kMaxTokens; ++t)
-                if (t < m) {
-                    float v = wave_sum(acc[t]);
-                    if (lane == 0) T_out[(size_t)t * rank_pad + j] = v;
                 }
+            }
         }
+        bufA = bufB;
+        cur = nxt;
     }
+
+    float *Told = a.T + (size_t)((epoch & 1u) ^ 1u) * kMaxTokens * rp;
+    for (int j = blockIdx.x * kDecThreads + threadIdx.x; j < kMaxTokens * rp; j += gridDim.x * kDecThreads)
+        Told[j] = 0.0f;
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.ctrl[1] = epoch + 1u;
 }
 
-// Y[t][o] = fp16(base[t][o] + sum_j T[t][j] L[o][j]); base == nullptr reads 0,
-// accumulate != 0 adds the fp16 value already in Y.
-__global__ __launch_bounds__(kGemvThreads) void gemv_adapter_out_kernel(
-    const float *__restrict__ base, const float *__restrict__ T, const half_t *__restrict__ L, int n,
-    int rank_pad, int m, int accumulate, half_t *__restrict__ Y)
+// ---- part 2: Y = scale * sum P + T L^T ----
+// NB = 128-bit L loads a lane issues at once (one per 32 ranks); rank_pad / 32
+// is a multiple of NB.
+template <int NB>
+__global__ __launch_bounds__(kDecThreads, 2) void decode_part2_kernel(DecodeArgs a)
 {
+    extern __shared__ __attribute__((aligned(16))) half_t lds[];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = blockIdx.x * kGemvWaves + threadIdx.x / kWave;
-    const int nwaves = gridDim.x * kGemvWaves;
-    for (int o = wave; o < n; o += nwaves) {
-        float acc[kMaxTokens];
+    const int wave = threadIdx.x / kWave;
+    const int lx = lane & 15;
+    const int ly = lane >> 4;
+    const int rp = a.rank_pad;
+    const int wtiles = (a.n + 15) / 16;
+    const int nbatch = rp / (32 * NB);
+    const int tile0 = blockIdx.x * kDecWaves + wave;
+    const int tstride = gridDim.x * kDecWaves;
+
+    // L of the first tile goes out first: it does not depend on T
+    uint4_t lvA[NB], lvB[NB];
+    auto issue_l = [&](int ot, int batch, uint4_t (&lv)[NB]) {
+        const int o = 16 * ot + lx;
+        const bool rowok = batch < nbatch && ot < wtiles && o < a.n;
+        // step t takes ranks 32 t + 8 ly .. + 7: 64 contiguous bytes per row and load
+        const half_t *lp = a.L + (size_t)(rowok ? o : 0) * rp + (rowok ? batch : 0) * 32 * NB + 8 * ly;
 #pragma unroll
-        for (int t = 0; t < kMaxTokens; ++t) acc[t] = 0.0f;
-        const half_t *lrow = L + (size_t)o * rank_pad;
-        for (int j0 = lane * 8; j0 < rank_pad; j0 += kWave * 8) {
-            half8_t lv = *reinterpret_cast<const half8_t *>(lrow + j0);
+        for (int t = 0; t < NB; ++t)
+            lv[t] = rowok ? *reinterpret_cast<const uint4_t *>(lp + 32 * t) : uint4_t{0u, 0u, 0u, 0u};
+    };
+    if (nbatch > 0) issue_l(tile0, 0, lvA);
+
+    // T = T0 + T1: one of the two buffers holds this call's sums, the other is
+    // zero (part 1 cleaned it), so no need to know which is which
+    const float *T0 = a.T;
+    const float *T1 = a.T + (size_t)kMaxTokens * rp;
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.ctrl[0] = a.ctrl[1];       // next call: next epoch
+
+
+    // T -> LDS as fp16 hi + lo, mp token rows then one zero row
+    const int ldt = rp + kLdsPad;
+    half_t *t_hi = lds;
+    half_t *t_lo = lds + (a.mp + 1) * ldt;
+    if (rp > 0) {
+        // 4 ranks per piece, 8 pieces per lane in flight before the LDS stores
+        const int per_row = rp / 4;
+        const int total = (a.mp + 1) * per_row;
+        for (int e0 = threadIdx.x; e0 < total; e0 += 8 * kDecThreads) {
+            float4_t v[8];
 #pragma unroll
-            for (int t = 0; t < kMaxTokens; ++t)
-                if (t < m) {
-                    const float *tp = T + (size_t)t * rank_pad + j0;
+            for (int i = 0; i < 8; ++i) {
+                const int e = e0 + i * kDecThreads;
+                const int row = e / per_row, c = e - row * per_row;
+                v[i] = float4_t{0.f, 0.f, 0.f, 0.f};
+                if (e < total && row < a.m)
+                    v[i] = *reinterpret_cast<const float4_t *>(T0 + (size_t)row * rp + 4 * c) +
+                           *reinterpret_cast<const float4_t *>(T1 + (size_t)row * rp + 4 * c);
+            }
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[t] = fmaf((float)lv[e], tp[e], acc[t]);
-                }
-        }
+            for (int i = 0; i < 8; ++i) {
+                const int e = e0 + i * kDecThreads;
+                const int row = e / per_row, c = e - row * per_row;
+                if (e < total) {
+                    half4_t hi, lo;
 #pragma unroll
-        for (int t = 0; t < kMaxTokens; ++t)
-            if (t < m) {
-                float v = wave_sum(acc[t]);
-                if (lane == 0) {
-                    if (base) v += base[(size_t)t * n + o];
-                    if (accumulate) v += (float)Y[(size_t)t * n + o];
-                    Y[(size_t)t * n + o] = (half_t)v;
+                    for (int x = 0; x < 4; ++x) {
+                        hi[x] = (half_t)v[i][x];
+                        lo[x] = (half_t)(v[i][x] - (float)hi[x]);
+                    }
+                    *reinterpret_cast<half4_t *>(t_hi + row * ldt + 4 * c) = hi;
+                    *reinterpret_cast<half4_t *>(t_lo + row * ldt + 4 * c) = lo;
                 }
             }
+        }
+        __syncthreads();
+    }
+    const int trow = lx < a.mp ? lx : a.mp;
+    const half_t *th = t_hi + trow * ldt + 8 * ly;
+    const half_t *tl = t_lo + trow * ldt + 8 * ly;
+
+    for (int ot = tile0; ot < wtiles; ot += tstride) {
+        float4_t acc = {0.f, 0.f, 0.f, 0.f}, accb = acc;
+        const int ob = 16 * ot + 4 * ly;
+        const bool vec = (ob + 3 < a.n) && (a.n & 3) == 0;
+        // packed term of this lane's 4 outputs: its loads go out before the matrix work
+        float q[4] = {0.f, 0.f, 0.f, 0.f};
+        float sc[4] = {0.f, 0.f, 0.f, 0.f};
+        if (a.P && lx < a.m) {
+            for (int slot = 0; slot < a.slots; ++slot) {
+                const float *pp = a.P + ((size_t)slot * a.m + lx) * a.n + ob;
+                if (vec) {
+                    const float4_t p4 = *reinterpret_cast<const float4_t *>(pp);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) q[v] += p4[v];
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (ob + v < a.n) q[v] += pp[v];
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (ob + v < a.n) sc[v] = a.scale[ob + v];
+        }
+        for (int batch = 0; batch < nbatch; ++batch) {
+            // next batch (of this tile or the first of the next tile) while this one is used
+            if (batch + 1 < nbatch)
+                issue_l(ot, batch + 1, lvB);
+            else
+                issue_l(ot + tstride, 0, lvB);
+#pragma unroll
+            for (int t = 0; t < NB; ++t) {
+                const half8_t bh = *reinterpret_cast<const half8_t *>(th + 32 * (batch * NB + t));
+                const half8_t bl = *reinterpret_cast<const half8_t *>(tl + 32 * (batch * NB + t));
+                const half8_t av = __builtin_bit_cast(half8_t, lvA[t]);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bh, acc, 0, 0, 0);
+                accb = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bl, accb, 0, 0, 0);
+            }
+#pragma unroll
+            for (int t = 0; t < NB; ++t) lvA[t] = lvB[t];
+        }
+        if (lx < a.m) {
+            half_t *yp = a.Y + (size_t)lx * a.n + ob;
+            float y[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                y[v] = acc[v] + accb[v] + sc[v] * q[v];
+                if (a.accumulate && ob + v < a.n) y[v] += (float)yp[v];
+            }
+            if (vec) {
+                half4_t h = {(half_t)y[0], (half_t)y[1], (half_t)y[2], (half_t)y[3]};
+                *reinterpret_cast<half4_t *>(yp) = h;
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (ob + v < a.n) yp[v] = (half_t)y[v];
+            }
+        }
     }
 }
 
-// Y[t][o] = fp16(base[t][o]) for a layer without adapters.
-__global__ __launch_bounds__(256) void gemv_store_kernel(const float *__restrict__ base, size_t total,
-                                                         half_t *__restrict__ Y)
+static int pad_tokens(int m) { return m <= 1 ? 1 : (m <= 4 ? 4 : (m <= 8 ? 8 : 16)); }
+
+// Chunk and slice geometry for a decode call (host side).
+DecodePlan plan_decode(int n, int k, int rank_pad, int m)
 {
-    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total;
-         i += (size_t)gridDim.x * blockDim.x)
-        Y[i] = (half_t)base[i];
+    DecodePlan p{};
+    p.mp = pad_tokens(m);
+    // largest chunk (whole units) whose X tile, with its zero row, fits the LDS budget
+    int kc_max = (kLdsBudget / (2 * (p.mp + 1)) - kLdsPad) / kUnitK * kUnitK;
+    if (kc_max < kUnitK) kc_max = kUnitK;
+    const int kpad = (k + kUnitK - 1) / kUnitK * kUnitK;
+    p.kc = kpad < kc_max ? kpad : kc_max;
+    p.nch = (k + p.kc - 1) / p.kc;
+    // inputs per packed-row task: one unit for small layers (more tasks in
+    // flight), more for large ones (fewer partial slots to write and re-read)
+    const long tiles = (n + 15) / 16;
+    int sl = kUnitK;
+    while (sl < p.kc && tiles * ((k + sl - 1) / sl) > 8192) sl *= 2;
+    p.sl = sl;
+    p.wsl_full = (p.kc + sl - 1) / sl;
+    const int klast = k - (p.nch - 1) * p.kc;
+    p.slots = (p.nch - 1) * p.wsl_full + (klast + sl - 1) / sl;
+    return p;
 }
 
-static int wave_grid(int rows)
+static int launch_decode(const DecodeArgs &a, const DecodePlan &p, hipStream_t st)
 {
-    int blocks = (rows + kGemvWaves - 1) / kGemvWaves;
-    const int cap = 256 * 8;
-    return blocks < cap ? (blocks < 1 ? 1 : blocks) : cap;
+    const size_t lds1 = (size_t)(p.mp + 1) * (p.kc + kLdsPad) * sizeof(half_t);
+    const size_t lds2 = (size_t)2 * (p.mp + 1) * (a.rank_pad + kLdsPad) * sizeof(half_t);
+    if (lds1 > 160 * 1024 || lds2 > 160 * 1024) return SLIM_ERR_SHAPE;
+    const long units_r = (long)(a.rank_pad / 16) * ((p.kc + kUnitR - 1) / kUnitR);
+    const long tasks_w = (long)((a.n_packed + 15) / 16) * p.wsl_full;
+    // blocks per chunk: at most about four per CU, and such that every wave gets
+    // the same number of tasks
+    const long tasks = units_r + tasks_w;
+    long resident = (160 * 1024) / (long)(lds1 > 0 ? lds1 : 1);    // blocks of this LDS size a CU holds
+    if (resident > 4) resident = 4;
+    if (resident < 1) resident = 1;
+    const long cap = 256 * resident / p.nch > 0 ? 256 * resident / p.nch : 1;
+    const long per_wave = (tasks + cap * kDecWaves - 1) / (cap * kDecWaves);
+    long b1 = (tasks + per_wave * kDecWaves - 1) / (per_wave * kDecWaves);
+    if (b1 < 1) b1 = 1;
+    if (units_r + tasks_w > 0)
+        hipLaunchKernelGGL(decode_part1_kernel, dim3((unsigned)(b1 * p.nch)), dim3(kDecThreads), lds1, st, a);
+    long b2 = ((a.n + 15) / 16 + kDecWaves - 1) / kDecWaves;
+    if (b2 > 1024) b2 = 1024;
+    const int steps = a.rank_pad / 32;
+    const dim3 g2((unsigned)b2), blk(kDecThreads);
+    if (steps % 13 == 0)
+        hipLaunchKernelGGL(decode_part2_kernel<13>, g2, blk, lds2, st, a);
+    else if (steps % 8 == 0)
+        hipLaunchKernelGGL(decode_part2_kernel<8>, g2, blk, lds2, st, a);
+    else if (steps % 4 == 0)
+        hipLaunchKernelGGL(decode_part2_kernel<4>, g2, blk, lds2, st, a);
+    else if (steps % 2 == 0)
+        hipLaunchKernelGGL(decode_part2_kernel<2>, g2, blk, lds2, st, a);
+    else
+        hipLaunchKernelGGL(decode_part2_kernel<1>, g2, blk, lds2, st, a);
+    return hip_status(hipGetLastError());
+}
+
+static void fill_plan(DecodeArgs &a, const DecodePlan &p)
+{
+    a.mp = p.mp;
+    a.kc = p.kc;
+    a.nch = p.nch;
+    a.sl = p.sl;
+    a.wsl_full = p.wsl_full;
+    a.slots = p.slots;
 }
 
 int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t *L, int n, int k, int rank_pad,
-                          half_t *Y, int accumulate, float *T, hipStream_t st)
+                          half_t *Y, int accumulate, float *T, unsigned *ctrl, hipStream_t st)
 {
-    hipLaunchKernelGGL(gemv_rows_kernel, dim3(wave_grid(rank_pad)), dim3(kGemvThreads), 0, st, nullptr, nullptr,
-                       nullptr, R, X, 0, k, rank_pad, m, nullptr, T);
-    hipLaunchKernelGGL(gemv_adapter_out_kernel, dim3(wave_grid(n)), dim3(kGemvThreads), 0, st, nullptr, T, L, n,
-                       rank_pad, m, accumulate, Y);
-    return hip_status(hipGetLastError());
+    DecodePlan p = plan_decode(n, k, rank_pad, m);
+    DecodeArgs a{};
+    a.R = R;
+    a.L = L;
+    a.X = X;
+    a.Y = Y;
+    a.T = T;
+    a.ctrl = ctrl;
+    a.n = n;
+    a.k = k;
+    a.rank_pad = rank_pad;
+    a.m = m;
+    a.n_packed = 0;
+    fill_plan(a, p);
+    a.slots = 0;
+    a.accumulate = accumulate;
+    return launch_decode(a, p, st);
 }
 
 }  // namespace slim
@@ -159,23 +571,28 @@ extern "C" int slim_linear_gemv(const slim_layer *layer, const slim_half *X, int
     if (!aligned16(layer->qvals) || !aligned16(layer->meta) || !aligned16(layer->scale) || !aligned16(X) ||
         !aligned16(Y) || !aligned16(layer->L) || !aligned16(layer->R) || !aligned16(workspace))
         return SLIM_ERR_ALIGN;
-    WorkspacePlan p = plan_workspace(s.n, s.k, layer->rank_pad, m);
-    if (!workspace || workspace_bytes < p.total) return SLIM_ERR_WORKSPACE;
+    WorkspacePlan w = plan_workspace(s.n, s.k, layer->rank_pad, m);
+    if (!workspace || workspace_bytes < w.total) return SLIM_ERR_WORKSPACE;
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
-    float *T = reinterpret_cast<float *>(ws + p.t_off);
-    float *acc = reinterpret_cast<float *>(ws + p.acc_off);
-    const int rp = layer->rank_pad;
-    hipLaunchKernelGGL(gemv_rows_kernel, dim3(wave_grid(s.n + rp)), dim3(kGemvThreads), 0, st, layer->qvals,
-                       layer->meta, layer->scale, reinterpret_cast<const half_t *>(layer->R),
-                       reinterpret_cast<const half_t *>(X), s.n, s.k, rp, m, acc, T);
-    if (rp > 0)
-        hipLaunchKernelGGL(gemv_adapter_out_kernel, dim3(wave_grid(s.n)), dim3(kGemvThreads), 0, st, acc, T,
-                           reinterpret_cast<const half_t *>(layer->L), s.n, rp, m, 0,
-                           reinterpret_cast<half_t *>(Y));
-    else
-        hipLaunchKernelGGL(gemv_store_kernel, dim3(wave_grid(s.n)), dim3(256), 0, st, acc, (size_t)m * s.n,
-                           reinterpret_cast<half_t *>(Y));
-    return hip_status(hipGetLastError());
+    DecodePlan p = plan_decode(s.n, s.k, layer->rank_pad, m);
+    DecodeArgs a{};
+    a.qvals = layer->qvals;
+    a.meta = layer->meta;
+    a.scale = layer->scale;
+    a.R = reinterpret_cast<const half_t *>(layer->R);
+    a.L = reinterpret_cast<const half_t *>(layer->L);
+    a.X = reinterpret_cast<const half_t *>(X);
+    a.Y = reinterpret_cast<half_t *>(Y);
+    a.P = reinterpret_cast<float *>(ws + w.acc_off);
+    a.T = reinterpret_cast<float *>(ws + w.dec_off + 256);
+    a.ctrl = reinterpret_cast<unsigned *>(ws + w.dec_off);
+    a.n = s.n;
+    a.k = s.k;
+    a.rank_pad = layer->rank_pad;
+    a.m = m;
+    a.n_packed = s.n;
+    fill_plan(a, p);
+    a.accumulate = 0;
+    return launch_decode(a, p, static_cast<hipStream_t>(stream));
 }

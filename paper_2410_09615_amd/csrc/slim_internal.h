@@ -46,12 +46,21 @@ inline int hip_status(hipError_t e) { return e == hipSuccess ? SLIM_OK : SLIM_ER
 // Workspace carve-up used by the forward entry points (offsets in bytes,
 // each a multiple of 256).
 struct WorkspacePlan {
-    size_t t_off, t_bytes;        // T = X R^T: fp32 [16][rank_pad] (gemv) or fp16 [m][rank_pad] (gemm)
-    size_t acc_off, acc_bytes;    // gemv: scaled quantized term, fp32 [m][n]
+    size_t dec_off, dec_bytes;    // decode state: 256 B of control words, then two T buffers fp32 [16][rank_pad]
+    size_t t_off, t_bytes;        // gemm: T = X R^T as fp16 [m][rank_pad]
+    size_t acc_off, acc_bytes;    // decode: partial quantized term, fp32 [slots][m][n]
     size_t part_off, part_bytes;  // gemm: split-K partials of T, fp32 [splits][m][rank_pad]
     int splits;                   // split-K factor of the T product
     size_t total;
 };
+
+// Geometry of a decode call: padded token count, k-chunk per block, inputs per
+// packed-row task, tasks per row tile in a full chunk, partial slots.
+struct DecodePlan {
+    int mp, kc, nch, sl, wsl_full, slots;
+};
+
+DecodePlan plan_decode(int n, int k, int rank_pad, int m);
 
 WorkspacePlan plan_workspace(int32_t n, int32_t k, int32_t rank_pad, int32_t m);
 
