@@ -294,6 +294,10 @@ static void launch_t(const half_t *X, int m, const half_t *R, int k, int rank_pa
     }
 }
 
+int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *scale, const half_t *X, const half_t *L,
+                       const half_t *T, half_t *Y, int n, int k, int rank_pad, int m,
+                       hipStream_t st);   // slim_gemm_sparse.hip
+
 int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t *L, int n, int k, int rank_pad,
                           half_t *Y, int accumulate, float *T, unsigned *counter, hipStream_t st);   // slim_gemv.hip
 
@@ -324,22 +328,8 @@ extern "C" int slim_linear_gemm(const slim_layer *layer, const slim_half *X, int
     const half_t *Xh = reinterpret_cast<const half_t *>(X);
     if (rp > 0) launch_t(Xh, m, reinterpret_cast<const half_t *>(layer->R), s.k, rp, T, P, p.splits, st);
 
-    GemmArgs g{};
-    g.n_rows = s.n;
-    g.m = m;
-    g.qvals = layer->qvals;
-    g.meta = layer->meta;
-    g.scale = layer->scale;
-    g.Bs = Xh;
-    g.ks = s.k;
-    g.Ad = reinterpret_cast<const half_t *>(layer->L);
-    g.Bd = T;
-    g.kd = rp;
-    g.Y = reinterpret_cast<half_t *>(Y);
-    g.mode = OUT_STORE;
-    dim3 grid((s.n + BO - 1) / BO, (m + BT - 1) / BT, 1);
-    hipLaunchKernelGGL(gemm_kernel, grid, dim3(kGemmThreads), 0, st, g);
-    return hip_status(hipGetLastError());
+    return launch_gemm_sparse(layer->qvals, layer->meta, layer->scale, Xh, reinterpret_cast<const half_t *>(layer->L),
+                              T, reinterpret_cast<half_t *>(Y), s.n, s.k, rp, m, st);
 }
 
 extern "C" int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, const slim_half *L, slim_shape shape,
