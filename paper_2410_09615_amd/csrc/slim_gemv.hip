@@ -62,6 +62,7 @@ struct DecodeArgs {
     int kc;              // inputs per chunk (multiple of kUnitK)
     int nch;             // number of chunks
     int sl;              // inputs per packed-row task (multiple of kUnitK)
+    int rsl;             // inputs per R task (multiple of kUnitR): fewer, larger atomic updates of T
     int wsl_full;        // tasks per row tile in a full chunk
     int slots;           // total partial slots
     int accumulate;      // slim_lowrank only: add the fp16 value already in Y
@@ -101,8 +102,11 @@ __device__ __forceinline__ Unit describe_unit(const DecodeArgs &a, const Part1Ge
     } else if (q < g.n_rtasks) {
         d.is_r = true;
         d.tile = q / g.rsub;
-        d.k0 = (q - d.tile * g.rsub) * kUnitR;
-        d.k1 = min(g.klen, d.k0 + kUnitR);
+        const int t0 = (q - d.tile * g.rsub) * a.rsl;
+        const int t1 = min(g.klen, t0 + a.rsl);
+        d.k0 = t0 + u * kUnitR;
+        d.k1 = min(t1, d.k0 + kUnitR);
+        d.last = d.k0 + kUnitR >= t1;
     } else {
         const int qq = q - g.n_rtasks;
         d.tile = qq / g.wsl;
@@ -194,7 +198,7 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_part1_kernel(DecodeArgs
     Part1Geom g;
     g.kbeg = chunk * a.kc;
     g.klen = min(a.k, g.kbeg + a.kc) - g.kbeg;
-    g.rsub = (g.klen + kUnitR - 1) / kUnitR;
+    g.rsub = (g.klen + a.rsl - 1) / a.rsl;
     g.n_rtasks = (rp / 16) * g.rsub;
     g.wsl = (g.klen + a.sl - 1) / a.sl;
     g.n_tasks = g.n_rtasks + ((a.n_packed + 15) / 16) * g.wsl;
@@ -456,6 +460,11 @@ DecodePlan plan_decode(int n, int k, int rank_pad, int m)
     int sl = kUnitK;
     while (sl < p.kc && tiles * ((k + sl - 1) / sl) > 8192) sl *= 2;
     p.sl = sl;
+    // R tasks: every task ends in one fp32 atomic per T element it touches, and
+    // those go to memory, so with many tokens take 4 units per task
+    // (only when there is enough work that waves run several tasks anyway).
+    const long small_tasks = tiles * ((k + sl - 1) / sl) + (long)(rank_pad / 16) * ((k + kUnitR - 1) / kUnitR);
+    p.rsl = (p.mp > 4 && small_tasks > 4096) ? 4 * kUnitR : kUnitR;
     p.wsl_full = (p.kc + sl - 1) / sl;
     const int klast = k - (p.nch - 1) * p.kc;
     p.slots = (p.nch - 1) * p.wsl_full + (klast + sl - 1) / sl;
@@ -467,7 +476,7 @@ static int launch_decode(const DecodeArgs &a, const DecodePlan &p, hipStream_t s
     const size_t lds1 = (size_t)(p.mp + 1) * (p.kc + kLdsPad) * sizeof(half_t);
     const size_t lds2 = (size_t)2 * (p.mp + 1) * (a.rank_pad + kLdsPad) * sizeof(half_t);
     if (lds1 > 160 * 1024 || lds2 > 160 * 1024) return SLIM_ERR_SHAPE;
-    const long units_r = (long)(a.rank_pad / 16) * ((p.kc + kUnitR - 1) / kUnitR);
+    const long units_r = (long)(a.rank_pad / 16) * ((p.kc + p.rsl - 1) / p.rsl);
     const long tasks_w = (long)((a.n_packed + 15) / 16) * p.wsl_full;
     // blocks per chunk: at most about four per CU, and such that every wave gets
     // the same number of tasks
@@ -504,6 +513,7 @@ static void fill_plan(DecodeArgs &a, const DecodePlan &p)
     a.kc = p.kc;
     a.nch = p.nch;
     a.sl = p.sl;
+    a.rsl = p.rsl;
     a.wsl_full = p.wsl_full;
     a.slots = p.slots;
 }

@@ -82,7 +82,7 @@ struct WorkspacePlan {
 // Geometry of a decode call: padded token count, k-chunk per block, inputs per
 // packed-row task, tasks per row tile in a full chunk, partial slots.
 struct DecodePlan {
-    int mp, kc, nch, sl, wsl_full, slots;
+    int mp, kc, nch, sl, rsl, wsl_full, slots;
 };
 
 DecodePlan plan_decode(int n, int k, int rank_pad, int m);
