@@ -4,8 +4,8 @@
 // Workgroup tile: 256 output rows x 128 tokens, 4 wavefronts, each 64 rows x
 // 128 tokens (2 x 4 accumulator tiles of 32 x 32, 128 VGPRs).
 //   A (weights): never touches LDS.  Per 128 inputs a lane loads 16 bytes of
-//     codes and 8 bytes of positions of its row straight from global memory,
-//     turns 4 code bytes into 8 fp16 values in registers, and passes the 16
+//     codes and 8 bytes of positions of its row straight from global memory
+//     (two stages ahead), turns 4 code bytes into 8 fp16 values in registers, and passes the 16
 //     position bits of those 4 groups as the index operand (the canonical
 //     metadata is that operand's format).  Each wavefront converts only its
 //     own rows, once, and uses them against all 128 tokens.
@@ -36,22 +36,8 @@ struct SparseGemmArgs {
     int n, k, rank_pad, m;
     int tiles_o;         // row tiles
     int tiles_total;     // row tiles x token tiles
+    int n_full;          // workgroups [0, n_full) take whole tiles, the rest half tiles (64 tokens)
 };
-
-constexpr int kXcds = 8;   // dies; workgroup b runs on die b % 8
-
-// Tile of workgroup b.  Tiles are numbered with the row tile running fastest
-// (w = token_tile * tiles_o + row_tile) and the range of w is cut into 8
-// contiguous pieces, one per die: the workgroups that share a die's L2 at any
-// time then work on the same one or two token tiles, so that X tile is fetched
-// from HBM once per die instead of once per workgroup.
-__device__ __forceinline__ int tile_of_block(int b, int tiles_total)
-{
-    const int xcd = b % kXcds, j = b / kXcds;
-    const int per = (tiles_total + kXcds - 1) / kXcds;
-    const int w = xcd * per + j;
-    return (j < per && w < tiles_total) ? w : -1;
-}
 
 // Copy a [128 tokens][128 inputs] piece of a row-major fp16 matrix (leading
 // dimension ld, valid extent rows x cols) into registers: lane -> 16 lanes per
@@ -86,10 +72,15 @@ __global__ __launch_bounds__(SG_THREADS, 2) void gemm_sparse_kernel(SparseGemmAr
     const int wave = tid / kWave;
     const int li = lane & 31;            // A row / B token within a 32-tile
     const int lb = lane >> 5;            // k-block of the lane
-    const int w = tile_of_block(blockIdx.x, a.tiles_total);
-    if (w < 0) return;
+    // Whole tiles first; the tiles that would make up a last, partly filled round
+    // of workgroups are cut in two along the tokens, so that round is short.
+    const int b = blockIdx.x;
+    const bool half_tile = b >= a.n_full;
+    const int w = half_tile ? a.n_full + (b - a.n_full) / 2 : b;
+    const int nt = half_tile ? 2 : 4;                        // 32-token accumulator tiles in use
     const int o0 = (w % a.tiles_o) * SG_BO + wave * 64;
-    const int t0 = (w / a.tiles_o) * SG_BT;
+    const int t0 = (w / a.tiles_o) * SG_BT + (half_tile ? 64 * ((b - a.n_full) & 1) : 0);
+    const int t_end = min(a.m, t0 + 32 * nt);                // tokens of this workgroup: [t0, t_end)
 
     float16_t acc[2][4];
 #pragma unroll
@@ -102,22 +93,31 @@ __global__ __launch_bounds__(SG_THREADS, 2) void gemm_sparse_kernel(SparseGemmAr
     // this lane's two weight rows (clamped: rows past n are computed and dropped)
     const int orow0 = min(o0 + li, a.n - 1);
     const int orow1 = min(o0 + 32 + li, a.n - 1);
-    const uint8_t *q0p = a.qvals + (size_t)orow0 * (a.k / 4) + 16 * lb;
-    const uint8_t *q1p = a.qvals + (size_t)orow1 * (a.k / 4) + 16 * lb;
-    const uint8_t *m0p = a.meta + (size_t)orow0 * (a.k / 8) + 8 * lb;
-    const uint8_t *m1p = a.meta + (size_t)orow1 * (a.k / 8) + 8 * lb;
+    // 32-bit byte offsets from the (uniform) base pointers keep address registers few
+    const uint32_t q0o = (uint32_t)orow0 * (uint32_t)(a.k / 4) + 16u * lb;
+    const uint32_t q1o = (uint32_t)orow1 * (uint32_t)(a.k / 4) + 16u * lb;
+    const uint32_t m0o = (uint32_t)orow0 * (uint32_t)(a.k / 8) + 8u * lb;
+    const uint32_t m1o = (uint32_t)orow1 * (uint32_t)(a.k / 8) + 8u * lb;
 
     uint4_t xreg[8];
-    uint4_t qa[2], qn[2];
-    uint2_t ma[2], mn[2];
     const int nsteps = a.k / SG_BK;
 
+    // weights of stages s, s+1, s+2: loaded two stages ahead into three rotating
+    // register slots (the main loop is unrolled by 6 so that the slots are static)
+    uint4_t qa[3][2];
+    uint2_t ma[3][2];
+    auto load_a = [&](int s, uint4_t (&q)[2], uint2_t (&mm)[2]) {
+        const int sc = min(s, nsteps - 1);                           // past the end: a harmless reload
+        q[0] = *reinterpret_cast<const uint4_t *>(a.qvals + (q0o + (uint32_t)sc * (SG_BK / 4)));
+        q[1] = *reinterpret_cast<const uint4_t *>(a.qvals + (q1o + (uint32_t)sc * (SG_BK / 4)));
+        mm[0] = *reinterpret_cast<const uint2_t *>(a.meta + (m0o + (uint32_t)sc * (SG_BK / 8)));
+        mm[1] = *reinterpret_cast<const uint2_t *>(a.meta + (m1o + (uint32_t)sc * (SG_BK / 8)));
+    };
+
     // prologue: stage 0
-    stage_load(a.X, a.k, a.m, a.k, t0, 0, xreg);
-    qa[0] = *reinterpret_cast<const uint4_t *>(q0p);
-    qa[1] = *reinterpret_cast<const uint4_t *>(q1p);
-    ma[0] = *reinterpret_cast<const uint2_t *>(m0p);
-    ma[1] = *reinterpret_cast<const uint2_t *>(m1p);
+    stage_load(a.X, a.k, t_end, a.k, t0, 0, xreg);
+    load_a(0, qa[0], ma[0]);
+    load_a(1, qa[1], ma[1]);
     stage_store(lds, xreg);
     __syncthreads();
 
@@ -125,23 +125,25 @@ __global__ __launch_bounds__(SG_THREADS, 2) void gemm_sparse_kernel(SparseGemmAr
     // it, inputs 16 t + 8 lb (values 0-7) and 64 + 16 t + 8 lb (values 8-15)
     const int boff = li * SG_LD + 8 * lb;
 
-    for (int s = 0; s < nsteps; ++s) {
-        const half_t *buf = lds + (s & 1) * SG_STAGE;
-        if (s + 1 < nsteps) {
-            stage_load(a.X, a.k, a.m, a.k, t0, (s + 1) * SG_BK, xreg);
-            qn[0] = *reinterpret_cast<const uint4_t *>(q0p + (s + 1) * (SG_BK / 4));
-            qn[1] = *reinterpret_cast<const uint4_t *>(q1p + (s + 1) * (SG_BK / 4));
-            mn[0] = *reinterpret_cast<const uint2_t *>(m0p + (s + 1) * (SG_BK / 8));
-            mn[1] = *reinterpret_cast<const uint2_t *>(m1p + (s + 1) * (SG_BK / 8));
-        }
+    for (int s0 = 0; s0 < nsteps; s0 += 6) {
+#pragma unroll
+      for (int u = 0; u < 6; ++u) {
+        const int s = s0 + u;
+        if (s >= nsteps) break;
+        const half_t *buf = lds + (u & 1) * SG_STAGE;               // stage s sits in buffer s & 1 (6 is even)
+        if (s + 1 < nsteps) stage_load(a.X, a.k, t_end, a.k, t0, (s + 1) * SG_BK, xreg);
+        load_a(s + 2, qa[(u + 2) % 3], ma[(u + 2) % 3]);
+        const uint4_t (&qc)[2] = qa[u % 3];
+        const uint2_t (&mc)[2] = ma[u % 3];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const half8_t a0 = codes_to_half8(qa[0][t]);
-            const half8_t a1 = codes_to_half8(qa[1][t]);
-            const int idx0 = (int)ma[0][t >> 1];
-            const int idx1 = (int)ma[1][t >> 1];
+            const half8_t a0 = codes_to_half8(qc[0][t]);
+            const half8_t a1 = codes_to_half8(qc[1][t]);
+            const int idx0 = (int)mc[0][t >> 1];
+            const int idx1 = (int)mc[1][t >> 1];
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
+                if (it >= nt) break;
                 const half_t *bp = buf + it * 32 * SG_LD + boff + 16 * t;
                 const half8_t b1 = *reinterpret_cast<const half8_t *>(bp);
                 const half8_t b2 = *reinterpret_cast<const half8_t *>(bp + 64);
@@ -156,14 +158,9 @@ __global__ __launch_bounds__(SG_THREADS, 2) void gemm_sparse_kernel(SparseGemmAr
                 }
             }
         }
-        if (s + 1 < nsteps) {
-            stage_store(lds + ((s + 1) & 1) * SG_STAGE, xreg);
-            qa[0] = qn[0];
-            qa[1] = qn[1];
-            ma[0] = mn[0];
-            ma[1] = mn[1];
-        }
+        if (s + 1 < nsteps) stage_store(lds + ((u + 1) & 1) * SG_STAGE, xreg);
         __syncthreads();
+      }
     }
 
     // row scale: accumulator element 4 blk + e of tile io is row 32 io + 8 blk + 4 lb + e
@@ -185,13 +182,13 @@ __global__ __launch_bounds__(SG_THREADS, 2) void gemm_sparse_kernel(SparseGemmAr
         const half_t *l0p = a.L + (size_t)orow0 * rp + 8 * lb;
         const half_t *l1p = a.L + (size_t)orow1 * rp + 8 * lb;
         const int rstages = (rp + SG_BK - 1) / SG_BK;
-        stage_load(a.T, rp, a.m, rp, t0, 0, xreg);
+        stage_load(a.T, rp, t_end, rp, t0, 0, xreg);
         stage_store(lds, xreg);
         __syncthreads();
         const int boff2 = li * SG_LD + 8 * lb;
         for (int s = 0; s < rstages; ++s) {
             const half_t *buf = lds + (s & 1) * SG_STAGE;
-            if (s + 1 < rstages) stage_load(a.T, rp, a.m, rp, t0, (s + 1) * SG_BK, xreg);
+            if (s + 1 < rstages) stage_load(a.T, rp, t_end, rp, t0, (s + 1) * SG_BK, xreg);
             const int jn = min(SG_BK, rp - s * SG_BK) / 16;      // dense steps in this stage
             uint4_t la[2], ln[2];
             la[0] = *reinterpret_cast<const uint4_t *>(l0p + s * SG_BK);
@@ -205,6 +202,7 @@ __global__ __launch_bounds__(SG_THREADS, 2) void gemm_sparse_kernel(SparseGemmAr
                 const half8_t a1 = __builtin_bit_cast(half8_t, la[1]);
 #pragma unroll
                 for (int it = 0; it < 4; ++it) {
+                    if (it >= nt) break;
                     const half8_t bv = *reinterpret_cast<const half8_t *>(buf + it * 32 * SG_LD + boff2 + 16 * j);
                     acc[0][it] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bv, acc[0][it], 0, 0, 0);
                     acc[1][it] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, bv, acc[1][it], 0, 0, 0);
@@ -222,7 +220,7 @@ __global__ __launch_bounds__(SG_THREADS, 2) void gemm_sparse_kernel(SparseGemmAr
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
         const int t = t0 + 32 * it + li;
-        if (t >= a.m) continue;
+        if (t >= t_end) continue;
 #pragma unroll
         for (int io = 0; io < 2; ++io)
 #pragma unroll
@@ -262,9 +260,14 @@ int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *s
     a.tiles_o = (n + SG_BO - 1) / SG_BO;
     const int tiles_t = (m + SG_BT - 1) / SG_BT;
     a.tiles_total = a.tiles_o * tiles_t;
-    const int per = (a.tiles_total + kXcds - 1) / kXcds;
+    // two workgroups per CU are resident: whole rounds of tiles stay whole, the
+    // remainder is cut into half tiles when those fit into one round
+    const int slots = 2 * 256;
+    const int rem = a.tiles_total % slots;
+    a.n_full = (rem != 0 && 2 * rem <= slots) ? a.tiles_total - rem : a.tiles_total;
+    const int blocks = a.n_full + 2 * (a.tiles_total - a.n_full);
     const size_t lds = (size_t)2 * SG_STAGE * sizeof(half_t);
-    hipLaunchKernelGGL(gemm_sparse_kernel, dim3((unsigned)(per * kXcds)), dim3(SG_THREADS), lds, st, a);
+    hipLaunchKernelGGL(gemm_sparse_kernel, dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
     return hip_status(hipGetLastError());
 }
 
