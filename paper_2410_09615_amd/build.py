@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-munsafe-fp-atomics",
+    # The prefill kernel addresses the accumulation registers by number from asm;
+    # the compiler must not park spilled values there.
+    "-mllvm", "-amdgpu-spill-vgpr-to-agpr=0",
     "-Wall", "-Wno-unused-function",
 ]
 

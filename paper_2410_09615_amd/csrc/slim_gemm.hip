@@ -317,7 +317,9 @@ extern "C" int slim_linear_gemm(const slim_layer *layer, const slim_half *X, int
     if (!aligned16(layer->qvals) || !aligned16(layer->meta) || !aligned16(layer->scale) || !aligned16(X) ||
         !aligned16(Y) || !aligned16(layer->L) || !aligned16(layer->R) || !aligned16(workspace))
         return SLIM_ERR_ALIGN;
-    if ((uint64_t)s.n * (uint64_t)(s.k / 4) > 0xFFFFFFFFull) return SLIM_ERR_SHAPE;   // 32-bit row offsets
+    // 32-bit offsets into the weights and into L
+    if ((uint64_t)s.n * (uint64_t)(s.k / 4) > 0xFFFFFFFFull || (uint64_t)s.n * (uint64_t)layer->rank_pad * 2 > 0xFFFFFFFFull)
+        return SLIM_ERR_SHAPE;
     WorkspacePlan p = plan_workspace(s.n, s.k, layer->rank_pad, m);
     if (!workspace || workspace_bytes < p.total) return SLIM_ERR_WORKSPACE;
 

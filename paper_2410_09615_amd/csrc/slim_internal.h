@@ -39,25 +39,34 @@ __device__ __forceinline__ float wave_max(float v)
 // Two's-complement nibble -> int in [-8, 7].
 __device__ __forceinline__ int nibble_to_int(uint32_t v) { return (int)(v & 7u) - (int)(v & 8u); }
 
-// Four packed groups (one dword of code bytes) -> eight fp16 values in
-// matrix-operand order: value 2g is the low nibble of byte g, value 2g+1 its
-// high nibble.
-__device__ __forceinline__ half8_t codes_to_half8(uint32_t q)
+// Code bytes -> fp16 in matrix-operand order.  codes_bias() turns the four
+// two's-complement nibble pairs of a dword into offset-by-8 form; code_pair()
+// then yields group g's two values: (low nibble, high nibble) of byte g.
+__device__ __forceinline__ uint32_t codes_bias(uint32_t q) { return q ^ 0x88888888u; }
+
+__device__ __forceinline__ half2_t code_pair(uint32_t x, int g)
 {
-    const uint32_t x = q ^ 0x88888888u;            // two's complement -> offset by 8
     const half2_t mul = {(half_t)1.0f, (half_t)0.0625f};
     const half2_t add = {(half_t)-1032.0f, (half_t)-72.0f};
+    // bytes [b, 0x64, b, 0x64]: both halves read 1024 + b; keep the low
+    // nibble in the low half and the high nibble (x16) in the high half.
+    // Selector bytes 4..7 pick bytes of the first operand, 0..3 of the second.
+    const uint32_t sel = ((4u + g) << 16) | (4u + g);
+    uint32_t v = __builtin_amdgcn_perm(x, 0x64646464u, sel);
+    v &= 0x64F0640Fu;
+    const half2_t h = __builtin_bit_cast(half2_t, v);
+    return __builtin_elementwise_fma(h, mul, add);   // (1024+n0)-1032, (1024+16 n1)/16-72
+}
+
+// Four packed groups (one dword of code bytes) -> eight fp16 values: value 2g
+// is the low nibble of byte g, value 2g+1 its high nibble.
+__device__ __forceinline__ half8_t codes_to_half8(uint32_t q)
+{
+    const uint32_t x = codes_bias(q);
     half8_t out;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        // bytes [b, 0x64, b, 0x64]: both halves read 1024 + b; keep the low
-        // nibble in the low half and the high nibble (x16) in the high half.
-        // Selector bytes 4..7 pick bytes of the first operand, 0..3 of the second.
-        const uint32_t sel = ((4u + g) << 16) | (4u + g);
-        uint32_t v = __builtin_amdgcn_perm(x, 0x64646464u, sel);
-        v &= 0x64F0640Fu;
-        half2_t h = __builtin_bit_cast(half2_t, v);
-        h = __builtin_elementwise_fma(h, mul, add);  // (1024+n0)-1032, (1024+16 n1)/16-72
+        const half2_t h = code_pair(x, g);
         out[2 * g] = h[0];
         out[2 * g + 1] = h[1];
     }
