@@ -32,10 +32,11 @@ METRIC = "layer µs, GB/s & TFLOP/s (% roofline), 2:4 int4+LoRA vs dense fp16 GE
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = 2500.0       # dense fp16/bf16 matrix peak
 CACHE_BYTES = 256 << 20         # Infinity Cache
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE), scaled by a copy kernel of known size; None until
-# measured.  Source: profiles/.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of the dominant kernel (slim_linear_gemv at 16 tokens on
+# the headline layer) from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE),
+# scaled by the 256 MiB copy below (one FETCH_SIZE unit = 2 KiB, one WRITE_SIZE
+# unit = 1 KiB).  Source: profiles/decode_gemv_llama7b_attn_16tok_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = 26.14e6   # 20.28 MB read + 5.86 MB written per slim_linear_gemv call at 16 tokens
 
 
 def parse_args():
