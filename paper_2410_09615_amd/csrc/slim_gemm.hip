@@ -1,254 +1,116 @@
 // slim_linear_gemm and slim_lowrank: prefill-shaped forward on the matrix cores.
 //
-// One tiled kernel computes C[o][t] = sum_k A[o][k] B[t][k] for a 128 x 128
-// tile of (output rows o) x (tokens t) per workgroup, in up to two phases that
-// share the fp32 accumulators:
-//   phase S  A = packed 2:4 int4 weights, expanded to dense fp16 tiles in LDS
-//            (codes only; exact), B = X;
-//   scale    accumulators times the fp32 row scale;
-//   phase D  A = dense fp16 rows (L, or R for the T = X R^T product), B = fp16
-//            (T, or X).
-// so the adapter term rides on the same accumulators as extra k-steps and Y
-// is rounded to fp16 once.
-#include "slim_internal.h"
+// The dense products of the path, C[t][o] (+)= sum_k A[o][k] B[t][k] with fp16
+// operands and fp32 accumulation, all go through one kernel:
+//   T = X R^T        (A = R, B = X; split along k when there are few tiles),
+//   Y (+)= T L^T     (A = L, B = T; slim_lowrank with more than 16 tokens).
+// The quantized term and its adapter continuation are in slim_gemm_sparse.hip.
+#include "slim_mma.h"
 
 namespace slim {
 
-constexpr int BO = 128;            // output rows per workgroup tile
-constexpr int BT = 128;            // tokens per workgroup tile
-constexpr int BK = 64;             // inputs per k-step
-constexpr int LDS_LD = BK + 8;     // padded row length in halves (144 B: 16-byte aligned)
-constexpr int kGemmThreads = 256;
-
 enum OutMode { OUT_STORE = 0, OUT_ACCUM = 1, OUT_PARTIAL = 2 };
 
-struct GemmArgs {
-    int n_rows;            // extent of o
-    int m;                 // extent of t
-    // phase S (ks == 0: absent)
-    const uint8_t *qvals;  // [n_rows][ks/4]
-    const uint8_t *meta;   // [n_rows][ks/8]
-    const float *scale;    // [n_rows]
-    const half_t *Bs;      // [m][ks]
-    int ks;
-    // phase D (kd == 0: absent); grid.z splits its k range
-    const half_t *Ad;      // [n_rows][kd]
-    const half_t *Bd;      // [m][kd]
-    int kd;
-    // output: Y[t][o] fp16 (ld = n_rows) or P[z][t][o] fp32
-    half_t *Y;
-    float *P;
+struct DenseGemmArgs {
+    const half_t *A;     // [rows][kt]
+    const half_t *B;     // [m][kt]
+    int rows, m, kt;     // kt: row length of A and B (the full k extent)
+    int ks;              // inputs per split (multiple of 128); grid.y splits
+    half_t *Y;           // fp16 [m][rows]   (OUT_STORE, OUT_ACCUM)
+    float *P;            // fp32 [splits][m][rows]   (OUT_PARTIAL)
     int mode;
+    int tiles_o;         // row tiles of 128 AT
 };
 
-__device__ __forceinline__ uint16_t code_to_half_bits(int c)
+// Workgroup: 4 wavefronts, tile (128 AT) rows x 128 tokens, each wavefront
+// (32 AT) rows x 128 tokens on fixed accumulators; the k-loop is dense_phase().
+template <int AT>
+__global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
 {
-    half_t h = (half_t)(float)c;
-    return __builtin_bit_cast(uint16_t, h);
-}
-
-// 8 packed groups (8 code bytes, 8 position nibbles) -> 32 fp16, as 4 x 16 B.
-__device__ __forceinline__ void expand8(uint2_t q, uint32_t me, uint4_t out[4])
-{
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        uint32_t b = ((j < 4 ? q.x : q.y) >> (8 * (j & 3))) & 0xFFu;
-        uint32_t nib = (me >> (4 * j)) & 0xFu;
-        uint64_t h0 = code_to_half_bits(nibble_to_int(b & 0xFu));
-        uint64_t h1 = code_to_half_bits(nibble_to_int(b >> 4));
-        uint64_t v = (h0 << (16 * (nib & 3u))) | (h1 << (16 * (nib >> 2)));
-        if (j & 1) {
-            out[j >> 1].z = (uint32_t)v;
-            out[j >> 1].w = (uint32_t)(v >> 32);
-        } else {
-            out[j >> 1].x = (uint32_t)v;
-            out[j >> 1].y = (uint32_t)(v >> 32);
-        }
-    }
-}
-
-__global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs a)
-{
-    __shared__ __attribute__((aligned(16))) half_t As[BO * LDS_LD];
-    __shared__ __attribute__((aligned(16))) half_t Bs[BT * LDS_LD];
-
+    constexpr int WROWS = 32 * AT;
+    extern __shared__ __attribute__((aligned(16))) half_t lds[];   // two stage buffers
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
-    const int wo = wave & 1, wt = wave >> 1;
-    const int o0 = blockIdx.x * BO;
-    const int t0 = blockIdx.y * BT;
+    const int li = lane & 31;
+    const int lb = lane >> 5;
+    const int w = blockIdx.x;
+    const int o0 = (w % a.tiles_o) * (4 * WROWS) + wave * WROWS;
+    const int t0 = (w / a.tiles_o) * 128;
+    const int t_end = min(a.m, t0 + 128);
+    const int k0 = blockIdx.y * a.ks;
+    const int klen = max(0, min(a.ks, a.kt - k0));      // a split past the end adds zeros
 
-    // loader role: one tile row and one 32-input half of the k-step
-    const int lrow = tid >> 1;
-    const int lhalf = tid & 1;
+    asm volatile("" : : : SLIM_ALL_ACC_REGS);
+    static_for<16 * AT * NT>([&](auto r) { acc_write<r>(0.0f); });
 
-    float16_t acc[2][2];
+    const uint32_t kt = (uint32_t)a.kt;
+    const int srow = tid >> 4, scol = (tid & 15) * 8;
+    half_t *const lw = lds + srow * SG_LD + scol;
+    const half_t *const lr = lds + li * SG_LD + 8 * lb;
+    uint4_t xs[XR];
+    auto stage_store = [&](int u, const uint4_t (&reg)[XR]) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-    uint4_t areg[4], breg[4];
-    uint2_t qreg;
-    uint32_t mreg;
-
-    auto load_b = [&](const half_t *B, int ldb, int kbase, int kend) {
-        const int t = t0 + lrow;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int kk = kbase + lhalf * 32 + c * 8;
-            uint4_t v = {0u, 0u, 0u, 0u};
-            if (t < a.m && kk < kend) v = *reinterpret_cast<const uint4_t *>(B + (size_t)t * ldb + kk);
-            breg[c] = v;
-        }
+        for (int p = 0; p < XR; ++p) *reinterpret_cast<uint4_t *>(lw + u * SG_STAGE + p * 16 * SG_LD) = reg[p];
     };
-    auto load_a_dense = [&](int kbase, int kend) {
-        const int o = o0 + lrow;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int kk = kbase + lhalf * 32 + c * 8;
-            uint4_t v = {0u, 0u, 0u, 0u};
-            if (o < a.n_rows && kk < kend) v = *reinterpret_cast<const uint4_t *>(a.Ad + (size_t)o * a.kd + kk);
-            areg[c] = v;
-        }
-    };
-    auto load_a_packed = [&](int kbase) {
-        const int o = o0 + lrow;
-        qreg = uint2_t{0u, 0u};
-        mreg = 0x44444444u;            // positions (0, 1) with zero codes
-        if (o < a.n_rows) {
-            const int g = (kbase + lhalf * 32) / 4;
-            qreg = *reinterpret_cast<const uint2_t *>(a.qvals + (size_t)o * (a.ks / 4) + g);
-            mreg = *reinterpret_cast<const uint32_t *>(a.meta + (size_t)o * (a.ks / 8) + g / 2);
-        }
-    };
-    auto store_lds = [&]() {
-        uint4_t *ad = reinterpret_cast<uint4_t *>(As + lrow * LDS_LD + lhalf * 32);
-        uint4_t *bd = reinterpret_cast<uint4_t *>(Bs + lrow * LDS_LD + lhalf * 32);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            ad[c] = areg[c];
-            bd[c] = breg[c];
-        }
-    };
-    auto compute = [&]() {
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            half8_t af[2], bf[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                af[i] = *reinterpret_cast<const half8_t *>(As + (wo * 64 + i * 32 + (lane & 31)) * LDS_LD + ks * 16 +
-                                                           8 * (lane >> 5));
-                bf[i] = *reinterpret_cast<const half8_t *>(Bs + (wt * 64 + i * 32 + (lane & 31)) * LDS_LD + ks * 16 +
-                                                           8 * (lane >> 5));
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
-        }
-    };
+    const rsrc_t da = make_rsrc(a.A, (uint32_t)a.rows * kt * 2u);
+    const rsrc_t db = make_rsrc(a.B, (uint32_t)a.m * kt * 2u);
+    const uint32_t av = ((uint32_t)(o0 + li) * kt + (uint32_t)k0 + 8u * lb) * 2u;
+    const uint32_t bv = ((uint32_t)(t0 + srow) * kt + (uint32_t)k0 + (uint32_t)scol) * 2u;
+    dense_phase<AT>(da, av, 64u * kt, db, bv, 32u * kt, klen, lr, xs, stage_store);
+    acc_settle();
 
-    // ---- phase S: packed weights against X ----
-    if (a.ks > 0) {
-        const int nk = a.ks / BK;
-        load_a_packed(0);
-        load_b(a.Bs, a.ks, 0, a.ks);
-        for (int kt = 0; kt < nk; ++kt) {
-            expand8(qreg, mreg, areg);
-            __syncthreads();
-            store_lds();
-            __syncthreads();
-            if (kt + 1 < nk) {
-                load_a_packed((kt + 1) * BK);
-                load_b(a.Bs, a.ks, (kt + 1) * BK, a.ks);
-            }
-            compute();
-        }
-        // row scale on the fp32 accumulators
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int blk = 0; blk < 4; ++blk)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int o = o0 + wo * 64 + i * 32 + 8 * blk + 4 * (lane >> 5) + e;
-                    const float s = o < a.n_rows ? a.scale[o] : 0.0f;
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) acc[i][j][4 * blk + e] *= s;
-                }
-    }
-
-    // ---- phase D: dense fp16 rows ----
-    if (a.kd > 0) {
-        const int steps = (a.kd + BK - 1) / BK;
-        const int per = (steps + gridDim.z - 1) / gridDim.z;
-        const int kt0 = blockIdx.z * per;
-        const int kt1 = min(steps, kt0 + per);
-        if (kt0 < kt1) {
-            load_a_dense(kt0 * BK, a.kd);
-            load_b(a.Bd, a.kd, kt0 * BK, a.kd);
-        }
-        for (int kt = kt0; kt < kt1; ++kt) {
-            __syncthreads();
-            store_lds();
-            __syncthreads();
-            if (kt + 1 < kt1) {
-                load_a_dense((kt + 1) * BK, a.kd);
-                load_b(a.Bd, a.kd, (kt + 1) * BK, a.kd);
-            }
-            compute();
-        }
-    }
-
-    // ---- output ----
-    const bool vec_ok = (a.n_rows % 4) == 0;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int t = t0 + wt * 64 + j * 32 + (lane & 31);
-            if (t >= a.m) continue;
-#pragma unroll
-            for (int blk = 0; blk < 4; ++blk) {
-                const int o = o0 + wo * 64 + i * 32 + 8 * blk + 4 * (lane >> 5);
-                if (o >= a.n_rows) continue;
+    // lane holds token t0 + 32 it + li, rows o .. o + 3 per (i, blk)
+    const bool vec_ok = (a.rows & 3) == 0;
+    static_for<NT>([&](auto itc) {
+        constexpr int it = itc;
+        const int t = t0 + 32 * it + li;
+        if (t >= t_end) return;
+        static_for<AT>([&](auto ic) {
+            constexpr int i = ic;
+            static_for<4>([&](auto bc) {
+                constexpr int blk = bc;
+                const int o = o0 + 32 * i + 8 * blk + 4 * lb;
+                if (o >= a.rows) return;
                 float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * blk + e];
+                v[0] = acc_read<16 * (i * NT + it) + 4 * blk + 0>();
+                v[1] = acc_read<16 * (i * NT + it) + 4 * blk + 1>();
+                v[2] = acc_read<16 * (i * NT + it) + 4 * blk + 2>();
+                v[3] = acc_read<16 * (i * NT + it) + 4 * blk + 3>();
                 if (a.mode == OUT_PARTIAL) {
-                    float *p = a.P + ((size_t)blockIdx.z * a.m + t) * a.n_rows + o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (o + e < a.n_rows) p[e] = v[e];
-                } else {
-                    half_t *y = a.Y + (size_t)t * a.n_rows + o;
+                    float *pp = a.P + ((size_t)blockIdx.y * a.m + t) * a.rows + o;
                     if (vec_ok) {
-                        half4_t h;
+                        *reinterpret_cast<float4_t *>(pp) = float4_t{v[0], v[1], v[2], v[3]};
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (o + e < a.rows) pp[e] = v[e];
+                    }
+                } else {
+                    half_t *y = a.Y + (size_t)t * a.rows + o;
+                    if (vec_ok) {
                         if (a.mode == OUT_ACCUM) {
-                            half4_t old = *reinterpret_cast<const half4_t *>(y);
+                            const half4_t old = *reinterpret_cast<const half4_t *>(y);
 #pragma unroll
                             for (int e = 0; e < 4; ++e) v[e] += (float)old[e];
                         }
+                        half4_t h;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) h[e] = (half_t)v[e];
                         *reinterpret_cast<half4_t *>(y) = h;
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (o + e < a.n_rows) {
+                            if (o + e < a.rows) {
                                 float x = v[e];
                                 if (a.mode == OUT_ACCUM) x += (float)y[e];
                                 y[e] = (half_t)x;
                             }
                     }
                 }
-            }
-        }
+            });
+        });
+    });
 }
 
 // T[i] = fp16(sum_z P[z][i])
@@ -263,35 +125,60 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     }
 }
 
-// Split-K factor for T = X R^T so that the launch has enough workgroups.
+// One dense product on up to 2^32 - 1 bytes of B: C = A B^T over `splits` k ranges.
+template <int AT>
+static void launch_dense(DenseGemmArgs a, int splits, hipStream_t st)
+{
+    a.tiles_o = (a.rows + 128 * AT - 1) / (128 * AT);
+    const int tiles_t = (a.m + 127) / 128;
+    const size_t lds = (size_t)2 * SG_STAGE * sizeof(half_t);
+    hipLaunchKernelGGL(gemm_dense_kernel<AT>, dim3((unsigned)(a.tiles_o * tiles_t), (unsigned)splits), dim3(256), lds,
+                       st, a);
+}
+
+// Largest token count whose rows of `row_halves` halves stay below 4 GiB
+// (buffer offsets are 32 bits wide), as a multiple of 128; 0 if even 128 do not.
+static int token_chunk(int row_halves)
+{
+    return (int)((0xFFFFFFFFull / (2ull * (uint64_t)row_halves)) / 128 * 128);
+}
+
+// Split-K factor for T = X R^T so that the launch has enough workgroups: row
+// tiles of 256 ranks x 128 tokens, k ranges of at least 512 inputs.
 int gemm_t_splits(int32_t m, int32_t rank_pad, int32_t k)
 {
-    long tiles = (long)((rank_pad + BO - 1) / BO) * ((m + BT - 1) / BT);
+    const long tiles = (long)((rank_pad + 255) / 256) * ((m + 127) / 128);
     int s = 1;
-    while (tiles * s < 192 && s < 8 && (k / BK) / (s * 2) >= 4) s *= 2;
+    while (tiles * s < 192 && s < 8 && k / (2 * s) >= 512) s *= 2;
     return s;
 }
 
 // T fp16 [m][rank_pad] = X R^T.
-static void launch_t(const half_t *X, int m, const half_t *R, int k, int rank_pad, half_t *T, float *P, int splits,
-                     hipStream_t st)
+static int launch_t(const half_t *X, int m, const half_t *R, int k, int rank_pad, half_t *T, float *P, int splits,
+                    hipStream_t st)
 {
-    GemmArgs g{};
-    g.n_rows = rank_pad;
-    g.m = m;
-    g.Ad = R;
-    g.Bd = X;
-    g.kd = k;
-    g.Y = T;
-    g.P = P;
+    if ((uint64_t)rank_pad * (uint64_t)k * 2 > 0xFFFFFFFFull) return SLIM_ERR_SHAPE;
+    const int chunk = token_chunk(k);
+    if (chunk < 128) return SLIM_ERR_SHAPE;
+    DenseGemmArgs g{};
+    g.A = R;
+    g.rows = rank_pad;
+    g.kt = k;
+    g.ks = ((k / 128 + splits - 1) / splits) * 128;
     g.mode = splits > 1 ? OUT_PARTIAL : OUT_STORE;
-    dim3 grid((rank_pad + BO - 1) / BO, (m + BT - 1) / BT, splits);
-    hipLaunchKernelGGL(gemm_kernel, grid, dim3(kGemmThreads), 0, st, g);
-    if (splits > 1) {
-        size_t count = (size_t)m * rank_pad;
-        int blocks = (int)((count + 255) / 256 < 4096 ? (count + 255) / 256 : 4096);
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks), dim3(256), 0, st, P, splits, count, T);
+    for (int t0 = 0; t0 < m; t0 += chunk) {
+        g.m = m - t0 < chunk ? m - t0 : chunk;
+        g.B = X + (size_t)t0 * k;
+        g.Y = T + (size_t)t0 * rank_pad;
+        g.P = P;
+        launch_dense<2>(g, splits, st);
+        if (splits > 1) {
+            const size_t count = (size_t)g.m * rank_pad;
+            const int blocks = (int)((count + 255) / 256 < 4096 ? (count + 255) / 256 : 4096);
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks), dim3(256), 0, st, P, splits, count, g.Y);
+        }
     }
+    return hip_status(hipGetLastError());
 }
 
 int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *scale, const half_t *X, const half_t *L,
@@ -329,7 +216,10 @@ extern "C" int slim_linear_gemm(const slim_layer *layer, const slim_half *X, int
     float *P = reinterpret_cast<float *>(ws + p.part_off);
     const int rp = layer->rank_pad;
     const half_t *Xh = reinterpret_cast<const half_t *>(X);
-    if (rp > 0) launch_t(Xh, m, reinterpret_cast<const half_t *>(layer->R), s.k, rp, T, P, p.splits, st);
+    if (rp > 0) {
+        const int rc = launch_t(Xh, m, reinterpret_cast<const half_t *>(layer->R), s.k, rp, T, P, p.splits, st);
+        if (rc != SLIM_OK) return rc;
+    }
 
     return launch_gemm_sparse(layer->qvals, layer->meta, layer->scale, Xh, reinterpret_cast<const half_t *>(layer->L),
                               T, reinterpret_cast<half_t *>(Y), s.n, s.k, rp, m, st);
@@ -358,17 +248,23 @@ extern "C" int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, c
                                      reinterpret_cast<float *>(ws + p.dec_off + 256),
                                      reinterpret_cast<unsigned *>(ws + p.dec_off), st);
 
+    if ((uint64_t)shape.n * (uint64_t)rank_pad * 2 > 0xFFFFFFFFull) return SLIM_ERR_SHAPE;
     half_t *T = reinterpret_cast<half_t *>(ws + p.t_off);
-    launch_t(Xh, m, Rh, shape.k, rank_pad, T, reinterpret_cast<float *>(ws + p.part_off), p.splits, st);
-    GemmArgs g{};
-    g.n_rows = shape.n;
-    g.m = m;
-    g.Ad = Lh;
-    g.Bd = T;
-    g.kd = rank_pad;
-    g.Y = Yh;
+    const int rc = launch_t(Xh, m, Rh, shape.k, rank_pad, T, reinterpret_cast<float *>(ws + p.part_off), p.splits, st);
+    if (rc != SLIM_OK) return rc;
+    const int chunk = token_chunk(rank_pad);
+    if (chunk < 128) return SLIM_ERR_SHAPE;
+    DenseGemmArgs g{};
+    g.A = Lh;
+    g.rows = shape.n;
+    g.kt = rank_pad;
+    g.ks = (rank_pad + 127) / 128 * 128;
     g.mode = accumulate ? OUT_ACCUM : OUT_STORE;
-    dim3 grid((shape.n + BO - 1) / BO, (m + BT - 1) / BT, 1);
-    hipLaunchKernelGGL(gemm_kernel, grid, dim3(kGemmThreads), 0, st, g);
+    for (int t0 = 0; t0 < m; t0 += chunk) {
+        g.m = m - t0 < chunk ? m - t0 : chunk;
+        g.B = T + (size_t)t0 * rank_pad;
+        g.Y = Yh + (size_t)t0 * shape.n;
+        launch_dense<4>(g, 1, st);
+    }
     return hip_status(hipGetLastError());
 }

@@ -21,17 +21,9 @@
 //   buffers.  One rounding to fp16 at the store.
 // All global reads are buffer loads: a uniform descriptor and a 32-bit offset,
 // and rows past the end of a matrix read as zero.
-#include <utility>
-
-#include "slim_internal.h"
+#include "slim_mma.h"
 
 namespace slim {
-
-constexpr int SG_BK = 128;              // inputs per stage
-constexpr int SG_LD = SG_BK + 8;        // LDS row length in halves (272 B)
-constexpr int SG_STAGE = 128 * SG_LD;   // halves per LDS buffer (128 tokens)
-constexpr int NT = 4;                   // token tiles of 32 per wavefront
-constexpr int XR = 8;                   // 128-bit pieces of an X stage per lane (16 token rows per pass)
 
 struct SparseGemmArgs {
     const uint8_t *qvals;
@@ -46,136 +38,6 @@ struct SparseGemmArgs {
     int tiles_total;     // row tiles x token tiles
     int n_full;          // tiles [0, n_full) run whole (AT = 4), the rest as two halves of 256 rows (AT = 2)
 };
-
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-
-// Raw buffer descriptor over `bytes` bytes at p (32-bit data format word of gfx9).
-__device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
-}
-
-// The whole byte offset goes into the per-lane offset operand: that is the part
-// the hardware checks against the descriptor's size (the scalar offset operand
-// is added to the address without a check).
-__device__ __forceinline__ uint4_t load16(rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
-{
-    return __builtin_bit_cast(uint4_t,
-                              __builtin_amdgcn_raw_buffer_load_b128(r, (int)(lane_off + uniform_off), 0, 0));
-}
-
-// Loads the compiler does not track.  Its wait-count pass is conservative
-// around loops that carry loads in flight from one iteration to the next (it
-// waited for loads issued moments earlier), so the main loop issues its global
-// loads from asm and places the waits itself with vm_wait_*(): loads complete in
-// order, vm_wait<N> returns once at most N are still in flight, and the values it
-// names only count as defined from there on.  Every such load must have landed
-// (vm_wait<0>) before its destination registers may die.
-__device__ __forceinline__ uint4_t load16_untracked(uint4_t desc, uint32_t off)
-{
-    uint4_t v;
-    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(v) : "v"(off), "s"(desc));
-    return v;
-}
-__device__ __forceinline__ uint2_t load8_untracked(uint4_t desc, uint32_t off)
-{
-    uint2_t v;
-    asm volatile("buffer_load_dwordx2 %0, %1, %2, 0 offen" : "=v"(v) : "v"(off), "s"(desc));
-    return v;
-}
-template <int N>
-__device__ __forceinline__ void vm_wait_a(uint4_t (&q)[4], uint2_t (&mm)[4])
-{
-    asm volatile("s_waitcnt vmcnt(%8)"
-                 : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]), "+v"(mm[0]), "+v"(mm[1]), "+v"(mm[2]), "+v"(mm[3])
-                 : "n"(N));
-}
-template <int N>
-__device__ __forceinline__ void vm_wait_a(uint4_t (&q)[2], uint2_t (&mm)[2])
-{
-    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(q[0]), "+v"(q[1]), "+v"(mm[0]), "+v"(mm[1]) : "n"(N));
-}
-template <int N>
-__device__ __forceinline__ void vm_wait_x(uint4_t (&x)[8])
-{
-    asm volatile("s_waitcnt vmcnt(%8)"
-                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
-                 : "n"(N));
-}
-// Descriptor words for a raw buffer of `bytes` bytes (same as make_rsrc).
-__device__ __forceinline__ uint4_t make_desc(const void *p, uint32_t bytes)
-{
-    const uint64_t a = reinterpret_cast<uint64_t>(p);
-    return uint4_t{(uint32_t)a, (uint32_t)(a >> 32) & 0xFFFFu, bytes, 0x00020000u};
-}
-
-// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>).
-template <int... Is, class F>
-__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f)
-{
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_impl(std::make_integer_sequence<int, N>{}, f);
-}
-
-// Accumulators of a wavefront that owns 128 x 128 outputs: 256 registers, the
-// whole accumulation half of the register file, with everything else in the
-// ordinary half.  The compiler's allocator does not find this split (it spills),
-// so the accumulation registers are addressed by number from asm: tile T
-// occupies a[16 T .. 16 T + 15] and the compiler never sees a value in them.  It
-// is told that they are in use (clobber list at kernel entry) and the library is
-// built with spilling into accumulation registers switched off, so it has no
-// reason to touch them.  Being asm, these instructions are outside the
-// compiler's hazard bookkeeping: acc_settle() goes wherever accumulators pass
-// between matrix instructions and reads or writes of them.
-#define SLIM_A10(b) "a" #b "0", "a" #b "1", "a" #b "2", "a" #b "3", "a" #b "4", "a" #b "5", "a" #b "6", "a" #b "7", \
-                    "a" #b "8", "a" #b "9"
-#define SLIM_ALL_ACC_REGS                                                                                            \
-    "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", SLIM_A10(1), SLIM_A10(2), SLIM_A10(3), SLIM_A10(4),  \
-        SLIM_A10(5), SLIM_A10(6), SLIM_A10(7), SLIM_A10(8), SLIM_A10(9), SLIM_A10(10), SLIM_A10(11), SLIM_A10(12),   \
-        SLIM_A10(13), SLIM_A10(14), SLIM_A10(15), SLIM_A10(16), SLIM_A10(17), SLIM_A10(18), SLIM_A10(19),            \
-        SLIM_A10(20), SLIM_A10(21), SLIM_A10(22), SLIM_A10(23), SLIM_A10(24), "a250", "a251", "a252", "a253",        \
-        "a254", "a255"
-
-template <int R>
-__device__ __forceinline__ void acc_write(float v)
-{
-    asm volatile("v_accvgpr_write_b32 a[%1], %0" : : "v"(v), "n"(R));
-}
-template <int R>
-__device__ __forceinline__ float acc_read()
-{
-    float v;
-    asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(v) : "n"(R));
-    return v;
-}
-// longest result latency of a matrix instruction (16 passes) plus margin
-__device__ __forceinline__ void acc_settle() { asm volatile("s_nop 15\n\ts_nop 7"); }
-
-// Sparse step on accumulator tile T: a[16 T ..] += A(sparse, 32 x 32) B(32 x 32).
-// HI: the index operand's bits 31..16 hold this slice's positions, else bits 15..0.
-template <int T, bool HI>
-__device__ __forceinline__ void smfmac_fixed(half8_t av, half16_t bv, int idx)
-{
-    if (HI)
-        asm volatile("v_smfmac_f32_32x32x32_f16 a[%3:%4], %0, %1, %2 abid:1"
-                     :
-                     : "v"(av), "v"(bv), "v"(idx), "n"(16 * T), "n"(16 * T + 15));
-    else
-        asm volatile("v_smfmac_f32_32x32x32_f16 a[%3:%4], %0, %1, %2"
-                     :
-                     : "v"(av), "v"(bv), "v"(idx), "n"(16 * T), "n"(16 * T + 15));
-}
-template <int T>
-__device__ __forceinline__ void mfma_fixed(half8_t av, half8_t bv)
-{
-    asm volatile("v_mfma_f32_32x32x16_f16 a[%2:%3], %0, %1, a[%2:%3]"
-                 :
-                 : "v"(av), "v"(bv), "n"(16 * T), "n"(16 * T + 15));
-}
 
 // AT row tiles of 32 per wavefront; accumulator tile (i, it) is a[16 (i NT + it) ..].
 template <int AT>
@@ -286,26 +148,24 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
     // Fetches past the last stage stay inside the descriptors or read as zero and
     // are never used.
     {
-        const uint4_t dq = make_desc(a.qvals, (uint32_t)a.n * (k / 4));
-        const uint4_t dm = make_desc(a.meta, (uint32_t)a.n * (k / 8));
-        const uint4_t dx = make_desc(a.X, (uint32_t)a.m * k * 2);
+        const rsrc_t dq = make_rsrc(a.qvals, (uint32_t)a.n * (k / 4));
+        const rsrc_t dm = make_rsrc(a.meta, (uint32_t)a.n * (k / 8));
+        const rsrc_t dx = make_rsrc(a.X, (uint32_t)a.m * k * 2);
         auto fetch_a = [&](int j, int s, uint4_t (&q)[AT], uint2_t (&mm)[AT]) {    // j < 2 AT
             if (j < AT)
-                q[j] = load16_untracked(dq, qv + (uint32_t)j * 8u * k + (uint32_t)s * (SG_BK / 4));
+                q[j] = load16(dq, qv, (uint32_t)j * 8u * k + (uint32_t)s * (SG_BK / 4));
             else
-                mm[j - AT] = load8_untracked(dm, mv + (uint32_t)(j - AT) * 4u * k + (uint32_t)s * (SG_BK / 8));
+                mm[j - AT] = load8(dm, mv, (uint32_t)(j - AT) * 4u * k + (uint32_t)s * (SG_BK / 8));
         };
         auto fetch_x = [&](int p, int s, uint4_t (&reg)[XR]) {
-            reg[p] = load16_untracked(dx, xv + (uint32_t)s * (SG_BK * 2) + (uint32_t)p * 32u * k);
+            reg[p] = load16(dx, xv, (uint32_t)s * (SG_BK * 2) + (uint32_t)p * 32u * k);
         };
-        // in flight after the prologue, oldest first: X(0), A(0), X(1)
 #pragma unroll
         for (int p = 0; p < XR; ++p) fetch_x(p, 0, xr[0]);
 #pragma unroll
         for (int j = 0; j < 2 * AT; ++j) fetch_a(j, 0, qa[0], ma[0]);
 #pragma unroll
         for (int p = 0; p < XR; ++p) fetch_x(p, 1, xr[1]);
-        vm_wait_x<2 * AT + XR>(xr[0]);
         stage_store(0, xr[0]);
         __syncthreads();
         for (int s0 = 0; s0 < nsteps; s0 += 2) {
@@ -313,8 +173,6 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
                 constexpr int u = uc;
                 const int s = s0 + u;
                 if (s >= nsteps) return;
-                // in flight here, oldest first: A(s), X(s + 1)
-                vm_wait_a<XR>(qa[u], ma[u]);
                 compute_stage(u, qa[u], ma[u], [&](auto bc) {
                     constexpr int bi = bc;
                     if constexpr (bi < HB) {
@@ -329,17 +187,10 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
                             fetch_x(p, s + 2, xr[u]);
                     }
                 });
-                // in flight, oldest first: X(s + 1), A(s + 1), X(s + 2)
-                vm_wait_x<2 * AT + XR>(xr[u ^ 1]);
                 stage_store(u ^ 1, xr[u ^ 1]);
                 __syncthreads();
             });
         }
-        // the fetches past the last stage must land before their registers are reused
-        vm_wait_a<0>(qa[0], ma[0]);
-        vm_wait_a<0>(qa[1], ma[1]);
-        vm_wait_x<0>(xr[0]);
-        vm_wait_x<0>(xr[1]);
     }
 
     // row scale: accumulator element 4 blk + e of tile i is row 32 i + 8 blk + 4 lb + e
@@ -367,51 +218,14 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
         acc_settle();
     }
 
-    // adapter term: dense steps of 16 ranks; T staged like X, L rows from global
+    // adapter term: acc += L T^T as dense steps of 16 ranks; T staged like X, L rows from global
     if (a.rank_pad > 0) {
         const uint32_t rp = (uint32_t)a.rank_pad;
-        const rsrc_t rl = make_rsrc(a.L, (uint32_t)a.n * rp * 2u);
-        const rsrc_t rt = make_rsrc(a.T, (uint32_t)a.m * rp * 2u);
+        const rsrc_t dl = make_rsrc(a.L, (uint32_t)a.n * rp * 2u);
+        const rsrc_t dt = make_rsrc(a.T, (uint32_t)a.m * rp * 2u);
         const uint32_t lv = ((uint32_t)(o0 + li) * rp + 8u * lb) * 2u;
         const uint32_t tv = ((uint32_t)(t0 + srow) * rp + (uint32_t)scol) * 2u;
-        const int rstages = ((int)rp + SG_BK - 1) / SG_BK;
-        auto stage_load_t = [&](int s) {
-#pragma unroll
-            for (int p = 0; p < XR; ++p) xr[0][p] = load16(rt, tv, (uint32_t)s * (SG_BK * 2) + (uint32_t)p * 32u * rp);
-        };
-        // columns past rank_pad in the last stage hold other rows' data; they are
-        // staged but never multiplied (jn below)
-        stage_load_t(0);
-        stage_store(0, xr[0]);
-        __syncthreads();
-        for (int s = 0; s < rstages; ++s) {
-            const int u = s & 1;
-            if (s + 1 < rstages) stage_load_t(s + 1);
-            const int jn = min(SG_BK, (int)rp - s * SG_BK) / 16;      // dense steps in this stage
-            uint4_t la[AT], ln[AT];
-#pragma unroll
-            for (int i = 0; i < AT; ++i) la[i] = load16(rl, lv, ((uint32_t)i * 32u * rp + (uint32_t)s * SG_BK) * 2u);
-            for (int j = 0; j < jn; ++j) {
-                if (j + 1 < jn) {
-#pragma unroll
-                    for (int i = 0; i < AT; ++i)
-                        ln[i] = load16(rl, lv, ((uint32_t)i * 32u * rp + (uint32_t)(s * SG_BK + 16 * (j + 1))) * 2u);
-                }
-                static_for<NT>([&](auto itc) {
-                    constexpr int it = itc;
-                    const half8_t bv =
-                        *reinterpret_cast<const half8_t *>(lr + u * SG_STAGE + it * 32 * SG_LD + 16 * j);
-                    static_for<AT>([&](auto ic) {
-                        constexpr int i = ic;
-                        mfma_fixed<i * NT + it>(__builtin_bit_cast(half8_t, la[i]), bv);
-                    });
-                });
-#pragma unroll
-                for (int i = 0; i < AT; ++i) la[i] = ln[i];
-            }
-            if (s + 1 < rstages) stage_store(u ^ 1, xr[0]);
-            __syncthreads();
-        }
+        dense_phase<AT>(dl, lv, 64u * rp, dt, tv, 32u * rp, (int)rp, lr, xr[0], stage_store);
         acc_settle();
     }
 

@@ -1,0 +1,174 @@
+// Shared device code of the prefill kernels (matrix-core GEMMs with 128 tokens per
+// workgroup): buffer loads with and without compiler tracking, accumulators held
+// in the accumulation registers by number, and the dense k-loop both kernels use.
+#ifndef SLIM_MMA_H
+#define SLIM_MMA_H
+
+#include <utility>
+
+#include "slim_internal.h"
+
+namespace slim {
+
+constexpr int SG_BK = 128;              // inputs per stage
+constexpr int SG_LD = SG_BK + 8;        // LDS row length in halves (272 B)
+constexpr int SG_STAGE = 128 * SG_LD;   // halves per LDS buffer (128 tokens)
+constexpr int NT = 4;                   // token tiles of 32 per wavefront
+constexpr int XR = 8;                   // 128-bit pieces of an X stage per lane (16 token rows per pass)
+
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+// Raw buffer descriptor over `bytes` bytes at p (32-bit data format word of gfx9).
+__device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+// The whole byte offset goes into the per-lane offset operand: that is the part
+// the hardware checks against the descriptor's size (the scalar offset operand
+// is added to the address without a check).
+__device__ __forceinline__ uint4_t load16(rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_bit_cast(uint4_t,
+                              __builtin_amdgcn_raw_buffer_load_b128(r, (int)(lane_off + uniform_off), 0, 0));
+}
+
+__device__ __forceinline__ uint2_t load8(rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_bit_cast(uint2_t, __builtin_amdgcn_raw_buffer_load_b64(r, (int)(lane_off + uniform_off), 0, 0));
+}
+
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>).
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+// Accumulators of a wavefront that owns 128 x 128 outputs: 256 registers, the
+// whole accumulation half of the register file, with everything else in the
+// ordinary half.  The compiler's allocator does not find this split (it spills),
+// so the accumulation registers are addressed by number from asm: tile T
+// occupies a[16 T .. 16 T + 15] and the compiler never sees a value in them.  It
+// is told that they are in use (clobber list at kernel entry) and the library is
+// built with spilling into accumulation registers switched off, so it has no
+// reason to touch them.  Being asm, these instructions are outside the
+// compiler's hazard bookkeeping: acc_settle() goes wherever accumulators pass
+// between matrix instructions and reads or writes of them.
+#define SLIM_A10(b) "a" #b "0", "a" #b "1", "a" #b "2", "a" #b "3", "a" #b "4", "a" #b "5", "a" #b "6", "a" #b "7", \
+                    "a" #b "8", "a" #b "9"
+#define SLIM_ALL_ACC_REGS                                                                                            \
+    "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", SLIM_A10(1), SLIM_A10(2), SLIM_A10(3), SLIM_A10(4),  \
+        SLIM_A10(5), SLIM_A10(6), SLIM_A10(7), SLIM_A10(8), SLIM_A10(9), SLIM_A10(10), SLIM_A10(11), SLIM_A10(12),   \
+        SLIM_A10(13), SLIM_A10(14), SLIM_A10(15), SLIM_A10(16), SLIM_A10(17), SLIM_A10(18), SLIM_A10(19),            \
+        SLIM_A10(20), SLIM_A10(21), SLIM_A10(22), SLIM_A10(23), SLIM_A10(24), "a250", "a251", "a252", "a253",        \
+        "a254", "a255"
+
+template <int R>
+__device__ __forceinline__ void acc_write(float v)
+{
+    asm volatile("v_accvgpr_write_b32 a[%1], %0" : : "v"(v), "n"(R));
+}
+template <int R>
+__device__ __forceinline__ float acc_read()
+{
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(v) : "n"(R));
+    return v;
+}
+// longest result latency of a matrix instruction (16 passes) plus margin
+__device__ __forceinline__ void acc_settle() { asm volatile("s_nop 15\n\ts_nop 7"); }
+
+// Sparse step on accumulator tile T: a[16 T ..] += A(sparse, 32 x 32) B(32 x 32).
+// HI: the index operand's bits 31..16 hold this slice's positions, else bits 15..0.
+template <int T, bool HI>
+__device__ __forceinline__ void smfmac_fixed(half8_t av, half16_t bv, int idx)
+{
+    if (HI)
+        asm volatile("v_smfmac_f32_32x32x32_f16 a[%3:%4], %0, %1, %2 abid:1"
+                     :
+                     : "v"(av), "v"(bv), "v"(idx), "n"(16 * T), "n"(16 * T + 15));
+    else
+        asm volatile("v_smfmac_f32_32x32x32_f16 a[%3:%4], %0, %1, %2"
+                     :
+                     : "v"(av), "v"(bv), "v"(idx), "n"(16 * T), "n"(16 * T + 15));
+}
+template <int T>
+__device__ __forceinline__ void mfma_fixed(half8_t av, half8_t bv)
+{
+    asm volatile("v_mfma_f32_32x32x16_f16 a[%2:%3], %0, %1, a[%2:%3]"
+                 :
+                 : "v"(av), "v"(bv), "n"(16 * T), "n"(16 * T + 15));
+}
+
+// Dense continuation on the fixed accumulators: acc(i, it) += A_i B_it^T over K
+// inputs (K a multiple of 32), 16 per step of V_MFMA_F32_32X32X16_F16.
+//   A: rows from global memory, 16 bytes per lane, row tile and step (da, av:
+//      this lane's offset for tile 0, step 0; a_tile: bytes between row tiles; a step
+//      is 32 bytes further), fetched three steps ahead into four rotating sets;
+//   B: 128 tokens x 128 inputs per stage staged through the LDS buffers like X
+//      (db, bv: this lane's staging offset for stage 0; b_pass: bytes between
+//      the 16-row passes; a stage is 256 bytes further), next stage's loads
+//      issued during steps 0-3 of the current one.
+// Loads past the end stay inside the descriptors or read as zero and are not
+// used; issuing them anyway keeps one path through the loop body.
+// Starts and ends with every wavefront past a barrier.
+template <int AT, class Store>
+__device__ __forceinline__ void dense_phase(rsrc_t da, uint32_t av, uint32_t a_tile, rsrc_t db, uint32_t bv,
+                                            uint32_t b_pass, int K, const half_t *lr, uint4_t (&xs)[XR],
+                                            Store &&stage_store)
+{
+    const int nst = K / 16;                       // steps
+    const int stages = (K + SG_BK - 1) / SG_BK;
+    uint4_t la[4][AT];
+#pragma unroll
+    for (int p = 0; p < XR; ++p) xs[p] = load16(db, bv, (uint32_t)p * b_pass);
+#pragma unroll
+    for (int g = 0; g < 3; ++g)
+#pragma unroll
+        for (int i = 0; i < AT; ++i) la[g][i] = load16(da, av, (uint32_t)i * a_tile + (uint32_t)g * 32u);
+    stage_store(0, xs);
+    __syncthreads();
+    for (int s = 0; s < stages; ++s) {
+        const int u = s & 1;
+        const int jn = min(8, nst - 8 * s);       // steps in this stage
+        half8_t b_cur[NT], b_nxt[NT];
+#pragma unroll
+        for (int it = 0; it < NT; ++it)
+            b_cur[it] = *reinterpret_cast<const half8_t *>(lr + u * SG_STAGE + it * 32 * SG_LD);
+        static_for<8>([&](auto jc) {
+            constexpr int j = jc;
+            if (j >= jn) return;
+            const int g = 8 * s + j;
+            static_for<NT>([&](auto itc) {
+                constexpr int it = itc;
+                if constexpr (it < AT)
+                    la[(j + 3) & 3][it] = load16(da, av, (uint32_t)it * a_tile + (uint32_t)(g + 3) * 32u);
+                if constexpr (j < 4 && it < 2)
+                    xs[2 * j + it] =
+                        load16(db, bv, (uint32_t)(s + 1) * (SG_BK * 2) + (uint32_t)(2 * j + it) * b_pass);
+                if constexpr (j + 1 < 8)
+                    b_nxt[it] = *reinterpret_cast<const half8_t *>(lr + u * SG_STAGE + it * 32 * SG_LD + 16 * (j + 1));
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<AT>([&](auto ic) {
+                    constexpr int i = ic;
+                    mfma_fixed<i * NT + it>(__builtin_bit_cast(half8_t, la[j & 3][i]), b_cur[it]);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+#pragma unroll
+            for (int it = 0; it < NT; ++it) b_cur[it] = b_nxt[it];
+        });
+        if (s + 1 < stages) stage_store(u ^ 1, xs);
+        __syncthreads();
+    }
+}
+
+}  // namespace slim
+
+#endif  // SLIM_MMA_H
