@@ -94,6 +94,17 @@ def test_unpack_arbitrary_valid_bytes():
     assert np.array_equal(codes.cpu().numpy(), rc) and np.array_equal(mask.cpu().numpy(), rm)
 
 
+def test_lowrank_several_row_tiles():
+    n, k, r, m = 1100, 1280, 100, 300
+    L, R = wl.make_adapters(n, k, r, 31, 32)
+    X = wl.make_activations(m, k, True, 33, 34)
+    Lp, Rp = B.slim_pack_adapters(L.to(DEV), R.to(DEV))
+    ref = O.xr(X.numpy(), R.numpy()) @ L.numpy().astype(np.float64).T
+    Y = B.slim_lowrank(X.to(DEV), Rp, Lp, r)
+    torch.cuda.synchronize()
+    assert _relerr(Y.cpu().numpy(), ref) <= TOL_Y
+
+
 # ---- forward: decode ------------------------------------------------------------
 
 def _forward_case(shape, m, fn, seed=0, rows=None):
@@ -158,6 +169,21 @@ def test_gemm_llama7b_mlp_sampled_rows(shape, m):
     rows = np.random.default_rng(2).choice(shape.n, size=256, replace=False)
     rows.sort()
     assert _forward_case(shape, m, B.slim_linear_gemm, rows=rows) <= TOL_Y
+
+
+@pytest.mark.parametrize("shape,m", [(wl.L13B_UP, 4096), (wl.L70B_ATTN, 4096)], ids=lambda v: str(getattr(v, "name", v)))
+def test_gemm_full_size_sampled_rows(shape, m):
+    rows = np.random.default_rng(3).choice(shape.n, size=64, replace=False)
+    rows.sort()
+    assert _forward_case(shape, m, B.slim_linear_gemm, rows=rows) <= TOL_Y
+
+
+def test_gemm_whole_round_plus_remainder_tiles():
+    # 3 row tiles x 100 token tiles = 300 workgroup tiles: one whole round of 256 and a
+    # remainder that runs as half-height tiles; 3 stages of inputs (an odd count)
+    shape = _shape(1536, 384, 37)
+    rows = np.arange(0, 1536, 7)
+    assert _forward_case(shape, 12800, B.slim_linear_gemm, seed=13, rows=rows) <= TOL_Y
 
 
 def test_gemv_and_gemm_agree():
