@@ -8,8 +8,7 @@
 
 namespace slim {
 
-constexpr int kPackThreads = 256;
-constexpr int kPackCached = 12;   // float4 groups a lane keeps: rows up to 4*256*12 = 12288 inputs
+constexpr int kPackSlotsMax = 12;   // float4 groups a lane keeps at most: rows up to 4 * 1024 * 12 inputs stay in registers
 
 // Kept positions of one group: order by (|w| descending, position ascending),
 // take two, return them as i0 < i1 packed as i0 | (i1 << 2).
@@ -50,30 +49,35 @@ __device__ __forceinline__ uint32_t encode_group(float4 v, float s, uint32_t *m4
     return quantize_code(w0, s) | (quantize_code(w1, s) << 4);
 }
 
-template <bool CACHED>
-__global__ __launch_bounds__(kPackThreads) void pack_kernel(const float *__restrict__ W, int n, int k,
+// THREADS lanes per row; SLOTS = float4 groups of the row each lane keeps in
+// registers (the row has at most 4 THREADS SLOTS inputs); 0 = rows of any
+// length, read twice.  Few slots per lane keep the register count low enough
+// for eight wavefronts per SIMD, which is what hides the load latency here.
+template <int THREADS, int SLOTS>
+__global__ __launch_bounds__(THREADS) void pack_kernel(const float *__restrict__ W, int n, int k,
                                                             uint8_t *__restrict__ qvals,
                                                             uint8_t *__restrict__ meta,
                                                             float *__restrict__ scale)
 {
-    __shared__ float wave_part[kPackThreads / kWave];
+    __shared__ float wave_part[THREADS / kWave];
     const int ngroups = k / 4;
     const int tid = threadIdx.x;
     for (int o = blockIdx.x; o < n; o += gridDim.x) {
         const float4 *row = reinterpret_cast<const float4 *>(W + (size_t)o * k);
-        float4 cache[CACHED ? kPackCached : 1];
+        constexpr bool CACHED = SLOTS > 0;
+        float4 cache[CACHED ? SLOTS : 1];
         float a = 0.0f;
         if (CACHED) {
 #pragma unroll
-            for (int i = 0; i < kPackCached; ++i) {
-                int g = tid + i * kPackThreads;
+            for (int i = 0; i < SLOTS; ++i) {
+                int g = tid + i * THREADS;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (g < ngroups) v = row[g];
                 cache[i] = v;
                 a = fmaxf(a, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
             }
         } else {
-            for (int g = tid; g < ngroups; g += kPackThreads) {
+            for (int g = tid; g < ngroups; g += THREADS) {
                 float4 v = row[g];
                 a = fmaxf(a, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
             }
@@ -82,7 +86,9 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float *__restr
         __syncthreads();                       // wave_part is reused across rows
         if ((tid & (kWave - 1)) == 0) wave_part[tid / kWave] = a;
         __syncthreads();
-        a = fmaxf(fmaxf(wave_part[0], wave_part[1]), fmaxf(wave_part[2], wave_part[3]));
+        a = wave_part[0];
+#pragma unroll
+        for (int w = 1; w < THREADS / kWave; ++w) a = fmaxf(a, wave_part[w]);
         const float s = (a == 0.0f) ? 1.0f : a / 7.0f;
         if (tid == 0) scale[o] = s;
 
@@ -92,8 +98,8 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float *__restr
         // the stride are even, so both are active together.
         if (CACHED) {
 #pragma unroll
-            for (int i = 0; i < kPackCached; ++i) {
-                int g = tid + i * kPackThreads;
+            for (int i = 0; i < SLOTS; ++i) {
+                int g = tid + i * THREADS;
                 if (g < ngroups) {
                     uint32_t m4;
                     uint32_t q = encode_group(cache[i], s, &m4);
@@ -103,7 +109,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float *__restr
                 }
             }
         } else {
-            for (int g = tid; g < ngroups; g += kPackThreads) {
+            for (int g = tid; g < ngroups; g += THREADS) {
                 uint32_t m4;
                 uint32_t q = encode_group(row[g], s, &m4);
                 qrow[g] = (uint8_t)q;
@@ -167,13 +173,27 @@ extern "C" int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8
     if (shape.n < 1 || shape.k < 8 || shape.k % 8) return SLIM_ERR_SHAPE;
     if (!aligned16(W) || !aligned16(qvals) || !aligned16(meta) || !aligned16(scale)) return SLIM_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int grid = shape.n < 256 * 8 ? shape.n : 256 * 8;
-    if (shape.k / 4 <= kPackThreads * kPackCached)
-        hipLaunchKernelGGL(pack_kernel<true>, dim3(grid), dim3(kPackThreads), 0, st, W, shape.n, shape.k,
-                           qvals, meta, scale);
+    // lanes per row: enough that a lane keeps at most 4 groups, up to 1024
+    const int groups = shape.k / 4;
+    // (two rounds of resident workgroups at most; a workgroup walks the rows it owns)
+#define SLIM_PACK_LAUNCH(T, S)                                                                                \
+    hipLaunchKernelGGL((pack_kernel<T, S>), dim3(shape.n < 256 * (4096 / T) ? shape.n : 256 * (4096 / T)), dim3(T), 0, \
+                       st, W, shape.n, shape.k, qvals, meta, scale)
+    if (groups <= 256 * 2)
+        SLIM_PACK_LAUNCH(256, 2);
+    else if (groups <= 256 * 4)
+        SLIM_PACK_LAUNCH(256, 4);
+    else if (groups <= 512 * 4)
+        SLIM_PACK_LAUNCH(512, 4);
+    else if (groups <= 1024 * 4)
+        SLIM_PACK_LAUNCH(1024, 4);
+    else if (groups <= 1024 * 8)
+        SLIM_PACK_LAUNCH(1024, 8);
+    else if (groups <= 1024 * kPackSlotsMax)
+        SLIM_PACK_LAUNCH(1024, kPackSlotsMax);
     else
-        hipLaunchKernelGGL(pack_kernel<false>, dim3(grid), dim3(kPackThreads), 0, st, W, shape.n, shape.k,
-                           qvals, meta, scale);
+        SLIM_PACK_LAUNCH(1024, 0);
+#undef SLIM_PACK_LAUNCH
     return hip_status(hipGetLastError());
 }
 
