@@ -29,6 +29,15 @@
  *   meta[o][g/2] = m4(2*(g/2)) | (m4(2*(g/2)+1) << 4),  m4(g) = i0 | (i1 << 2)
  *   scale[o]     = fp32
  * 3 bits per original weight.
+ *
+ * Adapter layout (written by slim_pack_adapters, read by every kernel): an fp16
+ * matrix [rows][cols] (L: [n][rank_pad], R: [rank_pad][k]) is stored as tiles of
+ * 32 rows x 16 columns (1 KiB), row tile major, rows padded to 32 and columns to
+ * 16 with zeros; inside a tile the 64 pieces of 8 columns (16 bytes) are ordered
+ * (column half, row).  The piece with columns 8 c .. 8 c + 7 of row r starts at byte
+ *   ((r / 32) * (cols16 / 16) + c / 2) * 1024 + ((c % 2) * 32 + r % 32) * 16,
+ * cols16 = cols rounded up to 16.  This is the order in which a wavefront holds
+ * the A operand of the matrix instructions, so its loads are contiguous.
  */
 #ifndef SLIM_H
 #define SLIM_H
@@ -62,8 +71,8 @@ typedef struct {
     const uint8_t *qvals;   /* [n][k/4]                                              */
     const uint8_t *meta;    /* [n][k/8]                                              */
     const float *scale;     /* [n]                                                   */
-    const slim_half *L;     /* [n][rank_pad], columns >= rank are zero (NULL if rank == 0) */
-    const slim_half *R;     /* [rank_pad][k], rows >= rank are zero    (NULL if rank == 0) */
+    const slim_half *L;     /* [n][rank_pad] in the adapter layout, columns >= rank zero (NULL if rank == 0) */
+    const slim_half *R;     /* [rank_pad][k] in the adapter layout, rows >= rank zero    (NULL if rank == 0) */
     int32_t rank_pad;       /* slim_rank_pad(rank)                                   */
 } slim_layer;
 
@@ -98,8 +107,9 @@ int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8_t *meta, f
               void *stream);
 
 /*
- * slim_pack_adapters -- lay the fp16 adapters out for the kernels: copy
- * L [n][rank] into L_pad [n][rank_pad] and R [rank][k] into R_pad [rank_pad][k],
+ * slim_pack_adapters -- lay the fp16 adapters out for the kernels: L [n][rank]
+ * and R [rank][k], row-major, go into L_pad = [n][rank_pad] and R_pad =
+ * [rank_pad][k] in the adapter layout above (sizes from slim_packed_sizes),
  * zero-filling the padding.  No arithmetic.  rank must be >= 1.
  */
 int slim_pack_adapters(const slim_half *L, const slim_half *R, slim_shape shape,
@@ -148,7 +158,7 @@ int slim_linear_gemm(const slim_layer *layer, const slim_half *X, int32_t m, sli
 /*
  * slim_lowrank -- the adapter term alone (Sec. 3.2; cost O(2 b r d^2), App.
  * "Rank Analysis"):  Y = (X R^T) L^T  or, with accumulate != 0,  Y += ...
- * L [n][rank_pad], R [rank_pad][k] as in slim_layer; shape.rank >= 1;
+ * L, R as in slim_layer (adapter layout); shape.rank >= 1;
  * k % 128 == 0.  In accumulate mode Y is read as fp16, added to in fp32 and
  * rounded back once.
  */

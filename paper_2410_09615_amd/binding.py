@@ -114,8 +114,8 @@ class SlimLayer:
     qvals: torch.Tensor            # uint8 [n][k/4]
     meta: torch.Tensor             # uint8 [n][k/8]
     scale: torch.Tensor            # float32 [n]
-    L: torch.Tensor | None         # float16 [n][rank_pad]
-    R: torch.Tensor | None         # float16 [rank_pad][k]
+    L: torch.Tensor | None         # float16, tiled layout of [n][rank_pad]
+    R: torch.Tensor | None         # float16, tiled layout of [rank_pad][k]
 
     def c_struct(self) -> slim_layer:
         return slim_layer(slim_shape(self.n, self.k, self.rank), self.qvals.data_ptr(), self.meta.data_ptr(),
@@ -138,16 +138,17 @@ def slim_pack(W: torch.Tensor, qvals=None, meta=None, scale=None):
 
 
 def slim_pack_adapters(L: torch.Tensor, R: torch.Tensor):
-    """L fp16 [n][rank], R fp16 [rank][k] -> zero-padded (L_pad, R_pad)."""
+    """L fp16 [n][rank], R fp16 [rank][k] -> (L_pad, R_pad): zero-padded to rank_pad and laid out in
+    the kernels' tiled order (flat tensors; sizes from slim_packed_sizes)."""
     _dev(L, torch.float16, "L")
     _dev(R, torch.float16, "R")
     n, rank = L.shape
     k = R.shape[1]
     if R.shape[0] != rank:
         raise ValueError("L and R disagree on the rank")
-    rp = slim_rank_pad(rank)
-    L_pad = torch.empty(n, rp, dtype=torch.float16, device=L.device)
-    R_pad = torch.empty(rp, k, dtype=torch.float16, device=L.device)
+    sizes = slim_packed_sizes(n, k, rank)
+    L_pad = torch.empty(sizes["L"] // 2, dtype=torch.float16, device=L.device)
+    R_pad = torch.empty(sizes["R"] // 2, dtype=torch.float16, device=L.device)
     _check("slim_pack_adapters", lib().slim_pack_adapters(_ptr(L), _ptr(R), slim_shape(n, k, rank), _ptr(L_pad),
                                                           _ptr(R_pad), _stream(L)))
     return L_pad, R_pad
@@ -174,7 +175,7 @@ def compress(W: torch.Tensor, L: torch.Tensor | None = None, R: torch.Tensor | N
     if L is not None and L.shape[1] > 0:
         rank = L.shape[1]
         Lp, Rp = slim_pack_adapters(L, R)
-        rp = Lp.shape[1]
+        rp = slim_rank_pad(rank)
     return SlimLayer(n, k, rank, rp, qvals, meta, scale, Lp, Rp)
 
 
@@ -214,14 +215,14 @@ def slim_linear_gemm(layer: SlimLayer, X: torch.Tensor, Y=None, workspace=None) 
     return _forward("slim_linear_gemm", layer, X, Y, workspace)
 
 
-def slim_lowrank(X: torch.Tensor, R_pad: torch.Tensor, L_pad: torch.Tensor, rank: int, Y=None,
+def slim_lowrank(X: torch.Tensor, R_pad: torch.Tensor, L_pad: torch.Tensor, n: int, rank: int, Y=None,
                  accumulate: bool = False, workspace=None) -> torch.Tensor:
-    """Y (+)= (X R^T) L^T with padded adapters as produced by slim_pack_adapters."""
+    """Y [m][n] (+)= (X R^T) L^T with the adapters as produced by slim_pack_adapters."""
     _dev(X, torch.float16, "X")
     _dev(R_pad, torch.float16, "R_pad")
     _dev(L_pad, torch.float16, "L_pad")
     m, k = X.shape
-    n, rp = L_pad.shape
+    rp = slim_rank_pad(rank)
     if Y is None:
         if accumulate:
             raise ValueError("accumulate needs Y")

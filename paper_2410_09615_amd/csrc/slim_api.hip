@@ -52,8 +52,8 @@ extern "C" int slim_packed_sizes(slim_shape shape, size_t *qvals_bytes, size_t *
     if (meta_bytes) *meta_bytes = (size_t)shape.n * (shape.k / 8);
     if (scale_bytes) *scale_bytes = (size_t)shape.n * sizeof(float);
     if (rank_pad) *rank_pad = rp;
-    if (L_bytes) *L_bytes = (size_t)shape.n * rp * sizeof(slim_half);
-    if (R_bytes) *R_bytes = (size_t)rp * shape.k * sizeof(slim_half);
+    if (L_bytes) *L_bytes = rp ? tl_bytes(shape.n, rp) : 0;
+    if (R_bytes) *R_bytes = rp ? tl_bytes(rp, shape.k) : 0;
     return SLIM_OK;
 }
 

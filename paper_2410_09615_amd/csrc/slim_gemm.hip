@@ -12,7 +12,7 @@ namespace slim {
 enum OutMode { OUT_STORE = 0, OUT_ACCUM = 1, OUT_PARTIAL = 2 };
 
 struct DenseGemmArgs {
-    const half_t *A;     // [rows][kt]
+    const half_t *A;     // [rows][kt] in the tiled adapter layout
     const half_t *B;     // [m][kt]
     int rows, m, kt;     // kt: row length of A and B (the full k extent)
     int ks;              // inputs per split (multiple of 128); grid.y splits
@@ -53,11 +53,11 @@ __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
 #pragma unroll
         for (int p = 0; p < XR; ++p) *reinterpret_cast<uint4_t *>(lw + u * SG_STAGE + p * 16 * SG_LD) = reg[p];
     };
-    const rsrc_t da = make_rsrc(a.A, (uint32_t)a.rows * kt * 2u);
+    const rsrc_t da = make_rsrc(a.A, (uint32_t)tl_bytes(a.rows, a.kt));
     const rsrc_t db = make_rsrc(a.B, (uint32_t)a.m * kt * 2u);
-    const uint32_t av = ((uint32_t)(o0 + li) * kt + (uint32_t)k0 + 8u * lb) * 2u;
+    const uint32_t av = tl_piece((uint32_t)o0 + li, (uint32_t)k0 / 8 + lb, kt);      // k0 is a multiple of 128
     const uint32_t bv = ((uint32_t)(t0 + srow) * kt + (uint32_t)k0 + (uint32_t)scol) * 2u;
-    dense_phase<AT>(da, av, 64u * kt, db, bv, 32u * kt, klen, lr, xs, stage_store);
+    dense_phase<AT>(da, av, (kt / 16) * 1024u, 1024u, db, bv, 32u * kt, klen, lr, xs, stage_store);
     acc_settle();
 
     // lane holds token t0 + 32 it + li, rows o .. o + 3 per (i, blk)

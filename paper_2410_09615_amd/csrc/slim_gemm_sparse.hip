@@ -218,14 +218,15 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
         acc_settle();
     }
 
-    // adapter term: acc += L T^T as dense steps of 16 ranks; T staged like X, L rows from global
+    // adapter term: acc += L T^T as dense steps of 16 ranks; T staged like X; L in its
+    // tiled layout: one contiguous KiB per row tile and step
     if (a.rank_pad > 0) {
         const uint32_t rp = (uint32_t)a.rank_pad;
-        const rsrc_t dl = make_rsrc(a.L, (uint32_t)a.n * rp * 2u);
+        const rsrc_t dl = make_rsrc(a.L, (uint32_t)tl_bytes(a.n, a.rank_pad));
         const rsrc_t dt = make_rsrc(a.T, (uint32_t)a.m * rp * 2u);
-        const uint32_t lv = ((uint32_t)(o0 + li) * rp + 8u * lb) * 2u;
+        const uint32_t lv = tl_piece((uint32_t)o0 + li, lb, rp);
         const uint32_t tv = ((uint32_t)(t0 + srow) * rp + (uint32_t)scol) * 2u;
-        dense_phase<AT>(dl, lv, 64u * rp, dt, tv, 32u * rp, (int)rp, lr, xr[0], stage_store);
+        dense_phase<AT>(dl, lv, (rp / 16) * 1024u, 1024u, dt, tv, 32u * rp, (int)rp, lr, xr[0], stage_store);
         acc_settle();
     }
 

@@ -26,8 +26,9 @@
 //          L rows stream through the dense matrix instruction against T held
 //          in LDS as an fp16 hi/lo pair (T keeps fp32 accuracy).
 //
-// Every 128-bit load instruction of a wavefront covers 64 contiguous bytes
-// (R, L, metadata) or 128 bytes at stride 32 (codes) of each of 16 rows.
+// Every 128-bit load instruction of a wavefront covers four runs of 256
+// contiguous bytes (R, L: tiled layout), or 64 contiguous bytes (metadata) or
+// 128 bytes at stride 32 (codes) of each of 16 rows.
 //
 // State between calls lives in the head of the workspace: two T buffers used
 // alternately (a call accumulates into one and zeroes the other, which the
@@ -131,11 +132,14 @@ __device__ __forceinline__ void issue_unit(const DecodeArgs &a, const Part1Geom 
     const uint4_t zero = {0u, 0u, 0u, 0u};
     if (d.q < 0) return;
     if (d.is_r) {
-        const half_t *p = a.R + (size_t)(16 * d.tile + lx) * a.k + g.kbeg + d.k0 + 8 * ly;
+        // R in its tiled layout: step t reads the pieces (row, 4 t + ly) of the unit,
+        // four runs of 256 contiguous bytes per load instruction
+        const char *base = reinterpret_cast<const char *>(a.R) +
+                           tl_piece(16u * d.tile + lx, (uint32_t)(g.kbeg + d.k0) / 8 + ly, (uint32_t)a.k);
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             const bool valid = d.k0 + 32 * t < d.k1;
-            b.r[t] = valid ? *reinterpret_cast<const uint4_t *>(p + 32 * t) : zero;
+            b.r[t] = valid ? *reinterpret_cast<const uint4_t *>(base + 2048 * t) : zero;     // 4 pieces = 2 tiles on
         }
     } else {
         const int o = 16 * d.tile + lx;
@@ -324,11 +328,13 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_part2_kernel(DecodeArgs
     auto issue_l = [&](int ot, int batch, uint4_t (&lv)[NB]) {
         const int o = 16 * ot + lx;
         const bool rowok = batch < nbatch && ot < wtiles && o < a.n;
-        // step t takes ranks 32 t + 8 ly .. + 7: 64 contiguous bytes per row and load
-        const half_t *lp = a.L + (size_t)(rowok ? o : 0) * rp + (rowok ? batch : 0) * 32 * NB + 8 * ly;
+        // step t takes ranks 32 t + 8 ly .. + 7 of row o: piece (o, 4 (batch NB + t) + ly) of the
+        // tiled layout, four runs of 256 contiguous bytes per load instruction
+        const char *lp = reinterpret_cast<const char *>(a.L) +
+                         tl_piece((uint32_t)(rowok ? o : 0), 4u * (uint32_t)((rowok ? batch : 0) * NB) + ly, (uint32_t)rp);
 #pragma unroll
         for (int t = 0; t < NB; ++t)
-            lv[t] = rowok ? *reinterpret_cast<const uint4_t *>(lp + 32 * t) : uint4_t{0u, 0u, 0u, 0u};
+            lv[t] = rowok ? *reinterpret_cast<const uint4_t *>(lp + 2048 * t) : uint4_t{0u, 0u, 0u, 0u};
     };
     if (nbatch > 0) issue_l(tile0, 0, lvA);
 

@@ -73,6 +73,23 @@ __device__ __forceinline__ half8_t codes_to_half8(uint32_t q)
     return out;
 }
 
+// ---- device layout of the fp16 adapters (what slim_pack_adapters writes) ----
+// A matrix [rows][K] is stored as tiles of 32 rows x 16 columns, 1 KiB each,
+// row tile major; inside a tile the 64 pieces of 8 halves (16 bytes) are ordered
+// (column half, row): piece (r, h) at ((h * 32) + r) * 16.  That is the order in
+// which the 64 lanes of a wavefront hold the A operand of a 32 x 32 x 16 matrix
+// instruction, so one load instruction reads one contiguous KiB; the 16 x 16 x 32
+// instruction of the decode path reads four runs of 256 bytes.  rows is padded
+// to 32 and K to 16 with zeros.
+__host__ __device__ inline uint32_t tl_rows(int rows) { return (uint32_t)(rows + 31) / 32 * 32; }
+__host__ __device__ inline uint32_t tl_cols(int K) { return (uint32_t)(K + 15) / 16 * 16; }
+__host__ __device__ inline size_t tl_bytes(int rows, int K) { return (size_t)tl_rows(rows) * tl_cols(K) * 2; }
+// byte offset of the piece holding columns 8 c8 .. 8 c8 + 7 of `row`
+__host__ __device__ inline uint32_t tl_piece(uint32_t row, uint32_t c8, uint32_t kcols)
+{
+    return ((row >> 5) * (kcols >> 4) + (c8 >> 1)) * 1024u + (((c8 & 1u) << 5) + (row & 31u)) * 16u;
+}
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? SLIM_OK : SLIM_ERR_HIP; }

@@ -109,8 +109,8 @@ __device__ __forceinline__ void mfma_fixed(half8_t av, half8_t bv)
 // Dense continuation on the fixed accumulators: acc(i, it) += A_i B_it^T over K
 // inputs (K a multiple of 32), 16 per step of V_MFMA_F32_32X32X16_F16.
 //   A: rows from global memory, 16 bytes per lane, row tile and step (da, av:
-//      this lane's offset for tile 0, step 0; a_tile: bytes between row tiles; a step
-//      is 32 bytes further), fetched three steps ahead into four rotating sets;
+//      this lane's offset for tile 0, step 0; a_tile: bytes between row tiles;
+//      a_step: bytes between steps), fetched three steps ahead into four rotating sets;
 //   B: 128 tokens x 128 inputs per stage staged through the LDS buffers like X
 //      (db, bv: this lane's staging offset for stage 0; b_pass: bytes between
 //      the 16-row passes; a stage is 256 bytes further), next stage's loads
@@ -119,7 +119,8 @@ __device__ __forceinline__ void mfma_fixed(half8_t av, half8_t bv)
 // used; issuing them anyway keeps one path through the loop body.
 // Starts and ends with every wavefront past a barrier.
 template <int AT, class Store>
-__device__ __forceinline__ void dense_phase(rsrc_t da, uint32_t av, uint32_t a_tile, rsrc_t db, uint32_t bv,
+__device__ __forceinline__ void dense_phase(rsrc_t da, uint32_t av, uint32_t a_tile, uint32_t a_step, rsrc_t db,
+                                            uint32_t bv,
                                             uint32_t b_pass, int K, const half_t *lr, uint4_t (&xs)[XR],
                                             Store &&stage_store)
 {
@@ -131,7 +132,7 @@ __device__ __forceinline__ void dense_phase(rsrc_t da, uint32_t av, uint32_t a_t
 #pragma unroll
     for (int g = 0; g < 3; ++g)
 #pragma unroll
-        for (int i = 0; i < AT; ++i) la[g][i] = load16(da, av, (uint32_t)i * a_tile + (uint32_t)g * 32u);
+        for (int i = 0; i < AT; ++i) la[g][i] = load16(da, av, (uint32_t)i * a_tile + (uint32_t)g * a_step);
     stage_store(0, xs);
     __syncthreads();
     for (int s = 0; s < stages; ++s) {
@@ -148,7 +149,7 @@ __device__ __forceinline__ void dense_phase(rsrc_t da, uint32_t av, uint32_t a_t
             static_for<NT>([&](auto itc) {
                 constexpr int it = itc;
                 if constexpr (it < AT)
-                    la[(j + 3) & 3][it] = load16(da, av, (uint32_t)it * a_tile + (uint32_t)(g + 3) * 32u);
+                    la[(j + 3) & 3][it] = load16(da, av, (uint32_t)it * a_tile + (uint32_t)(g + 3) * a_step);
                 if constexpr (j < 4 && it < 2)
                     xs[2 * j + it] =
                         load16(db, bv, (uint32_t)(s + 1) * (SG_BK * 2) + (uint32_t)(2 * j + it) * b_pass);

@@ -141,16 +141,28 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
     }
 }
 
-// dst [rows][dst_cols] <- src [src_rows][src_cols], zero outside the source.
-__global__ __launch_bounds__(256) void pad_copy_kernel(const uint16_t *__restrict__ src, int src_rows,
-                                                       int src_cols, uint16_t *__restrict__ dst, int rows,
-                                                       int dst_cols)
+// dst (tiled layout of a [rows][kcols] matrix, see slim_internal.h) <- src
+// [src_rows][src_cols] row-major, zero outside the source.  One lane per piece
+// of 8 halves, pieces in destination order: the stores are contiguous.
+__global__ __launch_bounds__(256) void tile_copy_kernel(const uint16_t *__restrict__ src, int src_rows,
+                                                        int src_cols, uint16_t *__restrict__ dst, uint32_t rows,
+                                                        uint32_t kcols)
 {
-    size_t total = (size_t)rows * dst_cols;
-    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total;
-         i += (size_t)gridDim.x * blockDim.x) {
-        int r = (int)(i / dst_cols), c = (int)(i % dst_cols);
-        dst[i] = (r < src_rows && c < src_cols) ? src[(size_t)r * src_cols + c] : (uint16_t)0;
+    const size_t pieces = (size_t)rows * (kcols / 8);
+    for (size_t p = blockIdx.x * (size_t)blockDim.x + threadIdx.x; p < pieces;
+         p += (size_t)gridDim.x * blockDim.x) {
+        const uint32_t tile = (uint32_t)(p >> 6), q = (uint32_t)p & 63u;
+        const uint32_t rt = tile / (kcols >> 4), kt = tile - rt * (kcols >> 4);
+        const int row = (int)(rt * 32 + (q & 31u));
+        const int c0 = (int)(kt * 16 + (q >> 5) * 8);
+        uint16_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            v[e] = (row < src_rows && c0 + e < src_cols) ? src[(size_t)row * src_cols + c0 + e] : (uint16_t)0;
+        uint4_t out;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = (uint32_t)v[2 * e] | ((uint32_t)v[2 * e + 1] << 16);
+        reinterpret_cast<uint4_t *>(dst)[p] = out;
     }
 }
 
@@ -217,9 +229,9 @@ extern "C" int slim_pack_adapters(const slim_half *L, const slim_half *R, slim_s
     if (!aligned16(L_pad) || !aligned16(R_pad)) return SLIM_ERR_ALIGN;
     int rp = slim_rank_pad(shape.rank);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(pad_copy_kernel, dim3(grid_for((size_t)shape.n * rp, 256)), dim3(256), 0, st, L,
-                       shape.n, shape.rank, L_pad, shape.n, rp);
-    hipLaunchKernelGGL(pad_copy_kernel, dim3(grid_for((size_t)rp * shape.k, 256)), dim3(256), 0, st, R,
-                       shape.rank, shape.k, R_pad, rp, shape.k);
+    hipLaunchKernelGGL(tile_copy_kernel, dim3(grid_for(tl_bytes(shape.n, rp) / 16, 256)), dim3(256), 0, st, L, shape.n,
+                       shape.rank, L_pad, tl_rows(shape.n), tl_cols(rp));
+    hipLaunchKernelGGL(tile_copy_kernel, dim3(grid_for(tl_bytes(rp, shape.k) / 16, 256)), dim3(256), 0, st, R,
+                       shape.rank, shape.k, R_pad, tl_rows(rp), tl_cols(shape.k));
     return hip_status(hipGetLastError());
 }

@@ -12,6 +12,7 @@ import torch
 from oracle import slim_oracle as O
 from paper_2410_09615_amd import binding as B
 from paper_2410_09615_amd import workloads as wl
+from layouts import tile_fp16
 
 pytestmark = pytest.mark.gpu
 
@@ -75,12 +76,18 @@ def test_pack_bit_exact_full_size(shape):
     _assert_pack_equal(_gpu_layer(W, None, None), W)
 
 
-def test_pack_adapters_pads_with_zeros():
-    L, R = wl.make_adapters(300, 640, 51)
+@pytest.mark.parametrize("n,k,r", [(300, 640, 51), (64, 1024, 32), (33, 136, 1)])
+def test_pack_adapters_pads_and_tiles(n, k, r):
+    # zero padding to rank_pad (and to whole tiles), then the documented tile order
+    L, R = wl.make_adapters(n, k, r)
     Lp, Rp = B.slim_pack_adapters(L.to(DEV), R.to(DEV))
-    assert Lp.shape == (300, 64) and Rp.shape == (64, 640)
-    assert torch.equal(Lp[:, :51].cpu(), L) and torch.equal(Rp[:51].cpu(), R)
-    assert (Lp[:, 51:] == 0).all() and (Rp[51:] == 0).all()
+    rp = B.slim_rank_pad(r)
+    Lref = np.zeros((n, rp), np.float16)
+    Lref[:, :r] = L.numpy()
+    Rref = np.zeros((rp, k), np.float16)
+    Rref[:r] = R.numpy()
+    assert np.array_equal(Lp.cpu().numpy().view(np.uint16), tile_fp16(Lref).view(np.uint16))
+    assert np.array_equal(Rp.cpu().numpy().view(np.uint16), tile_fp16(Rref).view(np.uint16))
 
 
 def test_unpack_arbitrary_valid_bytes():
@@ -100,7 +107,7 @@ def test_lowrank_several_row_tiles():
     X = wl.make_activations(m, k, True, 33, 34)
     Lp, Rp = B.slim_pack_adapters(L.to(DEV), R.to(DEV))
     ref = O.xr(X.numpy(), R.numpy()) @ L.numpy().astype(np.float64).T
-    Y = B.slim_lowrank(X.to(DEV), Rp, Lp, r)
+    Y = B.slim_lowrank(X.to(DEV), Rp, Lp, n, r)
     torch.cuda.synchronize()
     assert _relerr(Y.cpu().numpy(), ref) <= TOL_Y
 
@@ -210,6 +217,6 @@ def test_lowrank(m, accumulate):
         Y0 = (torch.randn(m, n, generator=torch.Generator().manual_seed(9)) * ref.std()).to(torch.float16)
         ref = ref + Y0.numpy().astype(np.float64)
         Y0 = Y0.to(DEV)
-    Y = B.slim_lowrank(X.to(DEV), Rp, Lp, r, Y=Y0, accumulate=accumulate)
+    Y = B.slim_lowrank(X.to(DEV), Rp, Lp, n, r, Y=Y0, accumulate=accumulate)
     torch.cuda.synchronize()
     assert _relerr(Y.cpu().numpy(), ref) <= TOL_Y
