@@ -23,12 +23,24 @@
  *     error nothing has been enqueued.
  * fp16 values are IEEE binary16 bit patterns (`slim_half`).
  *
- * Canonical packed format (written by slim_pack, read by every kernel):
+ * Canonical packed bytes:
  *   group g of row o = inputs 4g .. 4g+3; i0 < i1 are its two kept positions
  *   qvals[o][g]  = (code(i0) & 15) | ((code(i1) & 15) << 4)   two's-complement nibbles
  *   meta[o][g/2] = m4(2*(g/2)) | (m4(2*(g/2)+1) << 4),  m4(g) = i0 | (i1 << 2)
  *   scale[o]     = fp32
  * 3 bits per original weight.
+ *
+ * Packed layout (written by slim_pack, read by every kernel, inverted by
+ * slim_unpack): a byte permutation of the canonical arrays.  They are cut into
+ * tiles of 32 rows x 128 inputs (32 bytes of qvals, 16 of meta per row), stored
+ * row tile major, KT = ceil(k / 128) tiles per row tile, 1024 bytes of qvals and
+ * 512 of meta each; inside a tile the pieces of 64 inputs (16 / 8 bytes) are
+ * ordered (input half, row):
+ *   qvals[o][g] at ((o/32) * KT + g/32) * 1024 + (((g%32)/16) * 32 + o%32) * 16 + g%16
+ *   meta[o][b]  at ((o/32) * KT + b/16) *  512 + (((b%16)/8)  * 32 + o%32) *  8 + b%8
+ * Rows are padded to a multiple of 32 and inputs to a multiple of 128 with zero
+ * bytes.  This is the lane order of the sparse matrix instructions' A operand, so
+ * a wavefront's load of a tile is contiguous.  scale stays [n].
  *
  * Adapter layout (written by slim_pack_adapters, read by every kernel): an fp16
  * matrix [rows][cols] (L: [n][rank_pad], R: [rank_pad][k]) is stored as tiles of
@@ -68,8 +80,8 @@ typedef struct {
 /* One compressed layer: device pointers to caller-owned buffers. */
 typedef struct {
     slim_shape shape;
-    const uint8_t *qvals;   /* [n][k/4]                                              */
-    const uint8_t *meta;    /* [n][k/8]                                              */
+    const uint8_t *qvals;   /* canonical [n][k/4] in the packed layout               */
+    const uint8_t *meta;    /* canonical [n][k/8] in the packed layout               */
     const float *scale;     /* [n]                                                   */
     const slim_half *L;     /* [n][rank_pad] in the adapter layout, columns >= rank zero (NULL if rank == 0) */
     const slim_half *R;     /* [rank_pad][k] in the adapter layout, rows >= rank zero    (NULL if rank == 0) */
@@ -99,8 +111,8 @@ int slim_packed_sizes(slim_shape shape, size_t *qvals_bytes, size_t *meta_bytes,
  *          binary32 division (1.0 for an all-zero row);
  *   codes  symmetric uniform 4-bit quantization (Sec. 2; Sec. 3.1 Eq. 2):
  *          round-half-even(W / scale) in binary32, clamped to [-8, 7];
- *   bytes  the canonical format above.
- * W [n][k] fp32 in; qvals [n][k/4], meta [n][k/8], scale [n] out.
+ *   bytes  the canonical bytes above, written in the packed layout.
+ * W [n][k] fp32 in; qvals, meta (sizes from slim_packed_sizes), scale [n] out.
  * W must be finite.  Errors: NULL, SHAPE (k % 8 != 0, n < 1), ALIGN, HIP.
  */
 int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8_t *meta, float *scale,
@@ -116,8 +128,9 @@ int slim_pack_adapters(const slim_half *L, const slim_half *R, slim_shape shape,
                        slim_half *L_pad, slim_half *R_pad, void *stream);
 
 /*
- * slim_unpack -- inverse of the canonical format, for tests and inspection:
- * codes [n][k] int8 (0 where dropped) and mask [n][k] uint8 (1 where kept).
+ * slim_unpack -- inverse of slim_pack's bytes (packed layout and canonical
+ * format), for tests and inspection: codes [n][k] int8 (0 where dropped) and
+ * mask [n][k] uint8 (1 where kept), row-major.
  */
 int slim_unpack(const uint8_t *qvals, const uint8_t *meta, slim_shape shape, int8_t *codes,
                 uint8_t *mask, void *stream);

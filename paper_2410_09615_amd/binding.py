@@ -111,8 +111,8 @@ class SlimLayer:
     k: int
     rank: int
     rank_pad: int
-    qvals: torch.Tensor            # uint8 [n][k/4]
-    meta: torch.Tensor             # uint8 [n][k/8]
+    qvals: torch.Tensor            # uint8, packed (tiled) layout of the canonical [n][k/4]
+    meta: torch.Tensor             # uint8, packed (tiled) layout of the canonical [n][k/8]
     scale: torch.Tensor            # float32 [n]
     L: torch.Tensor | None         # float16, tiled layout of [n][rank_pad]
     R: torch.Tensor | None         # float16, tiled layout of [rank_pad][k]
@@ -129,8 +129,8 @@ def slim_pack(W: torch.Tensor, qvals=None, meta=None, scale=None):
     n, k = W.shape
     sizes = slim_packed_sizes(n, k, 0)
     if qvals is None:
-        qvals = torch.empty(sizes["qvals"], dtype=torch.uint8, device=W.device).view(n, k // 4)
-        meta = torch.empty(sizes["meta"], dtype=torch.uint8, device=W.device).view(n, k // 8)
+        qvals = torch.empty(sizes["qvals"], dtype=torch.uint8, device=W.device)
+        meta = torch.empty(sizes["meta"], dtype=torch.uint8, device=W.device)
         scale = torch.empty(n, dtype=torch.float32, device=W.device)
     _check("slim_pack", lib().slim_pack(_ptr(W), slim_shape(n, k, 0), _ptr(qvals), _ptr(meta), _ptr(scale),
                                         _stream(W)))
@@ -154,12 +154,13 @@ def slim_pack_adapters(L: torch.Tensor, R: torch.Tensor):
     return L_pad, R_pad
 
 
-def slim_unpack(qvals: torch.Tensor, meta: torch.Tensor):
-    """(codes int8 [n][k], mask uint8 [n][k]) from the canonical bytes."""
+def slim_unpack(qvals: torch.Tensor, meta: torch.Tensor, n: int, k: int):
+    """(codes int8 [n][k], mask uint8 [n][k]) from the packed bytes of an n x k layer."""
     _dev(qvals, torch.uint8, "qvals")
     _dev(meta, torch.uint8, "meta")
-    n, kq = qvals.shape
-    k = kq * 4
+    sizes = slim_packed_sizes(n, k, 0)
+    if qvals.numel() < sizes["qvals"] or meta.numel() < sizes["meta"]:
+        raise ValueError("packed buffers are smaller than slim_packed_sizes says")
     codes = torch.empty(n, k, dtype=torch.int8, device=qvals.device)
     mask = torch.empty(n, k, dtype=torch.uint8, device=qvals.device)
     _check("slim_unpack", lib().slim_unpack(_ptr(qvals), _ptr(meta), slim_shape(n, k, 0), _ptr(codes), _ptr(mask),

@@ -48,8 +48,8 @@ extern "C" int slim_packed_sizes(slim_shape shape, size_t *qvals_bytes, size_t *
 {
     if (shape.n < 1 || shape.k < 8 || shape.k % 8 || shape.rank < 0) return SLIM_ERR_SHAPE;
     int32_t rp = slim_rank_pad(shape.rank);
-    if (qvals_bytes) *qvals_bytes = (size_t)shape.n * (shape.k / 4);
-    if (meta_bytes) *meta_bytes = (size_t)shape.n * (shape.k / 8);
+    if (qvals_bytes) *qvals_bytes = pk_qbytes(shape.n, shape.k);
+    if (meta_bytes) *meta_bytes = pk_mbytes(shape.n, shape.k);
     if (scale_bytes) *scale_bytes = (size_t)shape.n * sizeof(float);
     if (rank_pad) *rank_pad = rp;
     if (L_bytes) *L_bytes = rp ? tl_bytes(shape.n, rp) : 0;

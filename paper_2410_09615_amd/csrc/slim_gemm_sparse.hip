@@ -8,7 +8,8 @@
 // round of workgroups.
 //   A (weights): never touches LDS.  Per 128 inputs a lane loads 16 bytes of
 //     codes and 8 bytes of positions of each of its rows straight from global
-//     memory (one stage ahead), turns 4 code bytes into 8 fp16 values in
+//     memory (one stage ahead; the packed layout makes each load instruction one
+//     contiguous KiB or half KiB), turns 4 code bytes into 8 fp16 values in
 //     registers, and passes the 16 position bits of those 4 groups as the index
 //     operand (the canonical metadata is that operand's format).  Each wavefront
 //     converts only its own rows, once, and uses them against all its tokens.
@@ -68,10 +69,11 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
     const uint32_t k = (uint32_t)a.k;
     const int nsteps = a.k / SG_BK;
 
-    // this lane's row of tile 0 (rows past n read as zero); tile i and stage s
-    // are uniform terms
-    const uint32_t qv = (uint32_t)(o0 + li) * (k / 4) + 16u * lb;
-    const uint32_t mv = (uint32_t)(o0 + li) * (k / 8) + 8u * lb;
+    // this lane's piece of row tile 0, stage 0 in the packed layout (one KiB of
+    // codes, 512 bytes of positions per row tile and stage); tile i and stage s are
+    // uniform terms; row tiles past the end read as zero
+    const uint32_t qv = (uint32_t)(o0 / 32) * (k / 128) * 1024u + (uint32_t)(lb * 32 + li) * 16u;
+    const uint32_t mv = (uint32_t)(o0 / 32) * (k / 128) * 512u + (uint32_t)(lb * 32 + li) * 8u;
     uint4_t qa[2][AT];
     uint2_t ma[2][AT];
 
@@ -148,14 +150,14 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
     // Fetches past the last stage stay inside the descriptors or read as zero and
     // are never used.
     {
-        const rsrc_t dq = make_rsrc(a.qvals, (uint32_t)a.n * (k / 4));
-        const rsrc_t dm = make_rsrc(a.meta, (uint32_t)a.n * (k / 8));
+        const rsrc_t dq = make_rsrc(a.qvals, (uint32_t)pk_qbytes(a.n, a.k));
+        const rsrc_t dm = make_rsrc(a.meta, (uint32_t)pk_mbytes(a.n, a.k));
         const rsrc_t dx = make_rsrc(a.X, (uint32_t)a.m * k * 2);
         auto fetch_a = [&](int j, int s, uint4_t (&q)[AT], uint2_t (&mm)[AT]) {    // j < 2 AT
             if (j < AT)
-                q[j] = load16(dq, qv, (uint32_t)j * 8u * k + (uint32_t)s * (SG_BK / 4));
+                q[j] = load16(dq, qv, ((uint32_t)j * (k / 128) + (uint32_t)s) * 1024u);
             else
-                mm[j - AT] = load8(dm, mv, (uint32_t)(j - AT) * 4u * k + (uint32_t)s * (SG_BK / 8));
+                mm[j - AT] = load8(dm, mv, ((uint32_t)(j - AT) * (k / 128) + (uint32_t)s) * 512u);
         };
         auto fetch_x = [&](int p, int s, uint4_t (&reg)[XR]) {
             reg[p] = load16(dx, xv, (uint32_t)s * (SG_BK * 2) + (uint32_t)p * 32u * k);

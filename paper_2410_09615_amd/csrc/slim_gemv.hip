@@ -26,9 +26,9 @@
 //          L rows stream through the dense matrix instruction against T held
 //          in LDS as an fp16 hi/lo pair (T keeps fp32 accuracy).
 //
-// Every 128-bit load instruction of a wavefront covers four runs of 256
-// contiguous bytes (R, L: tiled layout), or 64 contiguous bytes (metadata) or
-// 128 bytes at stride 32 (codes) of each of 16 rows.
+// All operands are read in their tiled layouts: a load instruction of a
+// wavefront covers four runs of 256 contiguous bytes (R, L, codes) or of 128
+// (positions).
 //
 // State between calls lives in the head of the workspace: two T buffers used
 // alternately (a call accumulates into one and zeroes the other, which the
@@ -151,16 +151,24 @@ __device__ __forceinline__ void issue_unit(const DecodeArgs &a, const Part1Geom 
         const bool valid1 = rowok && kl1 < d.k1;
         const int kg0 = g.kbeg + (valid0 ? kl0 : 0);
         const int kg1 = g.kbeg + (valid1 ? kl1 : 0);
-        const uint4_t *qp0 = reinterpret_cast<const uint4_t *>(a.qvals + row * (a.k / 4) + kg0 / 4);
-        const uint4_t *mp0 = reinterpret_cast<const uint4_t *>(a.meta + row * (a.k / 8) + kg0 / 8);
-        const uint4_t *qp1 = reinterpret_cast<const uint4_t *>(a.qvals + row * (a.k / 4) + kg1 / 4);
-        const uint4_t *mp1 = reinterpret_cast<const uint4_t *>(a.meta + row * (a.k / 8) + kg1 / 8);
-        b.r[0] = valid0 ? qp0[0] : zero;
-        b.r[1] = valid0 ? qp0[1] : zero;
-        b.r[2] = valid0 ? mp0[0] : zero;
-        b.r[3] = valid1 ? qp1[0] : zero;
-        b.r[4] = valid1 ? qp1[1] : zero;
-        b.r[5] = valid1 ? mp1[0] : zero;
+        // The lane's 128 inputs are one tile column of the packed layout: its two
+        // pieces of codes lie 512 bytes apart, its two pieces of positions 256.
+        const uint32_t kt = pk_ktiles(a.k);
+        const uint8_t *qp0 = a.qvals + pk_qoff((uint32_t)row, (uint32_t)kg0 / 4, kt);
+        const uint8_t *mp0 = a.meta + pk_moff((uint32_t)row, (uint32_t)kg0 / 8, kt);
+        const uint8_t *qp1 = a.qvals + pk_qoff((uint32_t)row, (uint32_t)kg1 / 4, kt);
+        const uint8_t *mp1 = a.meta + pk_moff((uint32_t)row, (uint32_t)kg1 / 8, kt);
+        auto q16 = [](const uint8_t *p) { return *reinterpret_cast<const uint4_t *>(p); };
+        auto m16 = [](const uint8_t *p) {
+            const uint2_t lo = *reinterpret_cast<const uint2_t *>(p), hi = *reinterpret_cast<const uint2_t *>(p + 256);
+            return uint4_t{lo[0], lo[1], hi[0], hi[1]};
+        };
+        b.r[0] = valid0 ? q16(qp0) : zero;
+        b.r[1] = valid0 ? q16(qp0 + 512) : zero;
+        b.r[2] = valid0 ? m16(mp0) : zero;
+        b.r[3] = valid1 ? q16(qp1) : zero;
+        b.r[4] = valid1 ? q16(qp1 + 512) : zero;
+        b.r[5] = valid1 ? m16(mp1) : zero;
     }
 }
 

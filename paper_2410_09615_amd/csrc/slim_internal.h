@@ -90,6 +90,27 @@ __host__ __device__ inline uint32_t tl_piece(uint32_t row, uint32_t c8, uint32_t
     return ((row >> 5) * (kcols >> 4) + (c8 >> 1)) * 1024u + (((c8 & 1u) << 5) + (row & 31u)) * 16u;
 }
 
+// ---- device layout of the packed weights (what slim_pack writes) ----
+// The canonical bytes (qvals[o][g], one per group of 4 inputs; meta[o][g / 2]) are
+// stored as tiles of 32 rows x 128 inputs, row tile major: 1 KiB of codes and
+// 512 bytes of positions per tile.  Inside a tile the 64 pieces of 64 inputs
+// (16 code bytes / 8 position bytes) are ordered (input half, row): lane order of
+// the sparse 32 x 32 x 32 matrix instruction, so one load instruction reads one
+// contiguous KiB (codes) or 512 bytes (positions).  Rows are padded to 32 and
+// inputs to 128 with zero bytes.
+__host__ __device__ inline uint32_t pk_ktiles(int k) { return (uint32_t)(k + 127) / 128; }
+__host__ __device__ inline size_t pk_qbytes(int n, int k) { return (size_t)((n + 31) / 32) * pk_ktiles(k) * 1024; }
+__host__ __device__ inline size_t pk_mbytes(int n, int k) { return (size_t)((n + 31) / 32) * pk_ktiles(k) * 512; }
+// byte offsets of canonical qvals[o][g] and meta[o][b]
+__host__ __device__ inline size_t pk_qoff(uint32_t o, uint32_t g, uint32_t kt)
+{
+    return ((size_t)(o >> 5) * kt + (g >> 5)) * 1024u + ((((g >> 4) & 1u) << 5) + (o & 31u)) * 16u + (g & 15u);
+}
+__host__ __device__ inline size_t pk_moff(uint32_t o, uint32_t b, uint32_t kt)
+{
+    return ((size_t)(o >> 5) * kt + (b >> 4)) * 512u + ((((b >> 3) & 1u) << 5) + (o & 31u)) * 8u + (b & 7u);
+}
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? SLIM_OK : SLIM_ERR_HIP; }

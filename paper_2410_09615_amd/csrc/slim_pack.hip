@@ -49,6 +49,13 @@ __device__ __forceinline__ uint32_t encode_group(float4 v, float s, uint32_t *m4
     return quantize_code(w0, s) | (quantize_code(w1, s) << 4);
 }
 
+// Value of lane + N inside the lane's row of 16 (0 past the end of the row).
+template <int N>
+__device__ __forceinline__ uint32_t row_shl(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x100 + N, 0xf, 0xf, true);
+}
+
 // THREADS lanes per row; SLOTS = float4 groups of the row each lane keeps in
 // registers (the row has at most 4 THREADS SLOTS inputs); 0 = rows of any
 // length, read twice.  Few slots per lane keep the register count low enough
@@ -62,7 +69,25 @@ __global__ __launch_bounds__(THREADS) void pack_kernel(const float *__restrict__
     __shared__ float wave_part[THREADS / kWave];
     const int ngroups = k / 4;
     const int tid = threadIdx.x;
-    for (int o = blockIdx.x; o < n; o += gridDim.x) {
+    const uint32_t kt = pk_ktiles(k);
+    const int gpad = (int)kt * 32;             // groups per row of the tiled layout
+    const int npad = (n + 31) / 32 * 32;
+    // Workgroups go to the 8 dies round-robin and each die has its own L2.  The 32
+    // rows of a row tile write into the same cache lines, so they are kept on one
+    // die: die x takes a contiguous range of row tiles, its workgroups walk that
+    // range row by row.  (The grid is a multiple of 8.)
+    const int die = blockIdx.x & 7, local = blockIdx.x >> 3, per_die = gridDim.x >> 3;
+    const int rows_per_die = ((npad / 32 + 7) / 8) * 32;
+    const int o_end = min(npad, (die + 1) * rows_per_die);
+    for (int o = die * rows_per_die + local; o < o_end; o += per_die) {
+        if (o >= n) {
+            // padding row of the last row tile: zero bytes
+            for (int g = 16 * tid; g < gpad; g += 16 * THREADS) {
+                *reinterpret_cast<uint4_t *>(qvals + pk_qoff(o, g, kt)) = uint4_t{0u, 0u, 0u, 0u};
+                *reinterpret_cast<uint2_t *>(meta + pk_moff(o, g >> 1, kt)) = uint2_t{0u, 0u};
+            }
+            continue;
+        }
         const float4 *row = reinterpret_cast<const float4 *>(W + (size_t)o * k);
         constexpr bool CACHED = SLOTS > 0;
         float4 cache[CACHED ? SLOTS : 1];
@@ -92,29 +117,33 @@ __global__ __launch_bounds__(THREADS) void pack_kernel(const float *__restrict__
         const float s = (a == 0.0f) ? 1.0f : a / 7.0f;
         if (tid == 0) scale[o] = s;
 
-        uint8_t *qrow = qvals + (size_t)o * ngroups;
-        uint8_t *mrow = meta + (size_t)o * (ngroups / 2);
-        // Lanes g and g^1 hold the two groups of one metadata byte; ngroups and
-        // the stride are even, so both are active together.
+        // Sixteen consecutive lanes hold the 16 groups of one piece of the packed
+        // layout: their code bytes (and position nibbles) are gathered into the
+        // first of them with row shifts, which then stores 16 (8) bytes.  Groups
+        // past the end of the row (padding of the last tile) are zero bytes.  All
+        // lanes take part in the shifts; gpad is a multiple of 32.
+        auto emit = [&](int g, float4 v) {
+            uint32_t q = 0, m4 = 0;
+            if (g < ngroups) q = encode_group(v, s, &m4);
+            uint32_t d = q | (row_shl<1>(q) << 8);
+            d |= row_shl<2>(d) << 16;
+            const uint4_t piece = {d, row_shl<4>(d), row_shl<8>(d), row_shl<12>(d)};
+            uint32_t mb = m4 | (row_shl<1>(m4) << 4);
+            mb |= row_shl<2>(mb) << 8;
+            mb |= row_shl<4>(mb) << 16;
+            const uint2_t mpiece = {mb, row_shl<8>(mb)};
+            if ((g & 15) == 0 && g < gpad) {
+                *reinterpret_cast<uint4_t *>(qvals + pk_qoff(o, g, kt)) = piece;
+                *reinterpret_cast<uint2_t *>(meta + pk_moff(o, g >> 1, kt)) = mpiece;
+            }
+        };
         if (CACHED) {
 #pragma unroll
-            for (int i = 0; i < SLOTS; ++i) {
-                int g = tid + i * THREADS;
-                if (g < ngroups) {
-                    uint32_t m4;
-                    uint32_t q = encode_group(cache[i], s, &m4);
-                    qrow[g] = (uint8_t)q;
-                    uint32_t other = __shfl_xor(m4, 1, kWave);
-                    if ((g & 1) == 0) mrow[g >> 1] = (uint8_t)(m4 | (other << 4));
-                }
-            }
+            for (int i = 0; i < SLOTS; ++i) emit(tid + i * THREADS, cache[i]);
         } else {
-            for (int g = tid; g < ngroups; g += THREADS) {
-                uint32_t m4;
-                uint32_t q = encode_group(row[g], s, &m4);
-                qrow[g] = (uint8_t)q;
-                uint32_t other = __shfl_xor(m4, 1, kWave);
-                if ((g & 1) == 0) mrow[g >> 1] = (uint8_t)(m4 | (other << 4));
+            for (int g0 = 0; g0 < gpad; g0 += THREADS) {
+                const int g = g0 + tid;
+                emit(g, g < ngroups ? row[g] : make_float4(0.f, 0.f, 0.f, 0.f));
             }
         }
     }
@@ -122,13 +151,16 @@ __global__ __launch_bounds__(THREADS) void pack_kernel(const float *__restrict__
 
 // One lane decodes one group: 4 codes and 4 mask bytes, one dword store each.
 __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__ qvals,
-                                                     const uint8_t *__restrict__ meta, size_t total_groups,
+                                                     const uint8_t *__restrict__ meta, int n, int k,
                                                      int8_t *__restrict__ codes, uint8_t *__restrict__ mask)
 {
+    const uint32_t ngroups = (uint32_t)k / 4, kt = pk_ktiles(k);
+    const size_t total_groups = (size_t)n * ngroups;
     for (size_t g = blockIdx.x * (size_t)blockDim.x + threadIdx.x; g < total_groups;
          g += (size_t)gridDim.x * blockDim.x) {
-        uint32_t q = qvals[g];
-        uint32_t m4 = (meta[g >> 1] >> (4 * (g & 1))) & 0xFu;
+        const uint32_t o = (uint32_t)(g / ngroups), gi = (uint32_t)(g - (size_t)o * ngroups);
+        uint32_t q = qvals[pk_qoff(o, gi, kt)];
+        uint32_t m4 = (meta[pk_moff(o, gi >> 1, kt)] >> (4 * (gi & 1))) & 0xFu;
         uint32_t i0 = m4 & 3u, i1 = m4 >> 2;
         uint32_t c0 = (uint32_t)nibble_to_int(q & 0xFu) & 0xFFu;
         uint32_t c1 = (uint32_t)nibble_to_int(q >> 4) & 0xFFu;
@@ -166,6 +198,13 @@ __global__ __launch_bounds__(256) void tile_copy_kernel(const uint16_t *__restri
     }
 }
 
+// Workgroups for slim_pack: one per row up to `cap`, a multiple of 8.
+static int pack_grid(int npad, int cap)
+{
+    int g = npad < cap ? npad : cap;
+    return (g + 7) / 8 * 8;
+}
+
 static int grid_for(size_t items, int threads, int cap = 256 * 16)
 {
     size_t b = (items + threads - 1) / threads;
@@ -185,11 +224,12 @@ extern "C" int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8
     if (shape.n < 1 || shape.k < 8 || shape.k % 8) return SLIM_ERR_SHAPE;
     if (!aligned16(W) || !aligned16(qvals) || !aligned16(meta) || !aligned16(scale)) return SLIM_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const int npad = (shape.n + 31) / 32 * 32;      // the padding rows of the last tile get a workgroup too
     // lanes per row: enough that a lane keeps at most 4 groups, up to 1024
     const int groups = shape.k / 4;
     // (two rounds of resident workgroups at most; a workgroup walks the rows it owns)
 #define SLIM_PACK_LAUNCH(T, S)                                                                                \
-    hipLaunchKernelGGL((pack_kernel<T, S>), dim3(shape.n < 256 * (4096 / T) ? shape.n : 256 * (4096 / T)), dim3(T), 0, \
+    hipLaunchKernelGGL((pack_kernel<T, S>), dim3(pack_grid(npad, 256 * (4096 / T))), dim3(T), 0, \
                        st, W, shape.n, shape.k, qvals, meta, scale)
     if (groups <= 256 * 2)
         SLIM_PACK_LAUNCH(256, 2);
@@ -217,7 +257,7 @@ extern "C" int slim_unpack(const uint8_t *qvals, const uint8_t *meta, slim_shape
     if (!aligned16(qvals) || !aligned16(meta) || !aligned16(codes) || !aligned16(mask)) return SLIM_ERR_ALIGN;
     size_t groups = (size_t)shape.n * (shape.k / 4);
     hipLaunchKernelGGL(unpack_kernel, dim3(grid_for(groups, 256)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), qvals, meta, groups, codes, mask);
+                       static_cast<hipStream_t>(stream), qvals, meta, shape.n, shape.k, codes, mask);
     return hip_status(hipGetLastError());
 }
 

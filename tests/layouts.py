@@ -18,3 +18,19 @@ def tile_fp16(mat: np.ndarray, rows_to: int = 32, cols_to: int = 16) -> np.ndarr
     # [row tile][row in tile][col tile][half][8] -> [row tile][col tile][half][row in tile][8]
     t = full.reshape(rp // 32, 32, cp // 16, 2, 8).transpose(0, 2, 3, 1, 4)
     return np.ascontiguousarray(t).reshape(-1)
+
+
+def tile_packed(q: np.ndarray, meta: np.ndarray):
+    """Packed layout of the canonical qvals [n][k/4] and meta [n][k/8]: tiles of 32 rows x 128
+    inputs (32 code bytes / 16 position bytes per row), row tile major; inside a tile the pieces
+    of 64 inputs are ordered (input half, row).  Rows padded to 32, inputs to 128, with zeros."""
+    n, g = q.shape
+    npad = -(-n // 32) * 32
+    kt = -(-g // 32)
+    qf = np.zeros((npad, kt * 32), np.uint8)
+    qf[:n, :g] = q
+    mf = np.zeros((npad, kt * 16), np.uint8)
+    mf[:n, : meta.shape[1]] = meta
+    qt = qf.reshape(npad // 32, 32, kt, 2, 16).transpose(0, 2, 3, 1, 4)
+    mt = mf.reshape(npad // 32, 32, kt, 2, 8).transpose(0, 2, 3, 1, 4)
+    return np.ascontiguousarray(qt).reshape(-1), np.ascontiguousarray(mt).reshape(-1)

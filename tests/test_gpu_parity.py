@@ -12,7 +12,7 @@ import torch
 from oracle import slim_oracle as O
 from paper_2410_09615_amd import binding as B
 from paper_2410_09615_amd import workloads as wl
-from layouts import tile_fp16
+from layouts import tile_fp16, tile_packed
 
 pytestmark = pytest.mark.gpu
 
@@ -37,8 +37,9 @@ def _assert_pack_equal(layer, W):
     ref = O.compress(W.numpy())
     torch.cuda.synchronize()
     assert np.array_equal(layer.scale.cpu().numpy().view(np.uint32), ref.scale.view(np.uint32))
-    assert np.array_equal(layer.qvals.cpu().numpy(), ref.qvals)
-    assert np.array_equal(layer.meta.cpu().numpy(), ref.meta)
+    qt, mt = tile_packed(ref.qvals, ref.meta)       # the oracle's canonical bytes in the device order
+    assert np.array_equal(layer.qvals.cpu().numpy(), qt)
+    assert np.array_equal(layer.meta.cpu().numpy(), mt)
     return ref
 
 
@@ -52,7 +53,7 @@ def test_pack_bit_exact_small(n, k):
         W[2, : k // 2] = 0.0                         # zero groups
     layer = _gpu_layer(W, None, None)
     ref = _assert_pack_equal(layer, W)
-    codes, mask = B.slim_unpack(layer.qvals, layer.meta)
+    codes, mask = B.slim_unpack(layer.qvals, layer.meta, n, k)
     rc, rm = O.unpack(ref.qvals, ref.meta)
     assert np.array_equal(codes.cpu().numpy(), rc) and np.array_equal(mask.cpu().numpy(), rm)
 
@@ -96,7 +97,8 @@ def test_unpack_arbitrary_valid_bytes():
     n, k = 64, 1024
     q = rng.integers(0, 256, size=(n, k // 4), dtype=np.uint8)
     me = (valid[rng.integers(0, 6, size=(n, k // 8))] | (valid[rng.integers(0, 6, size=(n, k // 8))] << 4)).astype(np.uint8)
-    codes, mask = B.slim_unpack(torch.from_numpy(q).to(DEV), torch.from_numpy(me).to(DEV))
+    qt, mt = tile_packed(q, me)
+    codes, mask = B.slim_unpack(torch.from_numpy(qt).to(DEV), torch.from_numpy(mt).to(DEV), n, k)
     rc, rm = O.unpack(q, me)
     assert np.array_equal(codes.cpu().numpy(), rc) and np.array_equal(mask.cpu().numpy(), rm)
 
