@@ -49,17 +49,14 @@ __device__ __forceinline__ uint32_t encode_group(float4 v, float s, uint32_t *m4
     return quantize_code(w0, s) | (quantize_code(w1, s) << 4);
 }
 
-// Value of lane + N inside the lane's row of 16 (0 past the end of the row).
-template <int N>
-__device__ __forceinline__ uint32_t row_shl(uint32_t v)
-{
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x100 + N, 0xf, 0xf, true);
-}
-
 // THREADS lanes per row; SLOTS = float4 groups of the row each lane keeps in
 // registers (the row has at most 4 THREADS SLOTS inputs); 0 = rows of any
 // length, read twice.  Few slots per lane keep the register count low enough
 // for eight wavefronts per SIMD, which is what hides the load latency here.
+// The kernel is as much bound by its vector ALU work (top-2 selection, two IEEE
+// divisions per group) as by memory, so the stores stay plain byte stores: lane
+// t writes group t + i THREADS of slot i, whose place in the packed layout is a
+// per-lane base plus a constant per slot.
 template <int THREADS, int SLOTS>
 __global__ __launch_bounds__(THREADS) void pack_kernel(const float *__restrict__ W, int n, int k,
                                                             uint8_t *__restrict__ qvals,
@@ -70,7 +67,7 @@ __global__ __launch_bounds__(THREADS) void pack_kernel(const float *__restrict__
     const int ngroups = k / 4;
     const int tid = threadIdx.x;
     const uint32_t kt = pk_ktiles(k);
-    const int gpad = (int)kt * 32;             // groups per row of the tiled layout
+    const int gpad = (int)kt * 32;             // groups per row of the packed layout
     const int npad = (n + 31) / 32 * 32;
     // Workgroups go to the 8 dies round-robin and each die has its own L2.  The 32
     // rows of a row tile write into the same cache lines, so they are kept on one
@@ -80,11 +77,15 @@ __global__ __launch_bounds__(THREADS) void pack_kernel(const float *__restrict__
     const int rows_per_die = ((npad / 32 + 7) / 8) * 32;
     const int o_end = min(npad, (die + 1) * rows_per_die);
     for (int o = die * rows_per_die + local; o < o_end; o += per_die) {
+        // this lane's byte of slot 0 in the packed layout (group tid, position byte tid / 2)
+        uint8_t *const ql = qvals + pk_qoff(o, tid, kt);
+        uint8_t *const ml = meta + pk_moff(o, tid >> 1, kt);
+        constexpr size_t q_slot = (size_t)(THREADS / 32) * 1024, m_slot = (size_t)(THREADS / 32) * 512;
         if (o >= n) {
             // padding row of the last row tile: zero bytes
-            for (int g = 16 * tid; g < gpad; g += 16 * THREADS) {
-                *reinterpret_cast<uint4_t *>(qvals + pk_qoff(o, g, kt)) = uint4_t{0u, 0u, 0u, 0u};
-                *reinterpret_cast<uint2_t *>(meta + pk_moff(o, g >> 1, kt)) = uint2_t{0u, 0u};
+            for (int g = tid, i = 0; g < gpad; g += THREADS, ++i) {
+                ql[i * q_slot] = 0;
+                if ((g & 1) == 0) ml[i * m_slot] = 0;
             }
             continue;
         }
@@ -117,33 +118,25 @@ __global__ __launch_bounds__(THREADS) void pack_kernel(const float *__restrict__
         const float s = (a == 0.0f) ? 1.0f : a / 7.0f;
         if (tid == 0) scale[o] = s;
 
-        // Sixteen consecutive lanes hold the 16 groups of one piece of the packed
-        // layout: their code bytes (and position nibbles) are gathered into the
-        // first of them with row shifts, which then stores 16 (8) bytes.  Groups
-        // past the end of the row (padding of the last tile) are zero bytes.  All
-        // lanes take part in the shifts; gpad is a multiple of 32.
-        auto emit = [&](int g, float4 v) {
+        // Lanes g and g^1 hold the two groups of one position byte (the stride is
+        // even, so both are active together).  Groups past the end of the row
+        // (padding of the last tile) are zero bytes.
+        auto emit = [&](int i, int g, float4 v) {
             uint32_t q = 0, m4 = 0;
             if (g < ngroups) q = encode_group(v, s, &m4);
-            uint32_t d = q | (row_shl<1>(q) << 8);
-            d |= row_shl<2>(d) << 16;
-            const uint4_t piece = {d, row_shl<4>(d), row_shl<8>(d), row_shl<12>(d)};
-            uint32_t mb = m4 | (row_shl<1>(m4) << 4);
-            mb |= row_shl<2>(mb) << 8;
-            mb |= row_shl<4>(mb) << 16;
-            const uint2_t mpiece = {mb, row_shl<8>(mb)};
-            if ((g & 15) == 0 && g < gpad) {
-                *reinterpret_cast<uint4_t *>(qvals + pk_qoff(o, g, kt)) = piece;
-                *reinterpret_cast<uint2_t *>(meta + pk_moff(o, g >> 1, kt)) = mpiece;
+            const uint32_t other = __shfl_xor(m4, 1, kWave);
+            if (g < gpad) {
+                ql[i * q_slot] = (uint8_t)q;
+                if ((g & 1) == 0) ml[i * m_slot] = (uint8_t)(m4 | (other << 4));
             }
         };
         if (CACHED) {
 #pragma unroll
-            for (int i = 0; i < SLOTS; ++i) emit(tid + i * THREADS, cache[i]);
+            for (int i = 0; i < SLOTS; ++i) emit(i, tid + i * THREADS, cache[i]);
         } else {
-            for (int g0 = 0; g0 < gpad; g0 += THREADS) {
+            for (int g0 = 0, i = 0; g0 < gpad; g0 += THREADS, ++i) {
                 const int g = g0 + tid;
-                emit(g, g < ngroups ? row[g] : make_float4(0.f, 0.f, 0.f, 0.f));
+                emit(i, g, g < ngroups ? row[g] : make_float4(0.f, 0.f, 0.f, 0.f));
             }
         }
     }
@@ -229,8 +222,8 @@ extern "C" int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8
     const int groups = shape.k / 4;
     // (two rounds of resident workgroups at most; a workgroup walks the rows it owns)
 #define SLIM_PACK_LAUNCH(T, S)                                                                                \
-    hipLaunchKernelGGL((pack_kernel<T, S>), dim3(pack_grid(npad, 256 * (4096 / T))), dim3(T), 0, \
-                       st, W, shape.n, shape.k, qvals, meta, scale)
+    hipLaunchKernelGGL((pack_kernel<T, S>), dim3(pack_grid(npad, 256 * (4096 / T))), dim3(T), 0, st, W, shape.n, \
+                       shape.k, qvals, meta, scale)
     if (groups <= 256 * 2)
         SLIM_PACK_LAUNCH(256, 2);
     else if (groups <= 256 * 4)
