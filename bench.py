@@ -44,7 +44,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--legs", default="all", choices=["all", "decode", "none"])
+    ap.add_argument("--legs", default="all", choices=["all", "decode", "prefill", "none"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--tokens", default="1,4,16", help="token counts of one step (counter runs use one value)")
     return ap.parse_args()
@@ -265,13 +265,13 @@ def main():
         decode_cfgs = [(wl.L13B_ATTN, (1,)), (wl.L13B_UP, (1,)), (wl.L70B_ATTN, (1, 16)), (wl.L70B_UP, (1, 16))]
         prefill_cfgs = [(wl.L7B_UP, 2048), (wl.L7B_DOWN, 2048), (wl.L13B_ATTN, 4096), (wl.L13B_UP, 4096),
                         (wl.L70B_ATTN, 4096), (wl.L70B_UP, 4096)]
-        for shp, ms_ in decode_cfgs:
+        for shp, ms_ in (decode_cfgs if args.legs != "prefill" else []):
             r = Rotating(shp, ms_)
             for m in ms_:
                 legs.append(leg_record(r, m, B.slim_linear_gemv, 100, 10, "slim_linear_gemv"))
             del r
             torch.cuda.empty_cache()
-        if args.legs == "all":
+        if args.legs in ("all", "prefill"):
             for shp, m in prefill_cfgs:
                 r = Rotating(shp, (m,), min_copies=2, max_bytes=1 << 30)
                 legs.append(leg_record(r, m, B.slim_linear_gemm, 10, 3, "slim_linear_gemm"))

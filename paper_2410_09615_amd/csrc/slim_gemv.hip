@@ -130,6 +130,8 @@ __device__ __forceinline__ void issue_unit(const DecodeArgs &a, const Part1Geom 
                                            UnitRegs &b)
 {
     const uint4_t zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b.r[i] = zero;      // every register defined on every path
     if (d.q < 0) return;
     if (d.is_r) {
         // R in its tiled layout: step t reads the pieces (row, 4 t + ly) of the unit,
@@ -196,7 +198,7 @@ __device__ __forceinline__ void packed_half(const UnitRegs &b, const half_t *xk,
 }
 
 // ---- part 1: packed rows -> P, R rows -> T (atomics) ----
-__global__ __launch_bounds__(kDecThreads, 2) void decode_part1_kernel(DecodeArgs a)
+__global__ __launch_bounds__(kDecThreads, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_part1_kernel(DecodeArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) half_t lds[];
     const int lane = threadIdx.x & (kWave - 1);
@@ -304,7 +306,8 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_part1_kernel(DecodeArgs
                 }
             }
         }
-        bufA = bufB;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) bufA.r[i] = bufB.r[i];
         cur = nxt;
     }
 
@@ -315,34 +318,52 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_part1_kernel(DecodeArgs
 }
 
 // ---- part 2: Y = scale * sum P + T L^T ----
-// NB = 128-bit L loads a lane issues at once (one per 32 ranks); rank_pad / 32
-// is a multiple of NB.
+// Sixteen wavefronts per workgroup: four tiles of 16 output rows at a time, and
+// the ranks of each tile dealt out to four wavefronts (wavefront sp takes the
+// steps of 32 ranks sp, sp + 4, ...), so a layer with few row tiles still puts
+// enough loads in flight to stream L at memory speed.  The three partial sums
+// meet the first wavefront of the tile in LDS.  NB = 128-bit L loads a lane issues at
+// once (one per step); the next batch, or the first of the next tile, is in
+// flight during the matrix work.
+constexpr int kP2Waves = 16;
+constexpr int kP2Threads = kP2Waves * kWave;
+constexpr int kP2Split = 4;                          // wavefronts per tile
+constexpr int kP2Tiles = kP2Waves / kP2Split;        // tiles per workgroup and round
+constexpr int kP2RedBytes = 2 * kP2Tiles * (kP2Split - 1) * kWave * 16;   // two alternating sets of partial sums
+
 template <int NB>
-__global__ __launch_bounds__(kDecThreads, 2) void decode_part2_kernel(DecodeArgs a)
+__global__ __launch_bounds__(kP2Threads, 1) void decode_part2_kernel(DecodeArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) half_t lds[];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
+    const int ts = wave / kP2Split;      // tile slot of this wavefront
+    const int sp = wave % kP2Split;      // its share of the ranks
     const int lx = lane & 15;
     const int ly = lane >> 4;
     const int rp = a.rank_pad;
     const int wtiles = (a.n + 15) / 16;
-    const int nbatch = rp / (32 * NB);
-    const int tile0 = blockIdx.x * kDecWaves + wave;
-    const int tstride = gridDim.x * kDecWaves;
+    const int steps = rp / 32;
+    const int cnt = (steps - sp + kP2Split - 1) / kP2Split;          // steps of this wavefront (sp < steps or 0)
+    const int nbatch = cnt > 0 ? (cnt + NB - 1) / NB : 0;
+    const int tile0 = blockIdx.x * kP2Tiles + ts;
+    const int tstride = gridDim.x * kP2Tiles;
+    const int rounds = (wtiles - blockIdx.x * kP2Tiles + tstride - 1) / tstride;   // same for the whole workgroup
 
     // L of the first tile goes out first: it does not depend on T
     uint4_t lvA[NB], lvB[NB];
     auto issue_l = [&](int ot, int batch, uint4_t (&lv)[NB]) {
         const int o = 16 * ot + lx;
         const bool rowok = batch < nbatch && ot < wtiles && o < a.n;
-        // step t takes ranks 32 t + 8 ly .. + 7 of row o: piece (o, 4 (batch NB + t) + ly) of the
-        // tiled layout, four runs of 256 contiguous bytes per load instruction
-        const char *lp = reinterpret_cast<const char *>(a.L) +
-                         tl_piece((uint32_t)(rowok ? o : 0), 4u * (uint32_t)((rowok ? batch : 0) * NB) + ly, (uint32_t)rp);
+        // step t = sp + 4 (batch NB + x) takes ranks 32 t + 8 ly .. + 7 of row o: piece (o, 4 t + ly)
+        // of the tiled layout; consecutive steps of this wavefront lie 8 KiB apart
+        const int tb = sp + kP2Split * (rowok ? batch : 0) * NB;
+        const char *lp = reinterpret_cast<const char *>(a.L) + tl_piece((uint32_t)(rowok ? o : 0), 4u * tb + ly, (uint32_t)rp);
 #pragma unroll
-        for (int t = 0; t < NB; ++t)
-            lv[t] = rowok ? *reinterpret_cast<const uint4_t *>(lp + 2048 * t) : uint4_t{0u, 0u, 0u, 0u};
+        for (int x = 0; x < NB; ++x) {
+            const bool ok = rowok && tb + kP2Split * x < steps;
+            lv[x] = ok ? *reinterpret_cast<const uint4_t *>(lp + 2048 * kP2Split * x) : uint4_t{0u, 0u, 0u, 0u};
+        }
     };
     if (nbatch > 0) issue_l(tile0, 0, lvA);
 
@@ -352,20 +373,20 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_part2_kernel(DecodeArgs
     const float *T1 = a.T + (size_t)kMaxTokens * rp;
     if (blockIdx.x == 0 && threadIdx.x == 0) a.ctrl[0] = a.ctrl[1];       // next call: next epoch
 
-
     // T -> LDS as fp16 hi + lo, mp token rows then one zero row
     const int ldt = rp + kLdsPad;
     half_t *t_hi = lds;
     half_t *t_lo = lds + (a.mp + 1) * ldt;
+    float *red = reinterpret_cast<float *>(lds + 2 * (a.mp + 1) * ldt);
     if (rp > 0) {
-        // 4 ranks per piece, 8 pieces per lane in flight before the LDS stores
+        // 4 ranks per piece, up to 4 pieces per lane in flight before the LDS stores
         const int per_row = rp / 4;
         const int total = (a.mp + 1) * per_row;
-        for (int e0 = threadIdx.x; e0 < total; e0 += 8 * kDecThreads) {
-            float4_t v[8];
+        for (int e0 = threadIdx.x; e0 < total; e0 += 4 * kP2Threads) {
+            float4_t v[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int e = e0 + i * kDecThreads;
+            for (int i = 0; i < 4; ++i) {
+                const int e = e0 + i * kP2Threads;
                 const int row = e / per_row, c = e - row * per_row;
                 v[i] = float4_t{0.f, 0.f, 0.f, 0.f};
                 if (e < total && row < a.m)
@@ -373,8 +394,8 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_part2_kernel(DecodeArgs
                            *reinterpret_cast<const float4_t *>(T1 + (size_t)row * rp + 4 * c);
             }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int e = e0 + i * kDecThreads;
+            for (int i = 0; i < 4; ++i) {
+                const int e = e0 + i * kP2Threads;
                 const int row = e / per_row, c = e - row * per_row;
                 if (e < total) {
                     half4_t hi, lo;
@@ -388,20 +409,22 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_part2_kernel(DecodeArgs
                 }
             }
         }
-        __syncthreads();
     }
+    __syncthreads();
     const int trow = lx < a.mp ? lx : a.mp;
     const half_t *th = t_hi + trow * ldt + 8 * ly;
     const half_t *tl = t_lo + trow * ldt + 8 * ly;
 
-    for (int ot = tile0; ot < wtiles; ot += tstride) {
+    for (int round = 0; round < rounds; ++round) {
+        const int ot = tile0 + round * tstride;          // may lie past the last tile: then nothing is loaded or stored
         float4_t acc = {0.f, 0.f, 0.f, 0.f}, accb = acc;
         const int ob = 16 * ot + 4 * ly;
         const bool vec = (ob + 3 < a.n) && (a.n & 3) == 0;
-        // packed term of this lane's 4 outputs: its loads go out before the matrix work
+        // packed term of this lane's 4 outputs (first wavefront of the tile): its
+        // loads go out before the matrix work
         float q[4] = {0.f, 0.f, 0.f, 0.f};
         float sc[4] = {0.f, 0.f, 0.f, 0.f};
-        if (a.P && lx < a.m) {
+        if (sp == 0 && a.P && lx < a.m && ot < wtiles) {
             for (int slot = 0; slot < a.slots; ++slot) {
                 const float *pp = a.P + ((size_t)slot * a.m + lx) * a.n + ob;
                 if (vec) {
@@ -425,22 +448,32 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_part2_kernel(DecodeArgs
             else
                 issue_l(ot + tstride, 0, lvB);
 #pragma unroll
-            for (int t = 0; t < NB; ++t) {
-                const half8_t bh = *reinterpret_cast<const half8_t *>(th + 32 * (batch * NB + t));
-                const half8_t bl = *reinterpret_cast<const half8_t *>(tl + 32 * (batch * NB + t));
-                const half8_t av = __builtin_bit_cast(half8_t, lvA[t]);
+            for (int x = 0; x < NB; ++x) {
+                // steps past the end carry zero L values and read T inside the padded row
+                const int t = min(sp + kP2Split * (batch * NB + x), steps - 1);
+                const half8_t bh = *reinterpret_cast<const half8_t *>(th + 32 * t);
+                const half8_t bl = *reinterpret_cast<const half8_t *>(tl + 32 * t);
+                const half8_t av = __builtin_bit_cast(half8_t, lvA[x]);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bh, acc, 0, 0, 0);
                 accb = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bl, accb, 0, 0, 0);
             }
 #pragma unroll
-            for (int t = 0; t < NB; ++t) lvA[t] = lvB[t];
+            for (int x = 0; x < NB; ++x) lvA[x] = lvB[x];
         }
-        if (lx < a.m) {
+        acc += accb;
+        // partial sums of the other three wavefronts of the tile (alternating sets,
+        // so one barrier per round is enough)
+        float *rset = red + (size_t)((round & 1) * kP2Tiles + ts) * (kP2Split - 1) * kWave * 4;
+        if (sp != 0) *reinterpret_cast<float4_t *>(rset + ((sp - 1) * kWave + lane) * 4) = acc;
+        __syncthreads();
+        if (sp == 0 && lx < a.m && ot < wtiles) {
+#pragma unroll
+            for (int w = 0; w < kP2Split - 1; ++w) acc += *reinterpret_cast<const float4_t *>(rset + (w * kWave + lane) * 4);
             half_t *yp = a.Y + (size_t)lx * a.n + ob;
             float y[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                y[v] = acc[v] + accb[v] + sc[v] * q[v];
+                y[v] = acc[v] + sc[v] * q[v];
                 if (a.accumulate && ob + v < a.n) y[v] += (float)yp[v];
             }
             if (vec) {
@@ -468,6 +501,21 @@ DecodePlan plan_decode(int n, int k, int rank_pad, int m)
     const int kpad = (k + kUnitK - 1) / kUnitK * kUnitK;
     p.kc = kpad < kc_max ? kpad : kc_max;
     p.nch = (k + p.kc - 1) / p.kc;
+    // Every chunk gets the same number of workgroups, so chunks should be equal:
+    // of the chunk counts nch .. nch + 2 take the one that wastes the fewest units.
+    {
+        const int units = kpad / kUnitK;
+        int best = p.nch, best_waste = 1 << 30;
+        for (int c = p.nch; c <= p.nch + 2 && c <= units; ++c) {
+            const int waste = c * ((units + c - 1) / c) - units;
+            if (waste < best_waste) {
+                best_waste = waste;
+                best = c;
+            }
+        }
+        p.kc = ((units + best - 1) / best) * kUnitK;
+        p.nch = (k + p.kc - 1) / p.kc;
+    }
     // inputs per packed-row task: one unit for small layers (more tasks in
     // flight), more for large ones (fewer partial slots to write and re-read)
     const long tiles = (n + 15) / 16;
@@ -488,7 +536,7 @@ DecodePlan plan_decode(int n, int k, int rank_pad, int m)
 static int launch_decode(const DecodeArgs &a, const DecodePlan &p, hipStream_t st)
 {
     const size_t lds1 = (size_t)(p.mp + 1) * (p.kc + kLdsPad) * sizeof(half_t);
-    const size_t lds2 = (size_t)2 * (p.mp + 1) * (a.rank_pad + kLdsPad) * sizeof(half_t);
+    const size_t lds2 = (size_t)2 * (p.mp + 1) * (a.rank_pad + kLdsPad) * sizeof(half_t) + kP2RedBytes;
     if (lds1 > 160 * 1024 || lds2 > 160 * 1024) return SLIM_ERR_SHAPE;
     const long units_r = (long)(a.rank_pad / 16) * ((p.kc + p.rsl - 1) / p.rsl);
     const long tasks_w = (long)((a.n_packed + 15) / 16) * p.wsl_full;
@@ -504,20 +552,17 @@ static int launch_decode(const DecodeArgs &a, const DecodePlan &p, hipStream_t s
     if (b1 < 1) b1 = 1;
     if (units_r + tasks_w > 0)
         hipLaunchKernelGGL(decode_part1_kernel, dim3((unsigned)(b1 * p.nch)), dim3(kDecThreads), lds1, st, a);
-    long b2 = ((a.n + 15) / 16 + kDecWaves - 1) / kDecWaves;
-    if (b2 > 1024) b2 = 1024;
-    const int steps = a.rank_pad / 32;
-    const dim3 g2((unsigned)b2), blk(kDecThreads);
-    if (steps % 13 == 0)
-        hipLaunchKernelGGL(decode_part2_kernel<13>, g2, blk, lds2, st, a);
-    else if (steps % 8 == 0)
-        hipLaunchKernelGGL(decode_part2_kernel<8>, g2, blk, lds2, st, a);
-    else if (steps % 4 == 0)
+    long b2 = ((a.n + 15) / 16 + kP2Tiles - 1) / kP2Tiles;
+    if (b2 > 512) b2 = 512;
+    // L loads per lane and batch: the steps of 32 ranks are dealt out to 4 wavefronts
+    const int l_loads = (a.rank_pad / 32 + kP2Split - 1) / kP2Split;
+    const dim3 g2((unsigned)b2), blk(kP2Threads);
+    if (l_loads > 4)
+        hipLaunchKernelGGL(decode_part2_kernel<7>, g2, blk, lds2, st, a);
+    else if (l_loads > 2)
         hipLaunchKernelGGL(decode_part2_kernel<4>, g2, blk, lds2, st, a);
-    else if (steps % 2 == 0)
-        hipLaunchKernelGGL(decode_part2_kernel<2>, g2, blk, lds2, st, a);
     else
-        hipLaunchKernelGGL(decode_part2_kernel<1>, g2, blk, lds2, st, a);
+        hipLaunchKernelGGL(decode_part2_kernel<2>, g2, blk, lds2, st, a);
     return hip_status(hipGetLastError());
 }
 
