@@ -36,7 +36,7 @@ CACHE_BYTES = 256 << 20         # Infinity Cache
 # the headline layer) from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE),
 # scaled by the 256 MiB copy below (one FETCH_SIZE unit = 2 KiB, one WRITE_SIZE
 # unit = 1 KiB).  Source: profiles/decode_gemv_llama7b_attn_16tok_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = 26.14e6   # 20.28 MB read + 5.86 MB written per slim_linear_gemv call at 16 tokens
+MEASURED_TRAFFIC_BYTES = 18.32e6   # 15.41 MB read + 2.91 MB written per slim_linear_gemv call at 16 tokens
 
 
 def parse_args():
