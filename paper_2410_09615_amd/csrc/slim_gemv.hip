@@ -34,14 +34,15 @@
 // alternately (a call accumulates into one and zeroes the other, which the
 // previous call left dirty) and an epoch word that selects the buffer.  All of
 // it starts as zeros.
-#include "slim_internal.h"
+#include <cstdlib>
+#include <cstring>
+
+#include "slim_decode.h"
 
 namespace slim {
 
-constexpr int kMaxTokens = 16;
 constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / kWave;
-constexpr int kLdsPad = 8;                 // halves of padding per LDS row (16 B)
 constexpr int kLdsBudget = 72 * 1024;      // bytes of LDS per block: two blocks per CU
 constexpr int kUnitK = 1024;               // inputs per packed-row unit
 constexpr int kUnitR = 256;                // inputs per R unit
@@ -79,10 +80,6 @@ struct Unit {
     int slot_s;    // packed rows: slice index of the task in the chunk
     bool is_r;
     bool last;     // last unit of its task
-};
-
-struct UnitRegs {
-    uint4_t r[8];  // the 8 x 128-bit loads of one unit
 };
 
 // Geometry of part 1 for one block (one k-chunk).
@@ -174,29 +171,6 @@ __device__ __forceinline__ void issue_unit(const DecodeArgs &a, const Part1Geom 
     }
 }
 
-// One half (512 inputs) of a packed unit: 8 sparse matrix instructions.
-// B operand of instruction t: values 0-7 pair with the A lanes of k-block
-// (ly >> 1), values 8-15 with k-block 2 + (ly >> 1); inside the lane's 128
-// inputs they are the 8 inputs at 16 t + 8 (ly & 1).
-template <int H>
-__device__ __forceinline__ void packed_half(const UnitRegs &b, const half_t *xk, float4_t &acc0, float4_t &acc1)
-{
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        const uint32_t qd = t < 4 ? b.r[3 * H][t] : b.r[3 * H + 1][t - 4];
-        const half8_t av = codes_to_half8(qd);
-        const half8_t b1 = *reinterpret_cast<const half8_t *>(xk + 512 * H + 16 * t);
-        const half8_t b2 = *reinterpret_cast<const half8_t *>(xk + 512 * H + 256 + 16 * t);
-        const half16_t bv = __builtin_shufflevector(b1, b2, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-        const int idx = (int)b.r[3 * H + 2][t >> 1];
-        // even t: index bits 15..0, odd t: bits 31..16 of the position dword
-        if (t & 1)
-            acc1 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(av, bv, acc1, idx, 0, 1);
-        else
-            acc0 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(av, bv, acc0, idx, 0, 0);
-    }
-}
-
 // ---- part 1: packed rows -> P, R rows -> T (atomics) ----
 __global__ __launch_bounds__(kDecThreads, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_part1_kernel(DecodeArgs a)
 {
@@ -279,7 +253,7 @@ __global__ __launch_bounds__(kDecThreads, 2) __attribute__((amdgpu_waves_per_eu(
             }
         } else {
             packed_half<0>(bufA, xrow_packed + cur.k0, acc0, acc1);
-            packed_half<1>(bufA, xrow_packed + cur.k0, acc0, acc1);
+            packed_half<1>(bufA, xrow_packed + cur.k0 + 512, acc0, acc1);
         }
         if (cur.last) {
             // lane holds token lx, rows 16 tile + 4 ly .. + 3
@@ -619,6 +593,23 @@ extern "C" int slim_linear_gemv(const slim_layer *layer, const slim_half *X, int
     if (!workspace || workspace_bytes < w.total) return SLIM_ERR_WORKSPACE;
 
     char *ws = static_cast<char *>(workspace);
+    // Path: one launch where X fits the LDS of a compute unit, else the two-part
+    // kernels.  SLIM_DECODE_PATH = parts | roles | fused overrides (measurement).
+    {
+        const FusedPlan f = plan_fused(s.n, s.k, layer->rank_pad, m);
+        int mode = f.ok ? 2 : -1;
+        if (const char *env = getenv("SLIM_DECODE_PATH")) {
+            if (!strcmp(env, "parts")) mode = -1;
+            if (!strcmp(env, "roles") && f.ok) mode = 1;
+            if (!strcmp(env, "fused") && f.ok) mode = 2;
+        }
+        if (mode > 0)
+            return launch_decode_fused(layer, reinterpret_cast<const half_t *>(X), m, reinterpret_cast<half_t *>(Y),
+                                       reinterpret_cast<half_t *>(ws + w.t16_off),
+                                       reinterpret_cast<unsigned *>(ws + w.flag_off),
+                                       reinterpret_cast<unsigned *>(ws + w.dec_off) + 2, f, mode,
+                                       static_cast<hipStream_t>(stream));
+    }
     DecodePlan p = plan_decode(s.n, s.k, layer->rank_pad, m);
     DecodeArgs a{};
     a.qvals = layer->qvals;

@@ -118,7 +118,9 @@ inline int hip_status(hipError_t e) { return e == hipSuccess ? SLIM_OK : SLIM_ER
 // Workspace carve-up used by the forward entry points (offsets in bytes,
 // each a multiple of 256).
 struct WorkspacePlan {
-    size_t dec_off, dec_bytes;    // decode state: 256 B of control words, then two T buffers fp32 [16][rank_pad]
+    size_t dec_off, dec_bytes;    // decode state: 256 B of control words, then two T buffers fp32 [16][rank_pad],
+                                  // then (one-launch path) 512 B of flags and T as fp16 [16][rank_pad]
+    size_t flag_off, t16_off;     // the last two, as offsets into the workspace
     size_t t_off, t_bytes;        // gemm: T = X R^T as fp16 [m][rank_pad]
     size_t acc_off, acc_bytes;    // decode: partial quantized term, fp32 [slots][m][n]
     size_t part_off, part_bytes;  // gemm: split-K partials of T, fp32 [splits][m][rank_pad]

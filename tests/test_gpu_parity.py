@@ -131,30 +131,65 @@ def _forward_case(shape, m, fn, seed=0, rows=None):
     return _relerr(Yg, Yref)
 
 
+# slim_linear_gemv has a one-launch path (layers whose X fits the LDS of a compute
+# unit) and a two-part path (everything else); SLIM_DECODE_PATH forces one of
+# them, "roles" runs the one-launch kernel's two roles as two launches.
+@pytest.fixture(params=["auto", "parts", "roles", "fused"])
+def decode_path(request, monkeypatch):
+    if request.param == "auto":
+        monkeypatch.delenv("SLIM_DECODE_PATH", raising=False)
+    else:
+        monkeypatch.setenv("SLIM_DECODE_PATH", request.param)
+    return request.param
+
+
 @pytest.mark.parametrize("m", [1, 4, 8, 16])
-def test_gemv_tiny_layer(m):
+def test_gemv_tiny_layer(m, decode_path):
     assert _forward_case(wl.TINY, m, B.slim_linear_gemv) <= TOL_Y
 
 
 @pytest.mark.parametrize("m", [1, 4, 16])
-def test_gemv_llama7b_attention(m):
+def test_gemv_llama7b_attention(m, decode_path):
     assert _forward_case(wl.L7B_ATTN, m, B.slim_linear_gemv) <= TOL_Y
 
 
-@pytest.mark.parametrize("n,k,r,m", [(1000, 1280, 37, 3), (17, 128, 1, 5), (2049, 640, 33, 16), (130, 11008, 410, 2)])
-def test_gemv_ragged_shapes(n, k, r, m):
+@pytest.mark.parametrize("n,k,r,m", [(1000, 1280, 37, 3), (17, 128, 1, 5), (2049, 640, 33, 16), (130, 11008, 410, 2),
+                                     (5000, 2176, 100, 8), (48, 4096, 1024, 16)])
+def test_gemv_ragged_shapes(n, k, r, m, decode_path):
     assert _forward_case(_shape(n, k, r), m, B.slim_linear_gemv, seed=7) <= TOL_Y
 
 
-def test_gemv_without_adapters():
+def test_gemv_without_adapters(decode_path):
     assert _forward_case(_shape(512, 1024, 0), 4, B.slim_linear_gemv, seed=3) <= TOL_Y
 
 
-@pytest.mark.parametrize("shape,m", [(wl.L13B_UP, 1), (wl.L70B_ATTN, 16), (wl.L70B_UP, 1)], ids=lambda v: str(getattr(v, "name", v)))
-def test_gemv_full_size_sampled_rows(shape, m):
+@pytest.mark.parametrize("shape,m", [(wl.L13B_UP, 1), (wl.L70B_ATTN, 16), (wl.L70B_UP, 1), (wl.L70B_UP, 4), (wl.L7B_DOWN, 4)],
+                         ids=lambda v: str(getattr(v, "name", v)))
+def test_gemv_full_size_sampled_rows(shape, m, decode_path):
+    if decode_path in ("roles", "parts") and shape is not wl.L13B_UP:
+        pytest.skip("forced paths are covered at full size by one shape")
     rows = np.random.default_rng(1).choice(shape.n, size=512, replace=False)
     rows.sort()
     assert _forward_case(shape, m, B.slim_linear_gemv, rows=rows) <= TOL_Y
+
+
+def test_gemv_repeated_calls_one_workspace(monkeypatch):
+    """One workspace, many calls: the paths alternate, the token count changes, and
+    every call must give the result of a call on a fresh workspace (no state of an
+    earlier call may leak: flags, epochs, the T buffers)."""
+    shape = _shape(1000, 2048, 70)
+    W, L, R, X = wl.make_layer(shape, 16, seed=11)
+    layer = _gpu_layer(W, L, R)
+    ref_layer = O.compress(W.numpy())
+    ws = torch.zeros(max(B.slim_workspace_bytes(layer, m) for m in range(1, 17)), dtype=torch.uint8, device=DEV)
+    Xd = X.to(DEV)
+    for i, (path, m) in enumerate([("fused", 16), ("parts", 3), ("fused", 3), ("fused", 1), ("roles", 16), ("parts", 16),
+                                   ("fused", 8), ("fused", 16), ("parts", 1), ("fused", 2)]):
+        monkeypatch.setenv("SLIM_DECODE_PATH", path)
+        Y = B.slim_linear_gemv(layer, Xd[:m].contiguous(), workspace=ws)
+        torch.cuda.synchronize()
+        Yref = O.forward(ref_layer, L.numpy(), R.numpy(), X[:m].numpy())
+        assert _relerr(Y.cpu().numpy(), Yref) <= TOL_Y, (i, path, m)
 
 
 # ---- forward: prefill -----------------------------------------------------------
