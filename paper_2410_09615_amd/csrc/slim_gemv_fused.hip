@@ -37,7 +37,14 @@
 namespace slim {
 
 constexpr int kFusedMaxThreads = 512;
+constexpr int kFusedWavesPerSimd = 3;   // the kernel is compiled for this many wavefronts per SIMD (168 registers)
+constexpr int kFlagCopies = 16;      // copies of the flags (2 KiB apart); a workgroup polls one of them
+constexpr int kMaxShares = 4;         // R role: at most this many shares of the inputs (planes of T)
+constexpr int kShareTiles = 384;       // ... for layers of at most this many row tiles
+constexpr int kFusedResidentWaves = 4 * kFusedWavesPerSimd;     // wavefronts a compute unit holds at this kernel's register count
 constexpr int kSpinLimit = 1 << 16;
+constexpr int kXBatch = 16;       // X pieces a lane loads before it stores them to LDS
+constexpr uint32_t kNowhere = 0x80000000u;       // byte offset past the end of every buffer here (all are < 2 GiB)
 
 struct FusedArgs {
     const uint8_t *qvals;
@@ -47,7 +54,7 @@ struct FusedArgs {
     const half_t *L;
     const half_t *X;
     half_t *Y;
-    half_t *T;           // fp16 [16][rank_pad]
+    half_t *T;           // fp16 [kh][16][rank_pad]: T is the sum of the planes
     unsigned *flags;     // per tile of 16 ranks: epoch of the call that last completed it
     unsigned *err;       // set to 1 when a wait gave up
     unsigned epoch;
@@ -55,65 +62,60 @@ struct FusedArgs {
     int mp;              // token rows of the LDS tiles (1, 4, 8, 16)
     int kpad;            // k rounded up to 1024: extent of an X row in LDS
     int S;               // wavefronts per row tile
-    int n_r;             // R-role workgroups (rank_pad / 16)
+    int n_r;             // R-role workgroups: (rank_pad / 16) tiles x kh shares of the inputs
+    int kh;              // shares of the inputs in the R role = planes of T
+    int upk;             // units of 256 inputs per share
     int mode;            // 0: R role only; 1: Y role only, T complete; 2: both roles in this grid
 };
 
 // ---- R role ----
-__device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rt)
+__device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb)
 {
+    const int rt = rb / a.kh;                  // tile of 16 ranks
+    const int kh = rb - rt * a.kh;             // share of the inputs
+
     float *red = reinterpret_cast<float *>(lds_h);
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);    // uniform: lets the compiler keep what derives from it in scalar registers
     const int nw = blockDim.x / kWave;
     const int lx = lane & 15;       // A: rank within the tile; B, C: token
     const int ly = lane >> 4;
     const int rp = a.rank_pad;
     const int units = (a.k + 255) / 256;
-    const uint4_t zero = {0u, 0u, 0u, 0u};
+    const int u0 = kh * a.upk, u1 = min(units, u0 + a.upk);
 
+    // Buffer loads: one 32-bit offset per lane, no branches; an offset past the
+    // end of the buffer (kNowhere) reads as zero.
+    const rsrc_t r_rs = make_rsrc(a.R, (uint32_t)tl_bytes(rp, a.k));
+    const rsrc_t x_rs = make_rsrc(a.X, (uint32_t)a.m * a.k * 2u);
     auto issue_r = [&](int u, UnitRegs &b) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) b.r[t] = zero;
-        if (u >= units) return;
         // step t reads the pieces (rank, 32 u + 4 t + ly): two tiles (2 KiB) further per step
-        const char *base = reinterpret_cast<const char *>(a.R) + tl_piece(16u * rt + lx, 32u * u + ly, (uint32_t)a.k);
+        const uint32_t base = tl_piece(16u * rt + lx, 32u * u + ly, (uint32_t)a.k);
 #pragma unroll
-        for (int t = 0; t < 8; ++t)
-            if (256 * u + 32 * t < a.k) b.r[t] = *reinterpret_cast<const uint4_t *>(base + 2048 * t);
+        for (int t = 0; t < 8; ++t) b.r[t] = load16(r_rs, (u < u1 && 256 * u + 32 * t < a.k) ? base + 2048u * t : kNowhere, 0);
     };
     auto issue_x = [&](int u, uint4_t (&xb)[8]) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) xb[t] = zero;
-        if (u >= units || lx >= a.m) return;
-        const half_t *xp = a.X + (size_t)lx * a.k + 256 * u + 8 * ly;
+        const uint32_t base = ((uint32_t)lx * a.k + 256 * u + 8 * ly) * 2u;
 #pragma unroll
         for (int t = 0; t < 8; ++t)
-            if (256 * u + 32 * t < a.k) xb[t] = *reinterpret_cast<const uint4_t *>(xp + 32 * t);
+            xb[t] = load16(x_rs, (u < u1 && lx < a.m && 256 * u + 32 * t < a.k) ? base + 64u * t : kNowhere, 0);
     };
 
-    // two units per wavefront in flight at once (all of a 4096-input layer)
-    UnitRegs bufA, bufB;
-    uint4_t xa[8], xb[8];
+    UnitRegs buf;
+    uint4_t xb[8];
     float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
-    auto mma = [&](const UnitRegs &b, const uint4_t (&x)[8]) {
+    for (int u = u0 + wave; u < u1; u += nw) {
+        issue_r(u, buf);
+        issue_x(u, xb);
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            const half8_t av = __builtin_bit_cast(half8_t, b.r[t]);
-            const half8_t bv = __builtin_bit_cast(half8_t, x[t]);
+            const half8_t av = __builtin_bit_cast(half8_t, buf.r[t]);
+            const half8_t bv = __builtin_bit_cast(half8_t, xb[t]);
             if (t & 1)
                 acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
             else
                 acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
         }
-    };
-    for (int u = wave; u < units; u += 2 * nw) {
-        issue_r(u, bufA);
-        issue_x(u, xa);
-        issue_r(u + nw, bufB);       // past the last unit: zeros
-        issue_x(u + nw, xb);
-        mma(bufA, xa);
-        mma(bufB, xb);
     }
     // lane holds token lx, ranks 16 rt + 4 ly .. + 3
     float4_t acc = acc0 + acc1;
@@ -122,12 +124,13 @@ __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rt
     if (wave == 0) {
         for (int w = 0; w < nw - 1; ++w) acc += *reinterpret_cast<const float4_t *>(red + (w * kWave + lane) * 4);
         const half4_t h = {(half_t)acc[0], (half_t)acc[1], (half_t)acc[2], (half_t)acc[3]};
-        *reinterpret_cast<half4_t *>(a.T + (size_t)lx * rp + 16 * rt + 4 * ly) = h;
+        *reinterpret_cast<half4_t *>(a.T + ((size_t)kh * kMaxTokens + lx) * rp + 16 * rt + 4 * ly) = h;
         if (a.mode == 2) {
             // the tile of T, then the flag: the fence makes this wavefront's
             // stores visible device-wide before the flag can be seen
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            if (lane == 0) __hip_atomic_store(a.flags + rt, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane < kFlagCopies)
+                __hip_atomic_store(a.flags + 512 * lane + rb, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -136,7 +139,7 @@ __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rt
 __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, int ygrid)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);    // uniform: lets the compiler keep what derives from it in scalar registers
     const int nw = blockDim.x / kWave;
     const int lx = lane & 15;
     const int ly = lane >> 4;
@@ -166,32 +169,37 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     const uint32_t kt = pk_ktiles(a.k);
     const uint4_t zero = {0u, 0u, 0u, 0u};
 
-    // Loads of item j of row tile ot: what lies past the rows, the inputs or the ranks is zero.
+    // Loads of item j of row tile ot, as buffer loads: one 32-bit offset per lane,
+    // no branches.  Rows past n inside the last tile of 32 are zero bytes in the
+    // tiled layouts, tiles past the last one lie past the end of the buffer, and
+    // what lies past the inputs or the ranks gets the offset kNowhere: all zeros.
+    const rsrc_t q_rs = make_rsrc(a.qvals, (uint32_t)pk_qbytes(a.n, a.k));
+    const rsrc_t m_rs = make_rsrc(a.meta, (uint32_t)pk_mbytes(a.n, a.k));
+    const rsrc_t l_rs = make_rsrc(a.L, (uint32_t)tl_bytes(a.n, rp));
     auto issue_item = [&](int ot, int j, UnitRegs &b) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) b.r[i] = zero;
-        const int o = 16 * ot + lx;
-        if (j >= nI || ot >= wtiles || o >= a.n) return;
+        const uint32_t o = 16u * ot + lx;
         if (j < nP) {
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
                 const int h = s + S * (2 * j + x);
                 const int kl = 512 * h + 128 * ly;          // the lane's 128 inputs: one tile column of the packed layout
-                if (h < H && kl < a.k) {
-                    const uint8_t *qp = a.qvals + pk_qoff((uint32_t)o, (uint32_t)kl / 4, kt);
-                    const uint8_t *mp = a.meta + pk_moff((uint32_t)o, (uint32_t)kl / 8, kt);
-                    b.r[3 * x] = load_q16(qp);
-                    b.r[3 * x + 1] = load_q16(qp + 512);
-                    b.r[3 * x + 2] = load_m16(mp);
-                }
+                const bool ok = h < H && kl < a.k && ot < wtiles;
+                const uint32_t qo = ok ? (uint32_t)pk_qoff(o, (uint32_t)kl / 4, kt) : kNowhere;
+                const uint32_t mo = ok ? (uint32_t)pk_moff(o, (uint32_t)kl / 8, kt) : kNowhere;
+                b.r[3 * x] = load16(q_rs, qo, 0);
+                b.r[3 * x + 1] = load16(q_rs, qo, 512);
+                const uint2_t lo = load8(m_rs, mo, 0), hi = load8(m_rs, mo, 256);
+                b.r[3 * x + 2] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
             }
+            b.r[6] = zero;
+            b.r[7] = zero;
         } else {
             // step t = s + S (8 jl + i) takes ranks 32 t + 8 ly .. + 7 of row o: piece (o, 4 t + ly)
             const int t0 = s + S * 8 * (j - nP);
-            const char *lp = reinterpret_cast<const char *>(a.L) + tl_piece((uint32_t)o, 4u * t0 + ly, (uint32_t)rp);
+            const uint32_t base = tl_piece(o, 4u * t0 + ly, (uint32_t)rp);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                if (t0 + S * i < steps) b.r[i] = *reinterpret_cast<const uint4_t *>(lp + (size_t)2048 * S * i);
+                b.r[i] = load16(l_rs, (j < nI && ot < wtiles && t0 + S * i < steps) ? base + 2048u * S * i : kNowhere, 0);
         }
     };
 
@@ -199,22 +207,23 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     UnitRegs bufA, bufB;
     issue_item(tile0, 0, bufA);
 
-    // X -> LDS: rows >= m zero, inputs past k zero up to kpad
+    // X -> LDS: rows >= m zero, inputs past k zero up to kpad.  Up to 16 loads
+    // per lane go out before the first LDS store: the copy costs one memory
+    // round trip up to 128 KiB per workgroup.
     {
+        const rsrc_t x_rs = make_rsrc(a.X, (uint32_t)a.m * a.k * 2u);
         const int per_row = a.kpad / 8;
         const int total = rows_x * per_row;
-        for (int e0 = threadIdx.x; e0 < total; e0 += 8 * (int)blockDim.x) {
-            uint4_t v[8];
+        for (int e0 = threadIdx.x; e0 < total; e0 += kXBatch * (int)blockDim.x) {
+            uint4_t v[kXBatch];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < kXBatch; ++i) {
                 const int e = e0 + i * (int)blockDim.x;
                 const int row = e / per_row, c = e - row * per_row;
-                v[i] = zero;
-                if (e < total && row < a.m && c * 8 < a.k)
-                    v[i] = *reinterpret_cast<const uint4_t *>(a.X + (size_t)row * a.k + c * 8);
+                v[i] = load16(x_rs, (e < total && row < a.m && c * 8 < a.k) ? ((uint32_t)row * a.k + c * 8) * 2u : kNowhere, 0);
             }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < kXBatch; ++i) {
                 const int e = e0 + i * (int)blockDim.x;
                 const int row = e / per_row, c = e - row * per_row;
                 if (e < total) *reinterpret_cast<uint4_t *>(x_lds + row * ldx + c * 8) = v[i];
@@ -222,41 +231,50 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
         }
     }
     // T -> LDS (all threads; the caller has made T visible)
-    auto stage_t = [&]() {
+    auto stage_t = [&](int first, int stride) {
         const int per_row = rp / 8;
         const int total = rows_x * per_row;
-        for (int e = threadIdx.x; e < total; e += blockDim.x) {
+        for (int e = first; e < total; e += stride) {
             const int row = e / per_row, c = e - row * per_row;
-            uint4_t v = zero;
-            if (row < a.m) v = *reinterpret_cast<const uint4_t *>(a.T + (size_t)row * rp + c * 8);
-            *reinterpret_cast<uint4_t *>(t_lds + row * ldt + c * 8) = v;
+            half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (row < a.m)
+                for (int p = 0; p < a.kh; ++p)
+                    v += *reinterpret_cast<const half8_t *>(a.T + ((size_t)p * kMaxTokens + row) * rp + c * 8);
+            *reinterpret_cast<half8_t *>(t_lds + row * ldt + c * 8) = v;
         }
     };
-    // mode 2: wait for the flags of all rank tiles, then stage T
-    auto wait_and_stage_t = [&]() {
-        if (wave == 0) {
-            bool done = false;
-            for (int spin = 0; spin < kSpinLimit && !done; ++spin) {
-                bool mine = true;
-                for (int r = lane; r < a.n_r; r += kWave)
-                    mine = mine && __hip_atomic_load(a.flags + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
-                done = __all(mine);
-                if (!done) __builtin_amdgcn_s_sleep(8);
-            }
-            if (!done && lane == 0) __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            // what the R-role workgroups stored before raising their flags is read after this
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        }
-        __syncthreads();
-        stage_t();
-        __syncthreads();
-    };
+    // T is needed when the first rank step starts.  Two launches: it is complete,
+    // all threads stage it now.  One launch: wavefront 0 waits for the flags and
+    // stages T alone while the others work on the packed term; the workgroup meets
+    // at one barrier before its first rank step (t_ready).
     bool t_ready = rp == 0;
     if (a.mode == 1 && rp > 0) {
-        stage_t();
+        stage_t(threadIdx.x, blockDim.x);
         t_ready = true;
     }
     __syncthreads();
+    const unsigned *my_flags = a.flags + 512 * (yb % kFlagCopies);
+    auto wait_flags = [&]() {
+        bool done = false;
+        for (int spin = 0; spin < kSpinLimit && !done; ++spin) {
+            bool mine = true;
+            for (int r = lane; r < a.n_r; r += kWave)
+                mine = mine && __hip_atomic_load(my_flags + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
+            done = __all(mine);
+            if (!done) __builtin_amdgcn_s_sleep(8);
+        }
+        if (!done && lane == 0) __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // what the R-role workgroups stored before raising their flags is read after this
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    };
+    // the workgroup's meeting before its first rank step: wavefront 0 has seen the
+    // flags, then all threads stage T
+    auto meet_for_t = [&]() {
+        if (wave == 0) wait_flags();
+        __syncthreads();
+        stage_t(threadIdx.x, blockDim.x);
+        __syncthreads();
+    };
 
     // this lane's B-operand rows: its token, or the zero row
     const int trow = lx < a.mp ? lx : a.mp;       // mp == 16: always lx
@@ -267,23 +285,29 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
         const int ot = tile0 + round * tstride;     // past the last tile: nothing is loaded or stored
         const int ob = 16 * ot + 4 * ly;
         const bool vec = (ob + 3 < a.n) && (a.n & 3) == 0;
-        float sc[4] = {0.f, 0.f, 0.f, 0.f};
-        if (ot < wtiles) {
-            if (vec) {
-                const float4_t s4 = *reinterpret_cast<const float4_t *>(a.scale + ob);
+        float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+        // the packed term is scaled when its last item is done; the rank steps go on in the same registers
+        auto apply_scale = [&]() {
+            float4_t s4 = {0.f, 0.f, 0.f, 0.f};
+            if (ot < wtiles) {
+                if (vec) {
+                    s4 = *reinterpret_cast<const float4_t *>(a.scale + ob);
+                } else {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) sc[v] = s4[v];
-            } else {
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (ob + v < a.n) sc[v] = a.scale[ob + v];
+                    for (int v = 0; v < 4; ++v)
+                        if (ob + v < a.n) s4[v] = a.scale[ob + v];
+                }
             }
-        }
-        float4_t accp0 = {0.f, 0.f, 0.f, 0.f}, accp1 = accp0, accl0 = accp0, accl1 = accp0;
+            acc0 = (acc0 + acc1) * s4;
+            acc1 = float4_t{0.f, 0.f, 0.f, 0.f};
+        };
         for (int j = 0; j < nI; ++j) {
-            if (j == nP && !t_ready) {
-                wait_and_stage_t();
-                t_ready = true;
+            if (j == nP) {
+                apply_scale();
+                if (!t_ready) {
+                    meet_for_t();
+                    t_ready = true;
+                }
             }
             if (j + 1 < nI)
                 issue_item(ot, j + 1, bufB);
@@ -291,8 +315,8 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
                 issue_item(ot + tstride, 0, bufB);
             if (j < nP) {
                 const int h0 = min(s + S * (2 * j), Hp - 1), h1 = min(s + S * (2 * j + 1), Hp - 1);
-                packed_half<0>(bufA, xrow_packed + 512 * h0, accp0, accp1);
-                packed_half<1>(bufA, xrow_packed + 512 * h1, accp0, accp1);
+                packed_half<0>(bufA, xrow_packed + 512 * h0, acc0, acc1);
+                packed_half<1>(bufA, xrow_packed + 512 * h1, acc0, acc1);
             } else {
                 const int t0 = s + S * 8 * (j - nP);
 #pragma unroll
@@ -302,23 +326,21 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
                     const half8_t bv = *reinterpret_cast<const half8_t *>(trow_l + 32 * t);
                     const half8_t av = __builtin_bit_cast(half8_t, bufA.r[i]);
                     if (i & 1)
-                        accl1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, accl1, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
                     else
-                        accl0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, accl0, 0, 0, 0);
+                        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
                 }
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) bufA.r[i] = bufB.r[i];
         }
+        if (nL == 0) apply_scale();
         if (!t_ready) {          // a wavefront without rank steps still takes part in the barriers
-            wait_and_stage_t();
+            meet_for_t();
             t_ready = true;
         }
         // lane holds token lx, rows 16 ot + 4 ly .. + 3
-        const float4_t accp = accp0 + accp1;
-        float4_t y = accl0 + accl1;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) y[v] += sc[v] * accp[v];
+        float4_t y = acc0 + acc1;
         if (S > 1) {
             float *rset = red + (size_t)ts * (S - 1) * kWave * 4;
             if (s != 0) *reinterpret_cast<float4_t *>(rset + ((s - 1) * kWave + lane) * 4) = y;
@@ -341,7 +363,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     }
 }
 
-__global__ __launch_bounds__(kFusedMaxThreads, 1) void decode_fused_kernel(FusedArgs a)
+__global__ __launch_bounds__(kFusedMaxThreads, kFusedWavesPerSimd) void decode_fused_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) half_t lds[];
     if (a.mode == 0) {
@@ -357,41 +379,57 @@ __global__ __launch_bounds__(kFusedMaxThreads, 1) void decode_fused_kernel(Fused
 
 static int pad_tokens16(int m) { return m <= 1 ? 1 : (m <= 4 ? 4 : (m <= 8 ? 8 : 16)); }
 
-// Which layers take this path, and with what geometry.
-FusedPlan plan_fused(int n, int k, int rank_pad, int m)
+// Geometry for one workgroup size: the shares of the R role, and the largest S
+// (wavefronts per row tile) with which every workgroup is resident at once.
+static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
 {
     FusedPlan p{};
     p.mp = pad_tokens16(m);
     p.kpad = (k + 1023) / 1024 * 1024;
-    p.waves = kFusedMaxThreads / kWave;
-    p.n_r = rank_pad / 16;
-    const int rows_x = p.mp < kMaxTokens ? p.mp + 1 : kMaxTokens;
+    p.waves = waves;
     const long wtiles = (n + 15) / 16;
-    // Every workgroup should have a compute unit of its own (slots).  S wavefronts
-    // per row tile make a round S times shorter and ask for S times as many
-    // workgroup-rounds: take the S with the least rounds / S, the smaller S on a tie.
-    const int slots = 256 - (p.n_r < 128 ? p.n_r : 128);
-    p.S = 1;
-    double best = 1e30;
-    for (int S = 1; S <= p.waves; S *= 2) {
-        const int tpw = p.waves / S;
+    {
+        // Shares of the inputs in the R role: one unit per wavefront (T as early as
+        // possible) for layers with few row tiles, where the Y role is short and
+        // waits for T; one share otherwise, which leaves the compute units to the Y role.
+        const int units = (k + 255) / 256;
+        const int kh = wtiles <= kShareTiles ? (units + waves - 1) / waves : 1;
+        p.kh = kh < 1 ? 1 : (kh > kMaxShares ? kMaxShares : kh);
+        p.upk = (units + p.kh - 1) / p.kh;
+    }
+    p.n_r = (rank_pad / 16) * p.kh;
+    const int rows_x = p.mp < kMaxTokens ? p.mp + 1 : kMaxTokens;
+    const size_t lds_x = (size_t)rows_x * ((p.kpad + kLdsPad) + (rank_pad + kLdsPad)) * sizeof(half_t);
+    const size_t red_r = (size_t)(waves - 1) * kWave * 16;
+    for (int S = waves; S >= 1; S /= 2) {
+        const int tpw = waves / S;
+        const size_t red_y = S > 1 ? (size_t)tpw * (S - 1) * kWave * 16 : 0;
+        const size_t lds = lds_x + red_y > red_r ? lds_x + red_y : red_r;
+        if (lds > 160 * 1024) continue;
+        // workgroups a compute unit holds: registers allow kFusedResidentWaves wavefronts
+        long per_cu = kFusedResidentWaves / waves;
+        if (per_cu > (long)(160 * 1024 / lds)) per_cu = (long)(160 * 1024 / lds);
+        const long slots = 256 * per_cu - p.n_r;
         const long wgs = (wtiles + tpw - 1) / tpw;
-        const double cost = (double)((wgs + slots - 1) / slots) / S;
-        if (cost < best * 0.999) {
-            best = cost;
+        if (wgs <= slots) {
             p.S = S;
+            p.ygrid = (int)wgs;
+            p.lds = lds;
+            p.ok = p.n_r <= 512;
+            break;
         }
     }
-    const int tpw = p.waves / p.S;
-    long yg = (wtiles + tpw - 1) / tpw;
-    if (yg > slots) yg = slots;
-    p.ygrid = (int)yg;
-    const size_t red_y = p.S > 1 ? (size_t)tpw * (p.S - 1) * kWave * 16 : 0;
-    const size_t red_r = (size_t)(p.waves - 1) * kWave * 16;
-    const size_t lds_y = (size_t)rows_x * ((p.kpad + kLdsPad) + (rank_pad + kLdsPad)) * sizeof(half_t) + red_y;
-    p.lds = lds_y > red_r ? lds_y : red_r;
-    p.ok = p.lds <= 160 * 1024 && p.n_r <= 128;
     return p;
+}
+
+// Which layers take this path, and with what geometry.  Workgroups of 8
+// wavefronts, one per compute unit, measured best wherever they fit; layers
+// with more row tiles than that allows run workgroups of 4 wavefronts, three
+// per compute unit where the LDS permits.
+FusedPlan plan_fused(int n, int k, int rank_pad, int m)
+{
+    const FusedPlan a = plan_fused_waves(n, k, rank_pad, m, kFusedMaxThreads / kWave);
+    return a.ok ? a : plan_fused_waves(n, k, rank_pad, m, 4);
 }
 
 static std::atomic<unsigned> g_epoch{0};
@@ -422,6 +460,8 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     a.kpad = p.kpad;
     a.S = p.S;
     a.n_r = p.n_r;
+    a.kh = p.kh;
+    a.upk = p.upk;
     const dim3 blk(p.waves * kWave);
     if (mode == 2 || p.n_r == 0) {
         a.mode = p.n_r == 0 ? 1 : 2;

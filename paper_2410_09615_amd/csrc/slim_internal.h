@@ -111,6 +111,32 @@ __host__ __device__ inline size_t pk_moff(uint32_t o, uint32_t b, uint32_t kt)
     return ((size_t)(o >> 5) * kt + (b >> 4)) * 512u + ((((b >> 3) & 1u) << 5) + (o & 31u)) * 8u + (b & 7u);
 }
 
+#ifdef __HIPCC__
+// ---- buffer loads: descriptor + 32-bit byte offset, out-of-range reads return zero ----
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+// Raw buffer descriptor over `bytes` bytes at p (32-bit data format word of gfx9).
+__device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+// The whole byte offset goes into the per-lane offset operand: that is the part
+// the hardware checks against the descriptor's size (the scalar offset operand
+// is added to the address without a check).
+__device__ __forceinline__ uint4_t load16(rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_bit_cast(uint4_t,
+                              __builtin_amdgcn_raw_buffer_load_b128(r, (int)(lane_off + uniform_off), 0, 0));
+}
+
+__device__ __forceinline__ uint2_t load8(rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_bit_cast(uint2_t, __builtin_amdgcn_raw_buffer_load_b64(r, (int)(lane_off + uniform_off), 0, 0));
+}
+
+#endif
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? SLIM_OK : SLIM_ERR_HIP; }
@@ -119,7 +145,7 @@ inline int hip_status(hipError_t e) { return e == hipSuccess ? SLIM_OK : SLIM_ER
 // each a multiple of 256).
 struct WorkspacePlan {
     size_t dec_off, dec_bytes;    // decode state: 256 B of control words, then two T buffers fp32 [16][rank_pad],
-                                  // then (one-launch path) 512 B of flags and T as fp16 [16][rank_pad]
+                                  // then (one-launch path) 16 copies of 2 KiB of flags and T as up to four fp16 planes [16][rank_pad]
     size_t flag_off, t16_off;     // the last two, as offsets into the workspace
     size_t t_off, t_bytes;        // gemm: T = X R^T as fp16 [m][rank_pad]
     size_t acc_off, acc_bytes;    // decode: partial quantized term, fp32 [slots][m][n]

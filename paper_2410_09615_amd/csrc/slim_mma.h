@@ -16,28 +16,6 @@ constexpr int SG_STAGE = 128 * SG_LD;   // halves per LDS buffer (128 tokens)
 constexpr int NT = 4;                   // token tiles of 32 per wavefront
 constexpr int XR = 8;                   // 128-bit pieces of an X stage per lane (16 token rows per pass)
 
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-
-// Raw buffer descriptor over `bytes` bytes at p (32-bit data format word of gfx9).
-__device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
-}
-
-// The whole byte offset goes into the per-lane offset operand: that is the part
-// the hardware checks against the descriptor's size (the scalar offset operand
-// is added to the address without a check).
-__device__ __forceinline__ uint4_t load16(rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
-{
-    return __builtin_bit_cast(uint4_t,
-                              __builtin_amdgcn_raw_buffer_load_b128(r, (int)(lane_off + uniform_off), 0, 0));
-}
-
-__device__ __forceinline__ uint2_t load8(rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
-{
-    return __builtin_bit_cast(uint2_t, __builtin_amdgcn_raw_buffer_load_b64(r, (int)(lane_off + uniform_off), 0, 0));
-}
-
 // Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>).
 template <int... Is, class F>
 __device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f)
