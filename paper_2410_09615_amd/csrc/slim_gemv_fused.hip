@@ -43,7 +43,6 @@ constexpr int kMaxShares = 4;         // R role: at most this many shares of the
 constexpr int kShareTiles = 384;       // ... for layers of at most this many row tiles
 constexpr int kFusedResidentWaves = 4 * kFusedWavesPerSimd;     // wavefronts a compute unit holds at this kernel's register count
 constexpr int kSpinLimit = 1 << 16;
-constexpr int kXBatch = 16;       // X pieces a lane loads before it stores them to LDS
 constexpr uint32_t kNowhere = 0x80000000u;       // byte offset past the end of every buffer here (all are < 2 GiB)
 
 struct FusedArgs {
@@ -136,6 +135,7 @@ __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb
 }
 
 // ---- Y role ----
+template <int XB>
 __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, int ygrid)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -203,31 +203,58 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
         }
     };
 
-    // the first loads go out before anything else
+    // A wavefront's work is a sequence of items (nIe per round; a wavefront without
+    // any still takes part in the barriers).  Two register sets alternate: the
+    // loads of the item after next go out as soon as an item is done.
+    const int nIe = nI > 0 ? nI : 1;
+    auto advance = [&](int &r, int &j) {
+        if (++j >= nIe) {
+            j = 0;
+            ++r;
+        }
+    };
+    auto tile_of = [&](int r) { return tile0 + r * tstride; };   // r >= rounds: past the last tile, loads read zeros
+    int ir = 0, ij = 0;              // next item to load
     UnitRegs bufA, bufB;
-    issue_item(tile0, 0, bufA);
 
-    // X -> LDS: rows >= m zero, inputs past k zero up to kpad.  Up to 16 loads
-    // per lane go out before the first LDS store: the copy costs one memory
-    // round trip up to 128 KiB per workgroup.
+    // X -> LDS: rows >= m zero, inputs past k zero up to kpad.  A thread takes
+    // the pieces tid, tid + threads, ... of every row.  Order of the loads (they
+    // return in order): the thread's first 16 X pieces, then the first two items;
+    // the X pieces go to LDS while the items are still on their way, so the copy
+    // costs one round trip to the L2 up to 128 KiB per workgroup.
     {
         const rsrc_t x_rs = make_rsrc(a.X, (uint32_t)a.m * a.k * 2u);
-        const int per_row = a.kpad / 8;
-        const int total = rows_x * per_row;
-        for (int e0 = threadIdx.x; e0 < total; e0 += kXBatch * (int)blockDim.x) {
-            uint4_t v[kXBatch];
+        const int bd = blockDim.x;
+        const int per_row = a.kpad / 8;                  // pieces per row
+        const int cpr = (per_row + bd - 1) / bd;         // ... and thread
+        const int np = rows_x * cpr;
+        auto x_load = [&](int p) {
+            const int row = p / cpr, c = (int)threadIdx.x + (p - row * cpr) * bd;
+            return load16(x_rs, (p < np && row < a.m && c * 8 < a.k) ? ((uint32_t)row * a.k + c * 8) * 2u : kNowhere, 0);
+        };
+        auto x_store = [&](int p, uint4_t v) {
+            const int row = p / cpr, c = (int)threadIdx.x + (p - row * cpr) * bd;
+            if (p < np && c < per_row) *reinterpret_cast<uint4_t *>(x_lds + row * ldx + c * 8) = v;
+        };
+        // XB = pieces in the first batch: the kernel is built for 2, 6 and 16, the
+        // launch takes the smallest that covers the thread's pieces (or 16)
+        {
+            uint4_t v[XB];
 #pragma unroll
-            for (int i = 0; i < kXBatch; ++i) {
-                const int e = e0 + i * (int)blockDim.x;
-                const int row = e / per_row, c = e - row * per_row;
-                v[i] = load16(x_rs, (e < total && row < a.m && c * 8 < a.k) ? ((uint32_t)row * a.k + c * 8) * 2u : kNowhere, 0);
-            }
+            for (int i = 0; i < XB; ++i) v[i] = x_load(i);
+            issue_item(tile_of(ir), ij, bufA);
+            advance(ir, ij);
+            issue_item(tile_of(ir), ij, bufB);
+            advance(ir, ij);
 #pragma unroll
-            for (int i = 0; i < kXBatch; ++i) {
-                const int e = e0 + i * (int)blockDim.x;
-                const int row = e / per_row, c = e - row * per_row;
-                if (e < total) *reinterpret_cast<uint4_t *>(x_lds + row * ldx + c * 8) = v[i];
-            }
+            for (int i = 0; i < XB; ++i) x_store(i, v[i]);
+        }
+        for (int p0 = XB; p0 < np; p0 += 4) {
+            uint4_t v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = x_load(p0 + i);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x_store(p0 + i, v[i]);
         }
     }
     // T -> LDS (all threads; the caller has made T visible)
@@ -281,63 +308,63 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     const half_t *xrow_packed = x_lds + trow * ldx + 128 * (ly >> 1) + 8 * (ly & 1);
     const half_t *trow_l = t_lds + trow * ldt + 8 * ly;
 
-    for (int round = 0; round < rounds; ++round) {
-        const int ot = tile0 + round * tstride;     // past the last tile: nothing is loaded or stored
+    float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0, sc4 = acc0;
+    // item j of round r, its loads in cur
+    auto step = [&](int r, int j, const UnitRegs &cur) {
+        const int ot = tile_of(r);
         const int ob = 16 * ot + 4 * ly;
         const bool vec = (ob + 3 < a.n) && (a.n & 3) == 0;
-        float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
-        // the packed term is scaled when its last item is done; the rank steps go on in the same registers
-        auto apply_scale = [&]() {
-            float4_t s4 = {0.f, 0.f, 0.f, 0.f};
+        if (j == 0) {
+            acc0 = float4_t{0.f, 0.f, 0.f, 0.f};
+            acc1 = acc0;
+            // row scales of this lane's four outputs: needed when the packed items are done
+            sc4 = acc0;
             if (ot < wtiles) {
                 if (vec) {
-                    s4 = *reinterpret_cast<const float4_t *>(a.scale + ob);
+                    sc4 = *reinterpret_cast<const float4_t *>(a.scale + ob);
                 } else {
 #pragma unroll
                     for (int v = 0; v < 4; ++v)
-                        if (ob + v < a.n) s4[v] = a.scale[ob + v];
+                        if (ob + v < a.n) sc4[v] = a.scale[ob + v];
                 }
             }
-            acc0 = (acc0 + acc1) * s4;
-            acc1 = float4_t{0.f, 0.f, 0.f, 0.f};
-        };
-        for (int j = 0; j < nI; ++j) {
-            if (j == nP) {
-                apply_scale();
-                if (!t_ready) {
-                    meet_for_t();
-                    t_ready = true;
-                }
-            }
-            if (j + 1 < nI)
-                issue_item(ot, j + 1, bufB);
-            else
-                issue_item(ot + tstride, 0, bufB);
-            if (j < nP) {
-                const int h0 = min(s + S * (2 * j), Hp - 1), h1 = min(s + S * (2 * j + 1), Hp - 1);
-                packed_half<0>(bufA, xrow_packed + 512 * h0, acc0, acc1);
-                packed_half<1>(bufA, xrow_packed + 512 * h1, acc0, acc1);
-            } else {
-                const int t0 = s + S * 8 * (j - nP);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    // steps past the end carry zero L values and read T inside the row
-                    const int t = min(t0 + S * i, steps - 1);
-                    const half8_t bv = *reinterpret_cast<const half8_t *>(trow_l + 32 * t);
-                    const half8_t av = __builtin_bit_cast(half8_t, bufA.r[i]);
-                    if (i & 1)
-                        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
-                    else
-                        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) bufA.r[i] = bufB.r[i];
         }
-        if (nL == 0) apply_scale();
-        if (!t_ready) {          // a wavefront without rank steps still takes part in the barriers
-            meet_for_t();
-            t_ready = true;
+        if (j == nP) {
+            // the packed term is scaled once; the rank steps go on in the same registers
+            acc0 = (acc0 + acc1) * sc4;
+            acc1 = float4_t{0.f, 0.f, 0.f, 0.f};
+            if (!t_ready) {
+                meet_for_t();
+                t_ready = true;
+            }
+        }
+        if (j < nP) {
+            const int h0 = min(s + S * (2 * j), Hp - 1), h1 = min(s + S * (2 * j + 1), Hp - 1);
+            packed_half<0>(cur, xrow_packed + 512 * h0, acc0, acc1);
+            packed_half<1>(cur, xrow_packed + 512 * h1, acc0, acc1);
+        } else if (j < nI) {
+            const int t0 = s + S * 8 * (j - nP);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                // steps past the end carry zero L values and read T inside the row
+                const int t = min(t0 + S * i, steps - 1);
+                const half8_t bv = *reinterpret_cast<const half8_t *>(trow_l + 32 * t);
+                const half8_t av = __builtin_bit_cast(half8_t, cur.r[i]);
+                if (i & 1)
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
+                else
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
+            }
+        }
+        if (j != nIe - 1) return;
+        // ---- end of the round ----
+        if (nP == nIe) {             // no rank steps on this wavefront
+            acc0 = (acc0 + acc1) * sc4;
+            acc1 = float4_t{0.f, 0.f, 0.f, 0.f};
+            if (!t_ready) {          // it still takes part in the barriers
+                meet_for_t();
+                t_ready = true;
+            }
         }
         // lane holds token lx, rows 16 ot + 4 ly .. + 3
         float4_t y = acc0 + acc1;
@@ -359,21 +386,35 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
                     if (ob + v < a.n) yp[v] = (half_t)y[v];
             }
         }
-        if (S > 1 && round + 1 < rounds) __syncthreads();      // the partial sums are read before the next round writes
+        if (S > 1 && r + 1 < rounds) __syncthreads();      // the partial sums are read before the next round writes
+    };
+
+    int cr = 0, cj = 0;              // item being worked on
+    while (cr < rounds) {
+        step(cr, cj, bufA);
+        advance(cr, cj);
+        issue_item(tile_of(ir), ij, bufA);
+        advance(ir, ij);
+        if (cr >= rounds) break;
+        step(cr, cj, bufB);
+        advance(cr, cj);
+        issue_item(tile_of(ir), ij, bufB);
+        advance(ir, ij);
     }
 }
 
+template <int XB>
 __global__ __launch_bounds__(kFusedMaxThreads, kFusedWavesPerSimd) void decode_fused_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) half_t lds[];
     if (a.mode == 0) {
         role_r(a, lds, blockIdx.x);
     } else if (a.mode == 1) {
-        role_y(a, lds, blockIdx.x, gridDim.x);
+        role_y<XB>(a, lds, blockIdx.x, gridDim.x);
     } else if ((int)blockIdx.x < a.n_r) {
         role_r(a, lds, blockIdx.x);
     } else {
-        role_y(a, lds, (int)blockIdx.x - a.n_r, (int)gridDim.x - a.n_r);
+        role_y<XB>(a, lds, (int)blockIdx.x - a.n_r, (int)gridDim.x - a.n_r);
     }
 }
 
@@ -463,14 +504,25 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     a.kh = p.kh;
     a.upk = p.upk;
     const dim3 blk(p.waves * kWave);
+    // X pieces per thread: (token rows + zero row) x pieces of a row per thread
+    const int rows_x = p.mp < kMaxTokens ? p.mp + 1 : kMaxTokens;
+    const int np = rows_x * ((p.kpad / 8 + (int)blk.x - 1) / (int)blk.x);
+    auto launch = [&](unsigned grid) {
+        if (np <= 2)
+            hipLaunchKernelGGL(decode_fused_kernel<2>, dim3(grid), blk, p.lds, st, a);
+        else if (np <= 6)
+            hipLaunchKernelGGL(decode_fused_kernel<6>, dim3(grid), blk, p.lds, st, a);
+        else
+            hipLaunchKernelGGL(decode_fused_kernel<16>, dim3(grid), blk, p.lds, st, a);
+    };
     if (mode == 2 || p.n_r == 0) {
         a.mode = p.n_r == 0 ? 1 : 2;
-        hipLaunchKernelGGL(decode_fused_kernel, dim3((unsigned)(p.n_r + p.ygrid)), blk, p.lds, st, a);
+        launch((unsigned)(p.n_r + p.ygrid));
     } else {
         a.mode = 0;
-        hipLaunchKernelGGL(decode_fused_kernel, dim3((unsigned)p.n_r), blk, p.lds, st, a);
+        launch((unsigned)p.n_r);
         a.mode = 1;
-        hipLaunchKernelGGL(decode_fused_kernel, dim3((unsigned)p.ygrid), blk, p.lds, st, a);
+        launch((unsigned)p.ygrid);
     }
     return hip_status(hipGetLastError());
 }
