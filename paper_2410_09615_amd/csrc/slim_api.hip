@@ -11,9 +11,8 @@ WorkspacePlan plan_workspace(int32_t n, int32_t k, int32_t rank_pad, int32_t m)
 {
     WorkspacePlan p{};
     p.dec_off = 0;
-    p.flag_off = p.dec_off + 256 + 2 * round256((size_t)16 * rank_pad * sizeof(float));
-    p.t16_off = p.flag_off + 16 * 2048;
-    p.dec_bytes = p.t16_off + round256((size_t)4 * 16 * rank_pad * sizeof(uint16_t)) - p.dec_off;
+    p.t16_off = p.dec_off + 256 + 2 * round256((size_t)16 * rank_pad * sizeof(float));
+    p.dec_bytes = p.t16_off + round256((size_t)4 * 16 * (rank_pad / 4) * 16) - p.dec_off;
     p.t_off = p.dec_off + p.dec_bytes;
     p.t_bytes = m > 16 ? round256((size_t)m * rank_pad * sizeof(uint16_t)) : 0;
     p.acc_off = p.t_off + p.t_bytes;

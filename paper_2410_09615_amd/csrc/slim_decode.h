@@ -50,12 +50,11 @@ __device__ __forceinline__ void packed_half(const UnitRegs &b, const half_t *xh,
 // Geometry and launch of the one-launch decode path (slim_gemv_fused.hip).
 struct FusedPlan {
     bool ok;            // the layer and token count fit this path
-    int mp, kpad, S, waves, n_r, kh, upk, ygrid;
+    int mp, kpad, S, waves, helpers, n_r, kh, upk, ygrid;
     size_t lds;
 };
 FusedPlan plan_fused(int n, int k, int rank_pad, int m);
 // mode 2: one launch; mode 1: the two roles as two launches
-int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t *Y, half_t *T, unsigned *flags,
-                        unsigned *err, const FusedPlan &p, int mode, hipStream_t st);
+int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t *Y, void *T, unsigned *err, const FusedPlan &p, int mode, hipStream_t st);
 
 }  // namespace slim

@@ -605,9 +605,7 @@ extern "C" int slim_linear_gemv(const slim_layer *layer, const slim_half *X, int
         }
         if (mode > 0)
             return launch_decode_fused(layer, reinterpret_cast<const half_t *>(X), m, reinterpret_cast<half_t *>(Y),
-                                       reinterpret_cast<half_t *>(ws + w.t16_off),
-                                       reinterpret_cast<unsigned *>(ws + w.flag_off),
-                                       reinterpret_cast<unsigned *>(ws + w.dec_off) + 2, f, mode,
+                                       ws + w.t16_off, reinterpret_cast<unsigned *>(ws + w.dec_off) + 2, f, mode,
                                        static_cast<hipStream_t>(stream));
     }
     DecodePlan p = plan_decode(s.n, s.k, layer->rank_pad, m);

@@ -3,42 +3,49 @@
 //
 // Two kinds of workgroups share one grid:
 //
-//  R role  (the first rank_pad / 16 workgroups) one tile of 16 ranks each:
-//          T[:, tile] = X R[tile, :]^T over all inputs.  The wavefronts take
-//          units of 16 ranks x 256 inputs (R and X straight from memory into
-//          registers, dense 16 x 16 x 32 matrix instruction), add their partial
-//          tiles in LDS, and wavefront 0 writes the tile of T as fp16, makes it
-//          visible to the device and raises the tile's flag to the epoch of
-//          this call.  These workgroups wait for nothing.
-//  Y role  (all others) S wavefronts per tile of 16 output rows, 8 / S tiles
-//          per workgroup and round.  Wavefront s of a tile takes the halves
-//          (512 inputs) s, s + S, ... of the packed row tile through the
-//          structured-sparse matrix instruction against X held in LDS, then the
-//          steps of 32 ranks s, s + S, ... of the L row tile against T held in
-//          LDS.  Between the two it waits (once per workgroup) until every
-//          flag shows this call's epoch.  The S partial results, each already
-//          scale * packed + low-rank, meet in LDS and wavefront 0 of the tile
-//          stores Y.  Nothing goes through memory between the two terms: no
-//          partial sums, no atomics, no second launch.
+//  R role  (the first workgroups of the grid) one tile of 16 ranks and one share
+//          of the inputs each: T[:, tile] += X R[tile, share]^T.  The wavefronts
+//          take units of 16 ranks x 256 inputs (R and X straight from memory
+//          into registers, dense 16 x 16 x 32 matrix instruction), add their
+//          partial tiles in LDS, and wavefront 0 stores the tile as fp16 in
+//          16-byte pieces {epoch of this call, 0, four ranks of one token},
+//          written through to memory.  These workgroups wait for nothing.
+//  Y role  (all others) S wavefronts per tile of 16 output rows.  Wavefront s
+//          of a tile takes the halves (512 inputs) s, s + S, ... of the packed
+//          row tile through the structured-sparse matrix instruction against X
+//          held in LDS, then the steps of 32 ranks s, s + S, ... of the L row
+//          tile against T held in LDS.  One to four more wavefronts of the
+//          workgroup (helpers) do nothing but fetch T: they re-read its pieces
+//          until every piece carries this call's epoch, add the shares and put
+//          the sum into LDS, while the others are busy with the packed term;
+//          the workgroup meets at one barrier before its first rank step.  The
+//          S partial results, each already scale * packed + low-rank, meet in
+//          LDS and wavefront 0 of the tile stores Y.  Nothing goes through
+//          memory between the two terms but T itself: no partial sums, no
+//          atomics, no second launch.
+//
+// A piece is valid by itself (its epoch is unique to the call, process-wide), so
+// there are no flags to order against the data, nothing to reset between calls,
+// and a workspace may serve different layers in turn.
 //
 // Progress: workgroups start in the order of their index, so every R-role
 // workgroup has started before any Y-role workgroup can wait for it, and the
-// wait is bounded anyway (it gives up after kSpinLimit polls and records that
-// in the control words; the call then returns wrong numbers, not a hang).
+// wait is bounded anyway (a helper gives up after kSpinLimit reads and records
+// that in the control words; the call then returns wrong numbers, not a hang).
 //
-// The same kernel also runs the roles as two launches (mode 0, then mode 1),
-// with the kernel boundary in place of the flags.
+// The same kernel also runs the roles as two launches (mode 0, then mode 1).
 //
-// T is rounded to fp16 once here, as in the prefill path.
+// T is rounded to fp16 once per share here (prefill: once).
 #include <atomic>
+#include <type_traits>
 
 #include "slim_decode.h"
 
 namespace slim {
 
-constexpr int kFusedMaxThreads = 512;
+constexpr int kFusedMaxThreads = 768;      // 8 working wavefronts + up to 4 helpers
 constexpr int kFusedWavesPerSimd = 3;   // the kernel is compiled for this many wavefronts per SIMD (168 registers)
-constexpr int kFlagCopies = 16;      // copies of the flags (2 KiB apart); a workgroup polls one of them
+constexpr int kScopeDevice = 16;      // cache policy of a buffer access: device scope (written through / read from memory)
 constexpr int kMaxShares = 4;         // R role: at most this many shares of the inputs (planes of T)
 constexpr int kShareTiles = 384;       // ... for layers of at most this many row tiles
 constexpr int kFusedResidentWaves = 4 * kFusedWavesPerSimd;     // wavefronts a compute unit holds at this kernel's register count
@@ -53,8 +60,7 @@ struct FusedArgs {
     const half_t *L;
     const half_t *X;
     half_t *Y;
-    half_t *T;           // fp16 [kh][16][rank_pad]: T is the sum of the planes
-    unsigned *flags;     // per tile of 16 ranks: epoch of the call that last completed it
+    uint4_t *T;          // pieces {epoch, 0, 4 ranks fp16} [kh][16][rank_pad / 4]: T is the sum of the planes
     unsigned *err;       // set to 1 when a wait gave up
     unsigned epoch;
     int n, k, rank_pad, m;
@@ -64,6 +70,7 @@ struct FusedArgs {
     int n_r;             // R-role workgroups: (rank_pad / 16) tiles x kh shares of the inputs
     int kh;              // shares of the inputs in the R role = planes of T
     int upk;             // units of 256 inputs per share
+    int helpers;         // wavefronts of a workgroup that only fetch T (Y role)
     int mode;            // 0: R role only; 1: Y role only, T complete; 2: both roles in this grid
 };
 
@@ -123,14 +130,13 @@ __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb
     if (wave == 0) {
         for (int w = 0; w < nw - 1; ++w) acc += *reinterpret_cast<const float4_t *>(red + (w * kWave + lane) * 4);
         const half4_t h = {(half_t)acc[0], (half_t)acc[1], (half_t)acc[2], (half_t)acc[3]};
-        *reinterpret_cast<half4_t *>(a.T + ((size_t)kh * kMaxTokens + lx) * rp + 16 * rt + 4 * ly) = h;
-        if (a.mode == 2) {
-            // the tile of T, then the flag: the fence makes this wavefront's
-            // stores visible device-wide before the flag can be seen
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            if (lane < kFlagCopies)
-                __hip_atomic_store(a.flags + 512 * lane + rb, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        const uint2_t hb = __builtin_bit_cast(uint2_t, h);
+        // one 16-byte store per lane, through to memory: the piece with its epoch
+        const rsrc_t t_rs = make_rsrc(a.T, (uint32_t)a.kh * kMaxTokens * (rp / 4) * 16u);
+        const uint32_t off = (((uint32_t)kh * kMaxTokens + lx) * (rp / 4) + 4 * rt + ly) * 16u;
+        typedef unsigned int store4_t __attribute__((__vector_size__(16)));
+        const store4_t piece = {a.epoch, 0u, hb[0], hb[1]};
+        __builtin_amdgcn_raw_buffer_store_b128(piece, t_rs, (int)off, 0, kScopeDevice);
     }
 }
 
@@ -144,7 +150,8 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     const int lx = lane & 15;
     const int ly = lane >> 4;
     const int S = a.S;
-    const int tpw = nw / S;              // tiles per workgroup and round
+    const int nwc = nw - a.helpers;      // working wavefronts; the helpers come after them
+    const int tpw = nwc / S;             // tiles per workgroup and round
     const int ts = wave / S;             // tile slot of this wavefront
     const int s = wave - ts * S;         // its share of the inputs and of the ranks
     const int rp = a.rank_pad;
@@ -242,10 +249,12 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
             uint4_t v[XB];
 #pragma unroll
             for (int i = 0; i < XB; ++i) v[i] = x_load(i);
-            issue_item(tile_of(ir), ij, bufA);
-            advance(ir, ij);
-            issue_item(tile_of(ir), ij, bufB);
-            advance(ir, ij);
+            if (wave < nwc) {
+                issue_item(tile_of(ir), ij, bufA);
+                advance(ir, ij);
+                issue_item(tile_of(ir), ij, bufB);
+                advance(ir, ij);
+            }
 #pragma unroll
             for (int i = 0; i < XB; ++i) x_store(i, v[i]);
         }
@@ -257,51 +266,100 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
             for (int i = 0; i < 4; ++i) x_store(p0 + i, v[i]);
         }
     }
-    // T -> LDS (all threads; the caller has made T visible)
-    auto stage_t = [&](int first, int stride) {
-        const int per_row = rp / 8;
-        const int total = rows_x * per_row;
-        for (int e = first; e < total; e += stride) {
-            const int row = e / per_row, c = e - row * per_row;
-            half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (row < a.m)
-                for (int p = 0; p < a.kh; ++p)
-                    v += *reinterpret_cast<const half8_t *>(a.T + ((size_t)p * kMaxTokens + row) * rp + c * 8);
-            *reinterpret_cast<half8_t *>(t_lds + row * ldt + c * 8) = v;
-        }
-    };
-    // T is needed when the first rank step starts.  Two launches: it is complete,
-    // all threads stage it now.  One launch: wavefront 0 waits for the flags and
-    // stages T alone while the others work on the packed term; the workgroup meets
-    // at one barrier before its first rank step (t_ready).
-    bool t_ready = rp == 0;
-    if (a.mode == 1 && rp > 0) {
-        stage_t(threadIdx.x, blockDim.x);
-        t_ready = true;
-    }
     __syncthreads();
-    const unsigned *my_flags = a.flags + 512 * (yb % kFlagCopies);
-    auto wait_flags = [&]() {
-        bool done = false;
-        for (int spin = 0; spin < kSpinLimit && !done; ++spin) {
-            bool mine = true;
-            for (int r = lane; r < a.n_r; r += kWave)
-                mine = mine && __hip_atomic_load(my_flags + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
-            done = __all(mine);
-            if (!done) __builtin_amdgcn_s_sleep(8);
+
+    // ---- helpers: T -> LDS ----
+    // A helper lane owns (token, four ranks) pairs hl, hl + 64 helpers, ...; a pair
+    // has one piece per share.  It re-reads its pieces (device scope) until each
+    // carries this call's epoch, adds the shares and writes four halves to LDS.
+    if (wave >= nwc) {
+        const rsrc_t t_rs = make_rsrc(a.T, (uint32_t)a.kh * kMaxTokens * (rp / 4) * 16u);
+        const int hl = (int)threadIdx.x - nwc * kWave;
+        const int hn = a.helpers * kWave;
+        const int qpr = rp / 4;                           // pairs per token
+        const int pairs = a.m * qpr;
+        int spins = 0;
+        bool gave_up = false;
+        auto piece_off = [&](int pair, int share) {
+            const int row = pair / qpr, q = pair - row * qpr;
+            return pair < pairs ? (((uint32_t)share * kMaxTokens + row) * qpr + q) * 16u : kNowhere;
+        };
+        auto fetch = [&](auto khc) {
+            constexpr int KH = decltype(khc)::value;
+            constexpr int PB = 8 / KH;                    // pairs per batch: 8 loads in flight
+            // the first piece alone until it is there: a cheap poll while T is being made
+            {
+                const uint32_t off0 = piece_off(hl, 0);
+                bool there = off0 == kNowhere;
+                while (!__all(there) && spins < kSpinLimit) {
+                    const uint4_t pc = __builtin_bit_cast(uint4_t, __builtin_amdgcn_raw_buffer_load_b128(t_rs, (int)off0, 0, kScopeDevice));
+                    there = there || pc[0] == a.epoch;
+                    ++spins;
+                    if (!__all(there)) __builtin_amdgcn_s_sleep(4);
+                }
+            }
+            for (int p0 = hl; p0 < pairs; p0 += PB * hn) {        // p0 differs per lane: every lane runs its own count
+                uint4_t pc[PB * KH];
+                bool all_there = false;
+                while (!all_there) {
+#pragma unroll
+                    for (int i = 0; i < PB; ++i)
+#pragma unroll
+                        for (int h = 0; h < KH; ++h)
+                            pc[i * KH + h] = __builtin_bit_cast(
+                                uint4_t, __builtin_amdgcn_raw_buffer_load_b128(t_rs, (int)piece_off(p0 + i * hn, h), 0, kScopeDevice));
+                    all_there = true;
+#pragma unroll
+                    for (int i = 0; i < PB; ++i)
+#pragma unroll
+                        for (int h = 0; h < KH; ++h)
+                            all_there = all_there && (p0 + i * hn >= pairs || pc[i * KH + h][0] == a.epoch);
+                    if (!all_there) {
+                        if (++spins >= kSpinLimit) {
+                            gave_up = true;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(4);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < PB; ++i) {
+                    const int pair = p0 + i * hn;
+                    half4_t sum = {0, 0, 0, 0};
+#pragma unroll
+                    for (int h = 0; h < KH; ++h) sum += __builtin_bit_cast(half4_t, uint2_t{pc[i * KH + h][2], pc[i * KH + h][3]});
+                    if (pair < pairs) {
+                        const int row = pair / qpr, q = pair - row * qpr;
+                        *reinterpret_cast<half4_t *>(t_lds + row * ldt + 4 * q) = sum;
+                    }
+                }
+            }
+        };
+        if (rp > 0) {
+            // rows >= m and the zero row
+            for (int e = hl; e < (rows_x - a.m) * (rp / 8); e += hn) {
+                const int row = a.m + e / (rp / 8), c = e % (rp / 8);
+                *reinterpret_cast<uint4_t *>(t_lds + row * ldt + c * 8) = zero;
+            }
+            if (a.kh == 1)
+                fetch(std::integral_constant<int, 1>{});
+            else if (a.kh == 2)
+                fetch(std::integral_constant<int, 2>{});
+            else
+                fetch(std::integral_constant<int, 4>{});
+            if ((gave_up || spins >= kSpinLimit) && a.err) __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        if (!done && lane == 0) __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // what the R-role workgroups stored before raising their flags is read after this
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    };
-    // the workgroup's meeting before its first rank step: wavefront 0 has seen the
-    // flags, then all threads stage T
-    auto meet_for_t = [&]() {
-        if (wave == 0) wait_flags();
+        // the barriers of the working wavefronts: T, then those of every round
         __syncthreads();
-        stage_t(threadIdx.x, blockDim.x);
-        __syncthreads();
-    };
+        for (int r = 0; r < rounds; ++r)
+            if (S > 1) {
+                __syncthreads();
+                if (r + 1 < rounds) __syncthreads();
+            }
+        return;
+    }
+    bool t_ready = a.helpers == 0;
+    auto meet_for_t = [&]() { __syncthreads(); };     // the helpers arrive when T is in LDS
 
     // this lane's B-operand rows: its token, or the zero row
     const int trow = lx < a.mp ? lx : a.mp;       // mp == 16: always lx
@@ -428,27 +486,30 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
     p.mp = pad_tokens16(m);
     p.kpad = (k + 1023) / 1024 * 1024;
     p.waves = waves;
+    // helpers: enough lanes that one batch of 16 loads each covers T
+    p.helpers = rank_pad == 0 ? 0 : (p.mp <= 4 ? 1 : (p.mp <= 8 ? 2 : 4));
+    const int total = waves + p.helpers;          // wavefronts of a workgroup
     const long wtiles = (n + 15) / 16;
     {
-        // Shares of the inputs in the R role: one unit per wavefront (T as early as
-        // possible) for layers with few row tiles, where the Y role is short and
-        // waits for T; one share otherwise, which leaves the compute units to the Y role.
+        // Shares of the inputs in the R role (1, 2 or 4): one unit per wavefront (T as
+        // early as possible) for layers with few row tiles, where the Y role is short
+        // and waits for T; one share otherwise, which leaves the compute units to the Y role.
         const int units = (k + 255) / 256;
-        const int kh = wtiles <= kShareTiles ? (units + waves - 1) / waves : 1;
-        p.kh = kh < 1 ? 1 : (kh > kMaxShares ? kMaxShares : kh);
+        const int want = wtiles <= kShareTiles ? (units + total - 1) / total : 1;
+        p.kh = want <= 1 ? 1 : (want <= 2 ? 2 : kMaxShares);
         p.upk = (units + p.kh - 1) / p.kh;
     }
     p.n_r = (rank_pad / 16) * p.kh;
     const int rows_x = p.mp < kMaxTokens ? p.mp + 1 : kMaxTokens;
     const size_t lds_x = (size_t)rows_x * ((p.kpad + kLdsPad) + (rank_pad + kLdsPad)) * sizeof(half_t);
-    const size_t red_r = (size_t)(waves - 1) * kWave * 16;
+    const size_t red_r = (size_t)(total - 1) * kWave * 16;
     for (int S = waves; S >= 1; S /= 2) {
         const int tpw = waves / S;
         const size_t red_y = S > 1 ? (size_t)tpw * (S - 1) * kWave * 16 : 0;
         const size_t lds = lds_x + red_y > red_r ? lds_x + red_y : red_r;
         if (lds > 160 * 1024) continue;
         // workgroups a compute unit holds: registers allow kFusedResidentWaves wavefronts
-        long per_cu = kFusedResidentWaves / waves;
+        long per_cu = kFusedResidentWaves / total;
         if (per_cu > (long)(160 * 1024 / lds)) per_cu = (long)(160 * 1024 / lds);
         const long slots = 256 * per_cu - p.n_r;
         const long wgs = (wtiles + tpw - 1) / tpw;
@@ -469,15 +530,14 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
 // per compute unit where the LDS permits.
 FusedPlan plan_fused(int n, int k, int rank_pad, int m)
 {
-    const FusedPlan a = plan_fused_waves(n, k, rank_pad, m, kFusedMaxThreads / kWave);
+    const FusedPlan a = plan_fused_waves(n, k, rank_pad, m, 8);
     return a.ok ? a : plan_fused_waves(n, k, rank_pad, m, 4);
 }
 
 static std::atomic<unsigned> g_epoch{0};
 
 // mode: 2 = one launch, 1 = the two roles as two launches
-int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t *Y, half_t *T, unsigned *flags,
-                        unsigned *err, const FusedPlan &p, int mode, hipStream_t st)
+int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t *Y, void *T, unsigned *err, const FusedPlan &p, int mode, hipStream_t st)
 {
     FusedArgs a{};
     a.qvals = layer->qvals;
@@ -487,11 +547,10 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     a.L = reinterpret_cast<const half_t *>(layer->L);
     a.X = X;
     a.Y = Y;
-    a.T = T;
-    a.flags = flags;
+    a.T = static_cast<uint4_t *>(T);
     a.err = err;
     unsigned e = ++g_epoch;
-    if (e == 0) e = ++g_epoch;          // flags start as zeros: epoch 0 is never used
+    if (e == 0) e = ++g_epoch;          // a zero-filled workspace must not look valid: epoch 0 is never used
     a.epoch = e;
     a.n = layer->shape.n;
     a.k = layer->shape.k;
@@ -501,9 +560,10 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     a.kpad = p.kpad;
     a.S = p.S;
     a.n_r = p.n_r;
+    a.helpers = p.helpers;
     a.kh = p.kh;
     a.upk = p.upk;
-    const dim3 blk(p.waves * kWave);
+    const dim3 blk((p.waves + p.helpers) * kWave);
     // X pieces per thread: (token rows + zero row) x pieces of a row per thread
     const int rows_x = p.mp < kMaxTokens ? p.mp + 1 : kMaxTokens;
     const int np = rows_x * ((p.kpad / 8 + (int)blk.x - 1) / (int)blk.x);

@@ -145,8 +145,8 @@ inline int hip_status(hipError_t e) { return e == hipSuccess ? SLIM_OK : SLIM_ER
 // each a multiple of 256).
 struct WorkspacePlan {
     size_t dec_off, dec_bytes;    // decode state: 256 B of control words, then two T buffers fp32 [16][rank_pad],
-                                  // then (one-launch path) 16 copies of 2 KiB of flags and T as up to four fp16 planes [16][rank_pad]
-    size_t flag_off, t16_off;     // the last two, as offsets into the workspace
+                                  // then (one-launch path) T as up to four planes [16][rank_pad / 4] of 16-byte pieces
+    size_t t16_off;               // the last, as an offset into the workspace
     size_t t_off, t_bytes;        // gemm: T = X R^T as fp16 [m][rank_pad]
     size_t acc_off, acc_bytes;    // decode: partial quantized term, fp32 [slots][m][n]
     size_t part_off, part_bytes;  // gemm: split-K partials of T, fp32 [splits][m][rank_pad]
