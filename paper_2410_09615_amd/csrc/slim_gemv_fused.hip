@@ -44,11 +44,9 @@
 namespace slim {
 
 constexpr int kFusedMaxThreads = 768;      // 8 working wavefronts + up to 4 helpers
-constexpr int kFusedWavesPerSimd = 3;   // the kernel is compiled for this many wavefronts per SIMD (168 registers)
 constexpr int kScopeDevice = 16;      // cache policy of a buffer access: device scope (written through / read from memory)
 constexpr int kMaxShares = 4;         // R role: at most this many shares of the inputs (planes of T)
 constexpr int kShareTiles = 384;       // ... for layers of at most this many row tiles
-constexpr int kFusedResidentWaves = 4 * kFusedWavesPerSimd;     // wavefronts a compute unit holds at this kernel's register count
 constexpr int kSpinLimit = 1 << 16;
 constexpr uint32_t kNowhere = 0x80000000u;       // byte offset past the end of every buffer here (all are < 2 GiB)
 
@@ -64,7 +62,6 @@ struct FusedArgs {
     unsigned *err;       // set to 1 when a wait gave up
     unsigned epoch;
     int n, k, rank_pad, m;
-    int mp;              // token rows of the LDS tiles (1, 4, 8, 16)
     int kpad;            // k rounded up to 1024: extent of an X row in LDS
     int S;               // wavefronts per row tile
     int n_r;             // R-role workgroups: (rank_pad / 16) tiles x kh shares of the inputs
@@ -155,7 +152,8 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     const int ts = wave / S;             // tile slot of this wavefront
     const int s = wave - ts * S;         // its share of the inputs and of the ranks
     const int rp = a.rank_pad;
-    const int rows_x = a.mp < kMaxTokens ? a.mp + 1 : kMaxTokens;    // token rows, then a zero row if a lane needs one
+    const int rows_x = a.m;              // token rows in LDS; the lanes of the other columns of a matrix
+                                         // operand read row 0 and their results are not stored
     const int ldx = a.kpad + kLdsPad;
     const int ldt = rp + kLdsPad;
     half_t *x_lds = lds;
@@ -224,7 +222,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     int ir = 0, ij = 0;              // next item to load
     UnitRegs bufA, bufB;
 
-    // X -> LDS: rows >= m zero, inputs past k zero up to kpad.  A thread takes
+    // X -> LDS: m rows, inputs past k zero up to kpad.  A thread takes
     // the pieces tid, tid + threads, ... of every row.  Order of the loads (they
     // return in order): the thread's first 16 X pieces, then the first two items;
     // the X pieces go to LDS while the items are still on their way, so the copy
@@ -243,7 +241,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
             const int row = p / cpr, c = (int)threadIdx.x + (p - row * cpr) * bd;
             if (p < np && c < per_row) *reinterpret_cast<uint4_t *>(x_lds + row * ldx + c * 8) = v;
         };
-        // XB = pieces in the first batch: the kernel is built for 2, 6 and 16, the
+        // XB = pieces in the first batch: the kernel is built for 2, 8 and 16, the
         // launch takes the smallest that covers the thread's pieces (or 16)
         {
             uint4_t v[XB];
@@ -336,11 +334,6 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
             }
         };
         if (rp > 0) {
-            // rows >= m and the zero row
-            for (int e = hl; e < (rows_x - a.m) * (rp / 8); e += hn) {
-                const int row = a.m + e / (rp / 8), c = e % (rp / 8);
-                *reinterpret_cast<uint4_t *>(t_lds + row * ldt + c * 8) = zero;
-            }
             if (a.kh == 1)
                 fetch(std::integral_constant<int, 1>{});
             else if (a.kh == 2)
@@ -361,8 +354,8 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     bool t_ready = a.helpers == 0;
     auto meet_for_t = [&]() { __syncthreads(); };     // the helpers arrive when T is in LDS
 
-    // this lane's B-operand rows: its token, or the zero row
-    const int trow = lx < a.mp ? lx : a.mp;       // mp == 16: always lx
+    // this lane's B-operand rows: its token, or any row at all
+    const int trow = lx < a.m ? lx : 0;
     const half_t *xrow_packed = x_lds + trow * ldx + 128 * (ly >> 1) + 8 * (ly & 1);
     const half_t *trow_l = t_lds + trow * ldt + 8 * ly;
 
@@ -461,8 +454,10 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     }
 }
 
-template <int XB>
-__global__ __launch_bounds__(kFusedMaxThreads, kFusedWavesPerSimd) void decode_fused_kernel(FusedArgs a)
+// XB: X pieces of a thread in the first batch.  WPS: wavefronts per SIMD the
+// kernel is compiled for (4: 128 registers, 3: 168; the large batch needs them).
+template <int XB, int WPS>
+__global__ __launch_bounds__(kFusedMaxThreads, WPS) void decode_fused_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) half_t lds[];
     if (a.mode == 0) {
@@ -477,6 +472,12 @@ __global__ __launch_bounds__(kFusedMaxThreads, kFusedWavesPerSimd) void decode_f
 }
 
 static int pad_tokens16(int m) { return m <= 1 ? 1 : (m <= 4 ? 4 : (m <= 8 ? 8 : 16)); }
+
+// X pieces per thread: token rows x pieces of a row per thread.
+static int fused_x_pieces(int m, int kpad, int threads)
+{
+    return m * ((kpad / 8 + threads - 1) / threads);
+}
 
 // Geometry for one workgroup size: the shares of the R role, and the largest S
 // (wavefronts per row tile) with which every workgroup is resident at once.
@@ -500,16 +501,16 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
         p.upk = (units + p.kh - 1) / p.kh;
     }
     p.n_r = (rank_pad / 16) * p.kh;
-    const int rows_x = p.mp < kMaxTokens ? p.mp + 1 : kMaxTokens;
-    const size_t lds_x = (size_t)rows_x * ((p.kpad + kLdsPad) + (rank_pad + kLdsPad)) * sizeof(half_t);
+    const size_t lds_x = (size_t)m * ((p.kpad + kLdsPad) + (rank_pad + kLdsPad)) * sizeof(half_t);
     const size_t red_r = (size_t)(total - 1) * kWave * 16;
     for (int S = waves; S >= 1; S /= 2) {
         const int tpw = waves / S;
         const size_t red_y = S > 1 ? (size_t)tpw * (S - 1) * kWave * 16 : 0;
         const size_t lds = lds_x + red_y > red_r ? lds_x + red_y : red_r;
         if (lds > 160 * 1024) continue;
-        // workgroups a compute unit holds: registers allow kFusedResidentWaves wavefronts
-        long per_cu = kFusedResidentWaves / total;
+        // workgroups a compute unit holds: its registers take 16 wavefronts of the
+        // kernels with a small first X batch, 12 of the other
+        long per_cu = (fused_x_pieces(m, p.kpad, total * kWave) <= 8 ? 16 : 12) / total;
         if (per_cu > (long)(160 * 1024 / lds)) per_cu = (long)(160 * 1024 / lds);
         const long slots = 256 * per_cu - p.n_r;
         const long wgs = (wtiles + tpw - 1) / tpw;
@@ -556,7 +557,6 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     a.k = layer->shape.k;
     a.rank_pad = layer->rank_pad;
     a.m = m;
-    a.mp = p.mp;
     a.kpad = p.kpad;
     a.S = p.S;
     a.n_r = p.n_r;
@@ -564,16 +564,14 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     a.kh = p.kh;
     a.upk = p.upk;
     const dim3 blk((p.waves + p.helpers) * kWave);
-    // X pieces per thread: (token rows + zero row) x pieces of a row per thread
-    const int rows_x = p.mp < kMaxTokens ? p.mp + 1 : kMaxTokens;
-    const int np = rows_x * ((p.kpad / 8 + (int)blk.x - 1) / (int)blk.x);
+    const int np = fused_x_pieces(m, p.kpad, (int)blk.x);
     auto launch = [&](unsigned grid) {
         if (np <= 2)
-            hipLaunchKernelGGL(decode_fused_kernel<2>, dim3(grid), blk, p.lds, st, a);
-        else if (np <= 6)
-            hipLaunchKernelGGL(decode_fused_kernel<6>, dim3(grid), blk, p.lds, st, a);
+            hipLaunchKernelGGL((decode_fused_kernel<2, 4>), dim3(grid), blk, p.lds, st, a);
+        else if (np <= 8)
+            hipLaunchKernelGGL((decode_fused_kernel<8, 4>), dim3(grid), blk, p.lds, st, a);
         else
-            hipLaunchKernelGGL(decode_fused_kernel<16>, dim3(grid), blk, p.lds, st, a);
+            hipLaunchKernelGGL((decode_fused_kernel<16, 3>), dim3(grid), blk, p.lds, st, a);
     };
     if (mode == 2 || p.n_r == 0) {
         a.mode = p.n_r == 0 ? 1 : 2;
