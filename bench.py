@@ -36,7 +36,7 @@ CACHE_BYTES = 256 << 20         # Infinity Cache
 # the headline layer) from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE),
 # scaled by the 256 MiB copy below (one FETCH_SIZE unit = 2 KiB, one WRITE_SIZE
 # unit = 1 KiB).  Source: profiles/decode_gemv_llama7b_attn_16tok_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = 18.32e6   # 15.41 MB read + 2.91 MB written per slim_linear_gemv call at 16 tokens
+MEASURED_TRAFFIC_BYTES = 15.21e6   # 15.03 MB read + 0.18 MB written per slim_linear_gemv call at 16 tokens
 
 
 def parse_args():
@@ -200,7 +200,7 @@ def main():
     dom_bytes = A.layer_bytes(shape.n, shape.k, shape.r, dom_m)
     dom_ms = per_m[dom_m]["us"] * 1e-3
     roofline = {
-        "bound": "hbm", "kernel": f"slim_linear_gemv = decode_part1_kernel + decode_part2_kernel, {dom_m} tokens",
+        "bound": "hbm", "kernel": f"slim_linear_gemv = decode_fused_kernel (one launch), {dom_m} tokens",
         "achieved": round(dom_bytes / dom_ms * 1e-6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(dom_bytes / dom_ms * 1e-6 / HBM_PEAK_GBPS, 4),
         "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_bytes": dom_bytes,
