@@ -140,10 +140,14 @@ int slim_unpack(const uint8_t *qvals, const uint8_t *meta, slim_shape shape, int
  * The same size covers slim_linear_gemv (m <= 16), slim_linear_gemm and
  * slim_lowrank.
  * The workspace must be ZERO-FILLED ONCE before its first use (hipMemset):
- * its first bytes hold a small accumulator (T = X R^T of the decode path,
- * added to with atomics) and a counter that every decode call finds zero and
- * leaves zero.  Nothing else is carried between calls.  Two calls that
- * overlap in time need two workspaces.
+ * its first bytes hold the decode path's T = X R^T between the kernels' two
+ * phases (pieces tagged with a call number, never 0; two accumulators and a
+ * counter for the layers that take the two-launch path), and a fresh
+ * workspace must not look like finished work.  Nothing else is carried
+ * between calls.  Two calls that overlap in time need two workspaces.
+ * Diagnostics: word 2 of the workspace is set to 1 if a decode call gave up
+ * waiting for its own T (it never should; the call then returned wrong
+ * numbers instead of hanging).
  */
 int slim_workspace_bytes(const slim_layer *layer, int32_t m, size_t *bytes);
 
@@ -152,6 +156,11 @@ int slim_workspace_bytes(const slim_layer *layer, int32_t m, size_t *bytes);
  * "small batch sizes during decoding", Sec. 4 "Speedup").  Streams the packed
  * rows and the adapters once; fp16 inputs, fp32 accumulation, Y rounded once
  * to fp16.  X [m][k] fp16 in, Y [m][n] fp16 out.
+ * One kernel launch where m rows of X and T fit the LDS of a compute unit
+ * (m (k + rank_pad) fp16 within about 150 KiB), two launches otherwise.  The
+ * environment variable SLIM_DECODE_PATH = parts | roles | fused forces the
+ * two-launch kernels, the one-launch kernel's two roles as two launches, or
+ * the one-launch kernel where it is eligible (measurement and tests).
  * Requires k % 128 == 0.  Errors: NULL, SHAPE (m out of range, k), ALIGN,
  * WORKSPACE, HIP.
  */
