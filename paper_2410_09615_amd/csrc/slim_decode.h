@@ -50,7 +50,7 @@ __device__ __forceinline__ void packed_half(const UnitRegs &b, const half_t *xh,
 // Geometry and launch of the one-launch decode path (slim_gemv_fused.hip).
 struct FusedPlan {
     bool ok;            // the layer and token count fit this path
-    int mp, kpad, S, waves, helpers, n_r, kh, upk, ygrid;
+    int mp, kpad, kc, nch, S, waves, helpers, n_r, kh, upk, ygrid;
     size_t lds;
 };
 FusedPlan plan_fused(int n, int k, int rank_pad, int m);

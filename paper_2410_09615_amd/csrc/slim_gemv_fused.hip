@@ -37,6 +37,7 @@
 //
 // T is rounded to fp16 once per share here (prefill: once).
 #include <atomic>
+#include <cstdlib>
 #include <type_traits>
 
 #include "slim_decode.h"
@@ -47,7 +48,9 @@ constexpr int kFusedMaxThreads = 768;      // 8 working wavefronts + up to 4 hel
 constexpr int kScopeDevice = 16;      // cache policy of a buffer access: device scope (written through / read from memory)
 constexpr int kMaxShares = 4;         // R role: at most this many shares of the inputs (planes of T)
 constexpr int kShareTiles = 384;       // ... for layers of at most this many row tiles
+constexpr int kFusedWavesPerSimd = 4;   // the kernel is compiled for 128 registers: 16 wavefronts per compute unit
 constexpr int kSpinLimit = 1 << 16;
+constexpr int kWaitVm0 = 0x0F70;       // s_waitcnt vmcnt(0) (expcnt, lgkmcnt left alone): all vector memory loads of the wavefront are back
 constexpr uint32_t kNowhere = 0x80000000u;       // byte offset past the end of every buffer here (all are < 2 GiB)
 
 struct FusedArgs {
@@ -62,7 +65,9 @@ struct FusedArgs {
     unsigned *err;       // set to 1 when a wait gave up
     unsigned epoch;
     int n, k, rank_pad, m;
-    int kpad;            // k rounded up to 1024: extent of an X row in LDS
+    int kpad;            // k rounded up to 1024
+    int kc;              // inputs per chunk of X in LDS (multiple of 1024; kpad: all of X at once)
+    int nch;             // chunks: more than one -> two LDS buffers, the helpers stage chunk c + 1 during chunk c
     int S;               // wavefronts per row tile
     int n_r;             // R-role workgroups: (rank_pad / 16) tiles x kh shares of the inputs
     int kh;              // shares of the inputs in the R role = planes of T
@@ -138,7 +143,6 @@ __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb
 }
 
 // ---- Y role ----
-template <int XB>
 __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, int ygrid)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -154,18 +158,24 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     const int rp = a.rank_pad;
     const int rows_x = a.m;              // token rows in LDS; the lanes of the other columns of a matrix
                                          // operand read row 0 and their results are not stored
-    const int ldx = a.kpad + kLdsPad;
+    const int ldx = a.kc + kLdsPad;
     const int ldt = rp + kLdsPad;
+    const int nch = a.nch;
+    // LDS: one X buffer, then T, then the partial results; with chunks: two X
+    // buffers, T takes the place of the buffer that is free during the last chunk
     half_t *x_lds = lds;
-    half_t *t_lds = lds + rows_x * ldx;
-    float *red = reinterpret_cast<float *>(t_lds + rows_x * ldt);
+    const int xbuf = rows_x * ldx;               // halves per X buffer
+    half_t *t_lds = nch > 1 ? lds + (nch & 1) * xbuf : lds + xbuf;
+    float *red = reinterpret_cast<float *>(nch > 1 ? lds + 2 * xbuf : lds + xbuf + rows_x * ldt);
     const int wtiles = (a.n + 15) / 16;
     const int H = (a.k + 511) / 512;             // halves of a row
-    const int Hp = a.kpad / 512;
+    const int hc = a.kc / 512;                   // halves per chunk
     const int steps = rp / 32;                   // steps of 32 ranks
-    const int cnt_h = s < H ? (H - s + S - 1) / S : 0;
+    // halves of this wavefront per chunk: s, s + S, ... < hc (with chunks S divides hc: the same for all)
+    const int hpc = s < hc ? (hc - s + S - 1) / S : 0;
+    const int ipc = (hpc + 1) / 2;               // items (of two halves) per chunk
     const int cnt_l = s < steps ? (steps - s + S - 1) / S : 0;
-    const int nP = (cnt_h + 1) / 2;              // items of two halves
+    const int nP = nch * ipc;
     const int nL = (cnt_l + 7) / 8;              // items of eight steps
     const int nI = nP + nL;
     const int tile0 = yb * tpw + ts;
@@ -184,11 +194,13 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     auto issue_item = [&](int ot, int j, UnitRegs &b) {
         const uint32_t o = 16u * ot + lx;
         if (j < nP) {
+            const int c = j / ipc, jj = j - c * ipc;        // chunk, item within the chunk
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
-                const int h = s + S * (2 * j + x);
+                const int hl = s + S * (2 * jj + x);        // half within the chunk
+                const int h = c * hc + hl;
                 const int kl = 512 * h + 128 * ly;          // the lane's 128 inputs: one tile column of the packed layout
-                const bool ok = h < H && kl < a.k && ot < wtiles;
+                const bool ok = hl < hc && h < H && kl < a.k && ot < wtiles;
                 const uint32_t qo = ok ? (uint32_t)pk_qoff(o, (uint32_t)kl / 4, kt) : kNowhere;
                 const uint32_t mo = ok ? (uint32_t)pk_moff(o, (uint32_t)kl / 8, kt) : kNowhere;
                 b.r[3 * x] = load16(q_rs, qo, 0);
@@ -222,55 +234,54 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     int ir = 0, ij = 0;              // next item to load
     UnitRegs bufA, bufB;
 
-    // X -> LDS: m rows, inputs past k zero up to kpad.  A thread takes
-    // the pieces tid, tid + threads, ... of every row.  Order of the loads (they
-    // return in order): the thread's first 16 X pieces, then the first two items;
-    // the X pieces go to LDS while the items are still on their way, so the copy
-    // costs one round trip to the L2 up to 128 KiB per workgroup.
-    {
-        const rsrc_t x_rs = make_rsrc(a.X, (uint32_t)a.m * a.k * 2u);
-        const int bd = blockDim.x;
-        const int per_row = a.kpad / 8;                  // pieces per row
-        const int cpr = (per_row + bd - 1) / bd;         // ... and thread
-        const int np = rows_x * cpr;
-        auto x_load = [&](int p) {
-            const int row = p / cpr, c = (int)threadIdx.x + (p - row * cpr) * bd;
-            return load16(x_rs, (p < np && row < a.m && c * 8 < a.k) ? ((uint32_t)row * a.k + c * 8) * 2u : kNowhere, 0);
-        };
-        auto x_store = [&](int p, uint4_t v) {
-            const int row = p / cpr, c = (int)threadIdx.x + (p - row * cpr) * bd;
-            if (p < np && c < per_row) *reinterpret_cast<uint4_t *>(x_lds + row * ldx + c * 8) = v;
-        };
-        // XB = pieces in the first batch: the kernel is built for 2, 8 and 16, the
-        // launch takes the smallest that covers the thread's pieces (or 16)
-        {
-            uint4_t v[XB];
-#pragma unroll
-            for (int i = 0; i < XB; ++i) v[i] = x_load(i);
-            if (wave < nwc) {
-                issue_item(tile_of(ir), ij, bufA);
-                advance(ir, ij);
-                issue_item(tile_of(ir), ij, bufB);
-                advance(ir, ij);
-            }
-#pragma unroll
-            for (int i = 0; i < XB; ++i) x_store(i, v[i]);
-        }
-        for (int p0 = XB; p0 < np; p0 += 4) {
-            uint4_t v[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = x_load(p0 + i);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) x_store(p0 + i, v[i]);
-        }
+    // the first two items' loads go out before anything else
+    if (wave < nwc) {
+        issue_item(tile_of(ir), ij, bufA);
+        advance(ir, ij);
+        issue_item(tile_of(ir), ij, bufB);
+        advance(ir, ij);
     }
-    __syncthreads();
 
     // ---- helpers: T -> LDS ----
     // A helper lane owns (token, four ranks) pairs hl, hl + 64 helpers, ...; a pair
     // has one piece per share.  It re-reads its pieces (device scope) until each
     // carries this call's epoch, adds the shares and writes four halves to LDS.
     if (wave >= nwc) {
+        // X -> LDS, by the helpers alone, with loads that write LDS directly (no
+        // registers: a wavefront keeps dozens of KiB in flight).  One load
+        // instruction moves a row segment of 512 inputs (64 lanes x 16 bytes,
+        // contiguous in LDS); inputs past k read as zero.  Chunk c goes into
+        // buffer c & 1; chunks 0 and 1 go out at once, chunk c + 1 when the working
+        // wavefronts have left chunk c - 1 (the barrier that opens chunk c).
+        {
+            const rsrc_t x_rs = make_rsrc(a.X, (uint32_t)a.m * a.k * 2u);
+            const int hw = wave - nwc;                        // helper index
+            auto stage_chunk = [&](int c) {
+                half_t *dst = x_lds + (c & 1) * xbuf;
+                for (int idx = hw; idx < rows_x * hc; idx += a.helpers) {
+                    const int row = idx / hc, seg = idx - row * hc;
+                    const int col = c * a.kc + seg * 512 + lane * 8;
+                    const uint32_t off = col < a.k ? ((uint32_t)row * a.k + col) * 2u : kNowhere;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        x_rs, (__attribute__((address_space(3))) void *)(dst + row * ldx + seg * 512), 16, (int)off, 0, 0, 0);
+                }
+            };
+            stage_chunk(0);
+            if (nch > 1) {
+                stage_chunk(1);
+                // chunk 0 is complete when at most the loads of chunk 1 are outstanding;
+                // they return in order, so waiting for all of them is the simple upper bound
+            }
+            __builtin_amdgcn_s_waitcnt(kWaitVm0);
+            __syncthreads();                                  // chunk 0 (and 1) in LDS
+            for (int c = 1; c < nch; ++c) {
+                __syncthreads();                              // opens chunk c: chunk c - 1 is done with
+                if (c + 1 < nch) {
+                    stage_chunk(c + 1);
+                    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+                }
+            }
+        }
         const rsrc_t t_rs = make_rsrc(a.T, (uint32_t)a.kh * kMaxTokens * (rp / 4) * 16u);
         const int hl = (int)threadIdx.x - nwc * kWave;
         const int hn = a.helpers * kWave;
@@ -343,7 +354,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
             if ((gave_up || spins >= kSpinLimit) && a.err) __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         // the barriers of the working wavefronts: T, then those of every round
-        __syncthreads();
+        if (rp > 0) __syncthreads();
         for (int r = 0; r < rounds; ++r)
             if (S > 1) {
                 __syncthreads();
@@ -351,7 +362,8 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
             }
         return;
     }
-    bool t_ready = a.helpers == 0;
+    __syncthreads();                 // the helpers have put chunk 0 of X into LDS
+    bool t_ready = rp == 0;
     auto meet_for_t = [&]() { __syncthreads(); };     // the helpers arrive when T is in LDS
 
     // this lane's B-operand rows: its token, or any row at all
@@ -390,9 +402,12 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
             }
         }
         if (j < nP) {
-            const int h0 = min(s + S * (2 * j), Hp - 1), h1 = min(s + S * (2 * j + 1), Hp - 1);
-            packed_half<0>(cur, xrow_packed + 512 * h0, acc0, acc1);
-            packed_half<1>(cur, xrow_packed + 512 * h1, acc0, acc1);
+            const int c = j / ipc, jj = j - c * ipc;
+            if (c > 0 && jj == 0) __syncthreads();     // chunk c is in LDS; everybody has left chunk c - 1
+            const half_t *xc = xrow_packed + (c & 1) * xbuf;
+            const int h0 = min(s + S * (2 * jj), hc - 1), h1 = min(s + S * (2 * jj + 1), hc - 1);
+            packed_half<0>(cur, xc + 512 * h0, acc0, acc1);
+            packed_half<1>(cur, xc + 512 * h1, acc0, acc1);
         } else if (j < nI) {
             const int t0 = s + S * 8 * (j - nP);
 #pragma unroll
@@ -454,72 +469,91 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     }
 }
 
-// XB: X pieces of a thread in the first batch.  WPS: wavefronts per SIMD the
-// kernel is compiled for (4: 128 registers, 3: 168; the large batch needs them).
-template <int XB, int WPS>
-__global__ __launch_bounds__(kFusedMaxThreads, WPS) void decode_fused_kernel(FusedArgs a)
+__global__ __launch_bounds__(kFusedMaxThreads, kFusedWavesPerSimd) void decode_fused_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) half_t lds[];
     if (a.mode == 0) {
         role_r(a, lds, blockIdx.x);
     } else if (a.mode == 1) {
-        role_y<XB>(a, lds, blockIdx.x, gridDim.x);
+        role_y(a, lds, blockIdx.x, gridDim.x);
     } else if ((int)blockIdx.x < a.n_r) {
         role_r(a, lds, blockIdx.x);
     } else {
-        role_y<XB>(a, lds, (int)blockIdx.x - a.n_r, (int)gridDim.x - a.n_r);
+        role_y(a, lds, (int)blockIdx.x - a.n_r, (int)gridDim.x - a.n_r);
     }
 }
 
 static int pad_tokens16(int m) { return m <= 1 ? 1 : (m <= 4 ? 4 : (m <= 8 ? 8 : 16)); }
 
-// X pieces per thread: token rows x pieces of a row per thread.
-static int fused_x_pieces(int m, int kpad, int threads)
-{
-    return m * ((kpad / 8 + threads - 1) / threads);
-}
-
-// Geometry for one workgroup size: the shares of the R role, and the largest S
-// (wavefronts per row tile) with which every workgroup is resident at once.
+// Geometry for one workgroup size: all of X in LDS at once if it fits, else
+// chunks of 4096, 2048 or 1024 inputs in two buffers; the shares of the R role;
+// the largest S (wavefronts per row tile) with which every workgroup is
+// resident at once.
 static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
 {
     FusedPlan p{};
     p.mp = pad_tokens16(m);
     p.kpad = (k + 1023) / 1024 * 1024;
     p.waves = waves;
-    // helpers: enough lanes that one batch of 16 loads each covers T
-    p.helpers = rank_pad == 0 ? 0 : (p.mp <= 4 ? 1 : (p.mp <= 8 ? 2 : 4));
-    const int total = waves + p.helpers;          // wavefronts of a workgroup
     const long wtiles = (n + 15) / 16;
-    {
+    const int kcs[4] = {p.kpad, 4096, 2048, 1024};
+    // LDS of a compute unit; SLIM_DECODE_LDS_KB lowers it (tests: chunks on small layers)
+    size_t lds_cap = 160 * 1024;
+    if (const char *env = getenv("SLIM_DECODE_LDS_KB")) {
+        const long kb = atol(env);
+        if (kb >= 16 && kb <= 160) lds_cap = (size_t)kb * 1024;
+    }
+    for (int ci = 0; ci < 4 && !p.ok; ++ci) {
+        const int kc = kcs[ci];
+        if (ci > 0 && kc >= p.kpad) continue;
+        const int nch = (p.kpad + kc - 1) / kc;
+        const int hc = kc / 512;
+        if (nch > 1 && rank_pad > kc) continue;          // T takes the place of an X buffer
+        // helpers: they stage X (about 32 KiB per wavefront in flight) and fetch T (8 loads per
+        // lane and batch).  Beside 8 working wavefronts up to 4 of them fit the compute unit
+        // anyway; beside 4, fewer helpers mean more workgroups per compute unit.
+        int helpers = 4;
+        if (waves < 8) {
+            const int by_t = m <= 4 ? 1 : (m <= 8 ? 2 : 4);
+            const int by_x = (int)(((size_t)m * kc * 2 + 32767) / 32768);
+            helpers = by_x > by_t ? by_x : by_t;
+            if (helpers > 4) helpers = 4;
+        }
+        const int total = waves + helpers;            // wavefronts of a workgroup
         // Shares of the inputs in the R role (1, 2 or 4): one unit per wavefront (T as
         // early as possible) for layers with few row tiles, where the Y role is short
         // and waits for T; one share otherwise, which leaves the compute units to the Y role.
         const int units = (k + 255) / 256;
         const int want = wtiles <= kShareTiles ? (units + total - 1) / total : 1;
-        p.kh = want <= 1 ? 1 : (want <= 2 ? 2 : kMaxShares);
-        p.upk = (units + p.kh - 1) / p.kh;
-    }
-    p.n_r = (rank_pad / 16) * p.kh;
-    const size_t lds_x = (size_t)m * ((p.kpad + kLdsPad) + (rank_pad + kLdsPad)) * sizeof(half_t);
-    const size_t red_r = (size_t)(total - 1) * kWave * 16;
-    for (int S = waves; S >= 1; S /= 2) {
-        const int tpw = waves / S;
-        const size_t red_y = S > 1 ? (size_t)tpw * (S - 1) * kWave * 16 : 0;
-        const size_t lds = lds_x + red_y > red_r ? lds_x + red_y : red_r;
-        if (lds > 160 * 1024) continue;
-        // workgroups a compute unit holds: its registers take 16 wavefronts of the
-        // kernels with a small first X batch, 12 of the other
-        long per_cu = (fused_x_pieces(m, p.kpad, total * kWave) <= 8 ? 16 : 12) / total;
-        if (per_cu > (long)(160 * 1024 / lds)) per_cu = (long)(160 * 1024 / lds);
-        const long slots = 256 * per_cu - p.n_r;
-        const long wgs = (wtiles + tpw - 1) / tpw;
-        if (wgs <= slots) {
-            p.S = S;
-            p.ygrid = (int)wgs;
-            p.lds = lds;
-            p.ok = p.n_r <= 512;
-            break;
+        const int kh = want <= 1 ? 1 : (want <= 2 ? 2 : kMaxShares);
+        const int n_r = (rank_pad / 16) * kh;
+        const size_t lds_x = nch == 1 ? (size_t)m * ((kc + kLdsPad) + (rank_pad + kLdsPad)) * sizeof(half_t)
+                                      : (size_t)2 * m * (kc + kLdsPad) * sizeof(half_t);
+        const size_t red_r = (size_t)(total - 1) * kWave * 16;
+        for (int S = waves; S >= 1; S /= 2) {
+            if (nch > 1 && (S > hc || hc % S)) continue;     // every wavefront has the same items in every chunk
+            const int tpw = waves / S;
+            const size_t red_y = S > 1 ? (size_t)tpw * (S - 1) * kWave * 16 : 0;
+            const size_t lds = lds_x + red_y > red_r ? lds_x + red_y : red_r;
+            if (lds > lds_cap) continue;
+            // workgroups a compute unit holds
+            long per_cu = 4 * kFusedWavesPerSimd / total;
+            if (per_cu > (long)(160 * 1024 / lds)) per_cu = (long)(160 * 1024 / lds);
+            const long slots = 256 * per_cu - n_r;
+            const long wgs = (wtiles + tpw - 1) / tpw;
+            if (wgs <= slots) {
+                p.S = S;
+                p.ygrid = (int)wgs;
+                p.lds = lds;
+                p.kc = kc;
+                p.nch = nch;
+                p.helpers = helpers;
+                p.kh = kh;
+                p.upk = (units + kh - 1) / kh;
+                p.n_r = n_r;
+                p.ok = n_r <= 512;
+                break;
+            }
         }
     }
     return p;
@@ -558,21 +592,15 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     a.rank_pad = layer->rank_pad;
     a.m = m;
     a.kpad = p.kpad;
+    a.kc = p.kc;
+    a.nch = p.nch;
     a.S = p.S;
     a.n_r = p.n_r;
     a.helpers = p.helpers;
     a.kh = p.kh;
     a.upk = p.upk;
     const dim3 blk((p.waves + p.helpers) * kWave);
-    const int np = fused_x_pieces(m, p.kpad, (int)blk.x);
-    auto launch = [&](unsigned grid) {
-        if (np <= 2)
-            hipLaunchKernelGGL((decode_fused_kernel<2, 4>), dim3(grid), blk, p.lds, st, a);
-        else if (np <= 8)
-            hipLaunchKernelGGL((decode_fused_kernel<8, 4>), dim3(grid), blk, p.lds, st, a);
-        else
-            hipLaunchKernelGGL((decode_fused_kernel<16, 3>), dim3(grid), blk, p.lds, st, a);
-    };
+    auto launch = [&](unsigned grid) { hipLaunchKernelGGL(decode_fused_kernel, dim3(grid), blk, p.lds, st, a); };
     if (mode == 2 || p.n_r == 0) {
         a.mode = p.n_r == 0 ? 1 : 2;
         launch((unsigned)(p.n_r + p.ygrid));

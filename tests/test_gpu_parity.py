@@ -173,6 +173,16 @@ def test_gemv_full_size_sampled_rows(shape, m, decode_path):
     assert _forward_case(shape, m, B.slim_linear_gemv, rows=rows) <= TOL_Y
 
 
+@pytest.mark.parametrize("n,k,r,m,lds_kb", [(1000, 4096, 100, 16, 96), (1000, 4096, 100, 16, 48), (520, 11008, 410, 8, 64),
+                                            (300, 2176, 37, 5, 24), (2049, 8192, 33, 16, 160), (64, 3072, 0, 16, 40)])
+def test_gemv_one_launch_with_x_in_chunks(n, k, r, m, lds_kb, monkeypatch):
+    """The one-launch kernel with X streamed through LDS in chunks (a smaller LDS
+    budget forces the chunks on layers the oracle finishes quickly)."""
+    monkeypatch.setenv("SLIM_DECODE_PATH", "fused")
+    monkeypatch.setenv("SLIM_DECODE_LDS_KB", str(lds_kb))
+    assert _forward_case(_shape(n, k, r), m, B.slim_linear_gemv, seed=13) <= TOL_Y
+
+
 def test_gemv_repeated_calls_one_workspace(monkeypatch):
     """One workspace, many calls: the paths alternate, the token count changes, and
     every call must give the result of a call on a fresh workspace (no state of an
