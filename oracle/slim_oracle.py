@@ -225,3 +225,56 @@ def forward_explicit_dense(W: np.ndarray, L, R, X) -> np.ndarray:
     if L is not None and np.asarray(L).shape[1] > 0:
         Wd = Wd + np.asarray(L, np.float64) @ np.asarray(R, np.float64)
     return X @ Wd.T
+
+
+# ---- quantized adapters (Sec. 3.3, "Low-rank Adapter Quantization") -----------------
+# Plain numpy, one group at a time.  The steps that decide an integer (the scale
+# that is stored, the division, the rounding) are taken in the precision the
+# stored format fixes: the scale is a binary16 number, the quotient is binary32.
+
+ADAPTER_GROUP = 128
+
+
+def quantize_adapter(A: np.ndarray):
+    """4-bit AbsMax group quantization of one adapter matrix A [rows][cols] (fp16).
+
+    Every row is cut into groups of 128 consecutive elements (the last group of
+    a row may be shorter).  Per group: scale = max|a| / 7 in binary32, rounded to
+    binary16 (that is the number stored); a group of zeros gets scale 1, a scale
+    that rounds to zero gets the smallest positive binary16 number.  Codes:
+    clamp(rint(a / scale), -8, 7) with the quotient in binary32 and ties to even
+    (the clamp never acts: |a / scale| <= 7 (1 + 2^-11)).
+    Returns (codes int8 [rows][cols], scales float16 [rows][ceil(cols / 128)])."""
+    A = np.asarray(A)
+    assert A.dtype == np.float16 and A.ndim == 2
+    rows, cols = A.shape
+    groups = (cols + ADAPTER_GROUP - 1) // ADAPTER_GROUP
+    codes = np.zeros((rows, cols), np.int8)
+    scales = np.ones((rows, groups), np.float16)
+    tiny = np.float16(2.0 ** -24)
+    for r in range(rows):
+        for g in range(groups):
+            seg = A[r, g * ADAPTER_GROUP:(g + 1) * ADAPTER_GROUP].astype(np.float32)
+            amax = np.float32(np.max(np.abs(seg)))
+            if amax == 0:
+                s16 = np.float16(1.0)
+            else:
+                s16 = np.float16(np.float32(amax / np.float32(7.0)))
+                if s16 == 0:
+                    s16 = tiny
+            q = np.rint(seg / np.float32(s16))              # binary32 quotient, ties to even
+            codes[r, g * ADAPTER_GROUP:(g + 1) * ADAPTER_GROUP] = np.clip(q, -8, 7).astype(np.int8)
+            scales[r, g] = s16
+    return codes, scales
+
+
+def dequantize_adapter(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    """code * scale of its group, exact in float64: [rows][cols]."""
+    codes = np.asarray(codes, np.int8)
+    scales = np.asarray(scales, np.float16)
+    rows, cols = codes.shape
+    out = np.empty((rows, cols), np.float64)
+    for g in range(scales.shape[1]):
+        sl = slice(g * ADAPTER_GROUP, min(cols, (g + 1) * ADAPTER_GROUP))
+        out[:, sl] = codes[:, sl].astype(np.float64) * scales[:, g].astype(np.float64)[:, None]
+    return out
