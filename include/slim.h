@@ -86,6 +86,13 @@ typedef struct {
     const slim_half *L;     /* [n][rank_pad] in the adapter layout, columns >= rank zero (NULL if rank == 0) */
     const slim_half *R;     /* [rank_pad][k] in the adapter layout, rows >= rank zero    (NULL if rank == 0) */
     int32_t rank_pad;       /* slim_rank_pad(rank)                                   */
+    /* 4-bit adapters (Sec. 3.3): with adapter_bits == 4 the kernels read Lq, Ls, Rq, Rs
+     * (from slim_pack_adapters_q4) and ignore L and R; 0 or 16: fp16 adapters in L, R. */
+    int32_t adapter_bits;
+    const uint8_t *Lq;      /* codes of L [n][rank] in the 4-bit adapter layout      */
+    const slim_half *Ls;    /* its group scales                                      */
+    const uint8_t *Rq;      /* codes of R [rank][k]                                  */
+    const slim_half *Rs;    /* its group scales                                      */
 } slim_layer;
 
 /* Text for a status code; a static string, never NULL. */
@@ -126,6 +133,30 @@ int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8_t *meta, f
  */
 int slim_pack_adapters(const slim_half *L, const slim_half *R, slim_shape shape,
                        slim_half *L_pad, slim_half *R_pad, void *stream);
+
+/*
+ * 4-bit adapters (Sec. 3.3, "Low-rank Adapter Quantization"): AbsMax group
+ * quantization, groups of 128 consecutive elements of a row of L [n][rank] or
+ * R [rank][k] (the last group of a row may be shorter):
+ *   scale = max|a| / 7 as one binary32 division, rounded to binary16 (1 for a
+ *           group of zeros; the smallest positive binary16 if that rounds to 0);
+ *   code  = round-half-even(a / scale) in binary32, clamped to [-8, 7].
+ * 4-bit adapter layout: codes as two's-complement nibbles (even column in the
+ * low nibble) in tiles of 16 rows x 256 columns (2 KiB), row tile major; inside
+ * a tile the 32 bytes of row r, columns 64 q .. 64 q + 63 start at (4 r + q) * 32;
+ * rows padded to 16, columns to 256 with zero codes.  Scales: fp16
+ * [rows16][2 * ceil(cols / 256)], row-major, entry g = group g of the row.
+ * Sizes from slim_adapter_q4_sizes (HOST out-pointers).  A value is used as
+ * fp16(code * scale).  slim_linear_gemv reads the codes directly (a quarter of
+ * the adapter bytes); slim_linear_gemm expands them to fp16 in the workspace
+ * first.  slim_unpack_adapters_q4 returns codes int8 [rows][cols] and scales
+ * fp16 [rows][ceil(cols / 128)], row-major (tests, inspection).
+ */
+int slim_adapter_q4_sizes(int32_t rows, int32_t cols, size_t *codes_bytes, size_t *scales_bytes);
+int slim_pack_adapters_q4(const slim_half *L, const slim_half *R, slim_shape shape, uint8_t *Lq,
+                          slim_half *Ls, uint8_t *Rq, slim_half *Rs, void *stream);
+int slim_unpack_adapters_q4(const uint8_t *codes, const slim_half *scales, int32_t rows, int32_t cols,
+                            int8_t *out_codes, slim_half *out_scales, void *stream);
 
 /*
  * slim_unpack -- inverse of slim_pack's bytes (packed layout and canonical

@@ -30,13 +30,15 @@ class slim_shape(ctypes.Structure):
 class slim_layer(ctypes.Structure):
     _fields_ = [("shape", slim_shape), ("qvals", ctypes.c_void_p), ("meta", ctypes.c_void_p),
                 ("scale", ctypes.c_void_p), ("L", ctypes.c_void_p), ("R", ctypes.c_void_p),
-                ("rank_pad", ctypes.c_int32)]
+                ("rank_pad", ctypes.c_int32), ("adapter_bits", ctypes.c_int32), ("Lq", ctypes.c_void_p),
+                ("Ls", ctypes.c_void_p), ("Rq", ctypes.c_void_p), ("Rs", ctypes.c_void_p)]
 
 
 SLIM_OK, SLIM_ERR_NULL, SLIM_ERR_SHAPE, SLIM_ERR_ALIGN, SLIM_ERR_WORKSPACE, SLIM_ERR_HIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pack", "slim_pack_adapters",
-           "slim_unpack", "slim_workspace_bytes", "slim_linear_gemv", "slim_linear_gemm", "slim_lowrank"]
+           "slim_unpack", "slim_workspace_bytes", "slim_linear_gemv", "slim_linear_gemm", "slim_lowrank",
+           "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4"]
 
 
 def lib():
@@ -58,6 +60,9 @@ def lib():
         L.slim_pack_adapters.argtypes = [vp, vp, slim_shape, vp, vp, vp]
         L.slim_unpack.argtypes = [vp, vp, slim_shape, vp, vp, vp]
         L.slim_workspace_bytes.argtypes = [ctypes.POINTER(slim_layer), i32, psz]
+        L.slim_adapter_q4_sizes.argtypes = [i32, i32, psz, psz]
+        L.slim_pack_adapters_q4.argtypes = [vp, vp, slim_shape, vp, vp, vp, vp, vp]
+        L.slim_unpack_adapters_q4.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.slim_linear_gemv.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp, sz, vp]
         L.slim_linear_gemm.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp, sz, vp]
         L.slim_lowrank.argtypes = [vp, i32, vp, vp, slim_shape, i32, vp, ctypes.c_int, vp, sz, vp]
@@ -116,11 +121,17 @@ class SlimLayer:
     scale: torch.Tensor            # float32 [n]
     L: torch.Tensor | None         # float16, tiled layout of [n][rank_pad]
     R: torch.Tensor | None         # float16, tiled layout of [rank_pad][k]
+    adapter_bits: int = 16         # 4: the adapters are Lq, Ls, Rq, Rs (slim_pack_adapters_q4), L and R unused
+    Lq: torch.Tensor | None = None
+    Ls: torch.Tensor | None = None
+    Rq: torch.Tensor | None = None
+    Rs: torch.Tensor | None = None
 
     def c_struct(self) -> slim_layer:
+        p = lambda t: t.data_ptr() if t is not None else None
         return slim_layer(slim_shape(self.n, self.k, self.rank), self.qvals.data_ptr(), self.meta.data_ptr(),
-                          self.scale.data_ptr(), self.L.data_ptr() if self.L is not None else None,
-                          self.R.data_ptr() if self.R is not None else None, self.rank_pad)
+                          self.scale.data_ptr(), p(self.L), p(self.R), self.rank_pad, self.adapter_bits,
+                          p(self.Lq), p(self.Ls), p(self.Rq), p(self.Rs))
 
 
 def slim_pack(W: torch.Tensor, qvals=None, meta=None, scale=None):
@@ -168,15 +179,55 @@ def slim_unpack(qvals: torch.Tensor, meta: torch.Tensor, n: int, k: int):
     return codes, mask
 
 
-def compress(W: torch.Tensor, L: torch.Tensor | None = None, R: torch.Tensor | None = None) -> SlimLayer:
-    """slim_pack (+ slim_pack_adapters) into a SlimLayer."""
+def slim_adapter_q4_sizes(rows: int, cols: int) -> dict:
+    c, s = ctypes.c_size_t(), ctypes.c_size_t()
+    _check("slim_adapter_q4_sizes", lib().slim_adapter_q4_sizes(rows, cols, c, s))
+    return {"codes": c.value, "scales": s.value}
+
+
+def slim_pack_adapters_q4(L: torch.Tensor, R: torch.Tensor):
+    """L fp16 [n][rank], R fp16 [rank][k] -> (Lq, Ls, Rq, Rs): 4-bit group-128 codes in the kernels'
+    layout and fp16 group scales (flat tensors; sizes from slim_adapter_q4_sizes)."""
+    _dev(L, torch.float16, "L")
+    _dev(R, torch.float16, "R")
+    n, rank = L.shape
+    k = R.shape[1]
+    if R.shape[0] != rank:
+        raise ValueError("L and R disagree on the rank")
+    sl, sr = slim_adapter_q4_sizes(n, rank), slim_adapter_q4_sizes(rank, k)
+    Lq = torch.empty(sl["codes"], dtype=torch.uint8, device=L.device)
+    Ls = torch.empty(sl["scales"] // 2, dtype=torch.float16, device=L.device)
+    Rq = torch.empty(sr["codes"], dtype=torch.uint8, device=L.device)
+    Rs = torch.empty(sr["scales"] // 2, dtype=torch.float16, device=L.device)
+    _check("slim_pack_adapters_q4", lib().slim_pack_adapters_q4(_ptr(L), _ptr(R), slim_shape(n, k, rank), _ptr(Lq),
+                                                                _ptr(Ls), _ptr(Rq), _ptr(Rs), _stream(L)))
+    return Lq, Ls, Rq, Rs
+
+
+def slim_unpack_adapters_q4(codes: torch.Tensor, scales: torch.Tensor, rows: int, cols: int):
+    """(codes int8 [rows][cols], scales fp16 [rows][ceil(cols / 128)]) from the 4-bit adapter layout."""
+    _dev(codes, torch.uint8, "codes")
+    _dev(scales, torch.float16, "scales")
+    out_c = torch.empty(rows, cols, dtype=torch.int8, device=codes.device)
+    out_s = torch.empty(rows, (cols + 127) // 128, dtype=torch.float16, device=codes.device)
+    _check("slim_unpack_adapters_q4", lib().slim_unpack_adapters_q4(_ptr(codes), _ptr(scales), rows, cols, _ptr(out_c),
+                                                                    _ptr(out_s), _stream(codes)))
+    return out_c, out_s
+
+
+def compress(W: torch.Tensor, L: torch.Tensor | None = None, R: torch.Tensor | None = None,
+             adapter_bits: int = 16) -> SlimLayer:
+    """slim_pack (+ slim_pack_adapters, or slim_pack_adapters_q4 with adapter_bits=4) into a SlimLayer."""
     n, k = W.shape
     qvals, meta, scale = slim_pack(W)
-    rank, rp, Lp, Rp = 0, 0, None, None
-    if L is not None and L.shape[1] > 0:
-        rank = L.shape[1]
-        Lp, Rp = slim_pack_adapters(L, R)
-        rp = slim_rank_pad(rank)
+    if L is None or L.shape[1] == 0:
+        return SlimLayer(n, k, 0, 0, qvals, meta, scale, None, None)
+    rank = L.shape[1]
+    rp = slim_rank_pad(rank)
+    if adapter_bits == 4:
+        Lq, Ls, Rq, Rs = slim_pack_adapters_q4(L, R)
+        return SlimLayer(n, k, rank, rp, qvals, meta, scale, None, None, 4, Lq, Ls, Rq, Rs)
+    Lp, Rp = slim_pack_adapters(L, R)
     return SlimLayer(n, k, rank, rp, qvals, meta, scale, Lp, Rp)
 
 

@@ -7,7 +7,7 @@ static size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 int gemm_t_splits(int32_t m, int32_t rank_pad, int32_t k);   // slim_gemm.hip
 
-WorkspacePlan plan_workspace(int32_t n, int32_t k, int32_t rank_pad, int32_t m)
+WorkspacePlan plan_workspace(int32_t n, int32_t k, int32_t rank_pad, int32_t m, bool q4)
 {
     WorkspacePlan p{};
     p.dec_off = 0;
@@ -20,9 +20,29 @@ WorkspacePlan plan_workspace(int32_t n, int32_t k, int32_t rank_pad, int32_t m)
     p.part_off = p.acc_off + p.acc_bytes;
     p.splits = rank_pad > 0 ? gemm_t_splits(m, rank_pad, k) : 1;
     p.part_bytes = p.splits > 1 ? round256((size_t)p.splits * m * rank_pad * sizeof(float)) : 0;
-    p.total = p.part_off + p.part_bytes;
+    p.exp_off = p.part_off + p.part_bytes;
+    p.exp_bytes = q4 && rank_pad > 0 ? round256(tl_bytes(n, rank_pad)) + round256(tl_bytes(rank_pad, k)) : 0;
+    p.total = p.exp_off + p.exp_bytes;
     if (p.total < 256) p.total = 256;
     return p;
+}
+
+void launch_q4_expand(const uint8_t *codes, const half_t *scales, int rows, int K, int rows_t, int cols_t, half_t *out,
+                      hipStream_t st);   // slim_adapters_q4.hip
+
+int expand_q4_adapters(const slim_layer *layer, const WorkspacePlan &w, char *ws, slim_layer *out, hipStream_t st)
+{
+    const slim_shape s = layer->shape;
+    const int rp = layer->rank_pad;
+    half_t *Lx = reinterpret_cast<half_t *>(ws + w.exp_off);
+    half_t *Rx = reinterpret_cast<half_t *>(ws + w.exp_off + round256(tl_bytes(s.n, rp)));
+    launch_q4_expand(layer->Lq, reinterpret_cast<const half_t *>(layer->Ls), s.n, s.rank, (int)tl_rows(s.n), (int)tl_cols(rp), Lx, st);
+    launch_q4_expand(layer->Rq, reinterpret_cast<const half_t *>(layer->Rs), s.rank, s.k, (int)tl_rows(rp), (int)tl_cols(s.k), Rx, st);
+    *out = *layer;
+    out->L = reinterpret_cast<const slim_half *>(Lx);
+    out->R = reinterpret_cast<const slim_half *>(Rx);
+    out->adapter_bits = 16;
+    return hip_status(hipGetLastError());
 }
 
 }  // namespace slim
@@ -64,6 +84,6 @@ extern "C" int slim_workspace_bytes(const slim_layer *layer, int32_t m, size_t *
     const slim_shape s = layer->shape;
     if (s.n < 1 || s.k < 8 || s.k % 8 || s.rank < 0 || m < 1) return SLIM_ERR_SHAPE;
     if (layer->rank_pad != slim_rank_pad(s.rank)) return SLIM_ERR_SHAPE;
-    *bytes = plan_workspace(s.n, s.k, layer->rank_pad, m).total;
+    *bytes = plan_workspace(s.n, s.k, layer->rank_pad, m, layer->adapter_bits == 4).total;
     return SLIM_OK;
 }

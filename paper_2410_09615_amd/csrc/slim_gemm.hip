@@ -192,26 +192,38 @@ int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t 
 
 using namespace slim;
 
-extern "C" int slim_linear_gemm(const slim_layer *layer, const slim_half *X, int32_t m, slim_half *Y,
+extern "C" int slim_linear_gemm(const slim_layer *layer_in, const slim_half *X, int32_t m, slim_half *Y,
                                 void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!layer || !X || !Y) return SLIM_ERR_NULL;
+    if (!layer_in || !X || !Y) return SLIM_ERR_NULL;
+    const slim_layer *layer = layer_in;
     const slim_shape s = layer->shape;
     if (!layer->qvals || !layer->meta || !layer->scale) return SLIM_ERR_NULL;
-    if (s.rank > 0 && (!layer->L || !layer->R)) return SLIM_ERR_NULL;
+    const bool q4 = layer->adapter_bits == 4 && s.rank > 0;
+    if (q4 && (!layer->Lq || !layer->Ls || !layer->Rq || !layer->Rs)) return SLIM_ERR_NULL;
+    if (!q4 && s.rank > 0 && (!layer->L || !layer->R)) return SLIM_ERR_NULL;
     if (s.n < 1 || s.k < 128 || s.k % 128 || s.rank < 0 || m < 1) return SLIM_ERR_SHAPE;
     if (layer->rank_pad != slim_rank_pad(s.rank)) return SLIM_ERR_SHAPE;
     if (!aligned16(layer->qvals) || !aligned16(layer->meta) || !aligned16(layer->scale) || !aligned16(X) ||
-        !aligned16(Y) || !aligned16(layer->L) || !aligned16(layer->R) || !aligned16(workspace))
+        !aligned16(Y) || (!q4 && (!aligned16(layer->L) || !aligned16(layer->R))) || !aligned16(workspace))
+        return SLIM_ERR_ALIGN;
+    if (q4 && (!aligned16(layer->Lq) || !aligned16(layer->Ls) || !aligned16(layer->Rq) || !aligned16(layer->Rs)))
         return SLIM_ERR_ALIGN;
     // 32-bit offsets into the weights and into L
     if ((uint64_t)s.n * (uint64_t)(s.k / 4) > 0xFFFFFFFFull || (uint64_t)s.n * (uint64_t)layer->rank_pad * 2 > 0xFFFFFFFFull)
         return SLIM_ERR_SHAPE;
-    WorkspacePlan p = plan_workspace(s.n, s.k, layer->rank_pad, m);
+    WorkspacePlan p = plan_workspace(s.n, s.k, layer->rank_pad, m, q4);
     if (!workspace || workspace_bytes < p.total) return SLIM_ERR_WORKSPACE;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
+    // 4-bit adapters: this compute-bound path reads them as fp16, expanded once per call
+    slim_layer expanded;
+    if (q4) {
+        const int rc = expand_q4_adapters(layer, p, ws, &expanded, st);
+        if (rc != SLIM_OK) return rc;
+        layer = &expanded;
+    }
     half_t *T = reinterpret_cast<half_t *>(ws + p.t_off);
     float *P = reinterpret_cast<float *>(ws + p.part_off);
     const int rp = layer->rank_pad;
@@ -234,7 +246,7 @@ extern "C" int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, c
     if (rank_pad != slim_rank_pad(shape.rank)) return SLIM_ERR_SHAPE;
     if (!aligned16(X) || !aligned16(R) || !aligned16(L) || !aligned16(Y) || !aligned16(workspace))
         return SLIM_ERR_ALIGN;
-    WorkspacePlan p = plan_workspace(shape.n, shape.k, rank_pad, m);
+    WorkspacePlan p = plan_workspace(shape.n, shape.k, rank_pad, m, false);
     if (!workspace || workspace_bytes < p.total) return SLIM_ERR_WORKSPACE;
 
     hipStream_t st = static_cast<hipStream_t>(stream);

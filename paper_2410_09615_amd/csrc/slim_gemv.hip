@@ -577,19 +577,24 @@ int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t 
 
 using namespace slim;
 
-extern "C" int slim_linear_gemv(const slim_layer *layer, const slim_half *X, int32_t m, slim_half *Y,
+extern "C" int slim_linear_gemv(const slim_layer *layer_in, const slim_half *X, int32_t m, slim_half *Y,
                                 void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!layer || !X || !Y) return SLIM_ERR_NULL;
+    if (!layer_in || !X || !Y) return SLIM_ERR_NULL;
+    const slim_layer *layer = layer_in;
     const slim_shape s = layer->shape;
     if (!layer->qvals || !layer->meta || !layer->scale) return SLIM_ERR_NULL;
-    if (s.rank > 0 && (!layer->L || !layer->R)) return SLIM_ERR_NULL;
+    const bool q4 = layer->adapter_bits == 4 && s.rank > 0;
+    if (q4 && (!layer->Lq || !layer->Ls || !layer->Rq || !layer->Rs)) return SLIM_ERR_NULL;
+    if (!q4 && s.rank > 0 && (!layer->L || !layer->R)) return SLIM_ERR_NULL;
     if (s.n < 1 || s.k < 128 || s.k % 128 || s.rank < 0 || m < 1 || m > kMaxTokens) return SLIM_ERR_SHAPE;
     if (layer->rank_pad != slim_rank_pad(s.rank)) return SLIM_ERR_SHAPE;
     if (!aligned16(layer->qvals) || !aligned16(layer->meta) || !aligned16(layer->scale) || !aligned16(X) ||
-        !aligned16(Y) || !aligned16(layer->L) || !aligned16(layer->R) || !aligned16(workspace))
+        !aligned16(Y) || (!q4 && (!aligned16(layer->L) || !aligned16(layer->R))) || !aligned16(workspace))
         return SLIM_ERR_ALIGN;
-    WorkspacePlan w = plan_workspace(s.n, s.k, layer->rank_pad, m);
+    if (q4 && (!aligned16(layer->Lq) || !aligned16(layer->Ls) || !aligned16(layer->Rq) || !aligned16(layer->Rs)))
+        return SLIM_ERR_ALIGN;
+    WorkspacePlan w = plan_workspace(s.n, s.k, layer->rank_pad, m, q4);
     if (!workspace || workspace_bytes < w.total) return SLIM_ERR_WORKSPACE;
 
     char *ws = static_cast<char *>(workspace);
@@ -607,6 +612,13 @@ extern "C" int slim_linear_gemv(const slim_layer *layer, const slim_half *X, int
             return launch_decode_fused(layer, reinterpret_cast<const half_t *>(X), m, reinterpret_cast<half_t *>(Y),
                                        ws + w.t16_off, reinterpret_cast<unsigned *>(ws + w.dec_off) + 2, f, mode,
                                        static_cast<hipStream_t>(stream));
+    }
+    // the two-launch kernels read fp16 adapters: 4-bit ones are expanded in the workspace first
+    slim_layer expanded;
+    if (q4) {
+        const int rc = expand_q4_adapters(layer, w, ws, &expanded, static_cast<hipStream_t>(stream));
+        if (rc != SLIM_OK) return rc;
+        layer = &expanded;
     }
     DecodePlan p = plan_decode(s.n, s.k, layer->rank_pad, m);
     DecodeArgs a{};

@@ -57,14 +57,19 @@ struct FusedArgs {
     const uint8_t *qvals;
     const uint8_t *meta;
     const float *scale;
-    const half_t *R;
+    const half_t *R;     // fp16 adapters in the adapter layout, or
     const half_t *L;
+    const uint8_t *Rq;   // 4-bit adapters: codes in the 4-bit adapter layout and group scales
+    const uint8_t *Lq;
+    const half_t *Rs;
+    const half_t *Ls;
     const half_t *X;
     half_t *Y;
     uint4_t *T;          // pieces {epoch, 0, 4 ranks fp16} [kh][16][rank_pad / 4]: T is the sum of the planes
     unsigned *err;       // set to 1 when a wait gave up
     unsigned epoch;
     int n, k, rank_pad, m;
+    int rank;            // true rank (rows of R, columns of L that exist in the 4-bit buffers)
     int kpad;            // k rounded up to 1024
     int kc;              // inputs per chunk of X in LDS (multiple of 1024; kpad: all of X at once)
     int nch;             // chunks: more than one -> two LDS buffers, the helpers stage chunk c + 1 during chunk c
@@ -77,6 +82,7 @@ struct FusedArgs {
 };
 
 // ---- R role ----
+template <bool Q4>
 __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb)
 {
     const int rt = rb / a.kh;                  // tile of 16 ranks
@@ -94,35 +100,59 @@ __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb
 
     // Buffer loads: one 32-bit offset per lane, no branches; an offset past the
     // end of the buffer (kNowhere) reads as zero.
-    const rsrc_t r_rs = make_rsrc(a.R, (uint32_t)tl_bytes(rp, a.k));
     const rsrc_t x_rs = make_rsrc(a.X, (uint32_t)a.m * a.k * 2u);
-    auto issue_r = [&](int u, UnitRegs &b) {
-        // step t reads the pieces (rank, 32 u + 4 t + ly): two tiles (2 KiB) further per step
-        const uint32_t base = tl_piece(16u * rt + lx, 32u * u + ly, (uint32_t)a.k);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) b.r[t] = load16(r_rs, (u < u1 && 256 * u + 32 * t < a.k) ? base + 2048u * t : kNowhere, 0);
-    };
-    auto issue_x = [&](int u, uint4_t (&xb)[8]) {
-        const uint32_t base = ((uint32_t)lx * a.k + 256 * u + 8 * ly) * 2u;
-#pragma unroll
-        for (int t = 0; t < 8; ++t)
-            xb[t] = load16(x_rs, (u < u1 && lx < a.m && 256 * u + 32 * t < a.k) ? base + 64u * t : kNowhere, 0);
-    };
-
     UnitRegs buf;
     uint4_t xb[8];
     float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
-    for (int u = u0 + wave; u < u1; u += nw) {
-        issue_r(u, buf);
-        issue_x(u, xb);
+    if constexpr (!Q4) {
+        const rsrc_t r_rs = make_rsrc(a.R, (uint32_t)tl_bytes(rp, a.k));
+        for (int u = u0 + wave; u < u1; u += nw) {
+            // step t reads the pieces (rank, 32 u + 4 t + ly): two tiles (2 KiB) further per step
+            const uint32_t rbase = tl_piece(16u * rt + lx, 32u * u + ly, (uint32_t)a.k);
+            const uint32_t xbase = ((uint32_t)lx * a.k + 256 * u + 8 * ly) * 2u;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const half8_t av = __builtin_bit_cast(half8_t, buf.r[t]);
-            const half8_t bv = __builtin_bit_cast(half8_t, xb[t]);
-            if (t & 1)
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
-            else
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
+            for (int t = 0; t < 8; ++t) buf.r[t] = load16(r_rs, 256 * u + 32 * t < a.k ? rbase + 2048u * t : kNowhere, 0);
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                xb[t] = load16(x_rs, (lx < a.m && 256 * u + 32 * t < a.k) ? xbase + 64u * t : kNowhere, 0);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const half8_t av = __builtin_bit_cast(half8_t, buf.r[t]);
+                const half8_t bv = __builtin_bit_cast(half8_t, xb[t]);
+                if (t & 1)
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
+                else
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
+            }
+        }
+    } else {
+        // 4-bit R: lane (rank lx, quarter ly) owns 64 consecutive inputs of the unit (32
+        // bytes of codes, one scale: a quarter lies inside one group of 128); step t
+        // takes its inputs 8 t .. 8 t + 7, and the X operand follows the same order.
+        // (rows of R past the last stored tile of 16 lie past the end of the buffers: zeros)
+        const rsrc_t q_rs = make_rsrc(a.Rq, (uint32_t)q4_code_bytes(a.rank, a.k));
+        const rsrc_t s_rs = make_rsrc(a.Rs, (uint32_t)q4_scale_bytes(a.rank, a.k));
+        const uint32_t ct = q4_ctiles(a.k), gs = q4_groups(a.k);
+        for (int u = u0 + wave; u < u1; u += nw) {
+            const bool ok = 256 * u + 64 * ly < a.k;
+            const uint32_t qbase = ok ? q4_piece(16u * rt + lx, 4u * u + ly, ct) : kNowhere;
+            const uint32_t xbase = (ok && lx < a.m) ? ((uint32_t)lx * a.k + 256 * u + 64 * ly) * 2u : kNowhere;
+            buf.r[0] = load16(q_rs, qbase, 0);
+            buf.r[1] = load16(q_rs, qbase, 16);
+            const unsigned short sb = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(
+                s_rs, ok ? (int)(((16u * rt + lx) * gs + 2u * u + (ly >> 1)) * 2u) : (int)kNowhere, 0, 0);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) xb[t] = load16(x_rs, xbase, 16u * t);
+            const half_t sc = __builtin_bit_cast(half_t, sb);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const half8_t av = codes_to_half8(buf.r[t >> 2][t & 3]) * sc;
+                const half8_t bv = __builtin_bit_cast(half8_t, xb[t]);
+                if (t & 1)
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
+                else
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
+            }
         }
     }
     // lane holds token lx, ranks 16 rt + 4 ly .. + 3
@@ -143,6 +173,7 @@ __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb
 }
 
 // ---- Y role ----
+template <bool Q4>
 __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, int ygrid)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -174,9 +205,11 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     // halves of this wavefront per chunk: s, s + S, ... < hc (with chunks S divides hc: the same for all)
     const int hpc = s < hc ? (hc - s + S - 1) / S : 0;
     const int ipc = (hpc + 1) / 2;               // items (of two halves) per chunk
-    const int cnt_l = s < steps ? (steps - s + S - 1) / S : 0;
+    // rank work of this wavefront: steps of 32 ranks s, s + S, ... (fp16), or units of 256 ranks (4-bit)
+    const int units_l = (int)q4_ctiles(rp);
+    const int cnt_l = Q4 ? (s < units_l ? (units_l - s + S - 1) / S : 0) : (s < steps ? (steps - s + S - 1) / S : 0);
     const int nP = nch * ipc;
-    const int nL = (cnt_l + 7) / 8;              // items of eight steps
+    const int nL = Q4 ? (cnt_l + 1) / 2 : (cnt_l + 7) / 8;    // items of eight steps, or of two units
     const int nI = nP + nL;
     const int tile0 = yb * tpw + ts;
     const int tstride = ygrid * tpw;
@@ -190,7 +223,8 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     // what lies past the inputs or the ranks gets the offset kNowhere: all zeros.
     const rsrc_t q_rs = make_rsrc(a.qvals, (uint32_t)pk_qbytes(a.n, a.k));
     const rsrc_t m_rs = make_rsrc(a.meta, (uint32_t)pk_mbytes(a.n, a.k));
-    const rsrc_t l_rs = make_rsrc(a.L, (uint32_t)tl_bytes(a.n, rp));
+    const rsrc_t l_rs = Q4 ? make_rsrc(a.Lq, (uint32_t)q4_code_bytes(a.n, rp)) : make_rsrc(a.L, (uint32_t)tl_bytes(a.n, rp));
+    const rsrc_t ls_rs = make_rsrc(Q4 ? a.Ls : nullptr, Q4 ? (uint32_t)q4_scale_bytes(a.n, rp) : 0u);
     auto issue_item = [&](int ot, int j, UnitRegs &b) {
         const uint32_t o = 16u * ot + lx;
         if (j < nP) {
@@ -211,12 +245,30 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
             b.r[6] = zero;
             b.r[7] = zero;
         } else {
-            // step t = s + S (8 jl + i) takes ranks 32 t + 8 ly .. + 7 of row o: piece (o, 4 t + ly)
-            const int t0 = s + S * 8 * (j - nP);
-            const uint32_t base = tl_piece(o, 4u * t0 + ly, (uint32_t)rp);
+            if constexpr (!Q4) {
+                // step t = s + S (8 jl + i) takes ranks 32 t + 8 ly .. + 7 of row o: piece (o, 4 t + ly)
+                const int t0 = s + S * 8 * (j - nP);
+                const uint32_t base = tl_piece(o, 4u * t0 + ly, (uint32_t)rp);
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                b.r[i] = load16(l_rs, (j < nI && ot < wtiles && t0 + S * i < steps) ? base + 2048u * S * i : kNowhere, 0);
+                for (int i = 0; i < 8; ++i)
+                    b.r[i] = load16(l_rs, (j < nI && ot < wtiles && t0 + S * i < steps) ? base + 2048u * S * i : kNowhere, 0);
+            } else {
+                // two units of 256 ranks: 32 bytes of codes and a scale per lane and unit
+                const uint32_t ct = q4_ctiles(rp), gs = q4_groups(rp);
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {
+                    const int uu = s + S * (2 * (j - nP) + x);
+                    const bool ok = j < nI && ot < wtiles && uu < units_l && 256 * uu + 64 * ly < rp;
+                    const uint32_t qo = ok ? q4_piece(o, 4u * uu + ly, ct) : kNowhere;
+                    b.r[3 * x] = load16(l_rs, qo, 0);
+                    b.r[3 * x + 1] = load16(l_rs, qo, 16);
+                    const unsigned short sb = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(
+                        ls_rs, ok ? (int)((o * gs + 2u * uu + (ly >> 1)) * 2u) : (int)kNowhere, 0, 0);
+                    b.r[3 * x + 2] = uint4_t{sb, 0u, 0u, 0u};
+                }
+                b.r[6] = zero;
+                b.r[7] = zero;
+            }
         }
     };
 
@@ -409,17 +461,36 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
             packed_half<0>(cur, xc + 512 * h0, acc0, acc1);
             packed_half<1>(cur, xc + 512 * h1, acc0, acc1);
         } else if (j < nI) {
-            const int t0 = s + S * 8 * (j - nP);
+            if constexpr (!Q4) {
+                const int t0 = s + S * 8 * (j - nP);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                // steps past the end carry zero L values and read T inside the row
-                const int t = min(t0 + S * i, steps - 1);
-                const half8_t bv = *reinterpret_cast<const half8_t *>(trow_l + 32 * t);
-                const half8_t av = __builtin_bit_cast(half8_t, cur.r[i]);
-                if (i & 1)
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
-                else
-                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
+                for (int i = 0; i < 8; ++i) {
+                    // steps past the end carry zero L values and read T inside the row
+                    const int t = min(t0 + S * i, steps - 1);
+                    const half8_t bv = *reinterpret_cast<const half8_t *>(trow_l + 32 * t);
+                    const half8_t av = __builtin_bit_cast(half8_t, cur.r[i]);
+                    if (i & 1)
+                        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
+                    else
+                        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {
+                    const int uu = s + S * (2 * (j - nP) + x);
+                    const half_t sc = __builtin_bit_cast(half_t, (unsigned short)cur.r[3 * x + 2][0]);
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        // ranks 256 uu + 64 ly + 8 t .. + 7; past the end the codes are zero and T is read inside the row
+                        const int col = min(256 * uu + 64 * ly + 8 * t, rp - 8);
+                        const half8_t bv = *reinterpret_cast<const half8_t *>(t_lds + trow * ldt + col);
+                        const half8_t av = codes_to_half8(cur.r[3 * x + (t >> 2)][t & 3]) * sc;
+                        if (t & 1)
+                            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
+                        else
+                            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
+                    }
+                }
             }
         }
         if (j != nIe - 1) return;
@@ -469,17 +540,18 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     }
 }
 
+template <bool Q4>
 __global__ __launch_bounds__(kFusedMaxThreads, kFusedWavesPerSimd) void decode_fused_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) half_t lds[];
     if (a.mode == 0) {
-        role_r(a, lds, blockIdx.x);
+        role_r<Q4>(a, lds, blockIdx.x);
     } else if (a.mode == 1) {
-        role_y(a, lds, blockIdx.x, gridDim.x);
+        role_y<Q4>(a, lds, blockIdx.x, gridDim.x);
     } else if ((int)blockIdx.x < a.n_r) {
-        role_r(a, lds, blockIdx.x);
+        role_r<Q4>(a, lds, blockIdx.x);
     } else {
-        role_y(a, lds, (int)blockIdx.x - a.n_r, (int)gridDim.x - a.n_r);
+        role_y<Q4>(a, lds, (int)blockIdx.x - a.n_r, (int)gridDim.x - a.n_r);
     }
 }
 
@@ -580,6 +652,10 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     a.scale = layer->scale;
     a.R = reinterpret_cast<const half_t *>(layer->R);
     a.L = reinterpret_cast<const half_t *>(layer->L);
+    a.Rq = layer->Rq;
+    a.Lq = layer->Lq;
+    a.Rs = reinterpret_cast<const half_t *>(layer->Rs);
+    a.Ls = reinterpret_cast<const half_t *>(layer->Ls);
     a.X = X;
     a.Y = Y;
     a.T = static_cast<uint4_t *>(T);
@@ -590,6 +666,7 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     a.n = layer->shape.n;
     a.k = layer->shape.k;
     a.rank_pad = layer->rank_pad;
+    a.rank = layer->shape.rank;
     a.m = m;
     a.kpad = p.kpad;
     a.kc = p.kc;
@@ -600,7 +677,13 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     a.kh = p.kh;
     a.upk = p.upk;
     const dim3 blk((p.waves + p.helpers) * kWave);
-    auto launch = [&](unsigned grid) { hipLaunchKernelGGL(decode_fused_kernel, dim3(grid), blk, p.lds, st, a); };
+    const bool q4 = layer->adapter_bits == 4 && p.n_r > 0;
+    auto launch = [&](unsigned grid) {
+        if (q4)
+            hipLaunchKernelGGL(decode_fused_kernel<true>, dim3(grid), blk, p.lds, st, a);
+        else
+            hipLaunchKernelGGL(decode_fused_kernel<false>, dim3(grid), blk, p.lds, st, a);
+    };
     if (mode == 2 || p.n_r == 0) {
         a.mode = p.n_r == 0 ? 1 : 2;
         launch((unsigned)(p.n_r + p.ygrid));

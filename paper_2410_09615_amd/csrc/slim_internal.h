@@ -111,6 +111,25 @@ __host__ __device__ inline size_t pk_moff(uint32_t o, uint32_t b, uint32_t kt)
     return ((size_t)(o >> 5) * kt + (b >> 4)) * 512u + ((((b >> 3) & 1u) << 5) + (o & 31u)) * 8u + (b & 7u);
 }
 
+// ---- device layout of 4-bit adapters (what slim_pack_adapters_q4 writes) ----
+// Codes of a matrix [rows][K] (two's-complement nibbles, the even column in the
+// low nibble) are stored as tiles of 16 rows x 256 columns, 2 KiB each, row tile
+// major; inside a tile the piece of row r and quarter q (64 columns, 32 bytes)
+// starts at (4 r + q) * 32: lane (row, quarter) of a wavefront reads its 64
+// columns with two 128-bit loads and the wavefront reads the tile as one
+// contiguous run.  Rows are padded to 16 and columns to 256 with zero codes.
+// Scales: fp16 [rows16][2 * tiles per row], one per group of 128 columns.
+__host__ __device__ inline uint32_t q4_ctiles(int K) { return (uint32_t)(K + 255) / 256; }
+__host__ __device__ inline uint32_t q4_rows(int rows) { return (uint32_t)(rows + 15) / 16 * 16; }
+__host__ __device__ inline uint32_t q4_groups(int K) { return 2 * q4_ctiles(K); }
+__host__ __device__ inline size_t q4_code_bytes(int rows, int K) { return (size_t)(q4_rows(rows) / 16) * q4_ctiles(K) * 2048; }
+__host__ __device__ inline size_t q4_scale_bytes(int rows, int K) { return (size_t)q4_rows(rows) * q4_groups(K) * 2; }
+// byte offset of the piece holding columns 64 c64 .. 64 c64 + 63 of `row`
+__host__ __device__ inline uint32_t q4_piece(uint32_t row, uint32_t c64, uint32_t ctiles)
+{
+    return ((row >> 4) * ctiles + (c64 >> 2)) * 2048u + ((row & 15u) * 4u + (c64 & 3u)) * 32u;
+}
+
 #ifdef __HIPCC__
 // ---- buffer loads: descriptor + 32-bit byte offset, out-of-range reads return zero ----
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
@@ -150,6 +169,7 @@ struct WorkspacePlan {
     size_t t_off, t_bytes;        // gemm: T = X R^T as fp16 [m][rank_pad]
     size_t acc_off, acc_bytes;    // decode: partial quantized term, fp32 [slots][m][n]
     size_t part_off, part_bytes;  // gemm: split-K partials of T, fp32 [splits][m][rank_pad]
+    size_t exp_off, exp_bytes;    // 4-bit adapters expanded to fp16 (adapter layout): L then R
     int splits;                   // split-K factor of the T product
     size_t total;
 };
@@ -162,6 +182,9 @@ struct DecodePlan {
 
 DecodePlan plan_decode(int n, int k, int rank_pad, int m);
 
-WorkspacePlan plan_workspace(int32_t n, int32_t k, int32_t rank_pad, int32_t m);
+WorkspacePlan plan_workspace(int32_t n, int32_t k, int32_t rank_pad, int32_t m, bool q4);
+
+// 4-bit adapters of a layer -> fp16 in the workspace; returns the layer to run with (fp16 adapters).
+int expand_q4_adapters(const slim_layer *layer, const WorkspacePlan &w, char *ws, slim_layer *out, hipStream_t st);
 
 }  // namespace slim

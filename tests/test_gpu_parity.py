@@ -249,6 +249,78 @@ def test_gemv_and_gemm_agree():
     assert float((a - b).norm() / a.norm()) <= 1e-3
 
 
+# ---- 4-bit adapters (Sec. 3.3) ------------------------------------------------------
+
+def _q4_layer(W, L, R):
+    return B.compress(W.to(DEV), L.to(DEV), R.to(DEV), adapter_bits=4)
+
+
+@pytest.mark.parametrize("n,k,r", [(300, 640, 51), (64, 1024, 32), (33, 256, 1), (1000, 4096, 410), (520, 11008, 130)])
+def test_pack_adapters_q4_bit_exact(n, k, r):
+    """Codes and scales of both adapters equal the oracle's group quantizer bit for bit."""
+    L, R = wl.make_adapters(n, k, r, 31, 32)
+    L[0, : min(r, 3)] = 0                       # and a few special values: a zero run, a tiny value, a large one
+    R[0, 128:256] = 0                           # a whole group of zeros
+    R[r - 1, 5] = 2.0 ** -24
+    L[n - 1, r - 1] = 3.0
+    Lq, Ls, Rq, Rs = B.slim_pack_adapters_q4(L.to(DEV), R.to(DEV))
+    for (q, s, A, rows, cols) in ((Lq, Ls, L, n, r), (Rq, Rs, R, r, k)):
+        codes, scales = B.slim_unpack_adapters_q4(q, s, rows, cols)
+        torch.cuda.synchronize()
+        rc, rs = O.quantize_adapter(A.numpy())
+        assert np.array_equal(scales.cpu().numpy().view(np.uint16), rs.view(np.uint16))
+        assert np.array_equal(codes.cpu().numpy(), rc)
+
+
+def _forward_case_q4(shape, m, fn, seed=0, rows=None):
+    W, L, R, X = wl.make_layer(shape, m, seed=seed)
+    layer = _q4_layer(W, L, R)
+    Y = fn(layer, X.to(DEV))
+    torch.cuda.synchronize()
+    lc, ls = O.quantize_adapter(L.numpy())
+    rc, rs = O.quantize_adapter(R.numpy())
+    Yref = O.forward(O.compress(W.numpy()), O.dequantize_adapter(lc, ls), O.dequantize_adapter(rc, rs), X.numpy(), rows=rows)
+    Yg = Y.cpu().numpy()
+    if rows is not None:
+        Yg = Yg[:, rows]
+    assert np.isfinite(Yg).all()
+    return _relerr(Yg, Yref)
+
+
+@pytest.mark.parametrize("m", [1, 4, 8, 16])
+def test_gemv_q4_adapters_tiny_layer(m, decode_path):
+    assert _forward_case_q4(wl.TINY, m, B.slim_linear_gemv) <= TOL_Y
+
+
+@pytest.mark.parametrize("n,k,r,m", [(1000, 1280, 37, 3), (17, 128, 1, 5), (2049, 640, 33, 16), (130, 11008, 410, 2),
+                                     (5000, 2176, 100, 8), (48, 4096, 1024, 16), (300, 8192, 600, 16)])
+def test_gemv_q4_adapters_ragged_shapes(n, k, r, m):
+    assert _forward_case_q4(_shape(n, k, r), m, B.slim_linear_gemv, seed=7) <= TOL_Y
+
+
+@pytest.mark.parametrize("shape,m", [(wl.L7B_ATTN, 1), (wl.L7B_ATTN, 16), (wl.L70B_ATTN, 4)], ids=lambda v: str(getattr(v, "name", v)))
+def test_gemv_q4_adapters_full_size_sampled_rows(shape, m):
+    rows = np.random.default_rng(1).choice(shape.n, size=512, replace=False)
+    rows.sort()
+    assert _forward_case_q4(shape, m, B.slim_linear_gemv, rows=rows) <= TOL_Y
+
+
+@pytest.mark.parametrize("n,k,r,m", [(512, 512, 51, 200), (1000, 1280, 37, 129)])
+def test_gemm_q4_adapters(n, k, r, m):
+    assert _forward_case_q4(_shape(n, k, r), m, B.slim_linear_gemm, seed=5) <= TOL_Y
+
+
+def test_q4_adapters_change_the_result_as_much_as_the_quantization_says():
+    """The 4-bit layer is not the fp16 layer: the two forwards differ by about the
+    quantization error of the adapter term (a guard against a path that silently
+    reads the fp16 adapters)."""
+    W, L, R, X = wl.make_layer(wl.TINY, 4, seed=3)
+    y16 = B.slim_linear_gemv(_gpu_layer(W, L, R), X.to(DEV)).float()
+    y4 = B.slim_linear_gemv(_q4_layer(W, L, R), X.to(DEV)).float()
+    d = float((y16 - y4).norm() / y16.norm())
+    assert 1e-4 < d < 0.2
+
+
 # ---- slim_lowrank -----------------------------------------------------------------
 
 @pytest.mark.parametrize("m", [1, 16, 300])

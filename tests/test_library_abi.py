@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "slim.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(slim_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(slim_[a-z_0-9]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported():
@@ -44,7 +44,7 @@ def test_rank_pad_and_sizes():
 
 
 def test_workspace_query():
-    layer = B.slim_layer(B.slim_shape(4096, 4096, 410), None, None, None, None, None, 416)
+    layer = B.slim_layer(B.slim_shape(4096, 4096, 410), None, None, None, None, None, 416, 16, None, None, None, None)
     out = ctypes.c_size_t()
     assert B.lib().slim_workspace_bytes(ctypes.byref(layer), 16, out) == 0
     # at least T (fp32 [16][416]) and the quantized-term buffer (fp32 [16][4096])
