@@ -90,27 +90,30 @@ def main():
         """`copies` device copies of one compressed layer, plus X / Y / workspace
         per copy, so that consecutive calls touch different HBM."""
 
-        def __init__(self, shape, ms, min_copies=2, max_bytes=6 << 30, with_dense=True):
+        def __init__(self, shape, ms, min_copies=2, max_bytes=6 << 30, with_dense=True, adapter_bits=16):
             self.shape = shape
+            self.adapter_bits = adapter_bits
             W, L, R, _ = wl.make_layer(shape, 1)
             self.W_host = W
             self.L_host, self.R_host = L, R
             Wd = W.to(dev)
             t0 = time.perf_counter()
-            base = B.compress(Wd, L.to(dev), R.to(dev))
+            base = B.compress(Wd, L.to(dev), R.to(dev), adapter_bits=adapter_bits)
             torch.cuda.synchronize()
             self.first_compress_s = time.perf_counter() - t0
             self.base = base
             self.W_dev = Wd
-            layer_bytes = A.packed_weight_bytes(shape.n, shape.k) + A.adapter_bytes(shape.n, shape.k, shape.r)
+            layer_bytes = A.packed_weight_bytes(shape.n, shape.k) + (
+                A.adapter_bytes_q4(shape.n, shape.k, shape.r) if adapter_bits == 4 else A.adapter_bytes(shape.n, shape.k, shape.r))
             copies = max(min_copies, -(-2 * CACHE_BYTES // layer_bytes))
             copies = max(2, min(copies, max_bytes // max(layer_bytes, 1)))
             self.copies = int(copies)
             self.layers = [base]
+            cl = lambda t: None if t is None else t.clone()
             for _ in range(self.copies - 1):
                 self.layers.append(B.SlimLayer(base.n, base.k, base.rank, base.rank_pad, base.qvals.clone(),
-                                               base.meta.clone(), base.scale.clone(), base.L.clone(),
-                                               base.R.clone()))
+                                               base.meta.clone(), base.scale.clone(), cl(base.L), cl(base.R),
+                                               base.adapter_bits, cl(base.Lq), cl(base.Ls), cl(base.Rq), cl(base.Rs)))
             self.X = {}
             self.Y = {}
             self.ws = {}
@@ -144,7 +147,7 @@ def main():
         for i in range(max(3, warm // 3)):
             rot.dense_call(m, i)
         ms_dense = event_time_ms(lambda i: rot.dense_call(m, i), iters)
-        nbytes = A.layer_bytes(shape.n, shape.k, shape.r, m)
+        nbytes = A.layer_bytes(shape.n, shape.k, shape.r, m, rot.adapter_bits)
         feff = A.flops_eff(shape.n, shape.k, shape.r, m)
         rec = {
             "shape": shape.name, "tokens": m, "entry": kind, "us": round(ms * 1e3, 3),
@@ -154,6 +157,8 @@ def main():
             "byte_ratio_ceiling": round(A.dense_bytes(shape.n, shape.k, m) / nbytes, 2),
             "copies": rot.copies,
         }
+        if rot.adapter_bits == 4:
+            rec["adapters"] = "4-bit group-128"
         if kind == "slim_linear_gemv":
             rec["bound"] = "hbm"
             rec["roofline_frac"] = round(nbytes / ms * 1e-6 / HBM_PEAK_GBPS, 4)
@@ -267,6 +272,14 @@ def main():
                         (wl.L70B_ATTN, 4096), (wl.L70B_UP, 4096)]
         for shp, ms_ in (decode_cfgs if args.legs != "prefill" else []):
             r = Rotating(shp, ms_)
+            for m in ms_:
+                legs.append(leg_record(r, m, B.slim_linear_gemv, 100, 10, "slim_linear_gemv"))
+            del r
+            torch.cuda.empty_cache()
+        # 4-bit group-128 adapters (paper, Sec. 3.3): the same decode call on a quarter of the adapter bytes
+        q4_cfgs = [(wl.L7B_ATTN, (1, 16)), (wl.L70B_ATTN, (1,)), (wl.L70B_UP, (1, 16))]
+        for shp, ms_ in (q4_cfgs if args.legs != "prefill" else []):
+            r = Rotating(shp, ms_, adapter_bits=4)
             for m in ms_:
                 legs.append(leg_record(r, m, B.slim_linear_gemv, 100, 10, "slim_linear_gemv"))
             del r

@@ -6,7 +6,7 @@ has to move and compute, not the dense work it avoids:
   bytes      = N K / 4 (two int4 codes per group of 4 inputs)
              + N K / 8 (two 2-bit positions per group)
              + 4 N     (fp32 scale per output row)
-             + 2 r (N + K) (fp16 adapters, true rank)
+             + 2 r (N + K) (fp16 adapters, true rank; 4-bit adapters: r (N + K) / 2 + fp16 group scales)
              + 2 M K + 2 M N (fp16 X in, fp16 Y out)
   flops_alg  = 2 M N K / 2 + 2 M r (N + K)   (2:4 halves the weight term and
                quantization saves none: paper, App. "Computation Reduction
@@ -31,8 +31,15 @@ def adapter_bytes(n: int, k: int, r: int) -> int:
     return 2 * r * (n + k)
 
 
-def layer_bytes(n: int, k: int, r: int, m: int) -> int:
-    return packed_weight_bytes(n, k) + adapter_bytes(n, k, r) + 2 * m * k + 2 * m * n
+def adapter_bytes_q4(n: int, k: int, r: int) -> int:
+    """4-bit group-128 adapters (paper, Sec. 3.3): half a byte per element plus one
+    fp16 scale per group of 128 elements of a row of L [n][r] or R [r][k]."""
+    return (r * (n + k) + 1) // 2 + 2 * (n * ((r + 127) // 128) + r * ((k + 127) // 128))
+
+
+def layer_bytes(n: int, k: int, r: int, m: int, adapter_bits: int = 16) -> int:
+    ad = adapter_bytes_q4(n, k, r) if adapter_bits == 4 else adapter_bytes(n, k, r)
+    return packed_weight_bytes(n, k) + ad + 2 * m * k + 2 * m * n
 
 
 def dense_bytes(n: int, k: int, m: int) -> int:
