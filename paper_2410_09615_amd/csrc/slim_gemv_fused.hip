@@ -44,10 +44,9 @@
 
 namespace slim {
 
-constexpr int kFusedMaxThreads = 768;      // 8 working wavefronts + up to 4 helpers
+constexpr int kFusedMaxThreads = 1024;     // 8 working wavefronts + up to 8 helpers
 constexpr int kScopeDevice = 16;      // cache policy of a buffer access: device scope (written through / read from memory)
 constexpr int kMaxShares = 4;         // R role: at most this many shares of the inputs (planes of T)
-constexpr int kShareTiles = 384;       // ... for layers of at most this many row tiles
 constexpr int kFusedWavesPerSimd = 4;   // the kernel is compiled for 128 registers: 16 wavefronts per compute unit
 constexpr int kSpinLimit = 1 << 16;
 constexpr int kWaitVm0 = 0x0F70;       // s_waitcnt vmcnt(0) (expcnt, lgkmcnt left alone): all vector memory loads of the wavefront are back
@@ -105,24 +104,42 @@ __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb
     uint4_t xb[8];
     float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
     if constexpr (!Q4) {
+        // Two register sets for R alternate (both go out at once; a wavefront with more
+        // units refills a set as soon as it is consumed); the X operand, an L2 hit, is
+        // loaded when its unit is due.
         const rsrc_t r_rs = make_rsrc(a.R, (uint32_t)tl_bytes(rp, a.k));
-        for (int u = u0 + wave; u < u1; u += nw) {
+        auto issue_r = [&](int u, UnitRegs &b) {
             // step t reads the pieces (rank, 32 u + 4 t + ly): two tiles (2 KiB) further per step
             const uint32_t rbase = tl_piece(16u * rt + lx, 32u * u + ly, (uint32_t)a.k);
-            const uint32_t xbase = ((uint32_t)lx * a.k + 256 * u + 8 * ly) * 2u;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) buf.r[t] = load16(r_rs, 256 * u + 32 * t < a.k ? rbase + 2048u * t : kNowhere, 0);
+            for (int t = 0; t < 8; ++t)
+                b.r[t] = load16(r_rs, (u < u1 && 256 * u + 32 * t < a.k) ? rbase + 2048u * t : kNowhere, 0);
+        };
+        auto unit = [&](int u, const UnitRegs &b) {
+            const uint32_t xbase = ((uint32_t)lx * a.k + 256 * u + 8 * ly) * 2u;
 #pragma unroll
             for (int t = 0; t < 8; ++t)
                 xb[t] = load16(x_rs, (lx < a.m && 256 * u + 32 * t < a.k) ? xbase + 64u * t : kNowhere, 0);
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                const half8_t av = __builtin_bit_cast(half8_t, buf.r[t]);
+                const half8_t av = __builtin_bit_cast(half8_t, b.r[t]);
                 const half8_t bv = __builtin_bit_cast(half8_t, xb[t]);
                 if (t & 1)
                     acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
                 else
                     acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
+            }
+        };
+        UnitRegs buf2;
+        const int ua = u0 + wave;
+        issue_r(ua, buf);
+        issue_r(ua + nw, buf2);
+        for (int u = ua; u < u1; u += 2 * nw) {
+            unit(u, buf);
+            issue_r(u + 2 * nw, buf);
+            if (u + nw < u1) {
+                unit(u + nw, buf2);
+                issue_r(u + 3 * nw, buf2);
             }
         }
     } else {
@@ -348,17 +365,6 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
         auto fetch = [&](auto khc) {
             constexpr int KH = decltype(khc)::value;
             constexpr int PB = 8 / KH;                    // pairs per batch: 8 loads in flight
-            // the first piece alone until it is there: a cheap poll while T is being made
-            {
-                const uint32_t off0 = piece_off(hl, 0);
-                bool there = off0 == kNowhere;
-                while (!__all(there) && spins < kSpinLimit) {
-                    const uint4_t pc = __builtin_bit_cast(uint4_t, __builtin_amdgcn_raw_buffer_load_b128(t_rs, (int)off0, 0, kScopeDevice));
-                    there = there || pc[0] == a.epoch;
-                    ++spins;
-                    if (!__all(there)) __builtin_amdgcn_s_sleep(4);
-                }
-            }
             for (int p0 = hl; p0 < pairs; p0 += PB * hn) {        // p0 differs per lane: every lane runs its own count
                 uint4_t pc[PB * KH];
                 bool all_there = false;
@@ -584,7 +590,9 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
         // helpers: they stage X (about 32 KiB per wavefront in flight) and fetch T (8 loads per
         // lane and batch).  Beside 8 working wavefronts up to 4 of them fit the compute unit
         // anyway; beside 4, fewer helpers mean more workgroups per compute unit.
-        int helpers = 4;
+        // (with more than 8 tokens eight: T is then one batch per lane, and the workgroup has
+        // the compute unit to itself anyway)
+        int helpers = m > 8 ? 8 : 4;
         if (waves < 8) {
             const int by_t = m <= 4 ? 1 : (m <= 8 ? 2 : 4);
             const int by_x = (int)(((size_t)m * kc * 2 + 32767) / 32768);
@@ -592,13 +600,11 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
             if (helpers > 4) helpers = 4;
         }
         const int total = waves + helpers;            // wavefronts of a workgroup
-        // Shares of the inputs in the R role (1, 2 or 4): one unit per wavefront (T as
-        // early as possible) for layers with few row tiles, where the Y role is short
-        // and waits for T; one share otherwise, which leaves the compute units to the Y role.
+        // Shares of the inputs in the R role (1, 2 or 4): up to one unit per wavefront, so that
+        // T is there early; fewer if the workgroups would no longer all be resident.
         const int units = (k + 255) / 256;
-        const int want = wtiles <= kShareTiles ? (units + total - 1) / total : 1;
-        const int kh = want <= 1 ? 1 : (want <= 2 ? 2 : kMaxShares);
-        const int n_r = (rank_pad / 16) * kh;
+        const int want = (units + 7) / 8;              // as if eight wavefronts: also spreads R over more compute units
+        const int kh_max = want <= 1 ? 1 : (want <= 2 ? 2 : kMaxShares);
         const size_t lds_x = nch == 1 ? (size_t)m * ((kc + kLdsPad) + (rank_pad + kLdsPad)) * sizeof(half_t)
                                       : (size_t)2 * m * (kc + kLdsPad) * sizeof(half_t);
         const size_t red_r = (size_t)(total - 1) * kWave * 16;
@@ -611,9 +617,11 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
             // workgroups a compute unit holds
             long per_cu = 4 * kFusedWavesPerSimd / total;
             if (per_cu > (long)(160 * 1024 / lds)) per_cu = (long)(160 * 1024 / lds);
-            const long slots = 256 * per_cu - n_r;
             const long wgs = (wtiles + tpw - 1) / tpw;
-            if (wgs <= slots) {
+            int kh = kh_max;
+            while (kh > 1 && wgs + (long)(rank_pad / 16) * kh > 256 * per_cu) kh /= 2;
+            const int n_r = (rank_pad / 16) * kh;
+            if (wgs + n_r <= 256 * per_cu) {
                 p.S = S;
                 p.ygrid = (int)wgs;
                 p.lds = lds;
