@@ -37,7 +37,8 @@ struct SparseGemmArgs {
     int n, k, rank_pad, m;
     int tiles_o;         // row tiles of 512
     int tiles_total;     // row tiles x token tiles
-    int n_full;          // tiles [0, n_full) run whole (AT = 4), the rest as two halves of 256 rows (AT = 2)
+    int n_full;          // tiles [0, n_full) run whole (AT = 4), the rest as halves of 256 rows (AT = 2) or quarters (AT = 1)
+    int rem_split;       // pieces per remaining tile: 1 (none remain), 2 or 4
 };
 
 // AT row tiles of 32 per wavefront; accumulator tile (i, it) is a[16 (i NT + it) ..].
@@ -54,11 +55,11 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
     const int li = lane & 31;            // A row / B token within a 32-tile
     const int lb = lane >> 5;            // k-block of the lane
 
-    // AT = 4: workgroup b takes tile b.  AT = 2: workgroup b takes rows
-    // 256 (b & 1) .. + 255 of tile n_full + b / 2.
+    // AT = 4: workgroup b takes tile b.  AT = 2 (1): workgroup b takes the half
+    // (quarter) b % split of tile n_full + b / split.
     const int b = blockIdx.x;
     constexpr int split = 4 / AT;
-    const int w = a.n_full * (split - 1) + b / split;
+    const int w = (split > 1 ? a.n_full : 0) + b / split;
     const int o0 = (w % a.tiles_o) * 512 + (b % split) * (4 * WROWS) + wave * WROWS;
     const int t0 = (w / a.tiles_o) * 128;
     const int t_end = min(a.m, t0 + 128);                    // tokens of this workgroup: [t0, t_end)
@@ -266,14 +267,20 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
 }
 
 // Whole rounds of tiles (one workgroup per CU) stay whole; the remainder is cut
-// into halves of 256 rows (a second launch) when those fit into one round.
+// into quarters of 128 rows or halves of 256 rows (a second launch) when those
+// fit into one round: more compute units busy for a shorter time.
 static void plan_tiles(SparseGemmArgs &a, int slots)
 {
     a.tiles_o = (a.n + 511) / 512;
     const int tiles_t = (a.m + 127) / 128;
     a.tiles_total = a.tiles_o * tiles_t;
     const int rem = a.tiles_total % slots;
-    a.n_full = (rem != 0 && 2 * rem <= slots) ? a.tiles_total - rem : a.tiles_total;
+    a.rem_split = 1;
+    if (rem != 0 && 4 * rem <= slots)
+        a.rem_split = 4;
+    else if (rem != 0 && 2 * rem <= slots)
+        a.rem_split = 2;
+    a.n_full = a.rem_split > 1 ? a.tiles_total - rem : a.tiles_total;
 }
 
 // Buffer offsets are 32 bits wide: the caller has checked that the weight and
@@ -300,9 +307,12 @@ int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *s
         a.T = T ? T + (size_t)t0 * rank_pad : nullptr;
         a.Y = Y + (size_t)t0 * n;
         plan_tiles(a, 256);
-        const int n_half = 2 * (a.tiles_total - a.n_full);
+        const int n_rem = a.rem_split * (a.tiles_total - a.n_full);
         if (a.n_full > 0) hipLaunchKernelGGL(gemm_sparse_kernel<4>, dim3((unsigned)a.n_full), dim3(256), lds, st, a);
-        if (n_half > 0) hipLaunchKernelGGL(gemm_sparse_kernel<2>, dim3((unsigned)n_half), dim3(256), lds, st, a);
+        if (n_rem > 0 && a.rem_split == 2)
+            hipLaunchKernelGGL(gemm_sparse_kernel<2>, dim3((unsigned)n_rem), dim3(256), lds, st, a);
+        if (n_rem > 0 && a.rem_split == 4)
+            hipLaunchKernelGGL(gemm_sparse_kernel<1>, dim3((unsigned)n_rem), dim3(256), lds, st, a);
     }
     return hip_status(hipGetLastError());
 }
