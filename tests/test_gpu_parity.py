@@ -183,6 +183,24 @@ def test_gemv_one_launch_with_x_in_chunks(n, k, r, m, lds_kb, monkeypatch):
     assert _forward_case(_shape(n, k, r), m, B.slim_linear_gemv, seed=13) <= TOL_Y
 
 
+@pytest.mark.parametrize("m", list(range(1, 17)))
+def test_gemv_every_token_count(m):
+    assert _forward_case(_shape(777, 1408, 45), m, B.slim_linear_gemv, seed=100 + m) <= TOL_Y
+
+
+def test_gemv_never_gives_up_waiting():
+    """The one-launch kernel records in word 2 of the workspace if a helper ran out of
+    polls; it never should."""
+    W, L, R, X = wl.make_layer(wl.L7B_ATTN, 16, seed=1)
+    layer = _gpu_layer(W, L, R)
+    ws = B.alloc_workspace(layer, 16)
+    Xd = X.to(DEV)
+    for i in range(50):
+        B.slim_linear_gemv(layer, Xd[: 1 + i % 16].contiguous(), workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws.view(torch.int32)[2]) == 0
+
+
 def test_gemv_repeated_calls_one_workspace(monkeypatch):
     """One workspace, many calls: the paths alternate, the token count changes, and
     every call must give the result of a call on a fresh workspace (no state of an
@@ -303,6 +321,13 @@ def test_gemv_q4_adapters_full_size_sampled_rows(shape, m):
     rows = np.random.default_rng(1).choice(shape.n, size=512, replace=False)
     rows.sort()
     assert _forward_case_q4(shape, m, B.slim_linear_gemv, rows=rows) <= TOL_Y
+
+
+@pytest.mark.parametrize("n,k,r,m,lds_kb", [(1000, 4096, 100, 16, 96), (520, 11008, 410, 8, 64), (300, 2176, 37, 5, 24)])
+def test_gemv_q4_adapters_with_x_in_chunks(n, k, r, m, lds_kb, monkeypatch):
+    monkeypatch.setenv("SLIM_DECODE_PATH", "fused")
+    monkeypatch.setenv("SLIM_DECODE_LDS_KB", str(lds_kb))
+    assert _forward_case_q4(_shape(n, k, r), m, B.slim_linear_gemv, seed=17) <= TOL_Y
 
 
 @pytest.mark.parametrize("n,k,r,m", [(512, 512, 51, 200), (1000, 1280, 37, 129)])
