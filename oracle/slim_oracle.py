@@ -77,9 +77,17 @@ def _check(rc: int, what: str):
 
 # ---- steps 1-3 ---------------------------------------------------------------
 
-def mask_2of4(W: np.ndarray) -> np.ndarray:
-    """2:4 magnitude mask of W [n][k] (float32): uint8, 1 = kept."""
+def mask_2of4(W: np.ndarray, saliency: np.ndarray | None = None) -> np.ndarray:
+    """2:4 mask of W [n][k] (float32): uint8, 1 = kept.  Of every 4 consecutive
+    inputs the two of largest |w| are kept; with `saliency` [k] (one non-negative
+    number per input, e.g. the activation norm of Wanda's metric, Sec. 4) the two
+    of largest |w| * saliency[input], the product taken in binary32.  Ties: the
+    lower position first."""
     W = _c(W, np.float32)
+    if saliency is not None:
+        sal = _c(saliency, np.float32)
+        assert sal.shape == (W.shape[1],) and np.all(sal >= 0)
+        W = _c(np.abs(W) * sal[None, :], np.float32)         # binary32 products; the C code takes magnitudes of it
     n, k = W.shape
     mask = np.empty((n, k), np.uint8)
     _check(_load().slim_oracle_mask(_ptr(W), n, k, _ptr(mask)), "mask")
@@ -278,3 +286,64 @@ def dequantize_adapter(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
         sl = slice(g * ADAPTER_GROUP, min(cols, (g + 1) * ADAPTER_GROUP))
         out[:, sl] = codes[:, sl].astype(np.float64) * scales[:, g].astype(np.float64)[:, None]
     return out
+
+
+# ---- SLiM-Quant: per-tensor scale by numerical integration over the histogram --------
+# (Sec. 3.1, Eq. 4-7 and Alg. 1.)  Plain numpy, float64 for the error sums; the
+# bin of an element is decided in binary32 so that the counts are integers that
+# any implementation reproduces.
+
+def quant_bins(numel: int) -> int:
+    """Histogram resolution: one bin per 1000 elements, between 512 and 20000
+    (App. "Implementation Details")."""
+    return max(512, min(numel // 1000, 20000))
+
+
+def quant_histogram(W: np.ndarray):
+    """(counts int64 [B], M): histogram of |W| over [0, M], M = max|W|, B uniform
+    bins; bin = min(B - 1, floor(|w| * (B / M))) with B / M and the product in
+    binary32.  M == 0: all counts in bin 0."""
+    a = np.abs(np.asarray(W, np.float32)).ravel()
+    B = quant_bins(a.size)
+    M = np.float32(a.max())
+    if M == 0:
+        counts = np.zeros(B, np.int64)
+        counts[0] = a.size
+        return counts, M
+    inv = np.float32(np.float32(B) / M)
+    b = np.minimum(np.floor(a * inv).astype(np.int64), B - 1)
+    return np.bincount(b, minlength=B).astype(np.int64), M
+
+
+def quant_error(counts: np.ndarray, M, alpha: float) -> float:
+    """E_quant(alpha) + E_clip(alpha) (Eq. 5-7) with the density replaced by the
+    histogram: every element of a bin sits at the bin's centre.  Symmetric 4-bit
+    grid with 7 steps up to alpha: a magnitude x <= alpha becomes
+    rint(x / (alpha / 7)) * (alpha / 7), a larger one is clipped to alpha."""
+    B = counts.shape[0]
+    x = (np.arange(B, dtype=np.float64) + 0.5) * (float(M) / B)
+    step = alpha / 7.0
+    inside = x <= alpha
+    err = np.where(inside, np.rint(x / step) * step - x, alpha - x)
+    return float(np.dot(counts.astype(np.float64), err * err))
+
+
+def quant_search(W: np.ndarray):
+    """alpha* of Alg. 1: the error at 10 uniform samples alpha = M i / 10, i = 1..10
+    (the last one is AbsMax), then at 21 samples of a tenth of that spacing around
+    the best one (those inside (0, M]); the first minimum wins.  Returns
+    (alpha float32, scale float32 = alpha / 7 in binary32, or 1 for a zero tensor)."""
+    counts, M = quant_histogram(W)
+    if M == 0:
+        return np.float32(0.0), np.float32(1.0)
+    eta = float(M) / 10.0
+    cand = [eta * i for i in range(1, 11)]
+    errs = [quant_error(counts, M, a) for a in cand]
+    lo = cand[int(np.argmin(errs))]
+    for j in range(-10, 11):
+        a = lo + eta * (j / 10.0)
+        if 0.0 < a <= float(M):
+            cand.append(a)
+            errs.append(quant_error(counts, M, a))
+    alpha = np.float32(cand[int(np.argmin(errs))])
+    return alpha, np.float32(alpha / np.float32(7.0))

@@ -1,0 +1,144 @@
+"""Pins of the oracle's SLiM-Quant scale search (Sec. 3.1, Eq. 4-7, Alg. 1) and of
+the saliency-weighted 2:4 mask.  No GPU."""
+import numpy as np
+import pytest
+
+from oracle import slim_oracle as O
+
+
+def test_bins_rule():
+    # App. "Implementation Details": max(512, min(numel / 1000, 20000))
+    assert O.quant_bins(512 * 512) == 512
+    assert O.quant_bins(4096 * 4096) == 16777
+    assert O.quant_bins(28672 * 8192) == 20000
+    assert O.quant_bins(10) == 512
+
+
+def test_histogram_counts_by_brute_force():
+    rng = np.random.default_rng(1)
+    W = rng.standard_normal((40, 300)).astype(np.float32)
+    counts, M = O.quant_histogram(W)
+    assert counts.sum() == W.size and float(M) == float(np.abs(W).max())
+    B = counts.shape[0]
+    mine = np.zeros(B, np.int64)
+    inv = np.float32(np.float32(B) / M)
+    for v in np.abs(W).ravel():
+        mine[min(B - 1, int(np.floor(np.float32(v) * inv)))] += 1
+    assert np.array_equal(mine, counts)
+    assert counts[-1] >= 1                     # the maximum itself lands in the last bin
+
+
+def test_error_is_the_mse_of_the_quantizer_when_the_weights_sit_on_bin_centres():
+    """Weights placed exactly on the centres of the histogram: the integral over the
+    histogram is then the plain sum of squared errors of quantizing those weights with
+    step alpha / 7 and clipping at alpha, computed here element by element."""
+    B = 512
+    M = 2.0
+    centres = (np.arange(B) + 0.5) * (M / B)
+    reps = np.random.default_rng(2).integers(0, 5, size=B)
+    w = np.repeat(centres, reps)
+    counts = reps.astype(np.int64)
+    for alpha in (2.0, 1.3, 0.37, 0.05):
+        step = alpha / 7
+        total = 0.0
+        for x in w:
+            q = min(7, int(np.rint(x / step)))             # codes 0..7 on magnitudes
+            total += (q * step - x) ** 2
+        assert np.isclose(O.quant_error(counts, np.float32(M), alpha), total, rtol=1e-12)
+
+
+def test_a_few_outliers_are_clipped():
+    """Most of the mass near zero and a handful of large values: AbsMax wastes the grid on
+    the outliers, the search picks an alpha far below the maximum and a smaller error."""
+    rng = np.random.default_rng(3)
+    W = (rng.standard_normal((600, 1000)) * 0.01).astype(np.float32)
+    W[0, :4] = [1.0, -1.0, 0.9, 0.8]
+    alpha, scale = O.quant_search(W)
+    counts, M = O.quant_histogram(W)
+    assert float(M) == 1.0
+    assert float(alpha) < 0.2
+    assert O.quant_error(counts, M, float(alpha)) < 0.25 * O.quant_error(counts, M, 1.0)
+    assert float(scale) == float(np.float32(alpha) / np.float32(7.0))
+
+
+def test_alpha_is_the_first_minimum_over_the_candidates_and_never_worse_than_absmax():
+    rng = np.random.default_rng(4)
+    W = rng.laplace(size=(300, 700)).astype(np.float32)
+    alpha, _ = O.quant_search(W)
+    counts, M = O.quant_histogram(W)
+    eta = float(M) / 10
+    coarse = [eta * i for i in range(1, 11)]
+    e = [O.quant_error(counts, M, a) for a in coarse]
+    lo = coarse[int(np.argmin(e))]
+    fine = [lo + eta * (j / 10.0) for j in range(-10, 11)]
+    fine = [a for a in fine if 0 < a <= float(M)]
+    allc = coarse + fine
+    best = min(O.quant_error(counts, M, a) for a in allc)
+    assert O.quant_error(counts, M, float(alpha)) <= best * (1 + 1e-6)      # alpha is stored as binary32
+    assert O.quant_error(counts, M, float(alpha)) <= O.quant_error(counts, M, float(M)) * (1 + 1e-6)
+    assert np.float32(alpha) in [np.float32(a) for a in allc]
+
+
+def test_scale_equivariance_and_symmetries():
+    rng = np.random.default_rng(5)
+    W = rng.standard_normal((128, 512)).astype(np.float32)
+    a1, s1 = O.quant_search(W)
+    a2, s2 = O.quant_search(W * np.float32(8.0))               # a power of two: exact
+    assert float(a2) == 8.0 * float(a1) and float(s2) == 8.0 * float(s1)
+    a3, _ = O.quant_search(-W)
+    a4, _ = O.quant_search(W[::-1, ::-1])
+    assert float(a3) == float(a1) and float(a4) == float(a1)
+
+
+def test_zero_tensor():
+    alpha, scale = O.quant_search(np.zeros((8, 64), np.float32))
+    assert float(alpha) == 0.0 and float(scale) == 1.0
+
+
+def test_quantizing_with_the_searched_scale_lowers_the_true_error():
+    """The real test of the whole chain: codes computed with scale = alpha* / 7 (clamp now
+    acting) reproduce a heavy-tailed W with a smaller squared error than AbsMax / 7."""
+    rng = np.random.default_rng(6)
+    W = rng.standard_t(3, size=(256, 1024)).astype(np.float32)
+    keep = np.ones_like(W, np.uint8)
+    _, s = O.quant_search(W)
+    per_tensor = np.full(W.shape[0], s, np.float32)
+    absmax = np.full(W.shape[0], np.float32(np.abs(W).max()) / np.float32(7.0), np.float32)
+    e_search = np.sum((O.quantize(W, keep, per_tensor) * per_tensor[:, None].astype(np.float64) - W) ** 2)
+    e_absmax = np.sum((O.quantize(W, keep, absmax) * absmax[:, None].astype(np.float64) - W) ** 2)
+    assert e_search < 0.5 * e_absmax
+
+
+# ---- saliency-weighted mask -----------------------------------------------------------
+
+def test_saliency_mask_brute_force_and_special_cases():
+    rng = np.random.default_rng(7)
+    W = rng.standard_normal((16, 64)).astype(np.float32)
+    sal = rng.uniform(0.1, 5.0, size=64).astype(np.float32)
+    mask = O.mask_2of4(W, sal)
+    assert np.all(mask.reshape(16, 16, 4).sum(axis=2) == 2)
+    for o in range(16):
+        for g in range(16):
+            metric = (np.abs(W[o, 4 * g:4 * g + 4]) * sal[4 * g:4 * g + 4]).astype(np.float32)
+            order = sorted(range(4), key=lambda i: (-float(metric[i]), i))
+            want = np.zeros(4, np.uint8)
+            want[order[:2]] = 1
+            assert np.array_equal(mask[o, 4 * g:4 * g + 4], want)
+    # a constant saliency is the magnitude mask; a zero saliency on two inputs drops them
+    assert np.array_equal(O.mask_2of4(W, np.full(64, 2.0, np.float32)), O.mask_2of4(W))
+    z = np.ones(64, np.float32)
+    z[0::4] = 0
+    z[1::4] = 0
+    m = O.mask_2of4(W, z)
+    assert not m[:, 0::4].any() and not m[:, 1::4].any()
+
+
+def test_absmax_is_a_candidate_and_wins_when_the_weights_lie_on_its_grid():
+    """Weights on the 4-bit grid of alpha = max|w| itself: nothing beats AbsMax, and the
+    search must be able to return it (the tenth coarse sample)."""
+    M = 0.875
+    levels = np.arange(-7, 8) * (M / 7)
+    W = np.tile(levels.astype(np.float32), (64, 40))[:, :512]
+    alpha, scale = O.quant_search(W)
+    assert float(alpha) == float(np.float32(M))
+    assert float(scale) == 0.125
