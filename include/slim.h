@@ -126,6 +126,41 @@ int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8_t *meta, f
               void *stream);
 
 /*
+ * slim_pack_ex -- slim_pack with the two choices the paper's own pipeline makes
+ * differently (either pointer may be NULL, which gives slim_pack's behaviour):
+ *   saliency [k]  non-negative, one per input: the 2:4 mask keeps the two largest
+ *                 |w| * saliency[input] of a group (one binary32 product each;
+ *                 ties: lower position first).  With the activation norms of the
+ *                 inputs this is Wanda's metric, the pruning the paper applies
+ *                 (Sec. 3, Sec. 4); the vector is the caller's.
+ *   scale_in [n]  the scales to quantize with (copied to scale), e.g. the
+ *                 per-tensor alpha / 7 of slim_quant_search; values beyond the
+ *                 grid saturate at the codes -8 and 7.
+ */
+int slim_pack_ex(const float *W, slim_shape shape, const float *saliency, const float *scale_in,
+                 uint8_t *qvals, uint8_t *meta, float *scale, void *stream);
+
+/*
+ * slim_quant_search -- the per-tensor scale of SLiM-Quant (Sec. 3.1, Eq. 4-7,
+ * Alg. 1): alpha* minimises E_quant(alpha) + E_clip(alpha) of the symmetric
+ * 4-bit quantizer, integrated numerically over the histogram of |W|:
+ *   histogram  B = max(512, min(n k / 1000, 20000)) uniform bins over
+ *              [0, M], M = max|W| (App. "Implementation Details"); an element
+ *              counts at the centre of its bin; bin = min(B - 1, floor(|w| * (B / M)))
+ *              in binary32;
+ *   coarse     alpha = M i / 10, i = 1..10 (i = 10 is AbsMax);
+ *   fine       21 samples of a tenth of that spacing around the best coarse one,
+ *              those inside (0, M];
+ *   alpha*     the first minimum over all of them (fp64 error sums).
+ * W [n][k] fp32 in; scale_out [n] = alpha* / 7 in every row (1 for a zero
+ * tensor), ready for slim_pack_ex; alpha_out (one float, may be NULL) = alpha*.
+ * workspace: slim_quant_workspace_bytes (HOST out-pointer), need not be zeroed.
+ */
+int slim_quant_workspace_bytes(slim_shape shape, size_t *bytes);
+int slim_quant_search(const float *W, slim_shape shape, float *scale_out, float *alpha_out,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * slim_pack_adapters -- lay the fp16 adapters out for the kernels: L [n][rank]
  * and R [rank][k], row-major, go into L_pad = [n][rank_pad] and R_pad =
  * [rank_pad][k] in the adapter layout above (sizes from slim_packed_sizes),

@@ -38,7 +38,8 @@ SLIM_OK, SLIM_ERR_NULL, SLIM_ERR_SHAPE, SLIM_ERR_ALIGN, SLIM_ERR_WORKSPACE, SLIM
 
 EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pack", "slim_pack_adapters",
            "slim_unpack", "slim_workspace_bytes", "slim_linear_gemv", "slim_linear_gemm", "slim_lowrank",
-           "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4"]
+           "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4", "slim_pack_ex",
+           "slim_quant_workspace_bytes", "slim_quant_search"]
 
 
 def lib():
@@ -61,6 +62,9 @@ def lib():
         L.slim_unpack.argtypes = [vp, vp, slim_shape, vp, vp, vp]
         L.slim_workspace_bytes.argtypes = [ctypes.POINTER(slim_layer), i32, psz]
         L.slim_adapter_q4_sizes.argtypes = [i32, i32, psz, psz]
+        L.slim_pack_ex.argtypes = [vp, slim_shape, vp, vp, vp, vp, vp, vp]
+        L.slim_quant_workspace_bytes.argtypes = [slim_shape, psz]
+        L.slim_quant_search.argtypes = [vp, slim_shape, vp, vp, vp, sz, vp]
         L.slim_pack_adapters_q4.argtypes = [vp, vp, slim_shape, vp, vp, vp, vp, vp]
         L.slim_unpack_adapters_q4.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.slim_linear_gemv.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp, sz, vp]
@@ -146,6 +150,38 @@ def slim_pack(W: torch.Tensor, qvals=None, meta=None, scale=None):
     _check("slim_pack", lib().slim_pack(_ptr(W), slim_shape(n, k, 0), _ptr(qvals), _ptr(meta), _ptr(scale),
                                         _stream(W)))
     return qvals, meta, scale
+
+
+def slim_pack_ex(W: torch.Tensor, saliency: torch.Tensor | None = None, scale_in: torch.Tensor | None = None):
+    """slim_pack with a saliency-weighted 2:4 mask (saliency fp32 [k]) and/or given scales (fp32 [n])."""
+    _dev(W, torch.float32, "W")
+    n, k = W.shape
+    if saliency is not None:
+        _dev(saliency, torch.float32, "saliency")
+    if scale_in is not None:
+        _dev(scale_in, torch.float32, "scale_in")
+    sizes = slim_packed_sizes(n, k, 0)
+    qvals = torch.empty(sizes["qvals"], dtype=torch.uint8, device=W.device)
+    meta = torch.empty(sizes["meta"], dtype=torch.uint8, device=W.device)
+    scale = torch.empty(n, dtype=torch.float32, device=W.device)
+    _check("slim_pack_ex", lib().slim_pack_ex(_ptr(W), slim_shape(n, k, 0), _ptr(saliency) if saliency is not None else None,
+                                              _ptr(scale_in) if scale_in is not None else None, _ptr(qvals), _ptr(meta),
+                                              _ptr(scale), _stream(W)))
+    return qvals, meta, scale
+
+
+def slim_quant_search(W: torch.Tensor):
+    """SLiM-Quant scale search: (scale fp32 [n] = alpha* / 7 in every row, alpha* as a 1-element tensor)."""
+    _dev(W, torch.float32, "W")
+    n, k = W.shape
+    nbytes = ctypes.c_size_t()
+    _check("slim_quant_workspace_bytes", lib().slim_quant_workspace_bytes(slim_shape(n, k, 0), nbytes))
+    ws = torch.empty(nbytes.value, dtype=torch.uint8, device=W.device)
+    scale = torch.empty(n, dtype=torch.float32, device=W.device)
+    alpha = torch.empty(1, dtype=torch.float32, device=W.device)
+    _check("slim_quant_search", lib().slim_quant_search(_ptr(W), slim_shape(n, k, 0), _ptr(scale), _ptr(alpha), _ptr(ws),
+                                                        ws.numel(), _stream(W)))
+    return scale, alpha
 
 
 def slim_pack_adapters(L: torch.Tensor, R: torch.Tensor):

@@ -37,10 +37,12 @@ __device__ __forceinline__ uint32_t quantize_code(float w, float s)
     return (uint32_t)(int)q & 0xFu;
 }
 
-// Encode one group: returns the qvals byte, *m4 the metadata nibble.
-__device__ __forceinline__ uint32_t encode_group(float4 v, float s, uint32_t *m4)
+// Encode one group: returns the qvals byte, *m4 the metadata nibble.  sal: the
+// saliency of the four inputs (all ones: the magnitude mask); the products are
+// single binary32 multiplications.
+__device__ __forceinline__ uint32_t encode_group(float4 v, float s, uint32_t *m4, float4 sal = make_float4(1.f, 1.f, 1.f, 1.f))
 {
-    uint32_t sel = keep_two(fabsf(v.x), fabsf(v.y), fabsf(v.z), fabsf(v.w));
+    uint32_t sel = keep_two(fabsf(v.x) * sal.x, fabsf(v.y) * sal.y, fabsf(v.z) * sal.z, fabsf(v.w) * sal.w);
     uint32_t i0 = sel & 3u, i1 = sel >> 2;
     float w[4] = {v.x, v.y, v.z, v.w};
     float w0 = i0 == 0 ? w[0] : (i0 == 1 ? w[1] : w[2]);
@@ -57,11 +59,15 @@ __device__ __forceinline__ uint32_t encode_group(float4 v, float s, uint32_t *m4
 // divisions per group) as by memory, so the stores stay plain byte stores: lane
 // t writes group t + i THREADS of slot i, whose place in the packed layout is a
 // per-lane base plus a constant per slot.
-template <int THREADS, int SLOTS>
+// EX: the variant behind slim_pack_ex: saliency [k] (or null) weighs the
+// magnitudes in the 2:4 choice, scale_in [n] (or null) replaces AbsMax / 7.
+template <int THREADS, int SLOTS, bool EX = false>
 __global__ __launch_bounds__(THREADS) void pack_kernel(const float *__restrict__ W, int n, int k,
                                                             uint8_t *__restrict__ qvals,
                                                             uint8_t *__restrict__ meta,
-                                                            float *__restrict__ scale)
+                                                            float *__restrict__ scale,
+                                                            const float *__restrict__ saliency = nullptr,
+                                                            const float *__restrict__ scale_in = nullptr)
 {
     __shared__ float wave_part[THREADS / kWave];
     const int ngroups = k / 4;
@@ -115,7 +121,8 @@ __global__ __launch_bounds__(THREADS) void pack_kernel(const float *__restrict__
         a = wave_part[0];
 #pragma unroll
         for (int w = 1; w < THREADS / kWave; ++w) a = fmaxf(a, wave_part[w]);
-        const float s = (a == 0.0f) ? 1.0f : a / 7.0f;
+        float s = (a == 0.0f) ? 1.0f : a / 7.0f;
+        if (EX && scale_in) s = scale_in[o];
         if (tid == 0) scale[o] = s;
 
         // Lanes g and g^1 hold the two groups of one position byte (the stride is
@@ -123,7 +130,12 @@ __global__ __launch_bounds__(THREADS) void pack_kernel(const float *__restrict__
         // (padding of the last tile) are zero bytes.
         auto emit = [&](int i, int g, float4 v) {
             uint32_t q = 0, m4 = 0;
-            if (g < ngroups) q = encode_group(v, s, &m4);
+            if (g < ngroups) {
+                if (EX && saliency)
+                    q = encode_group(v, s, &m4, reinterpret_cast<const float4 *>(saliency)[g]);
+                else
+                    q = encode_group(v, s, &m4);
+            }
             const uint32_t other = __shfl_xor(m4, 1, kWave);
             if (g < gpad) {
                 ql[i * q_slot] = (uint8_t)q;
@@ -210,20 +222,17 @@ static int grid_for(size_t items, int threads, int cap = 256 * 16)
 
 using namespace slim;
 
-extern "C" int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8_t *meta, float *scale,
-                         void *stream)
+template <bool EX>
+static int launch_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8_t *meta, float *scale,
+                       const float *saliency, const float *scale_in, hipStream_t st)
 {
-    if (!W || !qvals || !meta || !scale) return SLIM_ERR_NULL;
-    if (shape.n < 1 || shape.k < 8 || shape.k % 8) return SLIM_ERR_SHAPE;
-    if (!aligned16(W) || !aligned16(qvals) || !aligned16(meta) || !aligned16(scale)) return SLIM_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const int npad = (shape.n + 31) / 32 * 32;      // the padding rows of the last tile get a workgroup too
     // lanes per row: enough that a lane keeps at most 4 groups, up to 1024
     const int groups = shape.k / 4;
     // (two rounds of resident workgroups at most; a workgroup walks the rows it owns)
-#define SLIM_PACK_LAUNCH(T, S)                                                                                \
-    hipLaunchKernelGGL((pack_kernel<T, S>), dim3(pack_grid(npad, 256 * (4096 / T))), dim3(T), 0, st, W, shape.n, \
-                       shape.k, qvals, meta, scale)
+#define SLIM_PACK_LAUNCH(T, S)                                                                                    \
+    hipLaunchKernelGGL((pack_kernel<T, S, EX>), dim3(pack_grid(npad, 256 * (4096 / T))), dim3(T), 0, st, W, shape.n, \
+                       shape.k, qvals, meta, scale, saliency, scale_in)
     if (groups <= 256 * 2)
         SLIM_PACK_LAUNCH(256, 2);
     else if (groups <= 256 * 4)
@@ -240,6 +249,26 @@ extern "C" int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8
         SLIM_PACK_LAUNCH(1024, 0);
 #undef SLIM_PACK_LAUNCH
     return hip_status(hipGetLastError());
+}
+
+extern "C" int slim_pack(const float *W, slim_shape shape, uint8_t *qvals, uint8_t *meta, float *scale,
+                         void *stream)
+{
+    if (!W || !qvals || !meta || !scale) return SLIM_ERR_NULL;
+    if (shape.n < 1 || shape.k < 8 || shape.k % 8) return SLIM_ERR_SHAPE;
+    if (!aligned16(W) || !aligned16(qvals) || !aligned16(meta) || !aligned16(scale)) return SLIM_ERR_ALIGN;
+    return launch_pack<false>(W, shape, qvals, meta, scale, nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int slim_pack_ex(const float *W, slim_shape shape, const float *saliency, const float *scale_in,
+                            uint8_t *qvals, uint8_t *meta, float *scale, void *stream)
+{
+    if (!W || !qvals || !meta || !scale) return SLIM_ERR_NULL;
+    if (shape.n < 1 || shape.k < 8 || shape.k % 8) return SLIM_ERR_SHAPE;
+    if (!aligned16(W) || !aligned16(qvals) || !aligned16(meta) || !aligned16(scale) || !aligned16(saliency) ||
+        !aligned16(scale_in))
+        return SLIM_ERR_ALIGN;
+    return launch_pack<true>(W, shape, qvals, meta, scale, saliency, scale_in, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int slim_unpack(const uint8_t *qvals, const uint8_t *meta, slim_shape shape, int8_t *codes,

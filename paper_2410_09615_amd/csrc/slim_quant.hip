@@ -1,0 +1,196 @@
+// slim_quant_search: the per-tensor scale of SLiM-Quant (Sec. 3.1, Eq. 4-7,
+// Alg. 1): alpha* minimises E_quant(alpha) + E_clip(alpha), the squared error of
+// the symmetric 4-bit quantizer with full scale alpha, integrated over the
+// histogram of |W| (every element of a bin taken at the bin's centre).
+//
+//   histogram  B = max(512, min(n k / 1000, 20000)) uniform bins over [0, M],
+//              M = max|W|; bin = min(B - 1, floor(|w| * (B / M))), quotient and
+//              product in binary32 (so the counts are reproducible integers)
+//   coarse     E at alpha = M i / 10, i = 1..10 (the last one is AbsMax)
+//   fine       E at 21 samples of a tenth of that spacing around the best
+//              coarse one (those inside (0, M])
+//   alpha*     the first minimum over all of them; scale = alpha* / 7 (binary32)
+//
+// Three passes over memory in all: max, histogram (both read W once, HBM-bound),
+// and the candidates, which only touch the histogram.  Everything stays on the
+// device; the error sums are fp64.
+#include "slim_internal.h"
+
+namespace slim {
+
+constexpr int kCoarse = 10;
+constexpr int kFine = 21;
+constexpr int kMaxBins = 20000;
+
+// workspace: [0] bits of M (uint), [16 .. 16 + 31] errors (double, byte offset 64),
+// [128 ..] counts (uint)
+struct QuantWs {
+    unsigned *mbits;
+    double *err;
+    unsigned *counts;
+};
+__host__ __device__ inline QuantWs quant_ws(void *ws)
+{
+    QuantWs q;
+    q.mbits = static_cast<unsigned *>(ws);
+    q.err = reinterpret_cast<double *>(static_cast<char *>(ws) + 64);
+    q.counts = static_cast<unsigned *>(ws) + 128;
+    return q;
+}
+
+__host__ __device__ inline int quant_bins(long numel)
+{
+    const long b = numel / 1000 < kMaxBins ? numel / 1000 : kMaxBins;
+    return (int)(b > 512 ? b : 512);
+}
+
+__global__ __launch_bounds__(256) void quant_zero_kernel(unsigned *ws, int words)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < words; i += gridDim.x * blockDim.x) ws[i] = 0u;
+}
+
+// M = max|W|: non-negative floats order like their bit patterns
+__global__ __launch_bounds__(256) void quant_absmax_kernel(const float *__restrict__ W, size_t numel4, unsigned *mbits)
+{
+    float a = 0.f;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < numel4; i += (size_t)gridDim.x * blockDim.x) {
+        const float4 v = reinterpret_cast<const float4 *>(W)[i];
+        a = fmaxf(a, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+    }
+    a = wave_max(a);
+    if ((threadIdx.x & (kWave - 1)) == 0) atomicMax(mbits, __float_as_uint(a));
+}
+
+// per-workgroup histogram in LDS, then one global add per non-empty bin
+__global__ __launch_bounds__(1024) void quant_hist_kernel(const float *__restrict__ W, size_t numel4, int B,
+                                                          const unsigned *mbits, unsigned *counts)
+{
+    extern __shared__ unsigned hist[];
+    for (int i = threadIdx.x; i < B; i += blockDim.x) hist[i] = 0u;
+    __syncthreads();
+    const float M = __uint_as_float(*mbits);
+    if (M > 0.f) {
+        const float inv = (float)B / M;
+        auto put = [&](float w) {
+            const int b = (int)floorf(fabsf(w) * inv);
+            atomicAdd(&hist[b < B - 1 ? b : B - 1], 1u);
+        };
+        for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < numel4; i += (size_t)gridDim.x * blockDim.x) {
+            const float4 v = reinterpret_cast<const float4 *>(W)[i];
+            put(v.x);
+            put(v.y);
+            put(v.z);
+            put(v.w);
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < B; i += blockDim.x)
+        if (hist[i]) atomicAdd(&counts[i], hist[i]);
+}
+
+// E(alpha) over the histogram: one workgroup, fp64
+__device__ __forceinline__ double quant_error_block(const unsigned *counts, int B, double M, double alpha, double *red)
+{
+    const double step = alpha / 7.0, width = M / B;
+    double e = 0.0;
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        const double x = ((double)b + 0.5) * width;
+        const double d = x <= alpha ? rint(x / step) * step - x : alpha - x;
+        e += (double)counts[b] * (d * d);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) e += __shfl_xor(e, off, kWave);
+    __syncthreads();
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = e;
+    __syncthreads();
+    double t = 0.0;
+    for (int w = 0; w < (int)blockDim.x / kWave; ++w) t += red[w];
+    return t;
+}
+
+// candidates 0..9 coarse, 10..30 fine (the fine ones need the coarse errors: second launch)
+__global__ __launch_bounds__(1024) void quant_eval_kernel(const unsigned *mbits, const unsigned *counts, int B, double *err,
+                                                          int first)
+{
+    __shared__ double red[16];
+    const int c = first + blockIdx.x;
+    const double M = (double)__uint_as_float(*mbits);
+    if (M == 0.0) return;
+    const double eta = M / 10.0;
+    double alpha;
+    if (c < kCoarse) {
+        alpha = eta * (c + 1);
+    } else {
+        int best = 0;
+        for (int i = 1; i < kCoarse; ++i)
+            if (err[i] < err[best]) best = i;
+        alpha = eta * (best + 1) + eta * ((c - kCoarse - 10) / 10.0);
+        if (!(alpha > 0.0 && alpha <= M)) {
+            if (threadIdx.x == 0) err[c] = __builtin_inf();
+            return;
+        }
+    }
+    const double e = quant_error_block(counts, B, M, alpha, red);
+    if (threadIdx.x == 0) err[c] = e;
+}
+
+// alpha* = first minimum; scale_out[o] = alpha* / 7 for every row
+__global__ __launch_bounds__(256) void quant_pick_kernel(const unsigned *mbits, const double *err, float *scale_out, int n,
+                                                         float *alpha_out)
+{
+    const double M = (double)__uint_as_float(*mbits);
+    float alpha = 0.f, s = 1.f;
+    if (M > 0.0) {
+        const double eta = M / 10.0;
+        int best = 0;
+        for (int i = 1; i < kCoarse; ++i)
+            if (err[i] < err[best]) best = i;
+        const double lo = eta * (best + 1);
+        int pick = best;
+        for (int c = kCoarse; c < kCoarse + kFine; ++c)
+            if (err[c] < err[pick]) pick = c;
+        const double a = pick < kCoarse ? eta * (pick + 1) : lo + eta * ((pick - kCoarse - 10) / 10.0);
+        alpha = (float)a;
+        s = alpha / 7.0f;
+    }
+    for (int o = blockIdx.x * blockDim.x + threadIdx.x; o < n; o += gridDim.x * blockDim.x) scale_out[o] = s;
+    if (alpha_out && blockIdx.x == 0 && threadIdx.x == 0) *alpha_out = alpha;
+}
+
+}  // namespace slim
+
+using namespace slim;
+
+extern "C" int slim_quant_workspace_bytes(slim_shape shape, size_t *bytes)
+{
+    if (!bytes) return SLIM_ERR_NULL;
+    if (shape.n < 1 || shape.k < 8 || shape.k % 8) return SLIM_ERR_SHAPE;
+    *bytes = (size_t)(128 + quant_bins((long)shape.n * shape.k)) * 4;
+    return SLIM_OK;
+}
+
+extern "C" int slim_quant_search(const float *W, slim_shape shape, float *scale_out, float *alpha_out, void *workspace,
+                                 size_t workspace_bytes, void *stream)
+{
+    if (!W || !scale_out || !workspace) return SLIM_ERR_NULL;
+    if (shape.n < 1 || shape.k < 8 || shape.k % 8) return SLIM_ERR_SHAPE;
+    if (!aligned16(W) || !aligned16(workspace)) return SLIM_ERR_ALIGN;
+    const size_t numel = (size_t)shape.n * shape.k;
+    const int B = quant_bins((long)numel);
+    if (workspace_bytes < (size_t)(128 + B) * 4) return SLIM_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const QuantWs q = quant_ws(workspace);
+    const size_t numel4 = numel / 4;
+    size_t g = (numel4 + 255) / 256;
+    const unsigned grid_a = (unsigned)(g < 4096 ? g : 4096);
+    g = (numel4 + 1023) / 1024;
+    const unsigned grid_h = (unsigned)(g < 512 ? g : 512);
+    hipLaunchKernelGGL(quant_zero_kernel, dim3(32), dim3(256), 0, st, q.mbits, 128 + B);
+    hipLaunchKernelGGL(quant_absmax_kernel, dim3(grid_a), dim3(256), 0, st, W, numel4, q.mbits);
+    hipLaunchKernelGGL(quant_hist_kernel, dim3(grid_h), dim3(1024), (size_t)B * 4, st, W, numel4, B, q.mbits, q.counts);
+    hipLaunchKernelGGL(quant_eval_kernel, dim3(kCoarse), dim3(1024), 0, st, q.mbits, q.counts, B, q.err, 0);
+    hipLaunchKernelGGL(quant_eval_kernel, dim3(kFine), dim3(1024), 0, st, q.mbits, q.counts, B, q.err, kCoarse);
+    hipLaunchKernelGGL(quant_pick_kernel, dim3((unsigned)((shape.n + 255) / 256)), dim3(256), 0, st, q.mbits, q.err,
+                       scale_out, shape.n, alpha_out);
+    return hip_status(hipGetLastError());
+}

@@ -267,6 +267,80 @@ def test_gemv_and_gemm_agree():
     assert float((a - b).norm() / a.norm()) <= 1e-3
 
 
+# ---- slim_pack_ex / slim_quant_search (SLiM-Quant scale, saliency-weighted mask) ---------
+
+def _assert_packed_equal(qvals, meta, scale, codes, mask, ref_scale):
+    qv, me = O.pack(codes, mask)
+    qt, mt = tile_packed(qv, me)
+    torch.cuda.synchronize()
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), ref_scale.view(np.uint32))
+    assert np.array_equal(qvals.cpu().numpy(), qt)
+    assert np.array_equal(meta.cpu().numpy(), mt)
+
+
+@pytest.mark.parametrize("n,k,dist", [(512, 512, "normal"), (300, 1280, "t3"), (4096, 4096, "normal"), (64, 256, "outliers"),
+                                      (33, 136, "zero")])
+def test_quant_search_matches_the_oracle(n, k, dist):
+    rng = np.random.default_rng(n + k)
+    if dist == "normal":
+        W = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    elif dist == "t3":
+        W = rng.standard_t(3, size=(n, k)).astype(np.float32)
+    elif dist == "outliers":
+        W = (rng.standard_normal((n, k)) * 0.01).astype(np.float32)
+        W[0, :3] = [1.0, -0.7, 0.5]
+    else:
+        W = np.zeros((n, k), np.float32)
+    scale, alpha = B.slim_quant_search(torch.from_numpy(W).to(DEV))
+    torch.cuda.synchronize()
+    ra, rs = O.quant_search(W)
+    assert float(alpha.cpu()[0]) == float(ra)
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), np.full(n, rs, np.float32).view(np.uint32))
+
+
+@pytest.mark.parametrize("n,k", [(512, 512), (37, 136), (130, 12800), (1000, 4096)])
+def test_pack_ex_bit_exact(n, k):
+    """Saliency-weighted mask and given scales, separately and together, against the
+    oracle's mask / quantize / pack with the same inputs."""
+    rng = np.random.default_rng(n * 7 + k)
+    W = rng.standard_t(4, size=(n, k)).astype(np.float32)
+    sal = rng.uniform(0.05, 8.0, size=k).astype(np.float32)
+    sal[::17] = 0.0
+    _, rs = O.quant_search(W)
+    given = np.full(n, rs, np.float32)
+    given[: n // 2] *= np.float32(1.5)                       # not all rows alike
+    Wd = torch.from_numpy(W).to(DEV)
+    for use_sal, use_scale in ((True, False), (False, True), (True, True), (False, False)):
+        q, m, s = B.slim_pack_ex(Wd, torch.from_numpy(sal).to(DEV) if use_sal else None,
+                                 torch.from_numpy(given).to(DEV) if use_scale else None)
+        mask = O.mask_2of4(W, sal if use_sal else None)
+        ref_scale = given if use_scale else O.row_scale(W)
+        codes = O.quantize(W, mask, ref_scale)
+        _assert_packed_equal(q, m, s, codes, mask, ref_scale)
+
+
+def test_forward_of_a_layer_packed_with_searched_scale_and_saliency_mask():
+    """The whole chain: search the scale, pack with it and a saliency vector, run the
+    decode and prefill forwards against the oracle's forward of the same packed layer."""
+    shape = _shape(640, 1024, 51)
+    W, L, R, X = wl.make_layer(shape, 8, seed=9)
+    sal = np.random.default_rng(8).uniform(0.1, 3.0, size=shape.k).astype(np.float32)
+    Wd = W.to(DEV)
+    scale, _ = B.slim_quant_search(Wd)
+    q, m, s = B.slim_pack_ex(Wd, torch.from_numpy(sal).to(DEV), scale)
+    Lp, Rp = B.slim_pack_adapters(L.to(DEV), R.to(DEV))
+    layer = B.SlimLayer(shape.n, shape.k, shape.r, B.slim_rank_pad(shape.r), q, m, s, Lp, Rp)
+    _, rs = O.quant_search(W.numpy())
+    mask = O.mask_2of4(W.numpy(), sal)
+    ref_scale = np.full(shape.n, rs, np.float32)
+    qv, me = O.pack(O.quantize(W.numpy(), mask, ref_scale), mask)
+    Yref = O.forward(O.PackedLayer(qv, me, ref_scale), L.numpy(), R.numpy(), X.numpy())
+    for fn in (B.slim_linear_gemv, B.slim_linear_gemm):
+        Y = fn(layer, X.to(DEV))
+        torch.cuda.synchronize()
+        assert _relerr(Y.cpu().numpy(), Yref) <= TOL_Y
+
+
 # ---- 4-bit adapters (Sec. 3.3) ------------------------------------------------------
 
 def _q4_layer(W, L, R):
