@@ -232,6 +232,22 @@ def main():
     legs.append({"shape": shape.name, "entry": "slim_pack", "us": round(ms_pack * 1e3, 2),
                  "GBps": round(pb / ms_pack * 1e-6, 1), "bound": "hbm",
                  "roofline_frac": round(pb / ms_pack * 1e-6 / HBM_PEAK_GBPS, 4)})
+    # slim_quant_search reads W twice (maximum, histogram); slim_pack_ex as slim_pack plus the saliency vector
+    for i in range(5):
+        B.slim_quant_search(wcopies[i % len(wcopies)])
+    ms_qs = event_time_ms(lambda i: B.slim_quant_search(wcopies[i % len(wcopies)]), 45)
+    qb = 2 * 4 * shape.n * shape.k
+    legs.append({"shape": shape.name, "entry": "slim_quant_search", "us": round(ms_qs * 1e3, 2),
+                 "GBps": round(qb / ms_qs * 1e-6, 1), "bound": "hbm",
+                 "roofline_frac": round(qb / ms_qs * 1e-6 / HBM_PEAK_GBPS, 4)})
+    sal = torch.rand(shape.k, device=dev) + 0.5
+    sc_in, _ = B.slim_quant_search(rot.W_dev)
+    for i in range(5):
+        B.slim_pack_ex(wcopies[i % len(wcopies)], sal, sc_in)
+    ms_px = event_time_ms(lambda i: B.slim_pack_ex(wcopies[i % len(wcopies)], sal, sc_in), 45)
+    legs.append({"shape": shape.name, "entry": "slim_pack_ex", "us": round(ms_px * 1e3, 2),
+                 "GBps": round(pb / ms_px * 1e-6, 1), "bound": "hbm",
+                 "roofline_frac": round(pb / ms_px * 1e-6 / HBM_PEAK_GBPS, 4)})
     del wcopies
 
     # ---------------- CPU oracle baseline (rank 0 = this process) ----------------

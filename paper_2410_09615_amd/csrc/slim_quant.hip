@@ -21,9 +21,10 @@ namespace slim {
 constexpr int kCoarse = 10;
 constexpr int kFine = 21;
 constexpr int kMaxBins = 20000;
+constexpr int kMaxBlocks = 1024;        // workgroups of the maximum pass (one partial maximum each)
 
-// workspace: [0] bits of M (uint), [16 .. 16 + 31] errors (double, byte offset 64),
-// [128 ..] counts (uint)
+// workspace (32-bit words): [0] bits of M, [16 .. 77] errors (31 doubles from byte 64),
+// [128 .. 128 + B) counts, then kMaxBlocks per-workgroup maxima
 struct QuantWs {
     unsigned *mbits;
     double *err;
@@ -44,31 +45,40 @@ __host__ __device__ inline int quant_bins(long numel)
     return (int)(b > 512 ? b : 512);
 }
 
-__global__ __launch_bounds__(256) void quant_zero_kernel(unsigned *ws, int words)
+// partial maxima of |W|, one per workgroup (no atomics: thousands of them on one
+// address would serialize at memory)
+__global__ __launch_bounds__(256) void quant_absmax_kernel(const float *__restrict__ W, size_t numel4, float *bmax,
+                                                           unsigned *ws, int words)
 {
+    __shared__ float part[4];
+    // the words the later kernels add into start at zero (this kernel runs before them)
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < words; i += gridDim.x * blockDim.x) ws[i] = 0u;
-}
-
-// M = max|W|: non-negative floats order like their bit patterns
-__global__ __launch_bounds__(256) void quant_absmax_kernel(const float *__restrict__ W, size_t numel4, unsigned *mbits)
-{
     float a = 0.f;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < numel4; i += (size_t)gridDim.x * blockDim.x) {
         const float4 v = reinterpret_cast<const float4 *>(W)[i];
         a = fmaxf(a, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
     }
     a = wave_max(a);
-    if ((threadIdx.x & (kWave - 1)) == 0) atomicMax(mbits, __float_as_uint(a));
+    if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x / kWave] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) bmax[blockIdx.x] = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
 }
 
 // per-workgroup histogram in LDS, then one global add per non-empty bin
 __global__ __launch_bounds__(1024) void quant_hist_kernel(const float *__restrict__ W, size_t numel4, int B,
-                                                          const unsigned *mbits, unsigned *counts)
+                                                          const float *bmax, int nblocks, unsigned *mbits, unsigned *counts)
 {
     extern __shared__ unsigned hist[];
+    __shared__ float part[16];
     for (int i = threadIdx.x; i < B; i += blockDim.x) hist[i] = 0u;
+    // M from the partial maxima (every workgroup for itself; workgroup 0 publishes it)
+    float a = (int)threadIdx.x < nblocks ? bmax[threadIdx.x] : 0.f;
+    a = wave_max(a);
+    if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x / kWave] = a;
     __syncthreads();
-    const float M = __uint_as_float(*mbits);
+    float M = part[0];
+    for (int w = 1; w < (int)blockDim.x / kWave; ++w) M = fmaxf(M, part[w]);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *mbits = __float_as_uint(M);
     if (M > 0.f) {
         const float inv = (float)B / M;
         auto put = [&](float w) {
@@ -165,7 +175,7 @@ extern "C" int slim_quant_workspace_bytes(slim_shape shape, size_t *bytes)
 {
     if (!bytes) return SLIM_ERR_NULL;
     if (shape.n < 1 || shape.k < 8 || shape.k % 8) return SLIM_ERR_SHAPE;
-    *bytes = (size_t)(128 + quant_bins((long)shape.n * shape.k)) * 4;
+    *bytes = (size_t)(128 + quant_bins((long)shape.n * shape.k) + kMaxBlocks) * 4;
     return SLIM_OK;
 }
 
@@ -177,17 +187,18 @@ extern "C" int slim_quant_search(const float *W, slim_shape shape, float *scale_
     if (!aligned16(W) || !aligned16(workspace)) return SLIM_ERR_ALIGN;
     const size_t numel = (size_t)shape.n * shape.k;
     const int B = quant_bins((long)numel);
-    if (workspace_bytes < (size_t)(128 + B) * 4) return SLIM_ERR_WORKSPACE;
+    if (workspace_bytes < (size_t)(128 + B + kMaxBlocks) * 4) return SLIM_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const QuantWs q = quant_ws(workspace);
     const size_t numel4 = numel / 4;
     size_t g = (numel4 + 255) / 256;
-    const unsigned grid_a = (unsigned)(g < 4096 ? g : 4096);
+    const unsigned grid_a = (unsigned)(g < (size_t)kMaxBlocks ? g : (size_t)kMaxBlocks);
+    float *bmax = reinterpret_cast<float *>(q.counts + B);
     g = (numel4 + 1023) / 1024;
     const unsigned grid_h = (unsigned)(g < 512 ? g : 512);
-    hipLaunchKernelGGL(quant_zero_kernel, dim3(32), dim3(256), 0, st, q.mbits, 128 + B);
-    hipLaunchKernelGGL(quant_absmax_kernel, dim3(grid_a), dim3(256), 0, st, W, numel4, q.mbits);
-    hipLaunchKernelGGL(quant_hist_kernel, dim3(grid_h), dim3(1024), (size_t)B * 4, st, W, numel4, B, q.mbits, q.counts);
+    hipLaunchKernelGGL(quant_absmax_kernel, dim3(grid_a), dim3(256), 0, st, W, numel4, bmax, q.mbits, 128 + B);
+    hipLaunchKernelGGL(quant_hist_kernel, dim3(grid_h), dim3(1024), (size_t)B * 4, st, W, numel4, B, bmax, (int)grid_a, q.mbits,
+                       q.counts);
     hipLaunchKernelGGL(quant_eval_kernel, dim3(kCoarse), dim3(1024), 0, st, q.mbits, q.counts, B, q.err, 0);
     hipLaunchKernelGGL(quant_eval_kernel, dim3(kFine), dim3(1024), 0, st, q.mbits, q.counts, B, q.err, kCoarse);
     hipLaunchKernelGGL(quant_pick_kernel, dim3((unsigned)((shape.n + 255) / 256)), dim3(256), 0, st, q.mbits, q.err,
