@@ -36,7 +36,7 @@ CACHE_BYTES = 256 << 20         # Infinity Cache
 # the headline layer) from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE),
 # scaled by the 256 MiB copy below (one FETCH_SIZE unit = 2 KiB, one WRITE_SIZE
 # unit = 1 KiB).  Source: profiles/decode_gemv_llama7b_attn_16tok_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = 15.13e6   # 14.95 MB read + 0.18 MB written per slim_linear_gemv call at 16 tokens
+MEASURED_TRAFFIC_BYTES = 15.85e6   # 15.67 MB read + 0.18 MB written per slim_linear_gemv call at 16 tokens
 
 
 def parse_args():
