@@ -86,7 +86,8 @@ def _ptr(t):
 
 
 def _stream(t: torch.Tensor):
-    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+    """Raw handle of torch's current stream on t's device."""
+    return ctypes.c_void_p(torch._C._cuda_getCurrentRawStream(t.device.index))
 
 
 def _dev(t: torch.Tensor, dtype, name: str):
@@ -136,6 +137,20 @@ class SlimLayer:
         return slim_layer(slim_shape(self.n, self.k, self.rank), self.qvals.data_ptr(), self.meta.data_ptr(),
                           self.scale.data_ptr(), p(self.L), p(self.R), self.rank_pad, self.adapter_bits,
                           p(self.Lq), p(self.Ls), p(self.Rq), p(self.Rs))
+
+    def c_ref(self):
+        """Pointer argument for the forward calls: the struct is built once per layer and rebuilt after
+        any field is assigned (a decode call is a few microseconds; building the struct costs one)."""
+        ref = self.__dict__.get("_ref")
+        if ref is None:
+            cs = self.c_struct()
+            ref = (ctypes.byref(cs), cs)
+            self.__dict__["_ref"] = ref
+        return ref[0]
+
+    def __setattr__(self, name, value):
+        self.__dict__.pop("_ref", None)
+        object.__setattr__(self, name, value)
 
 
 def slim_pack(W: torch.Tensor, qvals=None, meta=None, scale=None):
@@ -285,11 +300,15 @@ def _forward(fn_name: str, layer: SlimLayer, X: torch.Tensor, Y, workspace):
         raise ValueError("X has the wrong number of inputs")
     if Y is None:
         Y = torch.empty(m, layer.n, dtype=torch.float16, device=X.device)
+    elif Y.dtype != torch.float16 or Y.numel() != m * layer.n or Y.device != X.device or not Y.is_contiguous():
+        raise ValueError("Y must be contiguous float16 [m][n] on X's device")
     if workspace is None:
         workspace = alloc_workspace(layer, m)
-    cs = layer.c_struct()
-    fn = getattr(lib(), fn_name)
-    _check(fn_name, fn(ctypes.byref(cs), _ptr(X), m, _ptr(Y), _ptr(workspace), workspace.numel(), _stream(X)))
+    # plain integers for the pointers: with argtypes set ctypes converts them itself
+    status = getattr(lib(), fn_name)(layer.c_ref(), X.data_ptr(), m, Y.data_ptr(), workspace.data_ptr(),
+                                     workspace.numel(), torch._C._cuda_getCurrentRawStream(X.device.index))
+    if status != SLIM_OK:
+        _check(fn_name, status)
     return Y
 
 
