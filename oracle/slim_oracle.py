@@ -347,3 +347,40 @@ def quant_search(W: np.ndarray):
             errs.append(quant_error(counts, M, a))
     alpha = np.float32(cand[int(np.argmin(errs))])
     return alpha, np.float32(alpha / np.float32(7.0))
+
+
+# ---- low-rank adapters: Naive-LoRA and SLiM-LoRA (Sec. 3.2, Eq. 8-11, Alg. 2) ----------
+# Plain numpy in float64; the SVD is LAPACK's.  Orientation as everywhere in this
+# file: the paper's matrices transposed.  The paper's saliency diag(x) W scales
+# the input channels, which are the COLUMNS of W [n][k] here: S = E diag(x).
+
+def saliency_shift(x_tilde: np.ndarray) -> np.ndarray:
+    """x = x~ + min|x~| (Alg. 2, the step that keeps diag(x) invertible).  x~ is the
+    per-input-channel average magnitude of the calibration inputs; it has to be
+    positive and finite (with a zero entry the shift is zero and diag(x) singular)."""
+    x_tilde = np.asarray(x_tilde, np.float64)
+    assert x_tilde.ndim == 1 and np.all(np.isfinite(x_tilde)) and np.all(x_tilde > 0)
+    return x_tilde + np.min(np.abs(x_tilde))
+
+
+def compute_adapters(W: np.ndarray, Wc: np.ndarray, x_tilde, rank: int):
+    """Adapters with W ~= Wc + L R (Sec. 3.2), rank r, minimising the saliency-weighted
+    error ||(W - Wc - L R) diag(x)||_F (Eq. 9-11).
+
+    Steps of Alg. 2: E = W - Wc (the sign that makes W ~= Wc + L R); x from
+    saliency_shift (x_tilde None: x = 1, which is Naive-LoRA); S = E diag(x);
+    S = U Sigma V^T; the factor on the input-channel side carries Sigma and the
+    inverse saliency:  L = U_r [n][r],  R = Sigma_r V_r^T diag(1 / x) [r][k].
+    Returns (L, R, singular values of S), float64."""
+    W = np.asarray(W, np.float64)
+    Wc = np.asarray(Wc, np.float64)
+    n, k = W.shape
+    assert Wc.shape == (n, k) and 1 <= rank <= min(n, k)
+    x = np.ones(k) if x_tilde is None else saliency_shift(x_tilde)
+    assert x.shape == (k,)
+    E = W - Wc
+    S = E * x[None, :]
+    U, s, Vt = np.linalg.svd(S, full_matrices=False)
+    L = U[:, :rank]
+    R = (s[:rank, None] * Vt[:rank, :]) / x[None, :]
+    return L, R, s
