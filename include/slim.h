@@ -161,6 +161,36 @@ int slim_quant_search(const float *W, slim_shape shape, float *scale_out, float 
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * slim_compute_adapters -- the low-rank adapters of a compressed layer: Naive-LoRA
+ * and SLiM-LoRA (Sec. 3.2, Eq. 8-11, Alg. 2).  With E = W - W^C (so that
+ * W ~= W^C + L R), x = x_tilde + min|x_tilde| and the error saliency
+ * S = E diag(x) (input channels are the columns of W here), the adapters are the
+ * rank-r truncation of S with the saliency taken out again:
+ *   L [n][rank]  orthonormal columns spanning the leading left singular vectors of S,
+ *   R [rank][k]  (L^T S) diag(1 / x),
+ * both fp16, row-major (what slim_pack_adapters takes); L R minimises
+ * ||(W - W^C - L R) diag(x)||_F over rank-r products.
+ *   W [n][k] fp32, the dense weights; qvals, meta, scale: the layer slim_pack made of them;
+ *   x_tilde [k]  fp32, the mean magnitude of the calibration inputs per input channel,
+ *                positive and finite (the caller's; not checked); NULL: x = 1, Naive-LoRA;
+ *   shape.rank   1 <= rank <= min(n, k), slim_rank_pad(rank) <= 1024;
+ *   iters        rounds of the subspace iteration Q <- orth(S orth(S^T Q)) that stands in
+ *                for the SVD (0: 16).  It starts from a block of `rank` columns drawn
+ *                from `seed`; its distance from the exact truncation shows in diag;
+ *   diag         (may be NULL) four floats out: ||S||_F^2, the captured part
+ *                ||L^T S||_F^2 (the exact truncation captures the sum of the rank
+ *                largest squared singular values), max |L^T L - I|, 0.
+ * All dense work is fp32 on the matrix cores.  workspace:
+ * slim_adapters_workspace_bytes (HOST out-pointer; about 4 n k bytes plus the
+ * blocks), need not be zeroed.  Errors: NULL, SHAPE, ALIGN, WORKSPACE, HIP.
+ */
+int slim_adapters_workspace_bytes(slim_shape shape, size_t *bytes);
+int slim_compute_adapters(const float *W, const uint8_t *qvals, const uint8_t *meta, const float *scale,
+                          slim_shape shape, const float *x_tilde, int32_t iters, uint32_t seed,
+                          slim_half *L, slim_half *R, float *diag, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/*
  * slim_pack_adapters -- lay the fp16 adapters out for the kernels: L [n][rank]
  * and R [rank][k], row-major, go into L_pad = [n][rank_pad] and R_pad =
  * [rank_pad][k] in the adapter layout above (sizes from slim_packed_sizes),

@@ -39,7 +39,8 @@ SLIM_OK, SLIM_ERR_NULL, SLIM_ERR_SHAPE, SLIM_ERR_ALIGN, SLIM_ERR_WORKSPACE, SLIM
 EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pack", "slim_pack_adapters",
            "slim_unpack", "slim_workspace_bytes", "slim_linear_gemv", "slim_linear_gemm", "slim_lowrank",
            "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4", "slim_pack_ex",
-           "slim_quant_workspace_bytes", "slim_quant_search"]
+           "slim_quant_workspace_bytes", "slim_quant_search", "slim_adapters_workspace_bytes",
+           "slim_compute_adapters"]
 
 
 def lib():
@@ -65,6 +66,8 @@ def lib():
         L.slim_pack_ex.argtypes = [vp, slim_shape, vp, vp, vp, vp, vp, vp]
         L.slim_quant_workspace_bytes.argtypes = [slim_shape, psz]
         L.slim_quant_search.argtypes = [vp, slim_shape, vp, vp, vp, sz, vp]
+        L.slim_adapters_workspace_bytes.argtypes = [slim_shape, psz]
+        L.slim_compute_adapters.argtypes = [vp, vp, vp, vp, slim_shape, vp, i32, ctypes.c_uint32, vp, vp, vp, vp, sz, vp]
         L.slim_pack_adapters_q4.argtypes = [vp, vp, slim_shape, vp, vp, vp, vp, vp]
         L.slim_unpack_adapters_q4.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.slim_linear_gemv.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp, sz, vp]
@@ -197,6 +200,29 @@ def slim_quant_search(W: torch.Tensor):
     _check("slim_quant_search", lib().slim_quant_search(_ptr(W), slim_shape(n, k, 0), _ptr(scale), _ptr(alpha), _ptr(ws),
                                                         ws.numel(), _stream(W)))
     return scale, alpha
+
+
+def slim_compute_adapters(W: torch.Tensor, qvals, meta, scale, rank: int, x_tilde: torch.Tensor | None = None,
+                          iters: int = 0, seed: int = 1):
+    """Adapters of a compressed layer (Naive-LoRA when x_tilde is None, else SLiM-LoRA):
+    (L fp16 [n][rank], R fp16 [rank][k], diag fp32 [4] = ||S||^2, captured ||L^T S||^2, max|L^T L - I|, 0)."""
+    _dev(W, torch.float32, "W")
+    n, k = W.shape
+    if x_tilde is not None:
+        _dev(x_tilde, torch.float32, "x_tilde")
+        if x_tilde.numel() != k:
+            raise ValueError("x_tilde must have one entry per input")
+    shape = slim_shape(n, k, rank)
+    nbytes = ctypes.c_size_t()
+    _check("slim_adapters_workspace_bytes", lib().slim_adapters_workspace_bytes(shape, nbytes))
+    ws = torch.empty(nbytes.value, dtype=torch.uint8, device=W.device)
+    L = torch.empty(n, rank, dtype=torch.float16, device=W.device)
+    R = torch.empty(rank, k, dtype=torch.float16, device=W.device)
+    diag = torch.empty(4, dtype=torch.float32, device=W.device)
+    _check("slim_compute_adapters",
+           lib().slim_compute_adapters(_ptr(W), _ptr(qvals), _ptr(meta), _ptr(scale), shape, _ptr(x_tilde), iters, seed,
+                                       _ptr(L), _ptr(R), _ptr(diag), _ptr(ws), ws.numel(), _stream(W)))
+    return L, R, diag
 
 
 def slim_pack_adapters(L: torch.Tensor, R: torch.Tensor):
