@@ -248,6 +248,16 @@ def main():
     legs.append({"shape": shape.name, "entry": "slim_pack_ex", "us": round(ms_px * 1e3, 2),
                  "GBps": round(pb / ms_px * 1e-6, 1), "bound": "hbm",
                  "roofline_frac": round(pb / ms_px * 1e-6 / HBM_PEAK_GBPS, 4)})
+    # slim_compute_adapters: the adapters of this layer from its dense weights (16 rounds of the subspace
+    # iteration); rate on the products with the error saliency alone, 2 (2 q + 2) n k rank_pad FLOPs
+    xt = torch.rand(shape.k, device=dev) + 0.1
+    B.slim_compute_adapters(rot.W_dev, q, me, sc, shape.r, xt)
+    torch.cuda.synchronize()
+    ms_ca = event_time_ms(lambda i: B.slim_compute_adapters(rot.W_dev, q, me, sc, shape.r, xt), 3)
+    ca_flops = 2.0 * (2 * 16 + 2) * shape.n * shape.k * B.slim_rank_pad(shape.r)
+    legs.append({"shape": shape.name, "entry": "slim_compute_adapters", "us": round(ms_ca * 1e3, 1),
+                 "TFLOPs": round(ca_flops / ms_ca * 1e-9, 2), "bound": "mfma", "dtype": "f32",
+                 "roofline_frac": round(ca_flops / ms_ca * 1e-9 / 157.3, 4)})
     del wcopies
 
     # ---------------- CPU oracle baseline (rank 0 = this process) ----------------

@@ -8,8 +8,9 @@
 // seeded random block of r columns.  The product Q Q^T S converges to the best rank-r
 // approximation of S (Eckart-Young); how far it is from it after `iters` rounds shows in the
 // captured energy ||Q^T S||_F^2 the call reports.  Everything is dense fp32 work on the matrix
-// cores (V_MFMA_F32_32X32X2_F32): five GEMM shapes through one kernel, orthonormalisation as
-// Cholesky QR (Gram matrix, Cholesky factor, inverse of the factor, one more GEMM).
+// cores (V_MFMA_F32_32X32X2_F32), all GEMM shapes through one kernel; orthonormalisation is
+// Cholesky QR in blocks of 64 columns (Gram matrix, then per block a small factor-and-invert
+// kernel and GEMMs for the panel, the trailing update and the application to the block).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -20,13 +21,15 @@ namespace slim {
 
 typedef float float16v_t __attribute__((ext_vector_type(16)));
 
-// ---- C = A B or A^T B, fp32, row-major, optional split over K with atomic adds ----
+// ---- C = alpha op(A) op(B) + beta C, fp32, row-major, optional split over K with atomic adds ----
 struct SgemmArgs {
     const float *A, *B;
     float *C;
     int M, N, K;          // C is [M][N]; K is the summed dimension
-    int lda, ldb, ldc;    // A is [M][K] (lda >= K), or [K][M] when transposed (lda >= M); B is [K][N]
+    int lda, ldb, ldc;    // A is [M][K], or [K][M] when TA; B is [K][N], or [N][K] when TB
     int kchunk;           // K values per grid.z slice (a multiple of 16); C is added to atomically when there are several
+    float alpha;
+    int beta;             // 0: C is overwritten (zeroed first when K is split), 1: added to
 };
 
 constexpr int kGM = 128, kGN = 128, kGK = 16, kGLd = kGK + 4;      // LDS rows of 16 k-values, padded to 20 floats
@@ -36,7 +39,7 @@ constexpr int kGM = 128, kGN = 128, kGK = 16, kGLd = kGK + 4;      // LDS rows o
 // (r = lane % 32, h = lane / 32) of a block reads the four k-values 8 s + 4 h .. + 3 of
 // its row with one 128-bit read and feeds them to four instructions; A and B use the
 // same assignment of k-values to (lane half, instruction), so the sum is complete.
-template <bool TA>
+template <bool TA, bool TB>
 __global__ __launch_bounds__(256) void sgemm_kernel(SgemmArgs a)
 {
     __shared__ __attribute__((aligned(16))) float As[kGM * kGLd];
@@ -75,11 +78,21 @@ __global__ __launch_bounds__(256) void sgemm_kernel(SgemmArgs a)
                                                : float4_t{0.f, 0.f, 0.f, 0.f};
             }
         }
+        if constexpr (TB) {
+            // B [N][K]: as the untransposed A
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int kk = k0 + (tid >> 5) + 8 * i, col = n0 + (tid & 31) * 4;
-            rb[i] = (kk < ke && col < a.N) ? *reinterpret_cast<const float4_t *>(a.B + (size_t)kk * a.ldb + col)
-                                           : float4_t{0.f, 0.f, 0.f, 0.f};
+            for (int i = 0; i < 2; ++i) {
+                const int col = n0 + (tid >> 2) + 64 * i, kk = k0 + (tid & 3) * 4;
+                rb[i] = (col < a.N && kk < ke) ? *reinterpret_cast<const float4_t *>(a.B + (size_t)col * a.ldb + kk)
+                                               : float4_t{0.f, 0.f, 0.f, 0.f};
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int kk = k0 + (tid >> 5) + 8 * i, col = n0 + (tid & 31) * 4;
+                rb[i] = (kk < ke && col < a.N) ? *reinterpret_cast<const float4_t *>(a.B + (size_t)kk * a.ldb + col)
+                                               : float4_t{0.f, 0.f, 0.f, 0.f};
+            }
         }
     };
     auto store_slab = [&]() {
@@ -93,10 +106,16 @@ __global__ __launch_bounds__(256) void sgemm_kernel(SgemmArgs a)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) As[((tid & 31) * 4 + e) * kGLd + (tid >> 5) + 8 * i] = ra[i][e];
         }
+        if constexpr (TB) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i)
+                *reinterpret_cast<float4_t *>(Bs + ((tid >> 2) + 64 * i) * kGLd + (tid & 3) * 4) = rb[i];
+        } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) Bs[((tid & 31) * 4 + e) * kGLd + (tid >> 5) + 8 * i] = rb[i][e];
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) Bs[((tid & 31) * 4 + e) * kGLd + (tid >> 5) + 8 * i] = rb[i][e];
+        }
     };
 
     // M and N are multiples of 4 wherever a 128-bit load straddles the edge (row counts
@@ -138,10 +157,11 @@ __global__ __launch_bounds__(256) void sgemm_kernel(SgemmArgs a)
                     const int row = m0 + wm + 32 * i + 8 * b + 4 * h + e;
                     if (row >= a.M) continue;
                     float *c = a.C + (size_t)row * a.ldc + col;
+                    const float v = a.alpha * acc[i][j][4 * b + e];
                     if (add)
-                        atomicAdd(c, acc[i][j][4 * b + e]);
+                        atomicAdd(c, v);
                     else
-                        *c = acc[i][j][4 * b + e];
+                        *c = a.beta ? *c + v : v;
                 }
         }
 }
@@ -158,11 +178,13 @@ static int launch_fill(float *p, size_t count, float v, hipStream_t st)
     return hip_status(hipGetLastError());
 }
 
-// C = op(A) B.  Few tiles and a long K: K is split over grid.z and C, zeroed first, is added to.
-static int sgemm(bool ta, const float *A, int lda, const float *B, int ldb, float *C, int ldc, int M, int N, int K,
-                 hipStream_t st)
+// C = alpha op(A) op(B) + beta C.  Few tiles and a long K: K is split over grid.z and C
+// (zeroed first when beta = 0) is added to.
+static int sgemm(bool ta, bool tb, const float *A, int lda, const float *B, int ldb, float *C, int ldc, int M, int N, int K,
+                 hipStream_t st, float alpha = 1.0f, int beta = 0)
 {
-    SgemmArgs a{A, B, C, M, N, K, lda, ldb, ldc, 0};
+    if (M <= 0 || N <= 0 || K <= 0) return SLIM_OK;
+    SgemmArgs a{A, B, C, M, N, K, lda, ldb, ldc, 0, alpha, beta};
     const int tm = (M + kGM - 1) / kGM, tn = (N + kGN - 1) / kGN;
     int splits = 1;
     if (tm * tn < 512) splits = (512 + tm * tn - 1) / (tm * tn);
@@ -170,20 +192,34 @@ static int sgemm(bool ta, const float *A, int lda, const float *B, int ldb, floa
     if (splits > kslabs / 4) splits = kslabs / 4 > 0 ? kslabs / 4 : 1;      // at least 64 k-values per slice
     a.kchunk = (kslabs + splits - 1) / splits * kGK;
     splits = (K + a.kchunk - 1) / a.kchunk;
-    if (splits > 1) {
+    if (splits > 1 && !beta) {
         if (ldc == N) {
             const int rc = launch_fill(C, (size_t)M * N, 0.f, st);
             if (rc != SLIM_OK) return rc;
         } else {
-            return SLIM_ERR_SHAPE;      // not used: every C here is contiguous
+            return SLIM_ERR_SHAPE;      // not used: a C that is overwritten with K split is contiguous here
         }
     }
     const dim3 grid(tn, tm, splits);
-    if (ta)
-        hipLaunchKernelGGL(sgemm_kernel<true>, grid, dim3(256), 0, st, a);
+    if (ta && !tb)
+        hipLaunchKernelGGL((sgemm_kernel<true, false>), grid, dim3(256), 0, st, a);
+    else if (!ta && tb)
+        hipLaunchKernelGGL((sgemm_kernel<false, true>), grid, dim3(256), 0, st, a);
+    else if (!ta && !tb)
+        hipLaunchKernelGGL((sgemm_kernel<false, false>), grid, dim3(256), 0, st, a);
     else
-        hipLaunchKernelGGL(sgemm_kernel<false>, grid, dim3(256), 0, st, a);
+        return SLIM_ERR_SHAPE;          // A^T B^T is not needed here
     return hip_status(hipGetLastError());
+}
+
+// One atomic add per workgroup of 256 threads (adds to one address serialise).
+__device__ __forceinline__ void block_add(float part, float *dst)
+{
+    __shared__ float red4[4];
+    part = wave_sum(part);
+    if ((threadIdx.x & 63) == 0) red4[threadIdx.x >> 6] = part;
+    __syncthreads();
+    if (threadIdx.x == 0) atomicAdd(dst, red4[0] + red4[1] + red4[2] + red4[3]);
 }
 
 // ---- x = x~ + min|x~| (Alg. 2), or ones ----
@@ -230,8 +266,7 @@ __global__ __launch_bounds__(256) void lora_error_kernel(const float *W, const u
         }
         *reinterpret_cast<float4_t *>(S + (size_t)o * k + 4 * g) = e;
     }
-    part = wave_sum(part);
-    if ((threadIdx.x & 63) == 0) atomicAdd(sq, part);
+    block_add(part, sq);
 }
 
 // ---- start block: uniform in (-1, 1) from a hash of (seed, element), columns >= r zero ----
@@ -255,65 +290,74 @@ __global__ void lora_init_kernel(float *Z, int rows, int l, int r, uint32_t seed
     }
 }
 
-// ---- Cholesky factor of the Gram matrix, in place (lower triangle), one workgroup ----
-// A pivot below 1e-9 of the largest diagonal entry marks a column that lies in the span of
-// the ones before it (or a padding column of zeros): it gets pivot 1 and a zero column, so
-// the orthonormalised block carries a zero column there.
+// ---- Cholesky QR in blocks of 64 columns ----
+// G = Lc Lc^T is factored block column by block column: the 64 x 64 diagonal block and its
+// inverse in one small workgroup (below), the panel under it and the trailing update as
+// GEMMs.  A pivot below 1e-9 of the largest diagonal entry of G marks a column that lies in
+// the span of the ones before it (or a padding column of zeros): it gets pivot 1 and a zero
+// column, so the orthonormalised block carries a (numerically) zero column there.
 constexpr int kMaxBlock = 1024;          // columns of the iteration block (rank_pad)
+constexpr int kCb = 64;                  // block width of the factorisation
 
-__global__ __launch_bounds__(1024) void lora_chol_kernel(float *G, int l)
+__global__ __launch_bounds__(1024) void lora_diagmax_kernel(const float *G, int l, float *out)
 {
-    __shared__ float col[kMaxBlock];
     __shared__ float red[16];
-    __shared__ float piv;
-    const int tid = threadIdx.x, T = blockDim.x;
     float mx = 0.f;
-    for (int i = tid; i < l; i += T) mx = fmaxf(mx, G[(size_t)i * l + i]);
+    for (int i = threadIdx.x; i < l; i += blockDim.x) mx = fmaxf(mx, G[(size_t)i * l + i]);
     mx = wave_max(mx);
-    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
     __syncthreads();
-    mx = red[0];
-    for (int w = 1; w < T / 64; ++w) mx = fmaxf(mx, red[w]);
-    const float floor_ = mx * 1e-9f;
-    for (int j = 0; j < l; ++j) {
-        if (tid == 0) {
-            const float d = G[(size_t)j * l + j];
-            piv = d > floor_ ? sqrtf(d) : 0.f;
-        }
-        __syncthreads();
-        const float p = piv;
-        const float inv = p > 0.f ? 1.0f / p : 0.f;
-        for (int i = j + 1 + tid; i < l; i += T) {
-            const float v = G[(size_t)i * l + j] * inv;
-            G[(size_t)i * l + j] = v;
-            col[i] = v;
-        }
-        if (tid == 0) G[(size_t)j * l + j] = p > 0.f ? p : 1.0f;
-        __syncthreads();
-        // trailing update of the lower triangle: G[i][c] -= col[i] col[c], j < c <= i
-        const int cnt = l - j - 1;
-        if (p > 0.f)
-            for (int idx = tid; idx < cnt * cnt; idx += T) {
-                const int i = j + 1 + idx / cnt, c = j + 1 + idx % cnt;
-                if (c <= i) G[(size_t)i * l + c] -= col[i] * col[c];
-            }
-        __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < (int)blockDim.x / 64; ++w) mx = fmaxf(mx, red[w]);
+        *out = mx;
     }
 }
 
-// ---- B = (inverse of the lower factor)^T: B[j][i] = X[i][j], X = Lc^-1; thread per column j of X ----
-__global__ __launch_bounds__(64) void lora_trinv_kernel(const float *Lc, float *B, int l)
+// Diagonal block at (j0, j0), width w <= 64: L11 replaces its lower triangle in G, and
+// X11 = L11^-1 (lower triangular, zeros above) goes to D[j0 .. j0 + w)[0 .. 64).
+__global__ __launch_bounds__(256) void lora_chol_diag_kernel(float *G, int l, int j0, int w, const float *gmax, float *D)
 {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= l) return;
-    float *row = B + (size_t)j * l;                 // column j of X, as a row of B
-    for (int i = 0; i < j; ++i) row[i] = 0.f;
-    row[j] = 1.0f / Lc[(size_t)j * l + j];
-    for (int i = j + 1; i < l; ++i) {
-        const float *li = Lc + (size_t)i * l;
-        float s = 0.f;
-        for (int p = j; p < i; ++p) s += li[p] * row[p];
-        row[i] = -s / li[i];
+    __shared__ float a[kCb][kCb + 1];
+    __shared__ float x[kCb][kCb + 1];
+    __shared__ float piv;
+    const int tid = threadIdx.x, T = blockDim.x, ty = tid >> 4, tx = tid & 15;
+    for (int idx = tid; idx < w * w; idx += T) {
+        const int i = idx / w, c = idx % w;
+        a[i][c] = G[(size_t)(j0 + i) * l + j0 + c];
+        x[i][c] = i == c ? 1.0f : 0.f;
+    }
+    const float floor_ = *gmax * 1e-9f;
+    // Column c of the factor and row c of the inverse are final after step c: the forward
+    // substitution L X = I runs along with the factorisation (x starts as the identity).
+    for (int c = 0; c < w; ++c) {
+        __syncthreads();
+        if (tid == 0) {
+            const float d = a[c][c];
+            const float pv = d > floor_ ? sqrtf(d) : 0.f;
+            piv = pv;
+            a[c][c] = pv > 0.f ? pv : 1.0f;
+        }
+        __syncthreads();
+        const float inv = piv > 0.f ? 1.0f / piv : 0.f;
+        const float dinv = 1.0f / a[c][c];
+        for (int i = c + 1 + tid; i < w; i += T) a[i][c] *= inv;
+        for (int cc = tid; cc <= c; cc += T) x[c][cc] *= dinv;
+        __syncthreads();
+        // threads as a 16 x 16 grid over (row, column): no divisions in the loops
+        for (int i = c + 1 + ty; i < w; i += 16) {
+            const float lic = a[i][c];
+            for (int cc = c + 1 + tx; cc <= i; cc += 16) a[i][cc] -= lic * a[cc][c];
+            for (int cc = tx; cc <= c; cc += 16) x[i][cc] -= lic * x[c][cc];
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < w * w; idx += T) {
+        const int i = idx / w, c = idx % w;
+        if (c <= i) G[(size_t)(j0 + i) * l + j0 + c] = a[i][c];
+    }
+    for (int idx = tid; idx < w * kCb; idx += T) {
+        const int i = idx / kCb, c = idx % kCb;
+        D[(size_t)(j0 + i) * kCb + c] = c < w ? x[i][c] : 0.f;
     }
 }
 
@@ -337,8 +381,7 @@ __global__ __launch_bounds__(256) void lora_out_r_kernel(const float *Rt, const 
         part += v * v;
         R[t] = (half_t)(v / x[j]);
     }
-    part = wave_sum(part);
-    if ((threadIdx.x & 63) == 0) atomicAdd(sq + 1, part);
+    block_add(part, sq + 1);
 }
 
 // sq[2] = max |G - I| over the leading r x r block (orthonormality of the final Q)
@@ -355,7 +398,7 @@ __global__ __launch_bounds__(256) void lora_ortho_kernel(const float *G, int l, 
 
 struct LoraPlan {
     int l;                      // columns of the iteration block: rank padded as the layer's adapters are
-    size_t x, S, Q, Y, Z, G, B, Rt, sq, total;      // byte offsets
+    size_t x, S, Q, Y, Z, G, B, Rt, sq, total;      // byte offsets (B: the inverses of the diagonal blocks, [l][64])
 };
 
 static size_t up256(size_t v) { return (v + 255) / 256 * 256; }
@@ -377,7 +420,7 @@ static LoraPlan plan_lora(int n, int k, int rank)
     p.Y = take(big * l);
     p.Z = take((size_t)k * l);
     p.G = take(l * l);
-    p.B = take(l * l);
+    p.B = take(l * kCb);
     p.Rt = take(l * k);
     p.sq = take(64);
     p.total = off;
@@ -432,40 +475,55 @@ extern "C" int slim_compute_adapters(const float *W, const uint8_t *qvals, const
     SLIM_TRY(launch_fill(sq, 64, 0.f, st));
     hipLaunchKernelGGL(lora_shift_kernel, dim3(1), dim3(1024), 0, st, x_tilde, k, x);
     SLIM_TRY(launched());
-    hipLaunchKernelGGL(lora_error_kernel, grid_for((size_t)n * (k / 4)), dim3(256), 0, st, W, qvals, meta, scale,
+    hipLaunchKernelGGL(lora_error_kernel, dim3(std::min(grid_for((size_t)n * (k / 4)).x, 1024u)), dim3(256), 0, st, W, qvals, meta, scale,
                        (const float *)x, n, k, S, sq);
     SLIM_TRY(launched());
     hipLaunchKernelGGL(lora_init_kernel, grid_for((size_t)k * l), dim3(256), 0, st, Z, k, l, r, seed);
     SLIM_TRY(launched());
 
-    // out = orth(in) for a block [rows][l]: G = in^T in = Lc Lc^T, out = in Lc^-T
-    auto orth = [&](const float *in, float *out, int rows) -> int {
-        int e = sgemm(true, in, l, in, l, G, l, l, l, rows, st);
+    // out = orth(in) for a block [rows][l] (in is overwritten): G = in^T in = Lc Lc^T, out = in Lc^-T
+    auto orth = [&](float *in, float *out, int rows) -> int {
+        int e = sgemm(true, false, in, l, in, l, G, l, l, l, rows, st);
         if (e != SLIM_OK) return e;
-        hipLaunchKernelGGL(lora_chol_kernel, dim3(1), dim3(1024), 0, st, G, l);
+        hipLaunchKernelGGL(lora_diagmax_kernel, dim3(1), dim3(1024), 0, st, (const float *)G, l, sq + 4);
         if ((e = launched()) != SLIM_OK) return e;
-        hipLaunchKernelGGL(lora_trinv_kernel, dim3((l + 63) / 64), dim3(64), 0, st, (const float *)G, B, l);
-        if ((e = launched()) != SLIM_OK) return e;
-        return sgemm(false, in, l, B, l, out, l, rows, l, l, st);
+        for (int j0 = 0; j0 < l; j0 += kCb) {
+            const int w = std::min(kCb, l - j0), below = l - j0 - w;
+            hipLaunchKernelGGL(lora_chol_diag_kernel, dim3(1), dim3(256), 0, st, G, l, j0, w, (const float *)(sq + 4), B);
+            if ((e = launched()) != SLIM_OK) return e;
+            float *panel = G + (size_t)(j0 + w) * l + j0;
+            // panel under the block: L21 = A21 L11^-T (in place: a workgroup has read its rows before it writes them)
+            if ((e = sgemm(false, true, panel, l, B + (size_t)j0 * kCb, kCb, panel, l, below, w, w, st)) != SLIM_OK) return e;
+            // what is left: A22 -= L21 L21^T
+            if ((e = sgemm(false, true, panel, l, panel, l, G + (size_t)(j0 + w) * l + j0 + w, l, below, below, w, st, -1.0f, 1)) != SLIM_OK)
+                return e;
+        }
+        // out = in Lc^-T by block columns: out_j = (in_j - out_{<j} Lc[j, <j]^T) X_jj^T
+        for (int j0 = 0; j0 < l; j0 += kCb) {
+            const int w = std::min(kCb, l - j0);
+            if ((e = sgemm(false, true, out, l, G + (size_t)j0 * l, l, in + j0, l, rows, w, j0, st, -1.0f, 1)) != SLIM_OK) return e;
+            if ((e = sgemm(false, true, in + j0, l, B + (size_t)j0 * kCb, kCb, out + j0, l, rows, w, w, st)) != SLIM_OK) return e;
+        }
+        return SLIM_OK;
     };
 
-    SLIM_TRY(sgemm(false, S, k, Z, l, Y, l, n, l, k, st));          // Y = S Z           [n][l]
+    SLIM_TRY(sgemm(false, false, S, k, Z, l, Y, l, n, l, k, st));          // Y = S Z           [n][l]
     SLIM_TRY(orth(Y, Q, n));
     for (int it = 0; it < q; ++it) {
-        SLIM_TRY(sgemm(true, S, k, Q, l, Y, l, k, l, n, st));       // Y = S^T Q         [k][l]
+        SLIM_TRY(sgemm(true, false, S, k, Q, l, Y, l, k, l, n, st));       // Y = S^T Q         [k][l]
         SLIM_TRY(orth(Y, Z, k));
-        SLIM_TRY(sgemm(false, S, k, Z, l, Y, l, n, l, k, st));      // Y = S Z           [n][l]
+        SLIM_TRY(sgemm(false, false, S, k, Z, l, Y, l, n, l, k, st));      // Y = S Z           [n][l]
         SLIM_TRY(orth(Y, Q, n));
     }
     SLIM_TRY(orth(Q, Y, n));                                        // second pass: orthonormal to rounding
-    SLIM_TRY(sgemm(true, Y, l, S, k, Rt, k, l, k, n, st));          // R~ = Q^T S        [l][k]
-    SLIM_TRY(sgemm(true, Y, l, Y, l, G, l, l, l, n, st));           // Gram of the final block, for the report
+    SLIM_TRY(sgemm(true, false, Y, l, S, k, Rt, k, l, k, n, st));          // R~ = Q^T S        [l][k]
+    SLIM_TRY(sgemm(true, false, Y, l, Y, l, G, l, l, l, n, st));           // Gram of the final block, for the report
     hipLaunchKernelGGL(lora_ortho_kernel, grid_for((size_t)r * r), dim3(256), 0, st, (const float *)G, l, r, sq);
     SLIM_TRY(launched());
     hipLaunchKernelGGL(lora_out_l_kernel, grid_for((size_t)n * r), dim3(256), 0, st, (const float *)Y, n, l, r,
                        reinterpret_cast<half_t *>(L));
     SLIM_TRY(launched());
-    hipLaunchKernelGGL(lora_out_r_kernel, grid_for((size_t)r * k), dim3(256), 0, st, (const float *)Rt, (const float *)x, k,
+    hipLaunchKernelGGL(lora_out_r_kernel, dim3(std::min(grid_for((size_t)r * k).x, 1024u)), dim3(256), 0, st, (const float *)Rt, (const float *)x, k,
                        r, reinterpret_cast<half_t *>(R), sq);
     SLIM_TRY(launched());
     if (diag) {
