@@ -284,6 +284,30 @@ int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, const slim_h
                  slim_shape shape, int32_t rank_pad, slim_half *Y, int accumulate,
                  void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Measurement aids (they compute nothing of the method): what this machine
+ * delivers on a plain streaming read and on back-to-back matrix instructions,
+ * to set beside the nominal peaks when a kernel's roofline fraction is quoted
+ * (Sec. 4 "Speedup" measures layers; these give the ceilings such a layer has
+ * here).
+ *   slim_probe_read  `repeats` launches; launch i reads `bytes` (>= 64 KiB; whole
+ *                    runs of 64 KiB) at buf + i * stride once, with 128-bit loads
+ *                    from up to 2048 workgroups (the buffer must hold
+ *                    (repeats - 1) * stride + bytes; a stride of at least
+ *                    `bytes` makes every launch read cold data).  The caller
+ *                    times the call.  sink: 4 device bytes, left unchanged.
+ *   slim_probe_mfma  `workgroups` x 4 wavefronts each issue 4 x iters matrix
+ *                    instructions on four independent accumulators:
+ *                    V_MFMA_F32_32X32X16_F16 (sparse = 0) or
+ *                    V_SMFMAC_F32_32X32X32_F16 (sparse = 1, counted as the dense
+ *                    32 x 32 x 32 product it stands for).  *flops (HOST pointer)
+ *                    receives the FLOPs of the launch; sink: 4 device bytes.
+ */
+int slim_probe_read(const void *buf, size_t bytes, int32_t repeats, size_t stride, void *sink,
+                    void *stream);
+int slim_probe_mfma(int32_t sparse, int32_t iters, int32_t workgroups, void *sink, double *flops,
+                    void *stream);
+
 #ifdef __cplusplus
 }
 #endif

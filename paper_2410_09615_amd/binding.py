@@ -40,7 +40,7 @@ EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pac
            "slim_unpack", "slim_workspace_bytes", "slim_linear_gemv", "slim_linear_gemm", "slim_lowrank",
            "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4", "slim_pack_ex",
            "slim_quant_workspace_bytes", "slim_quant_search", "slim_adapters_workspace_bytes",
-           "slim_compute_adapters"]
+           "slim_compute_adapters", "slim_probe_read", "slim_probe_mfma"]
 
 
 def lib():
@@ -68,6 +68,8 @@ def lib():
         L.slim_quant_search.argtypes = [vp, slim_shape, vp, vp, vp, sz, vp]
         L.slim_adapters_workspace_bytes.argtypes = [slim_shape, psz]
         L.slim_compute_adapters.argtypes = [vp, vp, vp, vp, slim_shape, vp, i32, ctypes.c_uint32, vp, vp, vp, vp, sz, vp]
+        L.slim_probe_read.argtypes = [vp, sz, i32, sz, vp, vp]
+        L.slim_probe_mfma.argtypes = [i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.slim_pack_adapters_q4.argtypes = [vp, vp, slim_shape, vp, vp, vp, vp, vp]
         L.slim_unpack_adapters_q4.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.slim_linear_gemv.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp, sz, vp]
@@ -223,6 +225,21 @@ def slim_compute_adapters(W: torch.Tensor, qvals, meta, scale, rank: int, x_tild
            lib().slim_compute_adapters(_ptr(W), _ptr(qvals), _ptr(meta), _ptr(scale), shape, _ptr(x_tilde), iters, seed,
                                        _ptr(L), _ptr(R), _ptr(diag), _ptr(ws), ws.numel(), _stream(W)))
     return L, R, diag
+
+
+def slim_probe_read(buf: torch.Tensor, nbytes: int, repeats: int, stride: int, sink: torch.Tensor):
+    """`repeats` streaming reads of nbytes at buf + i * stride (measurement aid; the caller times it)."""
+    if (repeats - 1) * stride + nbytes > buf.numel() * buf.element_size():
+        raise ValueError("the reads would run past the end of buf")
+    _check("slim_probe_read", lib().slim_probe_read(_ptr(buf), nbytes, repeats, stride, _ptr(sink), _stream(buf)))
+
+
+def slim_probe_mfma(sparse: bool, iters: int, workgroups: int, sink: torch.Tensor) -> float:
+    """Back-to-back matrix instructions (measurement aid); returns the FLOPs of the launch."""
+    flops = ctypes.c_double()
+    _check("slim_probe_mfma", lib().slim_probe_mfma(int(sparse), iters, workgroups, _ptr(sink), ctypes.byref(flops),
+                                                    _stream(sink)))
+    return flops.value
 
 
 def slim_pack_adapters(L: torch.Tensor, R: torch.Tensor):

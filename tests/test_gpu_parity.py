@@ -438,3 +438,20 @@ def test_lowrank(m, accumulate):
     Y = B.slim_lowrank(X.to(DEV), Rp, Lp, n, r, Y=Y0, accumulate=accumulate)
     torch.cuda.synchronize()
     assert _relerr(Y.cpu().numpy(), ref) <= TOL_Y
+
+
+# ---- measurement aids -------------------------------------------------------------
+
+def test_probes_run_and_report_their_work():
+    buf = torch.ones(8 << 20, dtype=torch.uint8, device=DEV)
+    sink = torch.zeros(4, dtype=torch.float32, device=DEV)
+    B.slim_probe_read(buf, 4 << 20, 2, 4 << 20, sink)
+    for sparse in (False, True):
+        flops = B.slim_probe_mfma(sparse, 8, 16, sink)
+        assert flops == 16 * 4 * 8 * 4 * 2 * 32 * 32 * (32 if sparse else 16)
+    torch.cuda.synchronize()
+    assert float(sink.abs().sum()) == 0.0                    # the sinks are never written
+    with pytest.raises(B.SlimError):
+        B.slim_probe_read(buf, 1024, 1, 0, sink)
+    with pytest.raises(ValueError):
+        B.slim_probe_read(buf, 8 << 20, 2, 4 << 20, sink)
