@@ -143,6 +143,26 @@ def decode_path(request, monkeypatch):
     return request.param
 
 
+@pytest.mark.parametrize("m", [1, 16])
+def test_gemv_launch_geometries_agree(m, monkeypatch):
+    """The same call through the three decode geometries (one launch, its two roles as two
+    launches, the two-launch kernels): the results differ only by reassociation of fp32 sums,
+    by the fp16 rounding of T's shares on the one-launch path and by the final rounding of Y
+    (2^-11 relative per element where a sum falls on the other side of a rounding boundary):
+    6e-4 in relative Frobenius norm, well inside the 2e-3 each has against the oracle; the two
+    launch forms of the one-launch kernel do the same arithmetic and agree exactly."""
+    shape = _shape(640, 2048, 102)
+    W, L, R, X = wl.make_layer(shape, m, seed=4)
+    layer = _gpu_layer(W, L, R)
+    Xd = X.to(DEV)
+    out = {}
+    for path in ("parts", "roles", "fused"):
+        monkeypatch.setenv("SLIM_DECODE_PATH", path)
+        out[path] = B.slim_linear_gemv(layer, Xd).float().cpu().numpy().astype(np.float64)
+    assert np.array_equal(out["roles"], out["fused"])
+    assert _relerr(out["parts"], out["fused"]) <= 6e-4
+
+
 @pytest.mark.parametrize("m", [1, 4, 8, 16])
 def test_gemv_tiny_layer(m, decode_path):
     assert _forward_case(wl.TINY, m, B.slim_linear_gemv) <= TOL_Y
