@@ -86,3 +86,23 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libslim.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         B.lib()
+
+
+def test_adapter_computation_workspace_query_and_validation():
+    lib = B.lib()
+    out = ctypes.c_size_t()
+    assert lib.slim_adapters_workspace_bytes(B.slim_shape(4096, 4096, 410), out) == 0
+    # the error saliency (fp32 [n][k]) and three blocks of rank_pad columns at least
+    assert out.value >= 4 * 4096 * 4096 + 3 * 4 * 4096 * 416
+    for bad in ((4096, 4096, 0), (64, 4096, 65), (4096, 4100, 16), (4096, 4096, 2000)):
+        assert lib.slim_adapters_workspace_bytes(B.slim_shape(*bad), out) == B.SLIM_ERR_SHAPE
+    assert lib.slim_adapters_workspace_bytes(B.slim_shape(4096, 4096, 410), None) == B.SLIM_ERR_NULL
+    assert lib.slim_compute_adapters(None, None, None, None, B.slim_shape(128, 128, 8), None, 0, 1, None, None, None,
+                                     None, 0, None) == B.SLIM_ERR_NULL
+
+
+def test_probe_validation():
+    lib = B.lib()
+    fl = ctypes.c_double()
+    assert lib.slim_probe_read(None, 1 << 20, 1, 0, None, None) == B.SLIM_ERR_NULL
+    assert lib.slim_probe_mfma(0, 16, 16, None, fl, None) == B.SLIM_ERR_NULL
