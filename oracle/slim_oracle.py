@@ -349,6 +349,15 @@ def quant_search(W: np.ndarray):
     return alpha, np.float32(alpha / np.float32(7.0))
 
 
+
+def quant_search_rows(W: np.ndarray):
+    """Alg. 1 with one scale per output row (the granularity of the packed format):
+    every row is searched as a tensor of its own.  Returns (alpha float32 [n],
+    scale float32 [n])."""
+    W = np.asarray(W, np.float32)
+    res = [quant_search(W[o]) for o in range(W.shape[0])]
+    return (np.array([r[0] for r in res], np.float32), np.array([r[1] for r in res], np.float32))
+
 # ---- low-rank adapters: Naive-LoRA and SLiM-LoRA (Sec. 3.2, Eq. 8-11, Alg. 2) ----------
 # Plain numpy in float64; the SVD is LAPACK's.  Orientation as everywhere in this
 # file: the paper's matrices transposed.  The paper's saliency diag(x) W scales

@@ -142,3 +142,37 @@ def test_absmax_is_a_candidate_and_wins_when_the_weights_lie_on_its_grid():
     alpha, scale = O.quant_search(W)
     assert float(alpha) == float(np.float32(M))
     assert float(scale) == 0.125
+
+
+# ---- one scale per row ---------------------------------------------------------
+
+def test_rows_search_is_the_tensor_search_of_every_row():
+    rng = np.random.default_rng(31)
+    W = rng.standard_t(4, size=(6, 2048)).astype(np.float32)
+    W[2] = 0.0                                               # a zero row: scale 1
+    W[3] *= np.float32(2.0 ** -7)                            # power-of-two scaling: alpha scales with it
+    W[4] = W[3] * np.float32(2.0 ** 7)
+    alpha, scale = O.quant_search_rows(W)
+    assert alpha.shape == (6,) and scale.shape == (6,)
+    for o in range(6):
+        a, s = O.quant_search(W[o:o + 1])
+        assert alpha[o] == a and scale[o] == s
+    assert alpha[2] == 0 and scale[2] == 1
+    assert alpha[4] == alpha[3] * np.float32(2.0 ** 7)
+    # rows do not influence one another
+    W2 = W.copy()
+    W2[0] *= 3.0
+    alpha2, _ = O.quant_search_rows(W2)
+    assert np.array_equal(alpha2[1:], alpha[1:])
+
+
+def test_rows_search_never_worse_than_absmax_per_row_on_its_histogram():
+    rng = np.random.default_rng(32)
+    W = rng.standard_normal((8, 4096)).astype(np.float32)
+    W[:, 0] *= 12.0                                          # one outlier per row
+    alpha, _ = O.quant_search_rows(W)
+    for o in range(8):
+        counts, M = O.quant_histogram(W[o])
+        assert counts.shape[0] == 512 and counts.sum() == 4096
+        assert O.quant_error(counts, M, float(alpha[o])) <= O.quant_error(counts, M, float(M))
+        assert alpha[o] < M                                   # the outlier is clipped
