@@ -272,6 +272,12 @@ def main():
     legs.append({"shape": shape.name, "entry": "slim_quant_search", "us": round(ms_qs * 1e3, 2),
                  "GBps": round(qb / ms_qs * 1e-6, 1), "bound": "hbm",
                  "roofline_frac": round(qb / ms_qs * 1e-6 / HBM_PEAK_GBPS, 4)})
+    for i in range(5):
+        B.slim_quant_search_rows(wcopies[i % len(wcopies)])
+    ms_qr = event_time_ms(lambda i: B.slim_quant_search_rows(wcopies[i % len(wcopies)]), 45)
+    legs.append({"shape": shape.name, "entry": "slim_quant_search_rows", "us": round(ms_qr * 1e3, 2),
+                 "GBps": round(qb / 2 / ms_qr * 1e-6, 1), "bound": "hbm",
+                 "roofline_frac": round(qb / 2 / ms_qr * 1e-6 / HBM_PEAK_GBPS, 4)})
     sal = torch.rand(shape.k, device=dev) + 0.5
     sc_in, _ = B.slim_quant_search(rot.W_dev)
     for i in range(5):

@@ -161,6 +161,16 @@ int slim_quant_search(const float *W, slim_shape shape, float *scale_out, float 
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * slim_quant_search_rows -- the same search (Sec. 3.1, Alg. 1) with one scale per
+ * output row, the granularity of this format: row o is its own tensor of k
+ * weights (histogram of max(512, min(k / 1000, 20000)) bins over [0, max|W[o]|]).
+ * scale_out [n] = alpha*(o) / 7 (1 for a zero row), alpha_out [n] (may be NULL).
+ * No workspace.  Errors: NULL, SHAPE (k % 8 != 0), ALIGN, HIP.
+ */
+int slim_quant_search_rows(const float *W, slim_shape shape, float *scale_out, float *alpha_out,
+                           void *stream);
+
+/*
  * slim_compute_adapters -- the low-rank adapters of a compressed layer: Naive-LoRA
  * and SLiM-LoRA (Sec. 3.2, Eq. 8-11, Alg. 2).  With E = W - W^C (so that
  * W ~= W^C + L R), x = x_tilde + min|x_tilde| and the error saliency

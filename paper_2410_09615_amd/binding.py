@@ -39,7 +39,7 @@ SLIM_OK, SLIM_ERR_NULL, SLIM_ERR_SHAPE, SLIM_ERR_ALIGN, SLIM_ERR_WORKSPACE, SLIM
 EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pack", "slim_pack_adapters",
            "slim_unpack", "slim_workspace_bytes", "slim_linear_gemv", "slim_linear_gemm", "slim_lowrank",
            "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4", "slim_pack_ex",
-           "slim_quant_workspace_bytes", "slim_quant_search", "slim_adapters_workspace_bytes",
+           "slim_quant_workspace_bytes", "slim_quant_search", "slim_quant_search_rows", "slim_adapters_workspace_bytes",
            "slim_compute_adapters", "slim_probe_read", "slim_probe_mfma"]
 
 
@@ -66,6 +66,7 @@ def lib():
         L.slim_pack_ex.argtypes = [vp, slim_shape, vp, vp, vp, vp, vp, vp]
         L.slim_quant_workspace_bytes.argtypes = [slim_shape, psz]
         L.slim_quant_search.argtypes = [vp, slim_shape, vp, vp, vp, sz, vp]
+        L.slim_quant_search_rows.argtypes = [vp, slim_shape, vp, vp, vp]
         L.slim_adapters_workspace_bytes.argtypes = [slim_shape, psz]
         L.slim_compute_adapters.argtypes = [vp, vp, vp, vp, slim_shape, vp, i32, ctypes.c_uint32, vp, vp, vp, vp, sz, vp]
         L.slim_probe_read.argtypes = [vp, sz, i32, sz, vp, vp]
@@ -201,6 +202,17 @@ def slim_quant_search(W: torch.Tensor):
     alpha = torch.empty(1, dtype=torch.float32, device=W.device)
     _check("slim_quant_search", lib().slim_quant_search(_ptr(W), slim_shape(n, k, 0), _ptr(scale), _ptr(alpha), _ptr(ws),
                                                         ws.numel(), _stream(W)))
+    return scale, alpha
+
+
+def slim_quant_search_rows(W: torch.Tensor):
+    """SLiM-Quant scale search per output row: (scale fp32 [n] = alpha*(o) / 7, alpha* fp32 [n])."""
+    _dev(W, torch.float32, "W")
+    n, k = W.shape
+    scale = torch.empty(n, dtype=torch.float32, device=W.device)
+    alpha = torch.empty(n, dtype=torch.float32, device=W.device)
+    _check("slim_quant_search_rows", lib().slim_quant_search_rows(_ptr(W), slim_shape(n, k, 0), _ptr(scale), _ptr(alpha),
+                                                                  _stream(W)))
     return scale, alpha
 
 

@@ -167,6 +167,75 @@ __global__ __launch_bounds__(256) void quant_pick_kernel(const unsigned *mbits, 
     if (alpha_out && blockIdx.x == 0 && threadIdx.x == 0) *alpha_out = alpha;
 }
 
+// ---- the same search with one scale per output row: one workgroup per row, everything in LDS ----
+// (the histogram of a row has quant_bins(k) bins: 512 for every k below 513000)
+__global__ __launch_bounds__(256) void quant_rows_kernel(const float *__restrict__ W, int n, int k, int B, float *scale_out,
+                                                         float *alpha_out)
+{
+    extern __shared__ unsigned hist[];
+    __shared__ double red[16];
+    __shared__ double err[kCoarse + kFine];
+    __shared__ float part[4];
+    const int k4 = k / 4;
+    for (int row = blockIdx.x; row < n; row += gridDim.x) {
+        const float4 *w4 = reinterpret_cast<const float4 *>(W + (size_t)row * k);
+        float a = 0.f;
+        for (int i = threadIdx.x; i < k4; i += blockDim.x) {
+            const float4 v = w4[i];
+            a = fmaxf(a, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
+        a = wave_max(a);
+        __syncthreads();                      // the previous row is done with hist, part and err
+        if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x / kWave] = a;
+        for (int i = threadIdx.x; i < B; i += blockDim.x) hist[i] = 0u;
+        __syncthreads();
+        const float Mf = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+        float alpha_f = 0.f, s = 1.f;
+        if (Mf > 0.f) {
+            const float inv = (float)B / Mf;
+            auto put = [&](float w) {
+                const int b = (int)floorf(fabsf(w) * inv);
+                atomicAdd(&hist[b < B - 1 ? b : B - 1], 1u);
+            };
+            for (int i = threadIdx.x; i < k4; i += blockDim.x) {
+                const float4 v = w4[i];
+                put(v.x);
+                put(v.y);
+                put(v.z);
+                put(v.w);
+            }
+            __syncthreads();
+            const double M = (double)Mf, eta = M / 10.0;
+            for (int c = 0; c < kCoarse; ++c) {
+                const double e = quant_error_block(hist, B, M, eta * (c + 1), red);
+                if (threadIdx.x == 0) err[c] = e;
+            }
+            __syncthreads();
+            int best = 0;
+            for (int i = 1; i < kCoarse; ++i)
+                if (err[i] < err[best]) best = i;
+            const double lo = eta * (best + 1);
+            for (int c = kCoarse; c < kCoarse + kFine; ++c) {
+                const double alpha = lo + eta * ((c - kCoarse - 10) / 10.0);
+                const bool ok = alpha > 0.0 && alpha <= M;                 // the same for every thread
+                const double e = ok ? quant_error_block(hist, B, M, alpha, red) : __builtin_inf();
+                if (threadIdx.x == 0) err[c] = e;
+            }
+            __syncthreads();
+            int pick = best;
+            for (int c = kCoarse; c < kCoarse + kFine; ++c)
+                if (err[c] < err[pick]) pick = c;
+            const double al = pick < kCoarse ? eta * (pick + 1) : lo + eta * ((pick - kCoarse - 10) / 10.0);
+            alpha_f = (float)al;
+            s = alpha_f / 7.0f;
+        }
+        if (threadIdx.x == 0) {
+            scale_out[row] = s;
+            if (alpha_out) alpha_out[row] = alpha_f;
+        }
+    }
+}
+
 }  // namespace slim
 
 using namespace slim;
@@ -203,5 +272,17 @@ extern "C" int slim_quant_search(const float *W, slim_shape shape, float *scale_
     hipLaunchKernelGGL(quant_eval_kernel, dim3(kFine), dim3(1024), 0, st, q.mbits, q.counts, B, q.err, kCoarse);
     hipLaunchKernelGGL(quant_pick_kernel, dim3((unsigned)((shape.n + 255) / 256)), dim3(256), 0, st, q.mbits, q.err,
                        scale_out, shape.n, alpha_out);
+    return hip_status(hipGetLastError());
+}
+
+extern "C" int slim_quant_search_rows(const float *W, slim_shape shape, float *scale_out, float *alpha_out, void *stream)
+{
+    if (!W || !scale_out) return SLIM_ERR_NULL;
+    if (shape.n < 1 || shape.k < 8 || shape.k % 8) return SLIM_ERR_SHAPE;
+    if (!aligned16(W)) return SLIM_ERR_ALIGN;
+    const int B = quant_bins((long)shape.k);
+    const unsigned grid = (unsigned)(shape.n < 4096 ? shape.n : 4096);
+    hipLaunchKernelGGL(quant_rows_kernel, dim3(grid), dim3(256), (size_t)B * 4, static_cast<hipStream_t>(stream), W, shape.n,
+                       shape.k, B, scale_out, alpha_out);
     return hip_status(hipGetLastError());
 }

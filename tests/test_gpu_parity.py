@@ -318,6 +318,28 @@ def test_quant_search_matches_the_oracle(n, k, dist):
     assert np.array_equal(scale.cpu().numpy().view(np.uint32), np.full(n, rs, np.float32).view(np.uint32))
 
 
+@pytest.mark.parametrize("n,k,dist", [(512, 512, "normal"), (37, 136, "t3"), (300, 4096, "outliers"), (5000, 1024, "t3")])
+def test_quant_search_rows_matches_the_oracle(n, k, dist):
+    rng = np.random.default_rng(n * 3 + k)
+    if dist == "normal":
+        W = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    elif dist == "t3":
+        W = rng.standard_t(3, size=(n, k)).astype(np.float32)
+    else:
+        W = (rng.standard_normal((n, k)) * 0.01).astype(np.float32)
+        W[:, 5] *= 40.0
+    W[n // 2] = 0.0                                          # a zero row
+    scale, alpha = B.slim_quant_search_rows(torch.from_numpy(W).to(DEV))
+    torch.cuda.synchronize()
+    ra, rs = O.quant_search_rows(W)
+    assert np.array_equal(alpha.cpu().numpy().view(np.uint32), ra.view(np.uint32))
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), rs.view(np.uint32))
+    # and the layer packed with these scales is the oracle's
+    q, m, s = B.slim_pack_ex(torch.from_numpy(W).to(DEV), None, scale)
+    mask = O.mask_2of4(W)
+    _assert_packed_equal(q, m, s, O.quantize(W, mask, rs), mask, rs)
+
+
 @pytest.mark.parametrize("n,k", [(512, 512), (37, 136), (130, 12800), (1000, 4096)])
 def test_pack_ex_bit_exact(n, k):
     """Saliency-weighted mask and given scales, separately and together, against the
