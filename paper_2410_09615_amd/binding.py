@@ -337,6 +337,41 @@ def compress(W: torch.Tensor, L: torch.Tensor | None = None, R: torch.Tensor | N
     return SlimLayer(n, k, rank, rp, qvals, meta, scale, Lp, Rp)
 
 
+def compress_dense(W: torch.Tensor, rank: int, x_tilde: torch.Tensor | None = None, saliency: torch.Tensor | None = None,
+                   scale_search: str = "absmax", adapter_bits: int = 16, iters: int = 0, seed: int = 1,
+                   return_adapters: bool = False):
+    """The whole offline chain on one dense layer, every step a call of the library:
+    scales (AbsMax per row, or slim_quant_search ("tensor") / slim_quant_search_rows ("rows")), 2:4 mask (by magnitude,
+    or weighted by `saliency`) and codes (slim_pack / slim_pack_ex), adapters of `rank` (slim_compute_adapters:
+    SLiM-LoRA with x_tilde, Naive-LoRA without; rank 0: none), their layout (fp16, or 4-bit groups of 128).
+    Returns the SlimLayer, or (SlimLayer, L fp16 [n][rank], R fp16 [rank][k]) with return_adapters."""
+    if scale_search == "absmax":
+        scale_in = None
+    elif scale_search == "tensor":
+        scale_in, _ = slim_quant_search(W)
+    elif scale_search == "rows":
+        scale_in, _ = slim_quant_search_rows(W)
+    else:
+        raise ValueError("scale_search is 'absmax', 'tensor' or 'rows'")
+    n, k = W.shape
+    if saliency is None and scale_in is None:
+        qvals, meta, scale = slim_pack(W)
+    else:
+        qvals, meta, scale = slim_pack_ex(W, saliency, scale_in)
+    if rank == 0:
+        layer = SlimLayer(n, k, 0, 0, qvals, meta, scale, None, None)
+        return (layer, None, None) if return_adapters else layer
+    L, R, _ = slim_compute_adapters(W, qvals, meta, scale, rank, x_tilde, iters, seed)
+    rp = slim_rank_pad(rank)
+    if adapter_bits == 4:
+        Lq, Ls, Rq, Rs = slim_pack_adapters_q4(L, R)
+        layer = SlimLayer(n, k, rank, rp, qvals, meta, scale, None, None, 4, Lq, Ls, Rq, Rs)
+    else:
+        Lp, Rp = slim_pack_adapters(L, R)
+        layer = SlimLayer(n, k, rank, rp, qvals, meta, scale, Lp, Rp)
+    return (layer, L, R) if return_adapters else layer
+
+
 def slim_workspace_bytes(layer: SlimLayer, m: int) -> int:
     out = ctypes.c_size_t()
     cs = layer.c_struct()

@@ -139,3 +139,33 @@ def test_compute_adapters_argument_errors():
         B.slim_compute_adapters(W, q, m, s, 65)              # rank above n
     with pytest.raises(B.SlimError):
         B.slim_compute_adapters(W, q, m, s, 0)
+
+
+@pytest.mark.parametrize("scale_search,adapter_bits,use_sal", [("absmax", 16, False), ("rows", 16, True), ("tensor", 4, True)])
+def test_whole_chain_from_dense_weights(scale_search, adapter_bits, use_sal):
+    """compress_dense: scales, mask, codes, computed adapters, their layout; the decode forward of the
+    result equals the oracle's forward of the same bytes and adapters, and is closer to the dense
+    layer than the forward without adapters."""
+    n, k, r, m = 512, 1024, 51, 8
+    W = wl.make_weight(n, k, seed=41)
+    X = wl.make_activations(m, k, seed=42)
+    xt = torch.from_numpy(_channel_magnitudes(k, 42)).to(DEV)
+    layer, Lt, Rt = B.compress_dense(W.to(DEV), r, xt, xt if use_sal else None, scale_search, adapter_bits,
+                                     return_adapters=True)
+    Y = B.slim_linear_gemv(layer, X.to(DEV))
+    torch.cuda.synchronize()
+    # the oracle's forward on what the library produced (bytes through slim_unpack, adapters as stored)
+    codes, mask = B.slim_unpack(layer.qvals, layer.meta, n, k)
+    Wc = codes.cpu().numpy().astype(np.float64) * layer.scale.cpu().numpy().astype(np.float64)[:, None]
+    if adapter_bits == 4:
+        cl, sl = B.slim_unpack_adapters_q4(layer.Lq, layer.Ls, n, r)
+        cr, sr = B.slim_unpack_adapters_q4(layer.Rq, layer.Rs, r, k)
+        Lf = O.dequantize_adapter(cl.cpu().numpy(), sl.cpu().numpy())
+        Rf = O.dequantize_adapter(cr.cpu().numpy(), sr.cpu().numpy())
+    else:
+        Lf, Rf = Lt.cpu().numpy().astype(np.float64), Rt.cpu().numpy().astype(np.float64)
+    Xn = X.numpy().astype(np.float64)
+    Yo = Xn @ Wc.T + (Xn @ Rf.T) @ Lf.T
+    assert np.linalg.norm(Y.cpu().numpy().astype(np.float64) - Yo) / np.linalg.norm(Yo) < 2e-3
+    dense = Xn @ W.numpy().astype(np.float64).T
+    assert np.linalg.norm(Yo - dense) < 0.95 * np.linalg.norm(Xn @ Wc.T - dense)
