@@ -393,3 +393,41 @@ def compute_adapters(W: np.ndarray, Wc: np.ndarray, x_tilde, rank: int):
     L = U[:, :rank]
     R = (s[:rank, None] * Vt[:rank, :]) / x[None, :]
     return L, R, s
+
+
+# ---- 8-bit input quantization (App. "Input Quantization") ------------------------------
+# AbsMax quantization of an input tensor to an FP8 format with one scale per tensor, as
+# the paper evaluates it (the quantized values, put back on the fp16 grid, are what the
+# layer then sees).  E4M3 and E5M2 are the OCP 8-bit formats: 4 exponent bits (bias 7),
+# 3 mantissa bits, largest finite value 448, subnormal spacing 2^-9; and 5 exponent bits
+# (bias 15), 2 mantissa bits, largest finite value 57344, subnormal spacing 2^-16.
+
+FP8_FORMATS = {"e4m3": (3, -6, 448.0), "e5m2": (2, -14, 57344.0)}      # mantissa bits, smallest normal exponent, largest value
+
+
+def fp8_round(v: np.ndarray, fmt: str) -> np.ndarray:
+    """Nearest value of the format (ties to even mantissa), |v| limited to the largest finite one."""
+    p, emin, fmax = FP8_FORMATS[fmt]
+    v = np.asarray(v, np.float64)
+    a = np.minimum(np.abs(v), fmax)
+    e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    e = np.maximum(e, emin)
+    q = np.exp2(e - p)                               # spacing of the format at this magnitude
+    r = np.rint(a / q) * q                           # rint: ties to even; a / q is exact (power of two)
+    return np.sign(v) * np.minimum(r, fmax)
+
+
+def input_quant_fp8(X: np.ndarray):
+    """X fp16 -> (X' fp16, scale float32, format name).  M = max|X|; the format is E4M3 unless
+    M exceeds its largest value 448, then E5M2; scale = M / (largest value of the format) in
+    binary32 (1 for a zero tensor); every element becomes fp8_round(x / scale) * scale, the
+    quotient and the product in binary32, the result rounded to fp16."""
+    X = np.asarray(X)
+    assert X.dtype == np.float16
+    xf = X.astype(np.float32)
+    M = np.float32(np.max(np.abs(xf))) if xf.size else np.float32(0)
+    fmt = "e4m3" if M <= np.float32(448.0) else "e5m2"
+    fmax = np.float32(FP8_FORMATS[fmt][2])
+    s = np.float32(1.0) if M == 0 else np.float32(M / fmax)
+    qv = fp8_round((xf / s).astype(np.float32), fmt).astype(np.float32)
+    return (qv * s).astype(np.float32).astype(np.float16), s, fmt

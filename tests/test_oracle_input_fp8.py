@@ -1,0 +1,94 @@
+"""Pins of the oracle's FP8 input quantization (App. "Input Quantization"): the two formats' value
+sets built from their bit definition (every code decoded by hand), nearest-value rounding against
+brute force over that set, ties to even, limits, the switch of format, idempotence and the error
+bound of each format."""
+import numpy as np
+import pytest
+
+from oracle import slim_oracle as O
+
+
+def _all_values(exp_bits, man_bits, bias, e4m3):
+    """Finite non-negative values of an 8-bit float from its bit fields."""
+    vals = []
+    for code in range(128):
+        e, m = code >> man_bits, code & ((1 << man_bits) - 1)
+        if e4m3:
+            if code == 0x7F:                     # the only NaN of E4M3; there are no infinities
+                continue
+        elif e == (1 << exp_bits) - 1:           # E5M2 keeps IEEE's infinities and NaNs
+            continue
+        vals.append(m * 2.0 ** (1 - bias - man_bits) if e == 0 else (1 + m / (1 << man_bits)) * 2.0 ** (e - bias))
+    return np.array(sorted(vals))
+
+
+E4M3 = _all_values(4, 3, 7, True)
+E5M2 = _all_values(5, 2, 15, False)
+
+
+def test_value_sets():
+    assert E4M3.max() == 448 and E4M3[1] == 2.0 ** -9 and len(E4M3) == 127
+    assert E5M2.max() == 57344 and E5M2[1] == 2.0 ** -16 and len(E5M2) == 124
+    for fmt, vals in (("e4m3", E4M3), ("e5m2", E5M2)):
+        assert np.array_equal(O.fp8_round(vals, fmt), vals)              # representable values stay
+        assert np.array_equal(O.fp8_round(-vals, fmt), -vals)
+
+
+@pytest.mark.parametrize("fmt,vals", [("e4m3", E4M3), ("e5m2", E5M2)])
+def test_rounding_is_nearest_value_by_brute_force(fmt, vals):
+    rng = np.random.default_rng(1)
+    x = np.concatenate([rng.uniform(0, vals.max(), 4000), rng.uniform(0, vals[8], 2000), 10.0 ** rng.uniform(-6, 4.6, 4000)])
+    x = x[x <= vals.max()]
+    got = O.fp8_round(x, fmt)
+    d = np.abs(x[:, None] - vals[None, :])
+    best = d.min(axis=1)
+    assert np.all(np.abs(got - x) <= best * (1 + 1e-12))
+    assert np.all(np.isin(got, vals))
+    # midpoints go to the neighbour with the even mantissa: every second value of the set
+    mid = (vals[:-1] + vals[1:]) / 2
+    r = O.fp8_round(mid, fmt)
+    even = np.where(np.arange(len(vals) - 1) % 2 == 0, vals[:-1], vals[1:])
+    assert np.array_equal(r, even)
+    # beyond the largest value: limited, not infinite
+    assert O.fp8_round(np.array([vals.max() * 1.5, -1e9]), fmt).tolist() == [vals.max(), -vals.max()]
+
+
+def test_input_quant_format_switch_scale_and_bounds():
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((16, 256)).astype(np.float16)
+    Xq, s, fmt = O.input_quant_fp8(X)
+    M = np.float32(np.abs(X.astype(np.float32)).max())
+    assert fmt == "e4m3" and s == np.float32(M / np.float32(448))
+    # 3 mantissa bits: relative error at most 2^-4 for values that are normal after scaling (+ the fp16 rounding)
+    xf = X.astype(np.float64)
+    big = np.abs(xf) >= float(s) * 2.0 ** -6
+    assert np.all(np.abs(Xq.astype(np.float64) - xf)[big] <= np.abs(xf)[big] * (2.0 ** -4 + 2.0 ** -10))
+    assert np.abs(Xq.astype(np.float64)).max() == float(M)                 # the maximum is kept exactly
+    # an outlier beyond 448 switches the format: 2 mantissa bits
+    X2 = X.copy()
+    X2[3, 7] = np.float16(900.0)
+    Xq2, s2, fmt2 = O.input_quant_fp8(X2)
+    assert fmt2 == "e5m2" and s2 == np.float32(np.float32(900.0) / np.float32(57344.0))
+    big2 = np.abs(X2.astype(np.float64)) >= float(s2) * 2.0 ** -14
+    err = np.abs(Xq2.astype(np.float64) - X2.astype(np.float64))
+    assert np.all(err[big2] <= np.abs(X2.astype(np.float64))[big2] * (2.0 ** -3 + 2.0 ** -10))
+    assert Xq2[3, 7] == np.float16(900.0)
+    # exactly 448 stays E4M3 with scale 1: the values then are the format's own
+    X3 = np.array([[448.0, 1.0, 0.3, -17.0, 2.0 ** -9, 2.0 ** -11]], np.float16)
+    Xq3, s3, fmt3 = O.input_quant_fp8(X3)
+    assert fmt3 == "e4m3" and s3 == 1.0
+    assert Xq3.tolist() == [[448.0, 1.0, 0.3125, -16.0, 2.0 ** -9, 0.0]]
+    # a zero tensor
+    Z, sz, fz = O.input_quant_fp8(np.zeros((2, 8), np.float16))
+    assert sz == 1.0 and fz == "e4m3" and not Z.any()
+
+
+def test_input_quant_is_idempotent_when_the_scale_is_a_power_of_two():
+    rng = np.random.default_rng(3)
+    X = (rng.standard_normal((8, 128)) * 3).astype(np.float16)
+    X[0, 0] = np.float16(448.0 / 64)              # max -> scale 2^-6: scaling is exact
+    X = np.clip(X, -7, 7).astype(np.float16)
+    Xq, s, fmt = O.input_quant_fp8(X)
+    assert s == np.float32(2.0 ** -6)
+    Xqq, s2, _ = O.input_quant_fp8(Xq)
+    assert s2 == s and np.array_equal(Xqq, Xq)
