@@ -295,6 +295,23 @@ int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, const slim_h
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * slim_input_quant_fp8 -- 8-bit input quantization as the paper evaluates it
+ * (App. "Input Quantization"): AbsMax quantization of an input tensor to FP8
+ * with one scale per tensor; Xq holds the quantized values back on the fp16
+ * grid, which is what the layer is then run on.
+ *   M = max|X|;  format E4M3 (largest value 448) unless M > 448, then E5M2
+ *   (largest value 57344);  scale = M / (largest value), one binary32 division
+ *   (1 for a zero tensor);  Xq = fp16( fp8(x / scale) * scale ), quotient and
+ *   product in binary32, fp8(): nearest value of the format, ties to even,
+ *   subnormals included.
+ * X, Xq: `count` fp16 values (Xq may be X); info: two floats out (scale; 0 for
+ * E4M3, 1 for E5M2); workspace: at least 1024 bytes, need not be zeroed.
+ * X must be finite.  Errors: NULL, SHAPE (count = 0), ALIGN, WORKSPACE, HIP.
+ */
+int slim_input_quant_fp8(const slim_half *X, size_t count, slim_half *Xq, float *info, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+/*
  * Measurement aids (they compute nothing of the method): what this machine
  * delivers on a plain streaming read and on back-to-back matrix instructions,
  * to set beside the nominal peaks when a kernel's roofline fraction is quoted

@@ -40,7 +40,7 @@ EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pac
            "slim_unpack", "slim_workspace_bytes", "slim_linear_gemv", "slim_linear_gemm", "slim_lowrank",
            "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4", "slim_pack_ex",
            "slim_quant_workspace_bytes", "slim_quant_search", "slim_quant_search_rows", "slim_adapters_workspace_bytes",
-           "slim_compute_adapters", "slim_probe_read", "slim_probe_mfma"]
+           "slim_compute_adapters", "slim_input_quant_fp8", "slim_probe_read", "slim_probe_mfma"]
 
 
 def lib():
@@ -69,6 +69,7 @@ def lib():
         L.slim_quant_search_rows.argtypes = [vp, slim_shape, vp, vp, vp]
         L.slim_adapters_workspace_bytes.argtypes = [slim_shape, psz]
         L.slim_compute_adapters.argtypes = [vp, vp, vp, vp, slim_shape, vp, i32, ctypes.c_uint32, vp, vp, vp, vp, sz, vp]
+        L.slim_input_quant_fp8.argtypes = [vp, sz, vp, vp, vp, sz, vp]
         L.slim_probe_read.argtypes = [vp, sz, i32, sz, vp, vp]
         L.slim_probe_mfma.argtypes = [i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.slim_pack_adapters_q4.argtypes = [vp, vp, slim_shape, vp, vp, vp, vp, vp]
@@ -237,6 +238,18 @@ def slim_compute_adapters(W: torch.Tensor, qvals, meta, scale, rank: int, x_tild
            lib().slim_compute_adapters(_ptr(W), _ptr(qvals), _ptr(meta), _ptr(scale), shape, _ptr(x_tilde), iters, seed,
                                        _ptr(L), _ptr(R), _ptr(diag), _ptr(ws), ws.numel(), _stream(W)))
     return L, R, diag
+
+
+def slim_input_quant_fp8(X: torch.Tensor):
+    """FP8 AbsMax quantization of an input tensor, values back on the fp16 grid:
+    (Xq fp16 like X, info fp32 [2] = scale, format (0: E4M3, 1: E5M2))."""
+    _dev(X, torch.float16, "X")
+    Xq = torch.empty_like(X)
+    info = torch.empty(2, dtype=torch.float32, device=X.device)
+    ws = torch.empty(1024, dtype=torch.uint8, device=X.device)
+    _check("slim_input_quant_fp8", lib().slim_input_quant_fp8(_ptr(X), X.numel(), _ptr(Xq), _ptr(info), _ptr(ws), ws.numel(),
+                                                              _stream(X)))
+    return Xq, info
 
 
 def slim_probe_read(buf: torch.Tensor, nbytes: int, repeats: int, stride: int, sink: torch.Tensor):

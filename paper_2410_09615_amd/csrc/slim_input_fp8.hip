@@ -1,0 +1,97 @@
+// 8-bit input quantization as the paper evaluates it (App. "Input Quantization"): AbsMax
+// quantization of an input tensor to FP8 with one scale per tensor; the quantized values,
+// back on the fp16 grid, are what the layer then sees.  E4M3 (largest value 448) unless the
+// tensor's maximum exceeds that, then E5M2 (largest value 57344).
+#include <hip/hip_runtime.h>
+
+#include "slim_internal.h"
+
+namespace slim {
+
+constexpr int kInMaxBlocks = 256;
+
+// partial maxima of |X|, one per workgroup (X as 16-byte pieces of 8 halves; `tail` halves after them)
+__global__ __launch_bounds__(256) void input_absmax_kernel(const half_t *__restrict__ X, size_t count, float *part)
+{
+    __shared__ float red[4];
+    const size_t n8 = count / 8;
+    float a = 0.f;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (size_t)gridDim.x * blockDim.x) {
+        const half8_t v = reinterpret_cast<const half8_t *>(X)[i];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf((float)v[e]));
+    }
+    if (blockIdx.x == 0)
+        for (size_t i = n8 * 8 + threadIdx.x; i < count; i += blockDim.x) a = fmaxf(a, fabsf((float)X[i]));
+    a = wave_max(a);
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+// nearest value of the format (mantissa bits P, smallest normal exponent EMIN, largest value fmax), ties to even
+template <int P, int EMIN>
+__device__ __forceinline__ float fp8_round(float v, float fmax)
+{
+    const float a = fminf(fabsf(v), fmax);
+    int e = (int)((__float_as_uint(a) >> 23) & 0xFFu) - 127;     // floor(log2 a) for a normal a; zero and tiny values fall below EMIN
+    e = e > EMIN ? e : EMIN;
+    const float q = __uint_as_float((uint32_t)(e - P + 127) << 23);      // spacing of the format at this magnitude
+    const float r = fminf(rintf(a / q) * q, fmax);                       // a / q is exact: a power of two
+    return copysignf(r, v);
+}
+
+__global__ __launch_bounds__(256) void input_fp8_kernel(const half_t *__restrict__ X, size_t count, const float *part, int nparts,
+                                                        half_t *Xq, float *info)
+{
+    __shared__ float red[4];
+    float a = (int)threadIdx.x < nparts ? part[threadIdx.x] : 0.f;
+    a = wave_max(a);
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = a;
+    __syncthreads();
+    const float M = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const bool e5 = M > 448.0f;
+    const float fmax = e5 ? 57344.0f : 448.0f;
+    const float s = M == 0.f ? 1.0f : M / fmax;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        info[0] = s;
+        info[1] = e5 ? 1.0f : 0.0f;
+    }
+    auto one = [&](half_t x) {
+        const float v = (float)x / s;
+        const float r = e5 ? fp8_round<2, -14>(v, fmax) : fp8_round<3, -6>(v, fmax);
+        return (half_t)(r * s);
+    };
+    const size_t n8 = count / 8;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (size_t)gridDim.x * blockDim.x) {
+        const half8_t v = reinterpret_cast<const half8_t *>(X)[i];
+        half8_t o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = one(v[e]);
+        reinterpret_cast<half8_t *>(Xq)[i] = o;
+    }
+    if (blockIdx.x == 0)
+        for (size_t i = n8 * 8 + threadIdx.x; i < count; i += blockDim.x) Xq[i] = one(X[i]);
+}
+
+}  // namespace slim
+
+using namespace slim;
+
+extern "C" int slim_input_quant_fp8(const slim_half *X, size_t count, slim_half *Xq, float *info, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    if (!X || !Xq || !info || !workspace) return SLIM_ERR_NULL;
+    if (count < 1) return SLIM_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Xq) || !aligned16(workspace)) return SLIM_ERR_ALIGN;
+    if (workspace_bytes < kInMaxBlocks * sizeof(float)) return SLIM_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t g = (count / 8 + 255) / 256;
+    const unsigned grid_a = (unsigned)(g < 1 ? 1 : (g < kInMaxBlocks ? g : kInMaxBlocks));
+    const unsigned grid_q = (unsigned)(g < 1 ? 1 : (g < 2048 ? g : 2048));
+    float *part = static_cast<float *>(workspace);
+    hipLaunchKernelGGL(input_absmax_kernel, dim3(grid_a), dim3(256), 0, st, reinterpret_cast<const half_t *>(X), count, part);
+    hipLaunchKernelGGL(input_fp8_kernel, dim3(grid_q), dim3(256), 0, st, reinterpret_cast<const half_t *>(X), count,
+                       (const float *)part, (int)grid_a, reinterpret_cast<half_t *>(Xq), info);
+    return hip_status(hipGetLastError());
+}

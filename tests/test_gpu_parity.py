@@ -497,3 +497,46 @@ def test_probes_run_and_report_their_work():
         B.slim_probe_read(buf, 1024, 1, 0, sink)
     with pytest.raises(ValueError):
         B.slim_probe_read(buf, 8 << 20, 2, 4 << 20, sink)
+
+
+# ---- FP8 input quantization (App. "Input Quantization") ---------------------------------
+
+@pytest.mark.parametrize("case", ["normal", "outliers", "beyond_e4m3", "tiny", "zero", "ragged"])
+def test_input_quant_fp8_bit_exact(case):
+    rng = np.random.default_rng(len(case))
+    if case == "normal":
+        X = rng.standard_normal((16, 4096)).astype(np.float16)
+    elif case == "outliers":
+        X = wl.make_activations(16, 4096, seed=5).numpy()
+    elif case == "beyond_e4m3":
+        X = (rng.standard_normal((8, 1024)) * 40).astype(np.float16)
+        X[2, 3] = np.float16(-3000.0)
+    elif case == "tiny":
+        X = (rng.standard_normal((4, 512)) * 1e-4).astype(np.float16)          # fp16 subnormals among them
+    elif case == "zero":
+        X = np.zeros((2, 128), np.float16)
+    else:
+        X = rng.standard_normal((3, 1001)).astype(np.float16)                  # a tail that is no 16-byte piece
+    Xq, info = B.slim_input_quant_fp8(torch.from_numpy(X).to(DEV))
+    torch.cuda.synchronize()
+    rq, rs, rf = O.input_quant_fp8(X)
+    info = info.cpu().numpy()
+    assert info[0].view(np.uint32) == np.float32(rs).view(np.uint32)
+    assert info[1] == (1.0 if rf == "e5m2" else 0.0)
+    assert np.array_equal(Xq.cpu().numpy().view(np.uint16), rq.view(np.uint16))
+
+
+def test_forward_on_fp8_quantized_input():
+    shape = _shape(512, 1024, 51)
+    W, L, R, X = wl.make_layer(shape, 8, seed=13)
+    layer = _gpu_layer(W, L, R)
+    Xq, _ = B.slim_input_quant_fp8(X.to(DEV))
+    Y = B.slim_linear_gemv(layer, Xq)
+    torch.cuda.synchronize()
+    ref = O.compress(W.numpy())
+    rq, _, _ = O.input_quant_fp8(X.numpy())
+    Yo = O.forward(ref, L.numpy(), R.numpy(), rq)
+    assert _relerr(Y.cpu().numpy(), Yo) <= TOL_Y
+    # and the quantization of the input costs accuracy of the order of its 2 to 3 mantissa bits, not more
+    Y0 = O.forward(ref, L.numpy(), R.numpy(), X.numpy())
+    assert 1e-3 < _relerr(Yo, Y0) < 0.1

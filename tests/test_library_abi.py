@@ -106,3 +106,8 @@ def test_probe_validation():
     fl = ctypes.c_double()
     assert lib.slim_probe_read(None, 1 << 20, 1, 0, None, None) == B.SLIM_ERR_NULL
     assert lib.slim_probe_mfma(0, 16, 16, None, fl, None) == B.SLIM_ERR_NULL
+
+
+def test_input_quant_validation():
+    lib = B.lib()
+    assert lib.slim_input_quant_fp8(None, 16, None, None, None, 0, None) == B.SLIM_ERR_NULL
