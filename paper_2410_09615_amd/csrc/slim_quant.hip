@@ -173,7 +173,6 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const float *__restrict
                                                          float *alpha_out)
 {
     extern __shared__ unsigned hist[];
-    __shared__ double red[16];
     __shared__ double err[kCoarse + kFine];
     __shared__ float part[4];
     const int k4 = k / 4;
@@ -206,20 +205,33 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const float *__restrict
             }
             __syncthreads();
             const double M = (double)Mf, eta = M / 10.0;
-            for (int c = 0; c < kCoarse; ++c) {
-                const double e = quant_error_block(hist, B, M, eta * (c + 1), red);
-                if (threadIdx.x == 0) err[c] = e;
+            // all candidates of a stage at once: G lanes share a candidate, each takes every G-th bin
+            auto eval = [&](int c, double alpha, bool ok, int j, int G) {
+                double e = 0.0;
+                if (ok) {
+                    const double step = alpha / 7.0, width = M / B;
+                    for (int b = j; b < B; b += G) {
+                        const double x = ((double)b + 0.5) * width;
+                        const double d = x <= alpha ? rint(x / step) * step - x : alpha - x;
+                        e += (double)hist[b] * (d * d);
+                    }
+                }
+                for (int off = G / 2; off >= 1; off >>= 1) e += __shfl_xor(e, off, kWave);
+                if (j == 0 && c < kCoarse + kFine) err[c] = ok ? e : __builtin_inf();
+            };
+            {
+                const int c = threadIdx.x >> 4;                     // 16 lanes per coarse candidate
+                eval(c, eta * (c + 1), c < kCoarse, threadIdx.x & 15, 16);
             }
             __syncthreads();
             int best = 0;
             for (int i = 1; i < kCoarse; ++i)
                 if (err[i] < err[best]) best = i;
             const double lo = eta * (best + 1);
-            for (int c = kCoarse; c < kCoarse + kFine; ++c) {
-                const double alpha = lo + eta * ((c - kCoarse - 10) / 10.0);
-                const bool ok = alpha > 0.0 && alpha <= M;                 // the same for every thread
-                const double e = ok ? quant_error_block(hist, B, M, alpha, red) : __builtin_inf();
-                if (threadIdx.x == 0) err[c] = e;
+            {
+                const int f = threadIdx.x >> 3;                     // 8 lanes per fine candidate
+                const double alpha = lo + eta * ((f - 10) / 10.0);
+                eval(kCoarse + f, alpha, f < kFine && alpha > 0.0 && alpha <= M, threadIdx.x & 7, 8);
             }
             __syncthreads();
             int pick = best;
