@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
     const int k0 = blockIdx.y * a.ks;
     const int klen = max(0, min(a.ks, a.kt - k0));      // a split past the end adds zeros
 
-    asm volatile("" : : : SLIM_ALL_ACC_REGS);
+    acc_reserve<AT>();
     static_for<16 * AT * NT>([&](auto r) { acc_write<r>(0.0f); });
 
     const uint32_t kt = (uint32_t)a.kt;

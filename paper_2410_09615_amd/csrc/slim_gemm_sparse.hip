@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
     const int t0 = (w / a.tiles_o) * 128;
     const int t_end = min(a.m, t0 + 128);                    // tokens of this workgroup: [t0, t_end)
 
-    asm volatile("" : : : SLIM_ALL_ACC_REGS);
+    acc_reserve<AT>();
     static_for<16 * AT * NT>([&](auto r) { acc_write<r>(0.0f); });
 
     const uint32_t k = (uint32_t)a.k;

@@ -40,12 +40,29 @@ __device__ __forceinline__ void static_for(F &&f)
 // between matrix instructions and reads or writes of them.
 #define SLIM_A10(b) "a" #b "0", "a" #b "1", "a" #b "2", "a" #b "3", "a" #b "4", "a" #b "5", "a" #b "6", "a" #b "7", \
                     "a" #b "8", "a" #b "9"
-#define SLIM_ALL_ACC_REGS                                                                                            \
+#define SLIM_ACC_REGS_64                                                                                             \
     "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", SLIM_A10(1), SLIM_A10(2), SLIM_A10(3), SLIM_A10(4),  \
-        SLIM_A10(5), SLIM_A10(6), SLIM_A10(7), SLIM_A10(8), SLIM_A10(9), SLIM_A10(10), SLIM_A10(11), SLIM_A10(12),   \
-        SLIM_A10(13), SLIM_A10(14), SLIM_A10(15), SLIM_A10(16), SLIM_A10(17), SLIM_A10(18), SLIM_A10(19),            \
-        SLIM_A10(20), SLIM_A10(21), SLIM_A10(22), SLIM_A10(23), SLIM_A10(24), "a250", "a251", "a252", "a253",        \
-        "a254", "a255"
+        SLIM_A10(5), "a60", "a61", "a62", "a63"
+#define SLIM_ACC_REGS_128                                                                                            \
+    SLIM_ACC_REGS_64, "a64", "a65", "a66", "a67", "a68", "a69", SLIM_A10(7), SLIM_A10(8), SLIM_A10(9), SLIM_A10(10), \
+        SLIM_A10(11), "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127"
+#define SLIM_ACC_REGS_256                                                                                            \
+    SLIM_ACC_REGS_128, "a128", "a129", SLIM_A10(13), SLIM_A10(14), SLIM_A10(15), SLIM_A10(16), SLIM_A10(17),         \
+        SLIM_A10(18), SLIM_A10(19), SLIM_A10(20), SLIM_A10(21), SLIM_A10(22), SLIM_A10(23), SLIM_A10(24), "a250",    \
+        "a251", "a252", "a253", "a254", "a255"
+
+// The accumulators of a kernel with AT row tiles per wavefront: a[0 .. 64 AT).  Fewer reserved
+// registers let two (AT = 2) or three (AT = 1) wavefronts share a SIMD.
+template <int AT>
+__device__ __forceinline__ void acc_reserve()
+{
+    if constexpr (AT == 1)
+        asm volatile("" : : : SLIM_ACC_REGS_64);
+    else if constexpr (AT == 2)
+        asm volatile("" : : : SLIM_ACC_REGS_128);
+    else
+        asm volatile("" : : : SLIM_ACC_REGS_256);
+}
 
 template <int R>
 __device__ __forceinline__ void acc_write(float v)
