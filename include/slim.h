@@ -274,6 +274,18 @@ int slim_linear_gemv(const slim_layer *layer, const slim_half *X, int32_t m, sli
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * slim_decode_plan -- what slim_linear_gemv would launch for this layer (only
+ * shape, rank_pad and adapter_bits are read) at m tokens; nothing is launched.
+ * out: 12 ints (HOST pointer): [0] path (2: one launch, 1: its two roles as two
+ * launches, 0: the two-launch kernels); for paths 1 and 2: [1] workgroups, [2]
+ * threads per workgroup, [3] LDS bytes per workgroup, [4] workgroups of the
+ * R role, [5] shares of the inputs in the R role, [6] wavefronts per row tile,
+ * [7] working and [8] helper wavefronts per workgroup, [9] inputs per chunk of
+ * X, [10] chunks, [11] workgroups of the Y role.  Errors: NULL, SHAPE.
+ */
+int slim_decode_plan(const slim_layer *layer, int32_t m, int32_t *out);
+
+/*
  * slim_linear_gemm -- prefill-shaped forward, any m >= 1 (meant for m >= 64):
  * matrix-core GEMM over the compressed weights with the adapter product
  * T = X R^T (rounded once to fp16) folded in as extra k-steps, row scale

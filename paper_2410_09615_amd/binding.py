@@ -37,7 +37,7 @@ class slim_layer(ctypes.Structure):
 SLIM_OK, SLIM_ERR_NULL, SLIM_ERR_SHAPE, SLIM_ERR_ALIGN, SLIM_ERR_WORKSPACE, SLIM_ERR_HIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pack", "slim_pack_adapters",
-           "slim_unpack", "slim_workspace_bytes", "slim_linear_gemv", "slim_linear_gemm", "slim_lowrank",
+           "slim_unpack", "slim_workspace_bytes", "slim_decode_plan", "slim_linear_gemv", "slim_linear_gemm", "slim_lowrank",
            "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4", "slim_pack_ex",
            "slim_quant_workspace_bytes", "slim_quant_search", "slim_quant_search_rows", "slim_adapters_workspace_bytes",
            "slim_compute_adapters", "slim_input_quant_fp8", "slim_probe_read", "slim_probe_mfma"]
@@ -62,6 +62,7 @@ def lib():
         L.slim_pack_adapters.argtypes = [vp, vp, slim_shape, vp, vp, vp]
         L.slim_unpack.argtypes = [vp, vp, slim_shape, vp, vp, vp]
         L.slim_workspace_bytes.argtypes = [ctypes.POINTER(slim_layer), i32, psz]
+        L.slim_decode_plan.argtypes = [ctypes.POINTER(slim_layer), i32, pi32]
         L.slim_adapter_q4_sizes.argtypes = [i32, i32, psz, psz]
         L.slim_pack_ex.argtypes = [vp, slim_shape, vp, vp, vp, vp, vp, vp]
         L.slim_quant_workspace_bytes.argtypes = [slim_shape, psz]
@@ -390,6 +391,17 @@ def slim_workspace_bytes(layer: SlimLayer, m: int) -> int:
     cs = layer.c_struct()
     _check("slim_workspace_bytes", lib().slim_workspace_bytes(ctypes.byref(cs), m, out))
     return out.value
+
+
+def slim_decode_plan(n: int, k: int, rank: int, m: int, adapter_bits: int = 16) -> dict:
+    """Launch geometry slim_linear_gemv would use (host logic only; no device needed)."""
+    layer = slim_layer(slim_shape(n, k, rank), None, None, None, None, None, slim_rank_pad(rank), adapter_bits, None, None,
+                       None, None)
+    out = (ctypes.c_int32 * 12)()
+    _check("slim_decode_plan", lib().slim_decode_plan(ctypes.byref(layer), m, out))
+    keys = ("path", "workgroups", "threads", "lds_bytes", "r_workgroups", "r_shares", "wavefronts_per_row_tile",
+            "working_wavefronts", "helper_wavefronts", "chunk_inputs", "chunks", "y_workgroups")
+    return dict(zip(keys, list(out)))
 
 
 def alloc_workspace(layer: SlimLayer, m: int) -> torch.Tensor:

@@ -641,3 +641,35 @@ extern "C" int slim_linear_gemv(const slim_layer *layer_in, const slim_half *X, 
     a.accumulate = 0;
     return launch_decode(a, p, static_cast<hipStream_t>(stream));
 }
+
+// What slim_linear_gemv would launch for this layer and token count (no launch, no device access).
+extern "C" int slim_decode_plan(const slim_layer *layer, int32_t m, int32_t *out)
+{
+    if (!layer || !out) return SLIM_ERR_NULL;
+    const slim_shape s = layer->shape;
+    if (s.n < 1 || s.k < 128 || s.k % 128 || s.rank < 0 || m < 1 || m > kMaxTokens) return SLIM_ERR_SHAPE;
+    if (layer->rank_pad != slim_rank_pad(s.rank)) return SLIM_ERR_SHAPE;
+    const FusedPlan f = plan_fused(s.n, s.k, layer->rank_pad, m);
+    int mode = f.ok ? 2 : -1;
+    if (const char *env = getenv("SLIM_DECODE_PATH")) {
+        if (!strcmp(env, "parts")) mode = -1;
+        if (!strcmp(env, "roles") && f.ok) mode = 1;
+        if (!strcmp(env, "fused") && f.ok) mode = 2;
+    }
+    for (int i = 0; i < 12; ++i) out[i] = 0;
+    out[0] = mode > 0 ? mode : 0;
+    if (mode > 0) {
+        out[1] = f.n_r + f.ygrid;
+        out[2] = (f.waves + f.helpers) * kWave;
+        out[3] = (int32_t)f.lds;
+        out[4] = f.n_r;
+        out[5] = f.kh;
+        out[6] = f.S;
+        out[7] = f.waves;
+        out[8] = f.helpers;
+        out[9] = f.kc;
+        out[10] = f.nch;
+        out[11] = f.ygrid;
+    }
+    return SLIM_OK;
+}

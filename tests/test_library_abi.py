@@ -111,3 +111,40 @@ def test_probe_validation():
 def test_input_quant_validation():
     lib = B.lib()
     assert lib.slim_input_quant_fp8(None, 16, None, None, None, 0, None) == B.SLIM_ERR_NULL
+
+
+def test_decode_plan_of_the_configured_shapes(monkeypatch):
+    """Host logic of slim_linear_gemv: every configured layer takes the one-launch path at every token
+    count, within what a compute unit holds (1024 threads, 160 KiB of LDS, 16 wavefronts), with all
+    workgroups resident at once and every row tile covered."""
+    from paper_2410_09615_amd import workloads as wl
+    monkeypatch.delenv("SLIM_DECODE_PATH", raising=False)
+    monkeypatch.delenv("SLIM_DECODE_LDS_KB", raising=False)
+    for shp in (wl.TINY, wl.L7B_ATTN, wl.L7B_UP, wl.L7B_DOWN, wl.L13B_ATTN, wl.L13B_UP, wl.L70B_ATTN, wl.L70B_UP):
+        for m in (1, 2, 4, 8, 16):
+            p = B.slim_decode_plan(shp.n, shp.k, shp.r, m)
+            assert p["path"] == 2, (shp.name, m)
+            assert p["threads"] % 64 == 0 and p["threads"] <= 1024
+            assert p["threads"] == 64 * (p["working_wavefronts"] + p["helper_wavefronts"])
+            assert p["lds_bytes"] <= 160 * 1024
+            per_cu = min(16 // (p["threads"] // 64), (160 * 1024) // p["lds_bytes"])
+            assert p["workgroups"] == p["r_workgroups"] + p["y_workgroups"] <= 256 * per_cu
+            assert p["r_workgroups"] == (B.slim_rank_pad(shp.r) // 16) * p["r_shares"] <= 512
+            tiles = (shp.n + 15) // 16
+            assert p["y_workgroups"] * (p["working_wavefronts"] // p["wavefronts_per_row_tile"]) >= tiles
+            assert p["chunk_inputs"] * p["chunks"] >= shp.k and p["chunk_inputs"] % 1024 == 0
+            if p["chunks"] > 1:
+                assert B.slim_rank_pad(shp.r) <= p["chunk_inputs"]        # T takes the place of an X buffer
+    # forced paths and errors
+    monkeypatch.setenv("SLIM_DECODE_PATH", "parts")
+    assert B.slim_decode_plan(4096, 4096, 410, 1)["path"] == 0
+    monkeypatch.setenv("SLIM_DECODE_PATH", "roles")
+    assert B.slim_decode_plan(4096, 4096, 410, 1)["path"] == 1
+    monkeypatch.delenv("SLIM_DECODE_PATH")
+    with pytest.raises(B.SlimError):
+        B.slim_decode_plan(4096, 4096, 410, 17)
+    with pytest.raises(B.SlimError):
+        B.slim_decode_plan(4096, 4100, 410, 1)
+    # a reduced LDS budget (what the chunk tests use) forces chunks
+    monkeypatch.setenv("SLIM_DECODE_LDS_KB", "24")
+    assert B.slim_decode_plan(640, 4096, 102, 8)["chunks"] > 1
