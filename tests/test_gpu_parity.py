@@ -193,13 +193,15 @@ def test_gemv_full_size_sampled_rows(shape, m, decode_path):
     assert _forward_case(shape, m, B.slim_linear_gemv, rows=rows) <= TOL_Y
 
 
-@pytest.mark.parametrize("n,k,r,m,lds_kb", [(1000, 4096, 100, 16, 96), (1000, 4096, 100, 16, 48), (520, 11008, 410, 8, 64),
-                                            (300, 2176, 37, 5, 24), (2049, 8192, 33, 16, 160), (64, 3072, 0, 16, 40)])
+@pytest.mark.parametrize("n,k,r,m,lds_kb", [(1000, 4096, 100, 16, 96), (1000, 4096, 100, 16, 72), (520, 11008, 410, 8, 64),
+                                            (300, 2176, 37, 5, 24), (2049, 8192, 33, 16, 160), (64, 3072, 0, 16, 70)])
 def test_gemv_one_launch_with_x_in_chunks(n, k, r, m, lds_kb, monkeypatch):
     """The one-launch kernel with X streamed through LDS in chunks (a smaller LDS
     budget forces the chunks on layers the oracle finishes quickly)."""
     monkeypatch.setenv("SLIM_DECODE_PATH", "fused")
     monkeypatch.setenv("SLIM_DECODE_LDS_KB", str(lds_kb))
+    plan = B.slim_decode_plan(n, k, r, m)
+    assert plan["path"] == 2 and plan["chunks"] > 1            # the case really runs what it is meant to
     assert _forward_case(_shape(n, k, r), m, B.slim_linear_gemv, seed=13) <= TOL_Y
 
 
@@ -443,6 +445,8 @@ def test_gemv_q4_adapters_full_size_sampled_rows(shape, m):
 def test_gemv_q4_adapters_with_x_in_chunks(n, k, r, m, lds_kb, monkeypatch):
     monkeypatch.setenv("SLIM_DECODE_PATH", "fused")
     monkeypatch.setenv("SLIM_DECODE_LDS_KB", str(lds_kb))
+    plan = B.slim_decode_plan(n, k, r, m, 4)
+    assert plan["path"] == 2 and plan["chunks"] > 1
     assert _forward_case_q4(_shape(n, k, r), m, B.slim_linear_gemv, seed=17) <= TOL_Y
 
 

@@ -146,5 +146,8 @@ def test_decode_plan_of_the_configured_shapes(monkeypatch):
     with pytest.raises(B.SlimError):
         B.slim_decode_plan(4096, 4100, 410, 1)
     # a reduced LDS budget (what the chunk tests use) forces chunks
-    monkeypatch.setenv("SLIM_DECODE_LDS_KB", "24")
-    assert B.slim_decode_plan(640, 4096, 102, 8)["chunks"] > 1
+    for n, k, r, m, lds_kb in [(1000, 4096, 100, 16, 96), (1000, 4096, 100, 16, 72), (520, 11008, 410, 8, 64),
+                               (300, 2176, 37, 5, 24), (2049, 8192, 33, 16, 160), (64, 3072, 0, 16, 70)]:
+        monkeypatch.setenv("SLIM_DECODE_LDS_KB", str(lds_kb))
+        p = B.slim_decode_plan(n, k, r, m)
+        assert p["path"] == 2 and p["chunks"] > 1 and p["lds_bytes"] <= lds_kb * 1024, (n, k, r, m, lds_kb)
