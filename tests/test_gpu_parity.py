@@ -265,7 +265,8 @@ def test_gemm_llama7b_mlp_sampled_rows(shape, m):
     assert _forward_case(shape, m, B.slim_linear_gemm, rows=rows) <= TOL_Y
 
 
-@pytest.mark.parametrize("shape,m", [(wl.L13B_UP, 4096), (wl.L70B_ATTN, 4096)], ids=lambda v: str(getattr(v, "name", v)))
+@pytest.mark.parametrize("shape,m", [(wl.L13B_ATTN, 4096), (wl.L13B_UP, 4096), (wl.L70B_ATTN, 4096), (wl.L70B_UP, 4096)],
+                         ids=lambda v: str(getattr(v, "name", v)))
 def test_gemm_full_size_sampled_rows(shape, m):
     rows = np.random.default_rng(3).choice(shape.n, size=64, replace=False)
     rows.sort()
