@@ -183,7 +183,8 @@ def test_gemv_without_adapters(decode_path):
     assert _forward_case(_shape(512, 1024, 0), 4, B.slim_linear_gemv, seed=3) <= TOL_Y
 
 
-@pytest.mark.parametrize("shape,m", [(wl.L13B_UP, 1), (wl.L70B_ATTN, 16), (wl.L70B_UP, 1), (wl.L70B_UP, 4), (wl.L7B_DOWN, 4)],
+@pytest.mark.parametrize("shape,m", [(wl.L13B_UP, 1), (wl.L70B_ATTN, 16), (wl.L70B_UP, 1), (wl.L70B_UP, 4), (wl.L7B_DOWN, 4),
+                                     (wl.L13B_ATTN, 1), (wl.L70B_ATTN, 1), (wl.L70B_UP, 16), (wl.L7B_UP, 16)],
                          ids=lambda v: str(getattr(v, "name", v)))
 def test_gemv_full_size_sampled_rows(shape, m, decode_path):
     if decode_path in ("roles", "parts") and shape is not wl.L13B_UP:
