@@ -406,7 +406,8 @@ FP8_FORMATS = {"e4m3": (3, -6, 448.0), "e5m2": (2, -14, 57344.0)}      # mantiss
 
 
 def fp8_round(v: np.ndarray, fmt: str) -> np.ndarray:
-    """Nearest value of the format (ties to even mantissa), |v| limited to the largest finite one."""
+    """Nearest value of the format (ties to even mantissa), |v| limited to the largest finite one;
+    the sign is kept also where the magnitude rounds to zero (IEEE 754 rounding, signed zeros)."""
     p, emin, fmax = FP8_FORMATS[fmt]
     v = np.asarray(v, np.float64)
     a = np.minimum(np.abs(v), fmax)
@@ -414,7 +415,7 @@ def fp8_round(v: np.ndarray, fmt: str) -> np.ndarray:
     e = np.maximum(e, emin)
     q = np.exp2(e - p)                               # spacing of the format at this magnitude
     r = np.rint(a / q) * q                           # rint: ties to even; a / q is exact (power of two)
-    return np.sign(v) * np.minimum(r, fmax)
+    return np.copysign(np.minimum(r, fmax), v)      # the formats have signed zeros: what rounds to zero keeps its sign
 
 
 def input_quant_fp8(X: np.ndarray):

@@ -519,8 +519,10 @@ def test_input_quant_fp8_bit_exact(case):
         X[2, 3] = np.float16(-3000.0)
     elif case == "tiny":
         X = (rng.standard_normal((4, 512)) * 1e-4).astype(np.float16)          # fp16 subnormals among them
+        X[0, :8] = np.array([-0.0, 0.0, -6e-8, 6e-8, -1e-7, 1e-7, -0.0, 0.0], np.float16)   # round to zero, sign kept
     elif case == "zero":
         X = np.zeros((2, 128), np.float16)
+        X[1, ::3] = np.float16(-0.0)                                           # signed zeros stay what they are
     else:
         X = rng.standard_normal((3, 1001)).astype(np.float16)                  # a tail that is no 16-byte piece
     Xq, info = B.slim_input_quant_fp8(torch.from_numpy(X).to(DEV))

@@ -92,3 +92,14 @@ def test_input_quant_is_idempotent_when_the_scale_is_a_power_of_two():
     assert s == np.float32(2.0 ** -6)
     Xqq, s2, _ = O.input_quant_fp8(Xq)
     assert s2 == s and np.array_equal(Xqq, Xq)
+
+
+def test_signed_zero_is_kept():
+    """Both formats have a negative zero: -0 stays -0, and a negative value below half the smallest
+    subnormal rounds to -0 (IEEE 754 round to nearest), through the whole quantizer as well."""
+    for fmt in ("e4m3", "e5m2"):
+        r = O.fp8_round(np.array([-0.0, 0.0, -1e-9, 1e-9]), fmt)
+        assert np.array_equal(np.signbit(r), [True, False, True, False]) and not r.any()
+    X = np.array([[1.0, -0.0, 0.0, -6e-8, 6e-8]], np.float16)        # 6e-8: the smallest fp16 subnormal
+    Xq, _, _ = O.input_quant_fp8(X)
+    assert Xq.view(np.uint16).tolist() == [[0x3C00, 0x8000, 0x0000, 0x8000, 0x0000]]
