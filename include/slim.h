@@ -186,7 +186,11 @@ int slim_quant_search_rows(const float *W, slim_shape shape, float *scale_out, f
  *   shape.rank   1 <= rank <= min(n, k), slim_rank_pad(rank) <= 1024;
  *   iters        rounds of the subspace iteration Q <- orth(S orth(S^T Q)) that stands in
  *                for the SVD (0: 16).  It starts from a block of `rank` columns drawn
- *                from `seed`; its distance from the exact truncation shows in diag;
+ *                from `seed`; its distance from the exact truncation shows in diag
+ *                (16 rounds: weighted residual within 0.3 % of the optimum for rank <=
+ *                min(n, k) / 4 on compression errors; a rank close to min(n, k) leaves a few
+ *                nearly equal singular values to separate and wants more rounds);
+ *                sums use atomic adds, so results differ in the last bits from call to call;
  *   diag         (may be NULL) four floats out: ||S||_F^2, the captured part
  *                ||L^T S||_F^2 (the exact truncation captures the sum of the rank
  *                largest squared singular values), max |L^T L - I|, 0.
