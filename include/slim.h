@@ -251,10 +251,10 @@ int slim_unpack(const uint8_t *qvals, const uint8_t *meta, slim_shape shape, int
  * slim_lowrank.
  * The workspace must be ZERO-FILLED ONCE before its first use (hipMemset):
  * its first bytes hold the decode path's T = X R^T between the kernels' two
- * phases (pieces tagged with a call number, never 0; two accumulators and a
- * counter for the layers that take the two-launch path), and a fresh
- * workspace must not look like finished work.  Nothing else is carried
- * between calls.  Two calls that overlap in time need two workspaces.
+ * phases (pieces tagged with a call number, never 0), and a fresh workspace
+ * must not look like finished work.  Nothing is carried between calls: one
+ * workspace (of the largest size needed) can serve any sequence of layers and
+ * token counts.  Two calls that overlap in time need two workspaces.
  * Diagnostics: word 2 of the workspace is set to 1 if a decode call gave up
  * waiting for its own T (it never should; the call then returned wrong
  * numbers instead of hanging).

@@ -30,10 +30,10 @@
 // wavefront covers four runs of 256 contiguous bytes (R, L, codes) or of 128
 // (positions).
 //
-// State between calls lives in the head of the workspace: two T buffers used
-// alternately (a call accumulates into one and zeroes the other, which the
-// previous call left dirty) and an epoch word that selects the buffer.  All of
-// it starts as zeros.
+// Nothing is carried between calls: T (fp32 [16][rank_pad] in the head of the
+// workspace) is zeroed by a small kernel ahead of part 1, which adds into it.
+// (Earlier the calls cleaned a second T buffer for one another; that breaks as
+// soon as layers of different rank share a workspace.)
 #include <cstdlib>
 #include <cstring>
 
@@ -57,7 +57,7 @@ struct DecodeArgs {
     half_t *Y;
     float *P;            // [slots][m][n]; nullptr: no packed term (slim_lowrank)
     float *T;            // two buffers of [16][rank_pad] fp32
-    unsigned *ctrl;      // [0] epoch, [1] epoch + 1 while a call is between its two launches
+    unsigned *ctrl;      // control words of the workspace (not used by these kernels)
     int n, k, rank_pad, m;
     int mp;              // token rows of the LDS tiles (1, 4, 8 or 16) before the zero row
     int n_packed;        // rows with a packed term in part 1 (n, or 0)
@@ -197,14 +197,8 @@ __global__ __launch_bounds__(kDecThreads, 2) __attribute__((amdgpu_waves_per_eu(
     Unit cur = describe_unit(a, g, (blockIdx.x / a.nch) * kDecWaves + wave, 0);
     issue_unit(a, g, cur, lx, ly, bufA);
 
-    // T of this call: the epoch selects one of two buffers.  The other one is
-    // dirty from the previous call and nobody uses it during this call: zero it
-    // here, so that part 2 can simply add the two buffers.  (A vector load: the
-    // wait for it must not sit on the scalar/LDS counter.)
-    // The epoch is first needed when an R unit is finished; the cleaning is
-    // done at the end of the kernel.
-    const unsigned epoch = __builtin_nontemporal_load(a.ctrl);
-    float *Tcur = a.T + (size_t)(epoch & 1u) * kMaxTokens * rp;
+    // T of this call: zeroed ahead of this kernel
+    float *Tcur = a.T;
 
     // stage this chunk of X: mp token rows (rows >= m zero), inputs beyond the
     // chunk zero up to kc, then one all-zero row
@@ -285,10 +279,6 @@ __global__ __launch_bounds__(kDecThreads, 2) __attribute__((amdgpu_waves_per_eu(
         cur = nxt;
     }
 
-    float *Told = a.T + (size_t)((epoch & 1u) ^ 1u) * kMaxTokens * rp;
-    for (int j = blockIdx.x * kDecThreads + threadIdx.x; j < kMaxTokens * rp; j += gridDim.x * kDecThreads)
-        Told[j] = 0.0f;
-    if (blockIdx.x == 0 && threadIdx.x == 0) a.ctrl[1] = epoch + 1u;
 }
 
 // ---- part 2: Y = scale * sum P + T L^T ----
@@ -341,11 +331,7 @@ __global__ __launch_bounds__(kP2Threads, 1) void decode_part2_kernel(DecodeArgs 
     };
     if (nbatch > 0) issue_l(tile0, 0, lvA);
 
-    // T = T0 + T1: one of the two buffers holds this call's sums, the other is
-    // zero (part 1 cleaned it), so no need to know which is which
     const float *T0 = a.T;
-    const float *T1 = a.T + (size_t)kMaxTokens * rp;
-    if (blockIdx.x == 0 && threadIdx.x == 0) a.ctrl[0] = a.ctrl[1];       // next call: next epoch
 
     // T -> LDS as fp16 hi + lo, mp token rows then one zero row
     const int ldt = rp + kLdsPad;
@@ -364,8 +350,7 @@ __global__ __launch_bounds__(kP2Threads, 1) void decode_part2_kernel(DecodeArgs 
                 const int row = e / per_row, c = e - row * per_row;
                 v[i] = float4_t{0.f, 0.f, 0.f, 0.f};
                 if (e < total && row < a.m)
-                    v[i] = *reinterpret_cast<const float4_t *>(T0 + (size_t)row * rp + 4 * c) +
-                           *reinterpret_cast<const float4_t *>(T1 + (size_t)row * rp + 4 * c);
+                    v[i] = *reinterpret_cast<const float4_t *>(T0 + (size_t)row * rp + 4 * c);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -507,6 +492,11 @@ DecodePlan plan_decode(int n, int k, int rank_pad, int m)
     return p;
 }
 
+__global__ void decode_zero_t_kernel(float *T, int count)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += gridDim.x * blockDim.x) T[i] = 0.0f;
+}
+
 static int launch_decode(const DecodeArgs &a, const DecodePlan &p, hipStream_t st)
 {
     const size_t lds1 = (size_t)(p.mp + 1) * (p.kc + kLdsPad) * sizeof(half_t);
@@ -524,6 +514,10 @@ static int launch_decode(const DecodeArgs &a, const DecodePlan &p, hipStream_t s
     const long per_wave = (tasks + cap * kDecWaves - 1) / (cap * kDecWaves);
     long b1 = (tasks + per_wave * kDecWaves - 1) / (per_wave * kDecWaves);
     if (b1 < 1) b1 = 1;
+    if (a.rank_pad > 0) {
+        const int count = kMaxTokens * a.rank_pad;
+        hipLaunchKernelGGL(decode_zero_t_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, a.T, count);
+    }
     if (units_r + tasks_w > 0)
         hipLaunchKernelGGL(decode_part1_kernel, dim3((unsigned)(b1 * p.nch)), dim3(kDecThreads), lds1, st, a);
     long b2 = ((a.n + 15) / 16 + kP2Tiles - 1) / kP2Tiles;

@@ -548,3 +548,36 @@ def test_forward_on_fp8_quantized_input():
     # and the quantization of the input costs accuracy of the order of its 2 to 3 mantissa bits, not more
     Y0 = O.forward(ref, L.numpy(), R.numpy(), X.numpy())
     assert 1e-3 < _relerr(Yo, Y0) < 0.1
+
+
+# ---- one workspace, several layers ---------------------------------------------------
+
+@pytest.mark.parametrize("path", ["auto", "parts", "roles", "fused"])
+def test_gemv_one_workspace_shared_by_layers_of_different_rank(path, monkeypatch):
+    """Nothing is carried between calls: layers of different shape and rank, fp16 and 4-bit
+    adapters, take turns on one workspace, on every decode geometry."""
+    if path == "auto":
+        monkeypatch.delenv("SLIM_DECODE_PATH", raising=False)
+    else:
+        monkeypatch.setenv("SLIM_DECODE_PATH", path)
+    cases = []
+    for i, (n, k, r) in enumerate([(640, 1024, 51), (300, 2176, 37), (1000, 4096, 100), (48, 4096, 1024)]):
+        shape = _shape(n, k, r)
+        W, L, R, _ = wl.make_layer(shape, 1, seed=70 + i)
+        if i % 2:
+            layer = _q4_layer(W, L, R)
+            lc, ls = O.quantize_adapter(L.numpy())
+            rc, rs = O.quantize_adapter(R.numpy())
+            Lr, Rr = O.dequantize_adapter(lc, ls), O.dequantize_adapter(rc, rs)
+        else:
+            layer, Lr, Rr = _gpu_layer(W, L, R), L.numpy(), R.numpy()
+        cases.append((shape, layer, O.compress(W.numpy()), Lr, Rr))
+    ws = torch.zeros(max(B.slim_workspace_bytes(c[1], 16) for c in cases), dtype=torch.uint8, device=DEV)
+    rng = np.random.default_rng(4)
+    for step in range(24):
+        shape, layer, ref, Lr, Rr = cases[int(rng.integers(0, len(cases)))]
+        m = int(rng.integers(1, 17))
+        X = wl.make_activations(m, shape.k, seed=90 + step)
+        Y = B.slim_linear_gemv(layer, X.to(DEV), workspace=ws)
+        torch.cuda.synchronize()
+        assert _relerr(Y.cpu().numpy(), O.forward(ref, Lr, Rr, X.numpy())) <= TOL_Y, (step, shape.name, m)
