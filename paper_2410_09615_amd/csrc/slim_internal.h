@@ -163,7 +163,7 @@ inline int hip_status(hipError_t e) { return e == hipSuccess ? SLIM_OK : SLIM_ER
 // Workspace carve-up used by the forward entry points (offsets in bytes,
 // each a multiple of 256).
 struct WorkspacePlan {
-    size_t dec_off, dec_bytes;    // decode state: 256 B of control words, then two T buffers fp32 [16][rank_pad],
+    size_t dec_off, dec_bytes;    // decode state: 256 B of control words, then T fp32 [16][rank_pad] of the two-launch path (room for two),
                                   // then (one-launch path) T as up to four planes [16][rank_pad / 4] of 16-byte pieces
     size_t t16_off;               // the last, as an offset into the workspace
     size_t t_off, t_bytes;        // gemm: T = X R^T as fp16 [m][rank_pad]
