@@ -581,3 +581,24 @@ def test_gemv_one_workspace_shared_by_layers_of_different_rank(path, monkeypatch
         Y = B.slim_linear_gemv(layer, X.to(DEV), workspace=ws)
         torch.cuda.synchronize()
         assert _relerr(Y.cpu().numpy(), O.forward(ref, Lr, Rr, X.numpy())) <= TOL_Y, (step, shape.name, m)
+
+
+def test_calls_follow_the_current_stream():
+    """The binding hands torch's current stream to the library: work enqueued on a side stream is
+    ordered after what that stream already holds (a fill of X) and is complete after its
+    synchronization, without a device-wide one."""
+    shape = _shape(640, 1024, 51)
+    W, L, R, X = wl.make_layer(shape, 4, seed=31)
+    layer = _gpu_layer(W, L, R)
+    ref = O.compress(W.numpy())
+    Yo = O.forward(ref, L.numpy(), R.numpy(), X.numpy())
+    side = torch.cuda.Stream(device=DEV)                     # default priority
+    Xd = torch.zeros_like(X, device=DEV)
+    Xsrc = X.to(DEV)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        Xd.copy_(Xsrc, non_blocking=True)                    # on the side stream, ahead of the calls
+        Y1 = B.slim_linear_gemv(layer, Xd)
+        Y2 = B.slim_linear_gemm(layer, Xd)
+    side.synchronize()
+    assert _relerr(Y1.cpu().numpy(), Yo) <= TOL_Y and _relerr(Y2.cpu().numpy(), Yo) <= TOL_Y
