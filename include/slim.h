@@ -18,7 +18,9 @@
  *   - matrices are row-major, contiguous, 16-byte aligned;
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream);
  *     all work is enqueued on it and the call returns without synchronizing;
- *   - the library allocates nothing and keeps no state between calls;
+ *   - the library allocates nothing and keeps no state between calls; the forward
+ *     entry points enqueue kernels only (no memset, copy or synchronization) and
+ *     may be captured into a HIP graph;
  *   - arguments are validated on the host before anything is launched; on an
  *     error nothing has been enqueued.
  * fp16 values are IEEE binary16 bit patterns (`slim_half`).
@@ -252,7 +254,9 @@ int slim_unpack(const uint8_t *qvals, const uint8_t *meta, slim_shape shape, int
  * The workspace must be ZERO-FILLED ONCE before its first use (hipMemset):
  * its first bytes hold the decode path's T = X R^T between the kernels' two
  * phases (pieces tagged with a call number, never 0), and a fresh workspace
- * must not look like finished work.  Nothing is carried between calls: one
+ * must not look like finished work (under stream capture the call number
+ * lives in word 3 of the workspace and a one-thread kernel enqueued ahead of
+ * the decode kernel advances it on every replay).  Nothing is carried between calls: one
  * workspace (of the largest size needed) can serve any sequence of layers and
  * token counts.  Two calls that overlap in time need two workspaces.
  * Diagnostics: word 2 of the workspace is set to 1 if a decode call gave up

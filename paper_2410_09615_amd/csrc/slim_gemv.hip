@@ -604,7 +604,8 @@ extern "C" int slim_linear_gemv(const slim_layer *layer_in, const slim_half *X, 
         }
         if (mode > 0)
             return launch_decode_fused(layer, reinterpret_cast<const half_t *>(X), m, reinterpret_cast<half_t *>(Y),
-                                       ws + w.t16_off, reinterpret_cast<unsigned *>(ws + w.dec_off) + 2, f, mode,
+                                       ws + w.t16_off, reinterpret_cast<unsigned *>(ws + w.dec_off) + 2,
+                                       reinterpret_cast<unsigned *>(ws + w.dec_off) + 3, f, mode,
                                        static_cast<hipStream_t>(stream));
     }
     // the two-launch kernels read fp16 adapters: 4-bit ones are expanded in the workspace first

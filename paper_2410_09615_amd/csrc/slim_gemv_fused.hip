@@ -66,7 +66,8 @@ struct FusedArgs {
     half_t *Y;
     uint4_t *T;          // pieces {epoch, 0, 4 ranks fp16} [kh][16][rank_pad / 4]: T is the sum of the planes
     unsigned *err;       // set to 1 when a wait gave up
-    unsigned epoch;
+    unsigned epoch;      // this call's number (top bit clear, never 0), or
+    const unsigned *epoch_ptr;   // under stream capture: where a small kernel ahead of this one has put it (top bit set)
     int n, k, rank_pad, m;
     int rank;            // true rank (rows of R, columns of L that exist in the 4-bit buffers)
     int kpad;            // k rounded up to 1024
@@ -79,6 +80,21 @@ struct FusedArgs {
     int helpers;         // wavefronts of a workgroup that only fetch T (Y role)
     int mode;            // 0: R role only; 1: Y role only, T complete; 2: both roles in this grid
 };
+
+// The number that tags this call's pieces of T.  A launch argument normally; a launch that is
+// being captured into a graph would replay with the same number and take the pieces of the
+// previous replay for its own, so there the number lives in the workspace and a one-thread
+// kernel ahead of this one advances it on every replay.  The top bit keeps the two kinds apart.
+__device__ __forceinline__ unsigned call_epoch(const FusedArgs &a)
+{
+    return a.epoch_ptr ? (__builtin_nontemporal_load(a.epoch_ptr) | 0x80000000u) : a.epoch;
+}
+
+__global__ void decode_epoch_bump_kernel(unsigned *ctr)
+{
+    const unsigned v = (*ctr + 1u) & 0x7FFFFFFFu;
+    *ctr = v ? v : 1u;
+}
 
 // ---- R role ----
 template <bool Q4>
@@ -184,7 +200,7 @@ __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb
         const rsrc_t t_rs = make_rsrc(a.T, (uint32_t)a.kh * kMaxTokens * (rp / 4) * 16u);
         const uint32_t off = (((uint32_t)kh * kMaxTokens + lx) * (rp / 4) + 4 * rt + ly) * 16u;
         typedef unsigned int store4_t __attribute__((__vector_size__(16)));
-        const store4_t piece = {a.epoch, 0u, hb[0], hb[1]};
+        const store4_t piece = {call_epoch(a), 0u, hb[0], hb[1]};
         __builtin_amdgcn_raw_buffer_store_b128(piece, t_rs, (int)off, 0, kScopeDevice);
     }
 }
@@ -358,6 +374,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
         const int pairs = a.m * qpr;
         int spins = 0;
         bool gave_up = false;
+        const unsigned epoch = call_epoch(a);
         auto piece_off = [&](int pair, int share) {
             const int row = pair / qpr, q = pair - row * qpr;
             return pair < pairs ? (((uint32_t)share * kMaxTokens + row) * qpr + q) * 16u : kNowhere;
@@ -380,7 +397,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
                     for (int i = 0; i < PB; ++i)
 #pragma unroll
                         for (int h = 0; h < KH; ++h)
-                            all_there = all_there && (p0 + i * hn >= pairs || pc[i * KH + h][0] == a.epoch);
+                            all_there = all_there && (p0 + i * hn >= pairs || pc[i * KH + h][0] == epoch);
                     if (!all_there) {
                         if (++spins >= kSpinLimit) {
                             gave_up = true;
@@ -652,7 +669,7 @@ FusedPlan plan_fused(int n, int k, int rank_pad, int m)
 static std::atomic<unsigned> g_epoch{0};
 
 // mode: 2 = one launch, 1 = the two roles as two launches
-int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t *Y, void *T, unsigned *err, const FusedPlan &p, int mode, hipStream_t st)
+int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t *Y, void *T, unsigned *err, unsigned *epoch_ctr, const FusedPlan &p, int mode, hipStream_t st)
 {
     FusedArgs a{};
     a.qvals = layer->qvals;
@@ -668,9 +685,15 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     a.Y = Y;
     a.T = static_cast<uint4_t *>(T);
     a.err = err;
-    unsigned e = ++g_epoch;
-    if (e == 0) e = ++g_epoch;          // a zero-filled workspace must not look valid: epoch 0 is never used
+    unsigned e = ++g_epoch & 0x7FFFFFFFu;
+    if (e == 0) e = ++g_epoch & 0x7FFFFFFFu;      // a zero-filled workspace must not look valid: epoch 0 is never used
     a.epoch = e;
+    a.epoch_ptr = nullptr;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) == hipSuccess && cap == hipStreamCaptureStatusActive) {
+        hipLaunchKernelGGL(decode_epoch_bump_kernel, dim3(1), dim3(1), 0, st, epoch_ctr);
+        a.epoch_ptr = epoch_ctr;
+    }
     a.n = layer->shape.n;
     a.k = layer->shape.k;
     a.rank_pad = layer->rank_pad;

@@ -396,6 +396,12 @@ __global__ __launch_bounds__(256) void lora_ortho_kernel(const float *G, int l, 
     if ((threadIdx.x & 63) == 0) atomicMax(reinterpret_cast<unsigned *>(sq + 2), __float_as_uint(mx));   // non-negative floats order as integers
 }
 
+// the four numbers of the report, out of the workspace (a kernel, so that the call is kernels only)
+__global__ void lora_report_kernel(const float *sq, float *diag)
+{
+    if (threadIdx.x < 4) diag[threadIdx.x] = threadIdx.x < 3 ? sq[threadIdx.x] : 0.f;
+}
+
 struct LoraPlan {
     int l;                      // columns of the iteration block: rank padded as the layer's adapters are
     size_t x, S, Q, Y, Z, G, B, Rt, sq, total;      // byte offsets (B: the inverses of the diagonal blocks, [l][64])
@@ -527,8 +533,8 @@ extern "C" int slim_compute_adapters(const float *W, const uint8_t *qvals, const
                        r, reinterpret_cast<half_t *>(R), sq);
     SLIM_TRY(launched());
     if (diag) {
-        const hipError_t e = hipMemcpyAsync(diag, sq, 4 * sizeof(float), hipMemcpyDeviceToDevice, st);
-        if (e != hipSuccess) return SLIM_ERR_HIP;
+        hipLaunchKernelGGL(lora_report_kernel, dim3(1), dim3(64), 0, st, (const float *)sq, diag);
+        SLIM_TRY(launched());
     }
 #undef SLIM_TRY
     return SLIM_OK;

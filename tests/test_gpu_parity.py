@@ -602,3 +602,65 @@ def test_calls_follow_the_current_stream():
         Y2 = B.slim_linear_gemm(layer, Xd)
     side.synchronize()
     assert _relerr(Y1.cpu().numpy(), Yo) <= TOL_Y and _relerr(Y2.cpu().numpy(), Yo) <= TOL_Y
+
+
+def test_forward_calls_captured_in_a_graph_replay_correctly():
+    """The forward entry points enqueue kernels only, so they can be captured into a HIP graph.
+    The one-launch decode kernel tags the pieces of T with a call number; under capture that number
+    is advanced on the device by a one-thread kernel ahead of it, so that a replay never takes the
+    previous replay's T for its own.  Several replays with different inputs, eager work and
+    synchronizations in between, each compared with the eager result and the oracle."""
+    shape_a, shape_b = _shape(640, 1024, 51), _shape(300, 2176, 37)
+    Wa, La, Ra, _ = wl.make_layer(shape_a, 1, seed=51)
+    Wb, Lb, Rb, _ = wl.make_layer(shape_b, 1, seed=52)
+    la, lb = _gpu_layer(Wa, La, Ra), _gpu_layer(Wb, Lb, Rb)
+    ra, rb = O.compress(Wa.numpy()), O.compress(Wb.numpy())
+    ws = torch.zeros(max(B.slim_workspace_bytes(la, 1), B.slim_workspace_bytes(lb, 16), B.slim_workspace_bytes(la, 64)),
+                     dtype=torch.uint8, device=DEV)
+    x1 = torch.zeros(1, shape_a.k, dtype=torch.float16, device=DEV)
+    x16 = torch.zeros(16, shape_b.k, dtype=torch.float16, device=DEV)
+    x64 = torch.zeros(64, shape_a.k, dtype=torch.float16, device=DEV)
+    y1 = torch.empty(1, shape_a.n, dtype=torch.float16, device=DEV)
+    y16 = torch.empty(16, shape_b.n, dtype=torch.float16, device=DEV)
+    y64 = torch.empty(64, shape_a.n, dtype=torch.float16, device=DEV)
+    for _ in range(2):                                       # eager calls first: the workspace has history
+        B.slim_linear_gemv(la, x1, y1, ws)
+        B.slim_linear_gemv(lb, x16, y16, ws)
+        B.slim_linear_gemm(la, x64, y64, ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.slim_linear_gemv(la, x1, y1, ws)
+        B.slim_linear_gemv(lb, x16, y16, ws)
+        B.slim_linear_gemm(la, x64, y64, ws)
+    for rep in range(4):
+        X1, X16, X64 = (wl.make_activations(m, k, seed=60 + 3 * rep + i) for i, (m, k) in
+                        enumerate([(1, shape_a.k), (16, shape_b.k), (64, shape_a.k)]))
+        x1.copy_(X1)
+        x16.copy_(X16)
+        x64.copy_(X64)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [y1.clone(), y16.clone(), y64.clone()]
+        e1 = B.slim_linear_gemv(la, x1, workspace=ws)        # the program's own eager work between replays
+        e16 = B.slim_linear_gemv(lb, x16, workspace=ws)
+        e64 = B.slim_linear_gemm(la, x64, workspace=ws)
+        torch.cuda.synchronize()
+        for g, e in zip(got, (e1, e16, e64)):
+            assert torch.equal(g, e), rep
+        assert _relerr(got[0].cpu().numpy(), O.forward(ra, La.numpy(), Ra.numpy(), X1.numpy())) <= TOL_Y
+        assert _relerr(got[1].cpu().numpy(), O.forward(rb, Lb.numpy(), Rb.numpy(), X16.numpy())) <= TOL_Y
+        assert _relerr(got[2].cpu().numpy(), O.forward(ra, La.numpy(), Ra.numpy(), X64.numpy())) <= TOL_Y
+    # replays back to back, nothing but new inputs in between: the pieces of T in the workspace are
+    # those of the previous replay when the next one starts
+    for rep in range(3):
+        X1 = wl.make_activations(1, shape_a.k, seed=80 + rep)
+        X16 = wl.make_activations(16, shape_b.k, seed=90 + rep)
+        x1.copy_(X1)
+        x16.copy_(X16)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert _relerr(y1.cpu().numpy(), O.forward(ra, La.numpy(), Ra.numpy(), X1.numpy())) <= TOL_Y
+        assert _relerr(y16.cpu().numpy(), O.forward(rb, Lb.numpy(), Rb.numpy(), X16.numpy())) <= TOL_Y
