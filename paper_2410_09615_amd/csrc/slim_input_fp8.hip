@@ -29,16 +29,15 @@ __global__ __launch_bounds__(256) void input_absmax_kernel(const half_t *__restr
     if (threadIdx.x == 0) part[blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
-// nearest value of the format (mantissa bits P, smallest normal exponent EMIN, largest value fmax), ties to even
+// nearest value of the format (mantissa bits P, smallest normal exponent EMIN, largest value fmax) to |v|, ties to even
 template <int P, int EMIN>
-__device__ __forceinline__ float fp8_round(float v, float fmax)
+__device__ __forceinline__ float fp8_round_abs(float v, float fmax)
 {
     const float a = fminf(fabsf(v), fmax);
     int e = (int)((__float_as_uint(a) >> 23) & 0xFFu) - 127;     // floor(log2 a) for a normal a; zero and tiny values fall below EMIN
     e = e > EMIN ? e : EMIN;
     const float q = __uint_as_float((uint32_t)(e - P + 127) << 23);      // spacing of the format at this magnitude
-    const float r = fminf(rintf(a / q) * q, fmax);                       // a / q is exact: a power of two
-    return copysignf(r, v);
+    return fminf(rintf(a / q) * q, fmax);                                // a / q is exact: a power of two
 }
 
 __global__ __launch_bounds__(256) void input_fp8_kernel(const half_t *__restrict__ X, size_t count, const float *part, int nparts,
@@ -57,10 +56,14 @@ __global__ __launch_bounds__(256) void input_fp8_kernel(const half_t *__restrict
         info[0] = s;
         info[1] = e5 ? 1.0f : 0.0f;
     }
+    // The sign is carried over as a bit: the product's conversion to half may be contracted into a
+    // fused multiply-add with a +0 addend, which would turn a result of -0 into +0.
     auto one = [&](half_t x) {
         const float v = (float)x / s;
-        const float r = e5 ? fp8_round<2, -14>(v, fmax) : fp8_round<3, -6>(v, fmax);
-        return (half_t)(r * s);
+        const float r = e5 ? fp8_round_abs<2, -14>(v, fmax) : fp8_round_abs<3, -6>(v, fmax);
+        const half_t h = (half_t)(r * s);
+        const uint16_t bits = (uint16_t)(__builtin_bit_cast(uint16_t, h) | (__builtin_bit_cast(uint16_t, x) & 0x8000u));
+        return __builtin_bit_cast(half_t, bits);
     };
     const size_t n8 = count / 8;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (size_t)gridDim.x * blockDim.x) {

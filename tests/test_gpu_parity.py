@@ -525,6 +525,7 @@ def test_input_quant_fp8_bit_exact(case):
         X[1, ::3] = np.float16(-0.0)                                           # signed zeros stay what they are
     else:
         X = rng.standard_normal((3, 1001)).astype(np.float16)                  # a tail that is no 16-byte piece
+        X[2, -3:] = np.array([-0.0, -6e-8, 0.0], np.float16)                   # signed zeros in that tail too
     Xq, info = B.slim_input_quant_fp8(torch.from_numpy(X).to(DEV))
     torch.cuda.synchronize()
     rq, rs, rf = O.input_quant_fp8(X)
