@@ -153,7 +153,11 @@ int slim_pack_ex(const float *W, slim_shape shape, const float *saliency, const 
  *   coarse     alpha = M i / 10, i = 1..10 (i = 10 is AbsMax);
  *   fine       21 samples of a tenth of that spacing around the best coarse one,
  *              those inside (0, M];
- *   alpha*     the first minimum over all of them (fp64 error sums).
+ *   alpha*     the first minimum over all of them (fp64 error sums).  The errors are,
+ *              up to the factor M^2, rationals with a small denominator, so two
+ *              candidates can have exactly equal errors; which of two candidates
+ *              whose errors agree to the rounding error of the sum is returned is
+ *              then decided by the order of the additions in the kernel.
  * W [n][k] fp32 in; scale_out [n] = alpha* / 7 in every row (1 for a zero
  * tensor), ready for slim_pack_ex; alpha_out (one float, may be NULL) = alpha*.
  * workspace: slim_quant_workspace_bytes (HOST out-pointer), need not be zeroed.

@@ -328,26 +328,65 @@ def quant_error(counts: np.ndarray, M, alpha: float) -> float:
     return float(np.dot(counts.astype(np.float64), err * err))
 
 
-def quant_search(W: np.ndarray):
-    """alpha* of Alg. 1: the error at 10 uniform samples alpha = M i / 10, i = 1..10
-    (the last one is AbsMax), then at 21 samples of a tenth of that spacing around
-    the best one (those inside (0, M]); the first minimum wins.  Returns
-    (alpha float32, scale float32 = alpha / 7 in binary32, or 1 for a zero tensor)."""
+def quant_search_candidates(W: np.ndarray, coarse_pick=None):
+    """The candidates of Alg. 1 in the order they are tried, and their errors:
+    10 uniform samples alpha = M i / 10, i = 1..10 (the last one is AbsMax), then 21
+    samples of a tenth of that spacing around the best one (those inside (0, M]).
+    `coarse_pick` puts the fine samples around that coarse candidate instead (0..9;
+    for the treatment of ties only).  Returns (candidates, errors), lists of float;
+    empty for a zero tensor."""
     counts, M = quant_histogram(W)
     if M == 0:
-        return np.float32(0.0), np.float32(1.0)
+        return [], []
     eta = float(M) / 10.0
     cand = [eta * i for i in range(1, 11)]
     errs = [quant_error(counts, M, a) for a in cand]
-    lo = cand[int(np.argmin(errs))]
+    lo = cand[int(np.argmin(errs)) if coarse_pick is None else coarse_pick]
     for j in range(-10, 11):
         a = lo + eta * (j / 10.0)
         if 0.0 < a <= float(M):
             cand.append(a)
             errs.append(quant_error(counts, M, a))
+    return cand, errs
+
+
+def quant_search(W: np.ndarray):
+    """alpha* of Alg. 1: the first minimum of the error over quant_search_candidates.
+    Returns (alpha float32, scale float32 = alpha / 7 in binary32, or 1 for a zero
+    tensor).
+
+    The errors are sums of up to 20000 non-negative binary64 terms.  With alpha / M a
+    multiple of 1/100 and the bin centres multiples of M / 2B they are, up to the
+    factor M^2, rationals with a small common denominator, so two candidates CAN have
+    exactly equal errors; which of them a binary64 evaluation calls smaller then
+    depends on the order of its additions.  A caller comparing another
+    implementation against this one has to accept any candidate whose error is
+    within that rounding error of the minimum (tests: quant_search_accepts)."""
+    cand, errs = quant_search_candidates(W)
+    if not cand:
+        return np.float32(0.0), np.float32(1.0)
     alpha = np.float32(cand[int(np.argmin(errs))])
     return alpha, np.float32(alpha / np.float32(7.0))
 
+
+def quant_search_accepts(W: np.ndarray, alpha, rel: float = 1e-12) -> bool:
+    """True if `alpha` (binary32) is what Alg. 1 can return for W when errors closer
+    than `rel` (relative; the rounding error of a sum of 20000 binary64 terms is below
+    5e-12, of 512 terms below 2e-13) count as equal: a candidate whose error is within
+    `rel` of the smallest one, on the fine grid around a coarse candidate that is
+    itself within `rel` of the best coarse one.  A zero tensor accepts alpha = 0 only."""
+    cand, errs = quant_search_candidates(W)
+    if not cand:
+        return float(alpha) == 0.0
+    coarse_best = min(errs[:10])
+    for c in range(10):
+        if errs[c] > coarse_best * (1.0 + rel):
+            continue
+        cv, ev = quant_search_candidates(W, coarse_pick=c)
+        best = min(ev)
+        if any(np.float32(a) == np.float32(alpha) and e <= best * (1.0 + rel) for a, e in zip(cv, ev)):
+            return True
+    return False
 
 
 def quant_search_rows(W: np.ndarray):

@@ -176,3 +176,73 @@ def test_rows_search_never_worse_than_absmax_per_row_on_its_histogram():
         assert counts.shape[0] == 512 and counts.sum() == 4096
         assert O.quant_error(counts, M, float(alpha[o])) <= O.quant_error(counts, M, float(M))
         assert alpha[o] < M                                   # the outlier is clipped
+
+
+def _row_with_two_equal_minima():
+    """A row of 4560 heavy-tailed weights (seeded, numpy only) whose errors at
+    alpha = 0.18 M and 0.19 M are the same rational number."""
+    rng = np.random.default_rng(105)
+    for _ in range(21):                                      # the generator's state is what matters
+        n = int(rng.integers(1, 900))
+        k = 8 * int(rng.integers(1, 700))
+        dist = rng.integers(0, 3)
+        W = (rng.standard_normal((n, k)) * 0.02 if dist == 0 else rng.standard_t(3, size=(n, k)) if dist == 1
+             else np.round(rng.standard_normal((n, k)) * 2) / 4).astype(np.float32)
+        rng.uniform(0, 3, size=k)
+        rng.choice([1.0, 50.0, 3000.0])
+    return W[426]
+
+
+def test_candidates_can_tie_exactly_and_both_are_accepted():
+    """alpha / M is a multiple of 1/100 and the bin centres are odd multiples of M / 2B, so
+    the error over M^2 is a rational with a small denominator, and two candidates can
+    have the same error exactly.  Which one a binary64 sum calls smaller depends on the
+    order of its additions: quant_search_accepts takes both and nothing else."""
+    from fractions import Fraction as F
+    w = _row_with_two_equal_minima()
+    counts, M = O.quant_histogram(w)
+    B = counts.shape[0]
+
+    def exact(num):                                          # error / M^2 at alpha = M num / 100
+        a = F(num, 100)
+        step = a / 7
+        e = F(0)
+        for b in np.nonzero(counts)[0]:
+            x = F(2 * int(b) + 1, 2 * B)
+            d = (round(x / step) * step - x) if x <= a else a - x       # round(): half to even, as rint
+            e += int(counts[b]) * d * d
+        return e
+
+    errs = {num: exact(num) for num in range(10, 31)}        # the fine grid around 0.2 M
+    assert errs[18] == errs[19] == min(errs.values())
+    assert sorted(errs.values())[2] > errs[18]
+    # the binary64 errors of the two agree to rounding, and are what the rational says
+    cand, e64 = O.quant_search_candidates(w)
+    eta = float(M) / 10.0
+    i18 = cand.index(2 * eta + eta * (-2 / 10.0))
+    i19 = cand.index(2 * eta + eta * (-1 / 10.0))
+    assert abs(e64[i18] - e64[i19]) <= 4e-16 * 512 * e64[i18]
+    assert abs(e64[i18] - float(errs[18]) * float(M) ** 2) <= 1e-12 * e64[i18]
+    alpha, _ = O.quant_search(w)
+    assert alpha in (np.float32(cand[i18]), np.float32(cand[i19]))
+    assert O.quant_search_accepts(w, np.float32(cand[i18])) and O.quant_search_accepts(w, np.float32(cand[i19]))
+    for i, a in enumerate(cand):
+        if i not in (i18, i19) and np.float32(a) not in (np.float32(cand[i18]), np.float32(cand[i19])):
+            assert not O.quant_search_accepts(w, np.float32(a))
+    assert not O.quant_search_accepts(w, np.float32(cand[i18] * 1.0001))           # not a candidate at all
+
+
+def test_accepts_is_the_search_itself_where_nothing_ties():
+    rng = np.random.default_rng(33)
+    for _ in range(20):
+        w = rng.standard_normal((3, 700)).astype(np.float32)
+        cand, errs = O.quant_search_candidates(w)
+        alpha, _ = O.quant_search(w)
+        srt = sorted(errs)
+        if srt[1] <= srt[0] * (1 + 1e-9) and errs.count(srt[0]) == 1:
+            continue                                         # a near tie of different candidates: not this test
+        assert O.quant_search_accepts(w, alpha)
+        ok = [np.float32(a) for a in cand if O.quant_search_accepts(w, np.float32(a))]
+        assert set(ok) == {alpha}
+    assert O.quant_search_accepts(np.zeros((2, 64), np.float32), np.float32(0.0))
+    assert not O.quant_search_accepts(np.zeros((2, 64), np.float32), np.float32(1.0))
