@@ -236,6 +236,8 @@ int slim_pack_adapters(const slim_half *L, const slim_half *R, slim_shape shape,
  * the adapter bytes); slim_linear_gemm expands them to fp16 in the workspace
  * first.  slim_unpack_adapters_q4 returns codes int8 [rows][cols] and scales
  * fp16 [rows][ceil(cols / 128)], row-major (tests, inspection).
+ * slim_pack_adapters_q4 requires k % 128 == 0, as the forward calls do (SHAPE
+ * otherwise); n and rank are free.
  */
 int slim_adapter_q4_sizes(int32_t rows, int32_t cols, size_t *codes_bytes, size_t *scales_bytes);
 int slim_pack_adapters_q4(const slim_half *L, const slim_half *R, slim_shape shape, uint8_t *Lq,
