@@ -297,6 +297,45 @@ def main():
                  "TFLOPs": round(ca_flops / ms_ca * 1e-9, 2), "bound": "mfma", "dtype": "f32",
                  "roofline_frac": round(ca_flops / ms_ca * 1e-9 / 157.3, 4)})
     del wcopies
+    # slim_pack_adapters_q4: the layer's fp16 adapters to 4-bit group-128 codes + fp16 scales (Sec. 3.3)
+    Ld, Rd = rot.L_host.to(dev), rot.R_host.to(dev)
+    for _ in range(3):
+        B.slim_pack_adapters_q4(Ld, Rd)
+    ms_q4 = event_time_ms(lambda i: B.slim_pack_adapters_q4(Ld, Rd), 30)
+    q4b = shape.r * (shape.n + shape.k) * (2 + 0.5) + 2 * (shape.n * ((shape.r + 127) // 128) + shape.r * (shape.k // 128))
+    legs.append({"shape": shape.name, "entry": "slim_pack_adapters_q4", "us": round(ms_q4 * 1e3, 2),
+                 "GBps": round(q4b / ms_q4 * 1e-6, 1), "bound": "hbm",
+                 "roofline_frac": round(q4b / ms_q4 * 1e-6 / HBM_PEAK_GBPS, 4), "note": "cache-resident inputs"})
+    # slim_lowrank alone: Y = (X R^T) L^T on this layer's adapters, decode and prefill shaped
+    for m_lr, iters in ((16, 100), (2048, 20)):
+        Xl = wl.make_activations(m_lr, shape.k, seed=3).to(dev)
+        Yl = torch.empty(m_lr, shape.n, dtype=torch.float16, device=dev)
+        wsl = B.alloc_workspace(rot.base, m_lr)
+        call = lambda i: B.slim_lowrank(Xl, rot.base.R, rot.base.L, shape.n, shape.r, Yl, False, wsl)
+        for i in range(5):
+            call(i)
+        ms_lr = event_time_ms(call, iters)
+        lr_bytes = 2 * shape.r * (shape.n + shape.k) + 2 * m_lr * (shape.n + shape.k)
+        lr_flops = 2.0 * m_lr * shape.r * (shape.n + shape.k)
+        rec = {"shape": shape.name, "entry": "slim_lowrank", "tokens": m_lr, "us": round(ms_lr * 1e3, 2),
+               "GBps": round(lr_bytes / ms_lr * 1e-6, 1), "TFLOPs": round(lr_flops / ms_lr * 1e-9, 2),
+               "note": "cache-resident adapters"}
+        if m_lr <= 16:
+            rec.update({"bound": "hbm", "roofline_frac": round(lr_bytes / ms_lr * 1e-6 / HBM_PEAK_GBPS, 4)})
+        else:
+            rec.update({"bound": "mfma", "roofline_frac": round(lr_flops / ms_lr * 1e-9 / MFMA_PEAK_TFLOPS, 4)})
+        legs.append(rec)
+        del Xl, Yl, wsl
+    # slim_input_quant_fp8 on a prefill-sized input (2048 tokens): reads X twice, writes it once
+    Xf = [wl.make_activations(2048, shape.k, seed=30 + c).to(dev) for c in range(4)]
+    for i in range(4):
+        B.slim_input_quant_fp8(Xf[i % 4])
+    ms_f8 = event_time_ms(lambda i: B.slim_input_quant_fp8(Xf[i % 4]), 40)
+    f8b = 3 * 2 * 2048 * shape.k
+    legs.append({"shape": f"X 2048 x {shape.k}", "entry": "slim_input_quant_fp8", "us": round(ms_f8 * 1e3, 2),
+                 "GBps": round(f8b / ms_f8 * 1e-6, 1), "bound": "hbm",
+                 "roofline_frac": round(f8b / ms_f8 * 1e-6 / HBM_PEAK_GBPS, 4), "note": "cache-resident inputs"})
+    del Xf, Ld, Rd
 
     # ---------------- CPU oracle baseline (rank 0 = this process) ----------------
     cpu_baseline = None

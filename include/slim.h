@@ -314,7 +314,11 @@ int slim_linear_gemm(const slim_layer *layer, const slim_half *X, int32_t m, sli
  * "Rank Analysis"):  Y = (X R^T) L^T  or, with accumulate != 0,  Y += ...
  * L, R as in slim_layer (adapter layout); shape.rank >= 1;
  * k % 128 == 0.  In accumulate mode Y is read as fp16, added to in fp32 and
- * rounded back once.
+ * rounded back once.  Up to 16 tokens the call is slim_linear_gemv's kernel
+ * without the packed term (one launch where that geometry fits), above that
+ * two dense matrix-core products with T = X R^T rounded to fp16 in between.
+ * Workspace as for the forward calls (slim_workspace_bytes of a layer of this
+ * shape).
  */
 int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, const slim_half *L,
                  slim_shape shape, int32_t rank_pad, slim_half *Y, int accumulate,

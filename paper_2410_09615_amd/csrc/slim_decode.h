@@ -56,7 +56,8 @@ struct FusedPlan {
 FusedPlan plan_fused(int n, int k, int rank_pad, int m);
 // mode 2: one launch; mode 1: the two roles as two launches
 // err, epoch_ctr: two control words of the workspace (error flag; call counter used under stream capture)
+// lowrank 1, 2: the low-rank term alone on the layer's fp16 adapters (packed buffers not read); 2 adds to Y
 int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t *Y, void *T, unsigned *err, unsigned *epoch_ctr,
-                        const FusedPlan &p, int mode, hipStream_t st);
+                        const FusedPlan &p, int mode, hipStream_t st, int lowrank = 0);
 
 }  // namespace slim

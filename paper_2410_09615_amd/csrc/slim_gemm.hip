@@ -185,8 +185,8 @@ int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *s
                        const half_t *T, half_t *Y, int n, int k, int rank_pad, int m,
                        hipStream_t st);   // slim_gemm_sparse.hip
 
-int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t *L, int n, int k, int rank_pad,
-                          half_t *Y, int accumulate, float *T, unsigned *counter, hipStream_t st);   // slim_gemv.hip
+int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t *L, int n, int k, int rank, int rank_pad,
+                          half_t *Y, int accumulate, float *T, void *T16, unsigned *ctrl, hipStream_t st);   // slim_gemv.hip
 
 }  // namespace slim
 
@@ -256,8 +256,8 @@ extern "C" int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, c
     const half_t *Lh = reinterpret_cast<const half_t *>(L);
     half_t *Yh = reinterpret_cast<half_t *>(Y);
     if (m <= 16)
-        return launch_lowrank_decode(Xh, m, Rh, Lh, shape.n, shape.k, rank_pad, Yh, accumulate,
-                                     reinterpret_cast<float *>(ws + p.dec_off + 256),
+        return launch_lowrank_decode(Xh, m, Rh, Lh, shape.n, shape.k, shape.rank, rank_pad, Yh, accumulate,
+                                     reinterpret_cast<float *>(ws + p.dec_off + 256), ws + p.t16_off,
                                      reinterpret_cast<unsigned *>(ws + p.dec_off), st);
 
     if ((uint64_t)shape.n * (uint64_t)rank_pad * 2 > 0xFFFFFFFFull) return SLIM_ERR_SHAPE;

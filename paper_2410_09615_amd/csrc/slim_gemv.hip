@@ -545,9 +545,24 @@ static void fill_plan(DecodeArgs &a, const DecodePlan &p)
     a.slots = p.slots;
 }
 
-int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t *L, int n, int k, int rank_pad,
-                          half_t *Y, int accumulate, float *T, unsigned *ctrl, hipStream_t st)
+// The one-launch kernel without its packed items where the geometry allows it (SLIM_DECODE_PATH =
+// parts keeps the two-part kernels, as for slim_linear_gemv); T16: the one-launch path's pieces of T.
+int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t *L, int n, int k, int rank, int rank_pad,
+                          half_t *Y, int accumulate, float *T, void *T16, unsigned *ctrl, hipStream_t st)
 {
+    {
+        const FusedPlan f = plan_fused(n, k, rank_pad, m);
+        const char *env = getenv("SLIM_DECODE_PATH");
+        if (f.ok && f.n_r > 0 && !(env && !strcmp(env, "parts"))) {
+            slim_layer lay{};
+            lay.shape = slim_shape{n, k, rank};
+            lay.L = reinterpret_cast<const slim_half *>(L);
+            lay.R = reinterpret_cast<const slim_half *>(R);
+            lay.rank_pad = rank_pad;
+            lay.adapter_bits = 16;
+            return launch_decode_fused(&lay, X, m, Y, T16, ctrl + 2, ctrl + 3, f, 2, st, accumulate ? 2 : 1);
+        }
+    }
     DecodePlan p = plan_decode(n, k, rank_pad, m);
     DecodeArgs a{};
     a.R = R;

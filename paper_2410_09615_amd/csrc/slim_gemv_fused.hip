@@ -78,7 +78,8 @@ struct FusedArgs {
     int kh;              // shares of the inputs in the R role = planes of T
     int upk;             // units of 256 inputs per share
     int helpers;         // wavefronts of a workgroup that only fetch T (Y role)
-    int mode;            // 0: R role only; 1: Y role only, T complete; 2: both roles in this grid
+    int mode;            // 0: R role only; 1: Y role only, T complete; 2: both roles in this grid;
+                         // + 4 (low-rank term alone, both roles): add to what Y holds
 };
 
 // The number that tags this call's pieces of T.  A launch argument normally; a launch that is
@@ -206,7 +207,9 @@ __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb
 }
 
 // ---- Y role ----
-template <bool Q4>
+// LR: the low-rank term alone (slim_lowrank): no packed items, no X in LDS, no row
+// scales; the barrier sequence is that of a layer whose X is one chunk.
+template <bool Q4, bool LR = false>
 __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, int ygrid)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -224,7 +227,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
                                          // operand read row 0 and their results are not stored
     const int ldx = a.kc + kLdsPad;
     const int ldt = rp + kLdsPad;
-    const int nch = a.nch;
+    const int nch = LR ? 1 : a.nch;
     // LDS: one X buffer, then T, then the partial results; with chunks: two X
     // buffers, T takes the place of the buffer that is free during the last chunk
     half_t *x_lds = lds;
@@ -237,7 +240,8 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     const int steps = rp / 32;                   // steps of 32 ranks
     // halves of this wavefront per chunk: s, s + S, ... < hc (with chunks S divides hc: the same for all)
     const int hpc = s < hc ? (hc - s + S - 1) / S : 0;
-    const int ipc = (hpc + 1) / 2;               // items (of two halves) per chunk
+    const int ipc = LR ? 0 : (hpc + 1) / 2;      // items (of two halves) per chunk
+    const int ipd = LR ? 1 : ipc;                // as a divisor (no packed items: never used)
     // rank work of this wavefront: steps of 32 ranks s, s + S, ... (fp16), or units of 256 ranks (4-bit)
     const int units_l = (int)q4_ctiles(rp);
     const int cnt_l = Q4 ? (s < units_l ? (units_l - s + S - 1) / S : 0) : (s < steps ? (steps - s + S - 1) / S : 0);
@@ -261,7 +265,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     auto issue_item = [&](int ot, int j, UnitRegs &b) {
         const uint32_t o = 16u * ot + lx;
         if (j < nP) {
-            const int c = j / ipc, jj = j - c * ipc;        // chunk, item within the chunk
+            const int c = j / ipd, jj = j - c * ipd;        // chunk, item within the chunk
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
                 const int hl = s + S * (2 * jj + x);        // half within the chunk
@@ -351,7 +355,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
                         x_rs, (__attribute__((address_space(3))) void *)(dst + row * ldx + seg * 512), 16, (int)off, 0, 0, 0);
                 }
             };
-            stage_chunk(0);
+            if constexpr (!LR) stage_chunk(0);
             if (nch > 1) {
                 stage_chunk(1);
                 // chunk 0 is complete when at most the loads of chunk 1 are outstanding;
@@ -457,7 +461,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
             acc1 = acc0;
             // row scales of this lane's four outputs: needed when the packed items are done
             sc4 = acc0;
-            if (ot < wtiles) {
+            if (!LR && ot < wtiles) {
                 if (vec) {
                     sc4 = *reinterpret_cast<const float4_t *>(a.scale + ob);
                 } else {
@@ -477,7 +481,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
             }
         }
         if (j < nP) {
-            const int c = j / ipc, jj = j - c * ipc;
+            const int c = j / ipd, jj = j - c * ipd;
             if (c > 0 && jj == 0) __syncthreads();     // chunk c is in LDS; everybody has left chunk c - 1
             const half_t *xc = xrow_packed + (c & 1) * xbuf;
             const int h0 = min(s + S * (2 * jj), hc - 1), h1 = min(s + S * (2 * jj + 1), hc - 1);
@@ -538,12 +542,17 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
         if (s == 0 && lx < a.m && ot < wtiles) {
             half_t *yp = a.Y + (size_t)lx * a.n + ob;
             if (vec) {
+                if (LR && (a.mode & 4)) {
+                    const half4_t old = *reinterpret_cast<const half4_t *>(yp);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) y[v] += (float)old[v];
+                }
                 const half4_t h = {(half_t)y[0], (half_t)y[1], (half_t)y[2], (half_t)y[3]};
                 *reinterpret_cast<half4_t *>(yp) = h;
             } else {
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    if (ob + v < a.n) yp[v] = (half_t)y[v];
+                    if (ob + v < a.n) yp[v] = (half_t)(LR && (a.mode & 4) ? y[v] + (float)yp[v] : y[v]);
             }
         }
         if (S > 1 && r + 1 < rounds) __syncthreads();      // the partial sums are read before the next round writes
@@ -563,18 +572,18 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     }
 }
 
-template <bool Q4>
+template <bool Q4, bool LR = false>
 __global__ __launch_bounds__(kFusedMaxThreads, kFusedWavesPerSimd) void decode_fused_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) half_t lds[];
     if (a.mode == 0) {
         role_r<Q4>(a, lds, blockIdx.x);
     } else if (a.mode == 1) {
-        role_y<Q4>(a, lds, blockIdx.x, gridDim.x);
+        role_y<Q4, LR>(a, lds, blockIdx.x, gridDim.x);
     } else if ((int)blockIdx.x < a.n_r) {
         role_r<Q4>(a, lds, blockIdx.x);
     } else {
-        role_y<Q4>(a, lds, (int)blockIdx.x - a.n_r, (int)gridDim.x - a.n_r);
+        role_y<Q4, LR>(a, lds, (int)blockIdx.x - a.n_r, (int)gridDim.x - a.n_r);
     }
 }
 
@@ -668,9 +677,11 @@ FusedPlan plan_fused(int n, int k, int rank_pad, int m)
 
 static std::atomic<unsigned> g_epoch{0};
 
-// mode: 2 = one launch, 1 = the two roles as two launches
-int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t *Y, void *T, unsigned *err, unsigned *epoch_ctr, const FusedPlan &p, int mode, hipStream_t st)
+// mode: 2 = one launch, 1 = the two roles as two launches.  lowrank: 0 = the layer; 1, 2 = the
+// low-rank term alone on the layer's fp16 adapters (its packed buffers are not read), 2 adds to Y.
+int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t *Y, void *T, unsigned *err, unsigned *epoch_ctr, const FusedPlan &p, int mode, hipStream_t st, int lowrank)
 {
+    if (lowrank && (layer->adapter_bits == 4 || p.n_r == 0)) return SLIM_ERR_SHAPE;
     FusedArgs a{};
     a.qvals = layer->qvals;
     a.meta = layer->meta;
@@ -710,13 +721,15 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
     const dim3 blk((p.waves + p.helpers) * kWave);
     const bool q4 = layer->adapter_bits == 4 && p.n_r > 0;
     auto launch = [&](unsigned grid) {
-        if (q4)
+        if (lowrank)
+            hipLaunchKernelGGL((decode_fused_kernel<false, true>), dim3(grid), blk, p.lds, st, a);
+        else if (q4)
             hipLaunchKernelGGL(decode_fused_kernel<true>, dim3(grid), blk, p.lds, st, a);
         else
             hipLaunchKernelGGL(decode_fused_kernel<false>, dim3(grid), blk, p.lds, st, a);
     };
     if (mode == 2 || p.n_r == 0) {
-        a.mode = p.n_r == 0 ? 1 : 2;
+        a.mode = p.n_r == 0 ? 1 : (lowrank == 2 ? 6 : 2);
         launch((unsigned)(p.n_r + p.ygrid));
     } else {
         a.mode = 0;

@@ -103,6 +103,25 @@ def test_unpack_arbitrary_valid_bytes():
     assert np.array_equal(codes.cpu().numpy(), rc) and np.array_equal(mask.cpu().numpy(), rm)
 
 
+@pytest.mark.parametrize("n,k,r,m", [(4096, 4096, 410, 16), (4096, 4096, 410, 1), (1000, 11008, 130, 5), (33, 256, 1, 16),
+                                     (28672, 8192, 820, 16)])
+def test_lowrank_decode_shapes(n, k, r, m):
+    """The low-rank term alone on layers of the configured sizes (several rounds of row tiles, X in
+    chunks, a rank of 1), plain and accumulating, on one workspace."""
+    L, R = wl.make_adapters(n, k, r, 41, 42)
+    X = wl.make_activations(m, k, True, 43, 44)
+    Lp, Rp = B.slim_pack_adapters(L.to(DEV), R.to(DEV))
+    ref = O.xr(X.numpy(), R.numpy()) @ L.numpy().astype(np.float64).T
+    tmp = B.SlimLayer(n, k, r, B.slim_rank_pad(r), Lp, Lp, Lp, Lp, Rp)
+    ws = B.alloc_workspace(tmp, m)
+    Y = B.slim_lowrank(X.to(DEV), Rp, Lp, n, r, workspace=ws)
+    torch.cuda.synchronize()
+    assert _relerr(Y.cpu().numpy(), ref) <= TOL_Y
+    Y2 = B.slim_lowrank(X.to(DEV), Rp, Lp, n, r, Y=Y.clone(), accumulate=True, workspace=ws)
+    torch.cuda.synchronize()
+    assert _relerr(Y2.cpu().numpy(), ref + Y.cpu().numpy().astype(np.float64)) <= TOL_Y
+
+
 def test_lowrank_several_row_tiles():
     n, k, r, m = 1100, 1280, 100, 300
     L, R = wl.make_adapters(n, k, r, 31, 32)
@@ -490,7 +509,14 @@ def test_q4_adapters_change_the_result_as_much_as_the_quantization_says():
 
 @pytest.mark.parametrize("m", [1, 16, 300])
 @pytest.mark.parametrize("accumulate", [False, True])
-def test_lowrank(m, accumulate):
+@pytest.mark.parametrize("path", ["auto", "parts"])
+def test_lowrank(m, accumulate, path, monkeypatch):
+    """Up to 16 tokens the call is the one-launch decode kernel without its packed items; "parts"
+    keeps the two-part kernels that serve where that geometry does not fit."""
+    if path == "parts":
+        if m > 16:
+            pytest.skip("the decode paths differ up to 16 tokens only")
+        monkeypatch.setenv("SLIM_DECODE_PATH", "parts")
     n, k, r = 640, 1280, 51
     L, R = wl.make_adapters(n, k, r, 21, 22)
     X = wl.make_activations(m, k, True, 23, 24)
