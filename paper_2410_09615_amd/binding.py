@@ -241,13 +241,22 @@ def slim_compute_adapters(W: torch.Tensor, qvals, meta, scale, rank: int, x_tild
     return L, R, diag
 
 
-def slim_input_quant_fp8(X: torch.Tensor):
+def slim_input_quant_fp8(X: torch.Tensor, Xq=None, info=None, workspace=None):
     """FP8 AbsMax quantization of an input tensor, values back on the fp16 grid:
-    (Xq fp16 like X, info fp32 [2] = scale, format (0: E4M3, 1: E5M2))."""
+    (Xq fp16 like X, info fp32 [2] = scale, format (0: E4M3, 1: E5M2)).  Xq, info and a
+    workspace of at least 1024 bytes may be passed in (a caller in a loop)."""
     _dev(X, torch.float16, "X")
-    Xq = torch.empty_like(X)
-    info = torch.empty(2, dtype=torch.float32, device=X.device)
-    ws = torch.empty(1024, dtype=torch.uint8, device=X.device)
+    if Xq is None:
+        Xq = torch.empty_like(X)
+    elif Xq.dtype != torch.float16 or Xq.numel() != X.numel() or Xq.device != X.device or not Xq.is_contiguous():
+        raise ValueError("Xq must be contiguous float16 with X's size on X's device")
+    if info is None:
+        info = torch.empty(2, dtype=torch.float32, device=X.device)
+    elif info.dtype != torch.float32 or info.numel() < 2 or info.device != X.device:
+        raise ValueError("info must be float32 [2] on X's device")
+    ws = workspace if workspace is not None else torch.empty(1024, dtype=torch.uint8, device=X.device)
+    if ws.device != X.device:
+        raise ValueError("workspace must be on X's device")
     _check("slim_input_quant_fp8", lib().slim_input_quant_fp8(_ptr(X), X.numel(), _ptr(Xq), _ptr(info), _ptr(ws), ws.numel(),
                                                               _stream(X)))
     return Xq, info

@@ -16,13 +16,24 @@ __global__ __launch_bounds__(256) void input_absmax_kernel(const half_t *__restr
     __shared__ float red[4];
     const size_t n8 = count / 8;
     float a = 0.f;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (size_t)gridDim.x * blockDim.x) {
-        const half8_t v = reinterpret_cast<const half8_t *>(X)[i];
+    // four independent loads per lane and round: the grid is small (one partial per workgroup)
+    const half8_t *X8 = reinterpret_cast<const half8_t *>(X);
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    auto take = [&](const half8_t &v) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf((float)v[e]));
+    };
+    for (; i + 3 * stride < n8; i += 4 * stride) {
+        const half8_t v0 = X8[i], v1 = X8[i + stride], v2 = X8[i + 2 * stride], v3 = X8[i + 3 * stride];
+        take(v0);
+        take(v1);
+        take(v2);
+        take(v3);
     }
+    for (; i < n8; i += stride) take(X8[i]);
     if (blockIdx.x == 0)
-        for (size_t i = n8 * 8 + threadIdx.x; i < count; i += blockDim.x) a = fmaxf(a, fabsf((float)X[i]));
+        for (size_t t = n8 * 8 + threadIdx.x; t < count; t += blockDim.x) a = fmaxf(a, fabsf((float)X[t]));
     a = wave_max(a);
     if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = a;
     __syncthreads();
@@ -37,7 +48,8 @@ __device__ __forceinline__ float fp8_round_abs(float v, float fmax)
     int e = (int)((__float_as_uint(a) >> 23) & 0xFFu) - 127;     // floor(log2 a) for a normal a; zero and tiny values fall below EMIN
     e = e > EMIN ? e : EMIN;
     const float q = __uint_as_float((uint32_t)(e - P + 127) << 23);      // spacing of the format at this magnitude
-    return fminf(rintf(a / q) * q, fmax);                                // a / q is exact: a power of two
+    const float qinv = __uint_as_float((uint32_t)(P - e + 127) << 23);   // 1 / q, a power of two as well: a * qinv = a / q exactly
+    return fminf(rintf(a * qinv) * q, fmax);
 }
 
 __global__ __launch_bounds__(256) void input_fp8_kernel(const half_t *__restrict__ X, size_t count, const float *part, int nparts,
