@@ -276,7 +276,14 @@ extern "C" int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, c
         g.m = m - t0 < chunk ? m - t0 : chunk;
         g.B = T + (size_t)t0 * rank_pad;
         g.Y = Yh + (size_t)t0 * shape.n;
-        launch_dense<4>(g, 1, st);
+        // the tallest row tile that still gives every compute unit a workgroup
+        const long tt = (g.m + 127) / 128;
+        if ((long)((shape.n + 511) / 512) * tt >= 256)
+            launch_dense<4>(g, 1, st);
+        else if ((long)((shape.n + 255) / 256) * tt >= 256)
+            launch_dense<2>(g, 1, st);
+        else
+            launch_dense<1>(g, 1, st);
     }
     return hip_status(hipGetLastError());
 }
