@@ -272,8 +272,8 @@ int slim_unpack(const uint8_t *qvals, const uint8_t *meta, slim_shape shape, int
 int slim_workspace_bytes(const slim_layer *layer, int32_t m, size_t *bytes);
 
 /*
- * slim_linear_gemv -- decode-shaped forward, 1 <= m <= 16 tokens (the paper's
- * "small batch sizes during decoding", Sec. 4 "Speedup").  Streams the packed
+ * slim_linear_gemv -- decode-shaped forward, 1 <= m <= 16 tokens (decoding runs
+ * on small batches: Sec. 4 "Speedup").  Streams the packed
  * rows and the adapters once; fp16 inputs, fp32 accumulation, Y rounded once
  * to fp16.  X [m][k] fp16 in, Y [m][n] fp16 out.
  * One kernel launch where m rows of X and T fit the LDS of a compute unit

@@ -209,11 +209,23 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const float *__restrict
             auto eval = [&](int c, double alpha, bool ok, int j, int G) {
                 double e = 0.0;
                 if (ok) {
-                    const double step = alpha / 7.0, width = M / B;
+                    // rint(x / step) without the binary64 division wherever that cannot change the result:
+                    // x * (1 / step) is within a few ulp of the quotient (at most 700), so the two round to the
+                    // same integer unless the product lies within 1e-9 of a half; there the quotient decides.
+                    // Empty bins add an exact zero and are skipped.
+                    const double step = alpha / 7.0, width = M / B, inv_step = 1.0 / step;
                     for (int b = j; b < B; b += G) {
+                        const unsigned cnt = hist[b];
+                        if (cnt == 0u) continue;
                         const double x = ((double)b + 0.5) * width;
-                        const double d = x <= alpha ? rint(x / step) * step - x : alpha - x;
-                        e += (double)hist[b] * (d * d);
+                        double d = alpha - x;
+                        if (x <= alpha) {
+                            const double q = x * inv_step;
+                            double r = rint(q);
+                            if (fabs(q - r) > 0.5 - 1e-9) r = rint(x / step);
+                            d = r * step - x;
+                        }
+                        e += (double)cnt * (d * d);
                     }
                 }
                 for (int off = G / 2; off >= 1; off >>= 1) e += __shfl_xor(e, off, kWave);
