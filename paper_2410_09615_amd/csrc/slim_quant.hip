@@ -85,8 +85,22 @@ __global__ __launch_bounds__(1024) void quant_hist_kernel(const float *__restric
             const int b = (int)floorf(fabsf(w) * inv);
             atomicAdd(&hist[b < B - 1 ? b : B - 1], 1u);
         };
-        for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < numel4; i += (size_t)gridDim.x * blockDim.x) {
-            const float4 v = reinterpret_cast<const float4 *>(W)[i];
+        const float4 *W4 = reinterpret_cast<const float4 *>(W);
+        const size_t stride = (size_t)gridDim.x * blockDim.x;
+        size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+        for (; i + stride < numel4; i += 2 * stride) {       // two loads in flight per lane
+            const float4 v = W4[i], u = W4[i + stride];
+            put(v.x);
+            put(v.y);
+            put(v.z);
+            put(v.w);
+            put(u.x);
+            put(u.y);
+            put(u.z);
+            put(u.w);
+        }
+        if (i < numel4) {
+            const float4 v = W4[i];
             put(v.x);
             put(v.y);
             put(v.z);
@@ -288,7 +302,10 @@ extern "C" int slim_quant_search(const float *W, slim_shape shape, float *scale_
     const unsigned grid_a = (unsigned)(g < (size_t)kMaxBlocks ? g : (size_t)kMaxBlocks);
     float *bmax = reinterpret_cast<float *>(q.counts + B);
     g = (numel4 + 1023) / 1024;
-    const unsigned grid_h = (unsigned)(g < 512 ? g : 512);
+    // every workgroup ends with one global add per non-empty bin of its own histogram: few workgroups
+    // (one per compute unit; half of that below 2^25 elements, where those adds outweigh the reading)
+    const size_t hcap = numel < ((size_t)1 << 25) ? 128 : 256;
+    const unsigned grid_h = (unsigned)(g < hcap ? g : hcap);
     hipLaunchKernelGGL(quant_absmax_kernel, dim3(grid_a), dim3(256), 0, st, W, numel4, bmax, q.mbits, 128 + B);
     hipLaunchKernelGGL(quant_hist_kernel, dim3(grid_h), dim3(1024), (size_t)B * 4, st, W, numel4, B, bmax, (int)grid_a, q.mbits,
                        q.counts);
