@@ -188,6 +188,7 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const float *__restrict
 {
     extern __shared__ unsigned hist[];
     __shared__ double err[kCoarse + kFine];
+    __shared__ double psum[(kCoarse + kFine) * 24];
     __shared__ float part[4];
     const int k4 = k / 4;
     for (int row = blockIdx.x; row < n; row += gridDim.x) {
@@ -242,12 +243,18 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const float *__restrict
                         e += (double)cnt * (d * d);
                     }
                 }
-                for (int off = G / 2; off >= 1; off >>= 1) e += __shfl_xor(e, off, kWave);
-                if (j == 0 && c < kCoarse + kFine) err[c] = ok ? e : __builtin_inf();
+                // the G partial sums of a candidate are added up in lane order by its first lane
+                if (c < kCoarse + kFine) psum[c * 24 + j] = e;
+                __syncthreads();
+                if (j == 0 && c < kCoarse + kFine) {
+                    double t = 0.0;
+                    for (int i = 0; i < G; ++i) t += psum[c * 24 + i];
+                    err[c] = ok ? t : __builtin_inf();
+                }
             };
             {
-                const int c = threadIdx.x >> 4;                     // 16 lanes per coarse candidate
-                eval(c, eta * (c + 1), c < kCoarse, threadIdx.x & 15, 16);
+                const int c = threadIdx.x / 24;                     // 24 lanes per coarse candidate: 240 of 256 busy
+                eval(c, eta * (c + 1), c < kCoarse, threadIdx.x - 24 * c, 24);
             }
             __syncthreads();
             int best = 0;
@@ -255,9 +262,9 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const float *__restrict
                 if (err[i] < err[best]) best = i;
             const double lo = eta * (best + 1);
             {
-                const int f = threadIdx.x >> 3;                     // 8 lanes per fine candidate
+                const int f = threadIdx.x / 12;                     // 12 lanes per fine candidate: 252 of 256 busy
                 const double alpha = lo + eta * ((f - 10) / 10.0);
-                eval(kCoarse + f, alpha, f < kFine && alpha > 0.0 && alpha <= M, threadIdx.x & 7, 8);
+                eval(kCoarse + f, alpha, f < kFine && alpha > 0.0 && alpha <= M, threadIdx.x - 12 * f, 12);
             }
             __syncthreads();
             int pick = best;
