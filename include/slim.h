@@ -318,7 +318,7 @@ int slim_linear_gemm(const slim_layer *layer, const slim_half *X, int32_t m, sli
  * without the packed term (one launch where that geometry fits), above that
  * two dense matrix-core products with T = X R^T rounded to fp16 in between.
  * Workspace as for the forward calls (slim_workspace_bytes of a layer of this
- * shape).
+ * shape); kernels only, so the call can be captured into a HIP graph like them.
  */
 int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, const slim_half *L,
                  slim_shape shape, int32_t rank_pad, slim_half *Y, int accumulate,

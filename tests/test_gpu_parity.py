@@ -689,16 +689,20 @@ def test_forward_calls_captured_in_a_graph_replay_correctly():
     y1 = torch.empty(1, shape_a.n, dtype=torch.float16, device=DEV)
     y16 = torch.empty(16, shape_b.n, dtype=torch.float16, device=DEV)
     y64 = torch.empty(64, shape_a.n, dtype=torch.float16, device=DEV)
+    ylr = torch.empty(16, shape_b.n, dtype=torch.float16, device=DEV)      # the adapter term of layer b alone
+    lowrank_b = lambda y: B.slim_lowrank(x16, lb.R, lb.L, shape_b.n, shape_b.r, y, False, ws)
     for _ in range(2):                                       # eager calls first: the workspace has history
         B.slim_linear_gemv(la, x1, y1, ws)
         B.slim_linear_gemv(lb, x16, y16, ws)
         B.slim_linear_gemm(la, x64, y64, ws)
+        lowrank_b(ylr)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         B.slim_linear_gemv(la, x1, y1, ws)
         B.slim_linear_gemv(lb, x16, y16, ws)
         B.slim_linear_gemm(la, x64, y64, ws)
+        lowrank_b(ylr)
     for rep in range(4):
         X1, X16, X64 = (wl.make_activations(m, k, seed=60 + 3 * rep + i) for i, (m, k) in
                         enumerate([(1, shape_a.k), (16, shape_b.k), (64, shape_a.k)]))
@@ -708,13 +712,15 @@ def test_forward_calls_captured_in_a_graph_replay_correctly():
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        got = [y1.clone(), y16.clone(), y64.clone()]
+        got = [y1.clone(), y16.clone(), y64.clone(), ylr.clone()]
         e1 = B.slim_linear_gemv(la, x1, workspace=ws)        # the program's own eager work between replays
         e16 = B.slim_linear_gemv(lb, x16, workspace=ws)
         e64 = B.slim_linear_gemm(la, x64, workspace=ws)
+        elr = lowrank_b(torch.empty_like(ylr))
         torch.cuda.synchronize()
-        for g, e in zip(got, (e1, e16, e64)):
+        for g, e in zip(got, (e1, e16, e64, elr)):
             assert torch.equal(g, e), rep
+        assert _relerr(got[3].cpu().numpy(), O.xr(X16.numpy(), Rb.numpy()) @ Lb.numpy().astype(np.float64).T) <= TOL_Y
         assert _relerr(got[0].cpu().numpy(), O.forward(ra, La.numpy(), Ra.numpy(), X1.numpy())) <= TOL_Y
         assert _relerr(got[1].cpu().numpy(), O.forward(rb, Lb.numpy(), Rb.numpy(), X16.numpy())) <= TOL_Y
         assert _relerr(got[2].cpu().numpy(), O.forward(ra, La.numpy(), Ra.numpy(), X64.numpy())) <= TOL_Y
@@ -730,3 +736,4 @@ def test_forward_calls_captured_in_a_graph_replay_correctly():
         torch.cuda.synchronize()
         assert _relerr(y1.cpu().numpy(), O.forward(ra, La.numpy(), Ra.numpy(), X1.numpy())) <= TOL_Y
         assert _relerr(y16.cpu().numpy(), O.forward(rb, Lb.numpy(), Rb.numpy(), X16.numpy())) <= TOL_Y
+        assert _relerr(ylr.cpu().numpy(), O.xr(X16.numpy(), Rb.numpy()) @ Lb.numpy().astype(np.float64).T) <= TOL_Y
