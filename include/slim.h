@@ -280,7 +280,10 @@ int slim_workspace_bytes(const slim_layer *layer, int32_t m, size_t *bytes);
  * (m (k + rank_pad) fp16 within about 150 KiB), two launches otherwise.  The
  * environment variable SLIM_DECODE_PATH = parts | roles | fused forces the
  * two-launch kernels, the one-launch kernel's two roles as two launches, or
- * the one-launch kernel where it is eligible (measurement and tests).
+ * the one-launch kernel where it is eligible (measurement and tests;
+ * slim_lowrank at up to 16 tokens honours "parts" as well).
+ * SLIM_DECODE_LDS_KB = 16..160 lowers the LDS the one-launch geometry may plan
+ * with (tests: X in chunks on small layers).
  * Requires k % 128 == 0.  Errors: NULL, SHAPE (m out of range, k), ALIGN,
  * WORKSPACE, HIP.
  */
