@@ -291,6 +291,34 @@ int slim_linear_gemv(const slim_layer *layer, const slim_half *X, int32_t m, sli
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * slim_linear_gemv_static -- slim_linear_gemv for callers that cannot allocate or
+ * carry a workspace: code recorded under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels, same results; the
+ * workspace is an array of SLIM_STATIC_SCRATCH_BYTES inside the library's own code
+ * object (one copy per GPU, zero when the library is loaded, held until the process
+ * ends).  The call allocates and frees nothing and enqueues kernels only.
+ *   - A call that needs more scratch than SLIM_STATIC_SCRATCH_BYTES is refused with
+ *     SLIM_ERR_WORKSPACE and nothing is enqueued.  The one-launch kernel needs
+ *     256 + 192 rank_pad + 256 * ceil(rank_pad / 4) bytes or so (under 200 KiB at rank 820);
+ *     where the two-launch kernels run, the whole of slim_workspace_bytes (partial sums of
+ *     slots x m x n floats; with 4-bit adapters also their fp16 expansion).  Every
+ *     configured LLaMA-2 shape up to 28672 x 8192, rank 820, 16 tokens fits, with fp16
+ *     and with 4-bit adapters.
+ *   - The array belongs to the device that is current at the call (the device of
+ *     `stream`); its address is looked up on the first call on each device -- make
+ *     that first call outside stream capture.
+ *   - Every call on a GPU shares that GPU's array: calls that overlap in time on one
+ *     GPU (two streams, two threads) race on it.  Calls in stream order do not, and
+ *     nothing has to be cleared between them (the kernels tag what they leave there
+ *     with a call number, as in a caller-owned workspace).
+ * Errors: as slim_linear_gemv, SLIM_ERR_WORKSPACE as above, SLIM_ERR_HIP if the
+ * array's address cannot be obtained.
+ */
+#define SLIM_STATIC_SCRATCH_BYTES (8u << 20)
+int slim_linear_gemv_static(const slim_layer *layer, const slim_half *X, int32_t m, slim_half *Y,
+                            void *stream);
+
+/*
  * slim_decode_plan -- what slim_linear_gemv would launch for this layer (only
  * shape, rank_pad and adapter_bits are read) at m tokens; nothing is launched.
  * out: 12 ints (HOST pointer): [0] path (2: one launch, 1: its two roles as two

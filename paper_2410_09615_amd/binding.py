@@ -37,7 +37,8 @@ class slim_layer(ctypes.Structure):
 SLIM_OK, SLIM_ERR_NULL, SLIM_ERR_SHAPE, SLIM_ERR_ALIGN, SLIM_ERR_WORKSPACE, SLIM_ERR_HIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pack", "slim_pack_adapters",
-           "slim_unpack", "slim_workspace_bytes", "slim_decode_plan", "slim_linear_gemv", "slim_linear_gemm", "slim_lowrank",
+           "slim_unpack", "slim_workspace_bytes", "slim_decode_plan", "slim_linear_gemv", "slim_linear_gemv_static", "slim_linear_gemm",
+           "slim_lowrank",
            "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4", "slim_pack_ex",
            "slim_quant_workspace_bytes", "slim_quant_search", "slim_quant_search_rows", "slim_adapters_workspace_bytes",
            "slim_compute_adapters", "slim_input_quant_fp8", "slim_probe_read", "slim_probe_mfma"]
@@ -77,6 +78,7 @@ def lib():
         L.slim_unpack_adapters_q4.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.slim_linear_gemv.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp, sz, vp]
         L.slim_linear_gemm.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp, sz, vp]
+        L.slim_linear_gemv_static.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp]
         L.slim_lowrank.argtypes = [vp, i32, vp, vp, slim_shape, i32, vp, ctypes.c_int, vp, sz, vp]
         for name in EXPORTS[2:]:
             getattr(L, name).restype = ctypes.c_int
@@ -439,6 +441,21 @@ def _forward(fn_name: str, layer: SlimLayer, X: torch.Tensor, Y, workspace):
 def slim_linear_gemv(layer: SlimLayer, X: torch.Tensor, Y=None, workspace=None) -> torch.Tensor:
     """Decode-shaped forward, 1 <= m <= 16."""
     return _forward("slim_linear_gemv", layer, X, Y, workspace)
+
+
+def slim_linear_gemv_static(layer: SlimLayer, X: torch.Tensor, Y: torch.Tensor) -> torch.Tensor:
+    """slim_linear_gemv on the library's own scratch array: no workspace, and Y is the caller's
+    (nothing is allocated on the way)."""
+    _dev(X, torch.float16, "X")
+    _dev(Y, torch.float16, "Y")
+    m, k = X.shape
+    if k != layer.k or Y.numel() != m * layer.n or Y.device != X.device:
+        raise ValueError("X must be [m][k] and Y [m][n] on one device")
+    status = lib().slim_linear_gemv_static(layer.c_ref(), X.data_ptr(), m, Y.data_ptr(),
+                                           torch._C._cuda_getCurrentRawStream(X.device.index))
+    if status != SLIM_OK:
+        _check("slim_linear_gemv_static", status)
+    return Y
 
 
 def slim_linear_gemm(layer: SlimLayer, X: torch.Tensor, Y=None, workspace=None) -> torch.Tensor:

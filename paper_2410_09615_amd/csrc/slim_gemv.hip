@@ -34,6 +34,7 @@
 // workspace) is zeroed by a small kernel ahead of part 1, which adds into it.
 // (Earlier the calls cleaned a second T buffer for one another; that breaks as
 // soon as layers of different rank share a workspace.)
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 
@@ -586,8 +587,52 @@ int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t 
 
 using namespace slim;
 
-extern "C" int slim_linear_gemv(const slim_layer *layer_in, const slim_half *X, int32_t m, slim_half *Y,
-                                void *workspace, size_t workspace_bytes, void *stream)
+// Scratch of slim_linear_gemv_static: the workspace of a decode call inside the library's own
+// code object, one copy per GPU, zero at load time (a zero-filled workspace is what the decode
+// kernels expect before their first call) and held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress; kernels and copies get the address it returns.
+static __device__ __align__(256) unsigned char scratch[SLIM_STATIC_SCRATCH_BYTES];
+
+namespace slim {
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Address of `scratch` on the current device, looked up once per device.
+static int scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SLIM_ERR_HIP;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SLIM_ERR_HIP;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);     // every thread finds the same address
+    }
+    *out = p;
+    return SLIM_OK;
+}
+
+// own_scratch: the workspace is the library's array; it has to hold what the chosen path uses
+// (the caller's has to hold slim_workspace_bytes, whatever the path).
+static int linear_gemv(const slim_layer *layer_in, const slim_half *X, int32_t m, slim_half *Y, void *workspace,
+                       size_t workspace_bytes, void *stream, bool own_scratch);
+
+}  // namespace slim
+
+extern "C" int slim_linear_gemv(const slim_layer *layer, const slim_half *X, int32_t m, slim_half *Y, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    return linear_gemv(layer, X, m, Y, workspace, workspace_bytes, stream, false);
+}
+
+extern "C" int slim_linear_gemv_static(const slim_layer *layer, const slim_half *X, int32_t m, slim_half *Y, void *stream)
+{
+    // arguments and size are checked on the host first; the array's address is looked up after that
+    return linear_gemv(layer, X, m, Y, nullptr, (size_t)SLIM_STATIC_SCRATCH_BYTES, stream, true);
+}
+
+int slim::linear_gemv(const slim_layer *layer_in, const slim_half *X, int32_t m, slim_half *Y, void *workspace,
+                      size_t workspace_bytes, void *stream, bool own_scratch)
 {
     if (!layer_in || !X || !Y) return SLIM_ERR_NULL;
     const slim_layer *layer = layer_in;
@@ -604,9 +649,9 @@ extern "C" int slim_linear_gemv(const slim_layer *layer_in, const slim_half *X, 
     if (q4 && (!aligned16(layer->Lq) || !aligned16(layer->Ls) || !aligned16(layer->Rq) || !aligned16(layer->Rs)))
         return SLIM_ERR_ALIGN;
     WorkspacePlan w = plan_workspace(s.n, s.k, layer->rank_pad, m, q4);
-    if (!workspace || workspace_bytes < w.total) return SLIM_ERR_WORKSPACE;
+    if (!own_scratch && (!workspace || workspace_bytes < w.total)) return SLIM_ERR_WORKSPACE;
 
-    char *ws = static_cast<char *>(workspace);
+    char *ws = nullptr;
     // Path: one launch where X fits the LDS of a compute unit, else the two-part
     // kernels.  SLIM_DECODE_PATH = parts | roles | fused overrides (measurement).
     {
@@ -617,6 +662,13 @@ extern "C" int slim_linear_gemv(const slim_layer *layer_in, const slim_half *X, 
             if (!strcmp(env, "roles") && f.ok) mode = 1;
             if (!strcmp(env, "fused") && f.ok) mode = 2;
         }
+        // the one-launch kernel uses the head of the workspace only (control words and T)
+        if (own_scratch) {
+            if (workspace_bytes < (mode > 0 ? w.dec_off + w.dec_bytes : w.total)) return SLIM_ERR_WORKSPACE;
+            const int rc = scratch_of_current_device(&workspace);
+            if (rc != SLIM_OK) return rc;
+        }
+        ws = static_cast<char *>(workspace);
         if (mode > 0)
             return launch_decode_fused(layer, reinterpret_cast<const half_t *>(X), m, reinterpret_cast<half_t *>(Y),
                                        ws + w.t16_off, reinterpret_cast<unsigned *>(ws + w.dec_off) + 2,

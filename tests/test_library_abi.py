@@ -151,3 +151,21 @@ def test_decode_plan_of_the_configured_shapes(monkeypatch):
         monkeypatch.setenv("SLIM_DECODE_LDS_KB", str(lds_kb))
         p = B.slim_decode_plan(n, k, r, m)
         assert p["path"] == 2 and p["chunks"] > 1 and p["lds_bytes"] <= lds_kb * 1024, (n, k, r, m, lds_kb)
+
+
+def test_static_scratch_call_validates_on_the_host():
+    """slim_linear_gemv_static checks arguments and the size of its own scratch array before anything
+    touches a device."""
+    lib = B.lib()
+    a = ctypes.c_void_p(0x1000)
+    layer = B.slim_layer(B.slim_shape(128, 256, 0), 0x1000, 0x1000, 0x1000, None, None, 0)
+    assert lib.slim_linear_gemv_static(None, a, 1, a, None) == B.SLIM_ERR_NULL
+    assert lib.slim_linear_gemv_static(ctypes.byref(layer), a, 0, a, None) == B.SLIM_ERR_SHAPE
+    assert lib.slim_linear_gemv_static(ctypes.byref(layer), a, 17, a, None) == B.SLIM_ERR_SHAPE
+    assert lib.slim_linear_gemv_static(ctypes.byref(layer), ctypes.c_void_p(0x1004), 1, a, None) == B.SLIM_ERR_ALIGN
+    # a layer whose decode call needs partial sums beyond the array: 16 tokens x 2^20 rows of floats per slot
+    huge = B.slim_layer(B.slim_shape(1 << 20, 8192, 0), 0x1000, 0x1000, 0x1000, None, None, 0)
+    out = ctypes.c_size_t()
+    assert lib.slim_workspace_bytes(ctypes.byref(huge), 16, out) == 0 and out.value > (8 << 20)
+    assert B.slim_decode_plan(1 << 20, 8192, 0, 16)["path"] == 0
+    assert lib.slim_linear_gemv_static(ctypes.byref(huge), a, 16, a, None) == B.SLIM_ERR_WORKSPACE
