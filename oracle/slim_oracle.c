@@ -234,11 +234,12 @@ int slim_oracle_xr(const double *X, const double *R, int64_t m, int64_t k, int64
  *   Y[i][t] = sum_k X[i][k] Wd[o][k] + sum_j T[i][j] L[o][j],  o = rows[t]
  * X [m][k], L [n][r], R [r][k] are fp64 copies of the fp16 inputs (exact).
  * r may be 0 (no adapters; L and R may then be NULL).  Y is [m][nrows].
+ * T_out (may be NULL): receives T = X R^T [m][r] as it was used, for error budgets in tests.
  */
 int slim_oracle_forward(const uint8_t *qvals, const uint8_t *meta, const float *scale,
                         const double *L, const double *R, const double *X,
                         int64_t n, int64_t k, int64_t r, int64_t m,
-                        const int64_t *rows, int64_t nrows, double *Y)
+                        const int64_t *rows, int64_t nrows, double *Y, double *T_out)
 {
     if (!qvals || !meta || !scale || !X || !Y) return -1;
     if (n <= 0 || k <= 0 || k % 8 || m <= 0 || r < 0) return -1;
@@ -253,6 +254,7 @@ int slim_oracle_forward(const uint8_t *qvals, const uint8_t *meta, const float *
         T = (double *)malloc(sizeof(double) * (size_t)m * (size_t)r);
         if (!T) return -3;
         slim_oracle_xr(X, R, m, k, r, T);
+        if (T_out) memcpy(T_out, T, sizeof(double) * (size_t)m * (size_t)r);
     }
     int fail = 0;
 #pragma omp parallel

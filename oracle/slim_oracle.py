@@ -48,7 +48,7 @@ def _load():
             "slim_oracle_unpack": [p, p, i64, i64, p, p],
             "slim_oracle_dequant": [p, p, p, i64, i64, p],
             "slim_oracle_xr": [p, p, i64, i64, i64, p],
-            "slim_oracle_forward": [p, p, p, p, p, p, i64, i64, i64, i64, p, i64, p],
+            "slim_oracle_forward": [p, p, p, p, p, p, i64, i64, i64, i64, p, i64, p, p],
         }.items():
             fn = getattr(lib, name)
             fn.argtypes = args
@@ -195,8 +195,9 @@ def xr(X: np.ndarray, R: np.ndarray) -> np.ndarray:
     return T
 
 
-def forward(layer: PackedLayer, L, R, X, rows=None) -> np.ndarray:
-    """Route (i): Y from the packed bytes, float64, [m][n] (or [m][len(rows)])."""
+def forward(layer: PackedLayer, L, R, X, rows=None, return_t: bool = False):
+    """Route (i): Y from the packed bytes, float64, [m][n] (or [m][len(rows)]).
+    return_t: also the intermediate T = X R^T [m][r] the call used (None without adapters)."""
     X = _c(X, np.float64)
     m, k = X.shape
     n = layer.n
@@ -216,9 +217,10 @@ def forward(layer: PackedLayer, L, R, X, rows=None) -> np.ndarray:
         nrows = rows_arr.shape[0]
     Y = np.empty((m, nrows), np.float64)
     qv, me, sc = _c(layer.qvals, np.uint8), _c(layer.meta, np.uint8), _c(layer.scale, np.float32)
+    T = np.empty((m, r), np.float64) if (return_t and r > 0) else None
     _check(_load().slim_oracle_forward(_ptr(qv), _ptr(me), _ptr(sc), _ptr(L), _ptr(R), _ptr(X),
-                                       n, k, r, m, _ptr(rows_arr), nrows, _ptr(Y)), "forward")
-    return Y
+                                       n, k, r, m, _ptr(rows_arr), nrows, _ptr(Y), _ptr(T)), "forward")
+    return (Y, T) if return_t else Y
 
 
 def forward_explicit_dense(W: np.ndarray, L, R, X) -> np.ndarray:

@@ -12,16 +12,18 @@ import torch
 from oracle import slim_oracle as O
 from paper_2410_09615_amd import binding as B
 from paper_2410_09615_amd import workloads as wl
+import functools
+
 from layouts import tile_fp16, tile_packed
+from parity import TOL_Y, assert_forward_close, element_tolerance, prefill_row_sample, relerr as _relerr
 
 pytestmark = pytest.mark.gpu
 
-TOL_Y = 2e-3
 DEV = "cuda:0"
-
-
-def _relerr(a, b):
-    return float(np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b))
+# roundings a value of T = X R^T goes through before it meets L (see parity.py): the one-launch decode
+# kernel rounds up to four shares and adds them in fp16; prefill rounds T once; 4-bit adapters add the
+# fp16 rounding of code * scale in R and in L
+CT_DECODE, CT_PREFILL, CT_Q4 = 7, 1, 2
 
 
 def _shape(n, k, r, outliers=True):
@@ -103,6 +105,28 @@ def test_unpack_arbitrary_valid_bytes():
     assert np.array_equal(codes.cpu().numpy(), rc) and np.array_equal(mask.cpu().numpy(), rm)
 
 
+def _assert_lowrank_close(Y, X, R, L, Y0=None, what="slim_lowrank"):
+    """Y against (X R^T) L^T (+ Y0) with T from the oracle, element by element and tile by tile."""
+    Xn = X.numpy().astype(np.float64)
+    L64 = L.numpy().astype(np.float64)
+    T = O.xr(Xn, R.numpy())
+    ref = T @ L64.T
+    if Y0 is not None:
+        ref = ref + Y0.astype(np.float64)
+    c_t = CT_DECODE if X.shape[0] <= 16 else CT_PREFILL
+    return assert_forward_close(Y.cpu().numpy(), ref, element_tolerance(ref, T, L64, None, Xn, c_t), what)
+
+
+def _assert_layer_close(Y, ref, Lr, Rr, X, c_t=CT_DECODE, what="forward"):
+    """Y (device, fp16) against the oracle's forward of a packed layer on X (host tensor or array)."""
+    Xn = (X.numpy() if hasattr(X, "numpy") else X).astype(np.float64)
+    L64 = None if Lr is None else np.asarray(Lr, np.float64)
+    R64 = None if Rr is None else np.asarray(Rr, np.float64)
+    Yref, T = O.forward(ref, L64, R64, Xn, return_t=True)
+    tol = element_tolerance(Yref, T, L64, ref.scale.astype(np.float64), Xn, c_t)
+    return assert_forward_close(Y.cpu().numpy(), Yref, tol, what)
+
+
 @pytest.mark.parametrize("n,k,r,m", [(4096, 4096, 410, 16), (4096, 4096, 410, 1), (1000, 11008, 130, 5), (33, 256, 1, 16),
                                      (28672, 8192, 820, 16)])
 def test_lowrank_decode_shapes(n, k, r, m):
@@ -111,15 +135,15 @@ def test_lowrank_decode_shapes(n, k, r, m):
     L, R = wl.make_adapters(n, k, r, 41, 42)
     X = wl.make_activations(m, k, True, 43, 44)
     Lp, Rp = B.slim_pack_adapters(L.to(DEV), R.to(DEV))
-    ref = O.xr(X.numpy(), R.numpy()) @ L.numpy().astype(np.float64).T
     tmp = B.SlimLayer(n, k, r, B.slim_rank_pad(r), Lp, Lp, Lp, Lp, Rp)
     ws = B.alloc_workspace(tmp, m)
     Y = B.slim_lowrank(X.to(DEV), Rp, Lp, n, r, workspace=ws)
     torch.cuda.synchronize()
-    assert _relerr(Y.cpu().numpy(), ref) <= TOL_Y
+    _assert_lowrank_close(Y, X, R, L)
     Y2 = B.slim_lowrank(X.to(DEV), Rp, Lp, n, r, Y=Y.clone(), accumulate=True, workspace=ws)
     torch.cuda.synchronize()
-    assert _relerr(Y2.cpu().numpy(), ref + Y.cpu().numpy().astype(np.float64)) <= TOL_Y
+    _assert_lowrank_close(Y2, X, R, L, Y0=Y.cpu().numpy())
+    assert int(ws.view(torch.int32)[2]) == 0
 
 
 def test_lowrank_several_row_tiles():
@@ -127,27 +151,54 @@ def test_lowrank_several_row_tiles():
     L, R = wl.make_adapters(n, k, r, 31, 32)
     X = wl.make_activations(m, k, True, 33, 34)
     Lp, Rp = B.slim_pack_adapters(L.to(DEV), R.to(DEV))
-    ref = O.xr(X.numpy(), R.numpy()) @ L.numpy().astype(np.float64).T
     Y = B.slim_lowrank(X.to(DEV), Rp, Lp, n, r)
     torch.cuda.synchronize()
-    assert _relerr(Y.cpu().numpy(), ref) <= TOL_Y
+    _assert_lowrank_close(Y, X, R, L)
 
 
 # ---- forward: decode ------------------------------------------------------------
 
-def _forward_case(shape, m, fn, seed=0, rows=None):
-    W, L, R, X = wl.make_layer(shape, m, seed=seed)
-    layer = _gpu_layer(W, L if shape.r > 0 else None, R if shape.r > 0 else None)
-    Y = fn(layer, X.to(DEV))
+@functools.lru_cache(maxsize=3)
+def _compressed(shape, seed, bits):
+    """One layer on both sides, kept for the cases that share it (the large shapes take seconds to
+    generate and to compress): the library's layer on the device, the oracle's packed layer, and the
+    adapters as the oracle's forward takes them (fp16 values, or the dequantized 4-bit ones)."""
+    W = wl.make_weight(shape.n, shape.k, seed + 0)
+    L = R = Lr = Rr = None
+    if shape.r > 0:
+        L, R = wl.make_adapters(shape.n, shape.k, shape.r, seed + 1, seed + 2)
+        if bits == 4:
+            lc, ls = O.quantize_adapter(L.numpy())
+            rc, rs = O.quantize_adapter(R.numpy())
+            Lr, Rr = O.dequantize_adapter(lc, ls), O.dequantize_adapter(rc, rs)
+        else:
+            Lr, Rr = L.numpy().astype(np.float64), R.numpy().astype(np.float64)
+    layer = B.compress(W.to(DEV), None if L is None else L.to(DEV), None if R is None else R.to(DEV), adapter_bits=bits)
     torch.cuda.synchronize()
-    ref_layer = O.compress(W.numpy())
-    Lr, Rr = (L.numpy(), R.numpy()) if shape.r > 0 else (None, None)
-    Yref = O.forward(ref_layer, Lr, Rr, X.numpy(), rows=rows)
+    return layer, O.compress(W.numpy()), Lr, Rr
+
+
+def _check_forward(layer, ref, Lr, Rr, X, fn, rows, c_t, what):
+    """fn(layer, X) on a workspace of its own against the oracle's forward on the same inputs: the three
+    bounds of parity.py, and the workspace's error word still clear.  Returns the whole-call error."""
+    m = X.shape[0]
+    ws = B.alloc_workspace(layer, m)
+    Y = fn(layer, X.to(DEV), workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws.view(torch.int32)[2]) == 0, "a decode call gave up waiting for its T"
+    Xn = X.numpy().astype(np.float64)
+    Yref, T = O.forward(ref, Lr, Rr, Xn, rows=rows, return_t=True)
+    sel = slice(None) if rows is None else rows
+    tol = element_tolerance(Yref, T, None if Lr is None else Lr[sel], ref.scale[sel].astype(np.float64), Xn, c_t)
     Yg = Y.cpu().numpy()
-    if rows is not None:
-        Yg = Yg[:, rows]
-    assert np.isfinite(Yg).all()
-    return _relerr(Yg, Yref)
+    return assert_forward_close(Yg if rows is None else Yg[:, rows], Yref, tol, what)["whole"]
+
+
+def _forward_case(shape, m, fn, seed=0, rows=None, bits=16):
+    layer, ref, Lr, Rr = _compressed(shape, seed, bits)
+    X = wl.make_activations(m, shape.k, shape.outliers, seed + 3, seed + 4)
+    c_t = (CT_DECODE if fn is B.slim_linear_gemv else CT_PREFILL) + (CT_Q4 if bits == 4 else 0)
+    return _check_forward(layer, ref, Lr, Rr, X, fn, rows, c_t, f"{fn.__name__} {shape.name} m={m} bits={bits}")
 
 
 # slim_linear_gemv has a one-launch path (layers whose X fits the LDS of a compute
@@ -202,15 +253,15 @@ def test_gemv_without_adapters(decode_path):
     assert _forward_case(_shape(512, 1024, 0), 4, B.slim_linear_gemv, seed=3) <= TOL_Y
 
 
-@pytest.mark.parametrize("shape,m", [(wl.L13B_UP, 1), (wl.L70B_ATTN, 16), (wl.L70B_UP, 1), (wl.L70B_UP, 4), (wl.L7B_DOWN, 4),
-                                     (wl.L13B_ATTN, 1), (wl.L70B_ATTN, 1), (wl.L70B_UP, 16), (wl.L7B_UP, 16)],
+# every configured decode shape and token count (the 7B attention projection has its own test above),
+# a few more, all output rows against the oracle; the forced paths on one 13B and one 70B layer
+@pytest.mark.parametrize("shape,m", [(wl.L13B_ATTN, 1), (wl.L13B_UP, 1), (wl.L70B_ATTN, 1), (wl.L70B_ATTN, 16), (wl.L70B_UP, 1),
+                                     (wl.L70B_UP, 16), (wl.L70B_UP, 4), (wl.L7B_DOWN, 4), (wl.L7B_UP, 16)],
                          ids=lambda v: str(getattr(v, "name", v)))
-def test_gemv_full_size_sampled_rows(shape, m, decode_path):
-    if decode_path in ("roles", "parts") and shape is not wl.L13B_UP:
-        pytest.skip("forced paths are covered at full size by one shape")
-    rows = np.random.default_rng(1).choice(shape.n, size=512, replace=False)
-    rows.sort()
-    assert _forward_case(shape, m, B.slim_linear_gemv, rows=rows) <= TOL_Y
+def test_gemv_full_size_all_rows(shape, m, decode_path):
+    if decode_path in ("roles", "parts") and not (shape is wl.L13B_UP or (shape is wl.L70B_UP and m == 16)):
+        pytest.skip("the forced paths run at full size on one 13B and one 70B layer")
+    assert _forward_case(shape, m, B.slim_linear_gemv) <= TOL_Y
 
 
 @pytest.mark.parametrize("n,k,r,m,lds_kb", [(1000, 4096, 100, 16, 96), (1000, 4096, 100, 16, 72), (520, 11008, 410, 8, 64),
@@ -258,8 +309,8 @@ def test_gemv_repeated_calls_one_workspace(monkeypatch):
         monkeypatch.setenv("SLIM_DECODE_PATH", path)
         Y = B.slim_linear_gemv(layer, Xd[:m].contiguous(), workspace=ws)
         torch.cuda.synchronize()
-        Yref = O.forward(ref_layer, L.numpy(), R.numpy(), X[:m].numpy())
-        assert _relerr(Y.cpu().numpy(), Yref) <= TOL_Y, (i, path, m)
+        _assert_layer_close(Y, ref_layer, L.numpy(), R.numpy(), X[:m], what=f"call {i} ({path}, m={m})")
+    assert int(ws.view(torch.int32)[2]) == 0
 
 
 # ---- forward: prefill -----------------------------------------------------------
@@ -278,18 +329,14 @@ def test_gemm_without_adapters():
     assert _forward_case(_shape(512, 1024, 0), 256, B.slim_linear_gemm, seed=4) <= TOL_Y
 
 
-@pytest.mark.parametrize("shape,m", [(wl.L7B_UP, 2048), (wl.L7B_DOWN, 2048)], ids=lambda v: str(getattr(v, "name", v)))
-def test_gemm_llama7b_mlp_sampled_rows(shape, m):
-    rows = np.random.default_rng(2).choice(shape.n, size=256, replace=False)
-    rows.sort()
-    assert _forward_case(shape, m, B.slim_linear_gemm, rows=rows) <= TOL_Y
-
-
-@pytest.mark.parametrize("shape,m", [(wl.L13B_ATTN, 4096), (wl.L13B_UP, 4096), (wl.L70B_ATTN, 4096), (wl.L70B_UP, 4096)],
-                         ids=lambda v: str(getattr(v, "name", v)))
+@pytest.mark.parametrize("shape,m", [(wl.L7B_UP, 2048), (wl.L7B_DOWN, 2048), (wl.L13B_ATTN, 4096), (wl.L13B_UP, 4096),
+                                     (wl.L70B_ATTN, 4096), (wl.L70B_UP, 4096)], ids=lambda v: str(getattr(v, "name", v)))
 def test_gemm_full_size_sampled_rows(shape, m):
-    rows = np.random.default_rng(3).choice(shape.n, size=64, replace=False)
-    rows.sort()
+    """Every configured prefill shape, all tokens, on at least 256 output rows: the first and last 32,
+    one of every 128 (every piece of a row tile that some workgroup owns), both sides of every workgroup
+    row tile, random ones."""
+    rows = prefill_row_sample(shape.n, 256, seed=2)
+    assert rows.size >= 256
     assert _forward_case(shape, m, B.slim_linear_gemm, rows=rows) <= TOL_Y
 
 
@@ -417,11 +464,11 @@ def test_forward_of_a_layer_packed_with_searched_scale_and_saliency_mask():
     mask = O.mask_2of4(W.numpy(), sal)
     ref_scale = np.full(shape.n, rs, np.float32)
     qv, me = O.pack(O.quantize(W.numpy(), mask, ref_scale), mask)
-    Yref = O.forward(O.PackedLayer(qv, me, ref_scale), L.numpy(), R.numpy(), X.numpy())
-    for fn in (B.slim_linear_gemv, B.slim_linear_gemm):
+    packed = O.PackedLayer(qv, me, ref_scale)
+    for fn, c_t in ((B.slim_linear_gemv, CT_DECODE), (B.slim_linear_gemm, CT_PREFILL)):
         Y = fn(layer, X.to(DEV))
         torch.cuda.synchronize()
-        assert _relerr(Y.cpu().numpy(), Yref) <= TOL_Y
+        _assert_layer_close(Y, packed, L.numpy(), R.numpy(), X, c_t, fn.__name__)
 
 
 # ---- 4-bit adapters (Sec. 3.3) ------------------------------------------------------
@@ -448,18 +495,7 @@ def test_pack_adapters_q4_bit_exact(n, k, r):
 
 
 def _forward_case_q4(shape, m, fn, seed=0, rows=None):
-    W, L, R, X = wl.make_layer(shape, m, seed=seed)
-    layer = _q4_layer(W, L, R)
-    Y = fn(layer, X.to(DEV))
-    torch.cuda.synchronize()
-    lc, ls = O.quantize_adapter(L.numpy())
-    rc, rs = O.quantize_adapter(R.numpy())
-    Yref = O.forward(O.compress(W.numpy()), O.dequantize_adapter(lc, ls), O.dequantize_adapter(rc, rs), X.numpy(), rows=rows)
-    Yg = Y.cpu().numpy()
-    if rows is not None:
-        Yg = Yg[:, rows]
-    assert np.isfinite(Yg).all()
-    return _relerr(Yg, Yref)
+    return _forward_case(shape, m, fn, seed=seed, rows=rows, bits=4)
 
 
 @pytest.mark.parametrize("m", [1, 4, 8, 16])
@@ -473,11 +509,16 @@ def test_gemv_q4_adapters_ragged_shapes(n, k, r, m):
     assert _forward_case_q4(_shape(n, k, r), m, B.slim_linear_gemv, seed=7) <= TOL_Y
 
 
-@pytest.mark.parametrize("shape,m", [(wl.L7B_ATTN, 1), (wl.L7B_ATTN, 16), (wl.L70B_ATTN, 4)], ids=lambda v: str(getattr(v, "name", v)))
-def test_gemv_q4_adapters_full_size_sampled_rows(shape, m):
-    rows = np.random.default_rng(1).choice(shape.n, size=512, replace=False)
-    rows.sort()
-    assert _forward_case_q4(shape, m, B.slim_linear_gemv, rows=rows) <= TOL_Y
+@pytest.mark.parametrize("shape,m", [(wl.L7B_ATTN, 1), (wl.L7B_ATTN, 16), (wl.L70B_ATTN, 4), (wl.L70B_UP, 1), (wl.L70B_UP, 16)],
+                         ids=lambda v: str(getattr(v, "name", v)))
+def test_gemv_q4_adapters_full_size_all_rows(shape, m):
+    assert _forward_case_q4(shape, m, B.slim_linear_gemv) <= TOL_Y
+
+
+@pytest.mark.parametrize("shape,m", [(wl.L7B_UP, 2048), (wl.L70B_ATTN, 4096)], ids=lambda v: str(getattr(v, "name", v)))
+def test_gemm_q4_adapters_full_size_sampled_rows(shape, m):
+    rows = prefill_row_sample(shape.n, 256, seed=3)
+    assert _forward_case_q4(shape, m, B.slim_linear_gemm, rows=rows) <= TOL_Y
 
 
 @pytest.mark.parametrize("n,k,r,m,lds_kb", [(1000, 4096, 100, 16, 96), (520, 11008, 410, 8, 64), (300, 2176, 37, 5, 24)])
@@ -521,15 +562,14 @@ def test_lowrank(m, accumulate, path, monkeypatch):
     L, R = wl.make_adapters(n, k, r, 21, 22)
     X = wl.make_activations(m, k, True, 23, 24)
     Lp, Rp = B.slim_pack_adapters(L.to(DEV), R.to(DEV))
-    ref = O.xr(X.numpy(), R.numpy()) @ L.numpy().astype(np.float64).T
-    Y0 = None
+    Y0 = Y0h = None
     if accumulate:
-        Y0 = (torch.randn(m, n, generator=torch.Generator().manual_seed(9)) * ref.std()).to(torch.float16)
-        ref = ref + Y0.numpy().astype(np.float64)
-        Y0 = Y0.to(DEV)
+        std = float((O.xr(X.numpy(), R.numpy()) @ L.numpy().astype(np.float64).T).std())
+        Y0h = (torch.randn(m, n, generator=torch.Generator().manual_seed(9)) * std).to(torch.float16)
+        Y0 = Y0h.to(DEV)
     Y = B.slim_lowrank(X.to(DEV), Rp, Lp, n, r, Y=Y0, accumulate=accumulate)
     torch.cuda.synchronize()
-    assert _relerr(Y.cpu().numpy(), ref) <= TOL_Y
+    _assert_lowrank_close(Y, X, R, L, Y0=None if Y0h is None else Y0h.numpy())
 
 
 # ---- measurement aids -------------------------------------------------------------
@@ -589,7 +629,7 @@ def test_forward_on_fp8_quantized_input():
     ref = O.compress(W.numpy())
     rq, _, _ = O.input_quant_fp8(X.numpy())
     Yo = O.forward(ref, L.numpy(), R.numpy(), rq)
-    assert _relerr(Y.cpu().numpy(), Yo) <= TOL_Y
+    _assert_layer_close(Y, ref, L.numpy(), R.numpy(), rq, what="forward on fp8-quantized input")
     # and the quantization of the input costs accuracy of the order of its 2 to 3 mantissa bits, not more
     Y0 = O.forward(ref, L.numpy(), R.numpy(), X.numpy())
     assert 1e-3 < _relerr(Yo, Y0) < 0.1
@@ -646,7 +686,8 @@ def test_gemv_one_workspace_shared_by_layers_of_different_rank(path, monkeypatch
         X = wl.make_activations(m, shape.k, seed=90 + step)
         Y = B.slim_linear_gemv(layer, X.to(DEV), workspace=ws)
         torch.cuda.synchronize()
-        assert _relerr(Y.cpu().numpy(), O.forward(ref, Lr, Rr, X.numpy())) <= TOL_Y, (step, shape.name, m)
+        _assert_layer_close(Y, ref, Lr, Rr, X, CT_DECODE + CT_Q4, f"step {step} {shape.name} m={m}")
+    assert int(ws.view(torch.int32)[2]) == 0
 
 
 def test_calls_follow_the_current_stream():
@@ -668,6 +709,8 @@ def test_calls_follow_the_current_stream():
         Y2 = B.slim_linear_gemm(layer, Xd)
     side.synchronize()
     assert _relerr(Y1.cpu().numpy(), Yo) <= TOL_Y and _relerr(Y2.cpu().numpy(), Yo) <= TOL_Y
+    _assert_layer_close(Y1, ref, L.numpy(), R.numpy(), X, CT_DECODE, "gemv on a side stream")
+    _assert_layer_close(Y2, ref, L.numpy(), R.numpy(), X, CT_PREFILL, "gemm on a side stream")
 
 
 def test_forward_calls_captured_in_a_graph_replay_correctly():
@@ -720,10 +763,10 @@ def test_forward_calls_captured_in_a_graph_replay_correctly():
         torch.cuda.synchronize()
         for g, e in zip(got, (e1, e16, e64, elr)):
             assert torch.equal(g, e), rep
-        assert _relerr(got[3].cpu().numpy(), O.xr(X16.numpy(), Rb.numpy()) @ Lb.numpy().astype(np.float64).T) <= TOL_Y
-        assert _relerr(got[0].cpu().numpy(), O.forward(ra, La.numpy(), Ra.numpy(), X1.numpy())) <= TOL_Y
-        assert _relerr(got[1].cpu().numpy(), O.forward(rb, Lb.numpy(), Rb.numpy(), X16.numpy())) <= TOL_Y
-        assert _relerr(got[2].cpu().numpy(), O.forward(ra, La.numpy(), Ra.numpy(), X64.numpy())) <= TOL_Y
+        _assert_lowrank_close(got[3], X16, Rb, Lb, what=f"replay {rep}: slim_lowrank")
+        _assert_layer_close(got[0], ra, La.numpy(), Ra.numpy(), X1, CT_DECODE, f"replay {rep}: gemv a")
+        _assert_layer_close(got[1], rb, Lb.numpy(), Rb.numpy(), X16, CT_DECODE, f"replay {rep}: gemv b")
+        _assert_layer_close(got[2], ra, La.numpy(), Ra.numpy(), X64, CT_PREFILL, f"replay {rep}: gemm a")
     # replays back to back, nothing but new inputs in between: the pieces of T in the workspace are
     # those of the previous replay when the next one starts
     for rep in range(3):
@@ -734,6 +777,7 @@ def test_forward_calls_captured_in_a_graph_replay_correctly():
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        assert _relerr(y1.cpu().numpy(), O.forward(ra, La.numpy(), Ra.numpy(), X1.numpy())) <= TOL_Y
-        assert _relerr(y16.cpu().numpy(), O.forward(rb, Lb.numpy(), Rb.numpy(), X16.numpy())) <= TOL_Y
-        assert _relerr(ylr.cpu().numpy(), O.xr(X16.numpy(), Rb.numpy()) @ Lb.numpy().astype(np.float64).T) <= TOL_Y
+        _assert_layer_close(y1, ra, La.numpy(), Ra.numpy(), X1, CT_DECODE, f"back-to-back replay {rep}: gemv a")
+        _assert_layer_close(y16, rb, Lb.numpy(), Rb.numpy(), X16, CT_DECODE, f"back-to-back replay {rep}: gemv b")
+        _assert_lowrank_close(ylr, X16, Rb, Lb, what=f"back-to-back replay {rep}: slim_lowrank")
+    assert int(ws.view(torch.int32)[2]) == 0
