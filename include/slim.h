@@ -18,9 +18,14 @@
  *   - matrices are row-major, contiguous, 16-byte aligned;
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream);
  *     all work is enqueued on it and the call returns without synchronizing;
- *   - the library allocates nothing and keeps no state between calls; the forward
- *     entry points enqueue kernels only (no memset, copy or synchronization) and
- *     may be captured into a HIP graph;
+ *   - the library allocates nothing; the forward entry points enqueue kernels only
+ *     (no memset, copy or synchronization) and may be captured into a HIP graph;
+ *   - what the library keeps between calls is: a process-wide call counter (the
+ *     number that tags a decode call's intermediate result), what it has read of
+ *     each device's properties (compute units, LDS), per thread the last decode
+ *     launch plans it computed, the device address of its own scratch array
+ *     (slim_linear_gemv_static) and the setting of slim_decode_override.  No result
+ *     depends on an earlier call;
  *   - arguments are validated on the host before anything is launched; on an
  *     error nothing has been enqueued.
  * fp16 values are IEEE binary16 bit patterns (`slim_half`).
@@ -71,7 +76,8 @@ typedef enum {
     SLIM_ERR_SHAPE = -2,      /* a dimension is out of the documented range           */
     SLIM_ERR_ALIGN = -3,      /* a pointer is not 16-byte aligned                     */
     SLIM_ERR_WORKSPACE = -4,  /* workspace missing or smaller than slim_workspace_bytes */
-    SLIM_ERR_HIP = -5         /* a HIP runtime call failed (launch error)             */
+    SLIM_ERR_HIP = -5,        /* a HIP runtime call failed (launch error)             */
+    SLIM_ERR_WAIT = -6        /* slim_workspace_check: a decode call gave up waiting  */
 } slim_status;
 
 /* d_out, d_in and the true adapter rank (0 = layer without adapters). */
@@ -262,29 +268,38 @@ int slim_unpack(const uint8_t *qvals, const uint8_t *meta, slim_shape shape, int
  * phases (pieces tagged with a call number, never 0), and a fresh workspace
  * must not look like finished work (under stream capture the call number
  * lives in word 3 of the workspace and a one-thread kernel enqueued ahead of
- * the decode kernel advances it on every replay).  Nothing is carried between calls: one
+ * the decode kernel advances it on every replay).  No result is carried between calls: one
  * workspace (of the largest size needed) can serve any sequence of layers and
  * token counts.  Two calls that overlap in time need two workspaces.
- * Diagnostics: word 2 of the workspace is set to 1 if a decode call gave up
- * waiting for its own T (it never should; the call then returned wrong
- * numbers instead of hanging).
+ * Diagnostics: the one-launch decode kernel waits, inside the kernel, for its own
+ * T = X R^T; the wait is bounded.  Should it ever run out (it never should),
+ * the outputs that depend on the missing part are NaN -- a failed call cannot
+ * pass for a result -- and word 2 of the workspace is set to 1.
+ * slim_workspace_check reads that word back: it synchronizes `stream` (so it is
+ * not for graph capture), returns SLIM_ERR_WAIT and clears the word if a call on
+ * this workspace gave up since the last check, else SLIM_OK.  workspace == NULL
+ * checks the library's own scratch array on the current device
+ * (slim_linear_gemv_static).
  */
 int slim_workspace_bytes(const slim_layer *layer, int32_t m, size_t *bytes);
+int slim_workspace_check(void *workspace, void *stream);
 
 /*
  * slim_linear_gemv -- decode-shaped forward, 1 <= m <= 16 tokens (decoding runs
  * on small batches: Sec. 4 "Speedup").  Streams the packed
  * rows and the adapters once; fp16 inputs, fp32 accumulation, Y rounded once
  * to fp16.  X [m][k] fp16 in, Y [m][n] fp16 out.
- * One kernel launch where m rows of X and T fit the LDS of a compute unit
- * (m (k + rank_pad) fp16 within about 150 KiB), two launches otherwise.  The
- * environment variable SLIM_DECODE_PATH = parts | roles | fused forces the
- * two-launch kernels, the one-launch kernel's two roles as two launches, or
- * the one-launch kernel where it is eligible (measurement and tests;
- * slim_lowrank at up to 16 tokens honours "parts" as well).
- * SLIM_DECODE_LDS_KB = 16..160 lowers the LDS the one-launch geometry may plan
- * with (tests: X in chunks on small layers).
- * Requires k % 128 == 0.  Errors: NULL, SHAPE (m out of range, k), ALIGN,
+ * One kernel launch wherever the geometry fits the device (every configured
+ * LLaMA-2 shape at every token count: X streams through the LDS of a compute
+ * unit in chunks where it does not fit whole), the two-launch kernels otherwise
+ * (rank_pad above the chunk size, more row tiles than resident workgroups).
+ * In the one-launch kernel T = X R^T is rounded to fp16 (per share of the
+ * inputs, at most four, added in fp16), so |T| must stay below 65504 -- four
+ * orders of magnitude above what N(0, 1) inputs with x20 outlier channels and
+ * N(0, 0.01) adapters give; the two-launch kernels keep T in fp32.
+ * Requires k % 128 == 0 and every buffer (packed codes, L, R, X, Y) below
+ * 2 GiB: the kernels address them with 32-bit offsets.
+ * Errors: NULL, SHAPE (m out of range, k, a buffer of 2 GiB or more), ALIGN,
  * WORKSPACE, HIP.
  */
 int slim_linear_gemv(const slim_layer *layer, const slim_half *X, int32_t m, slim_half *Y,
@@ -319,6 +334,24 @@ int slim_linear_gemv_static(const slim_layer *layer, const slim_half *X, int32_t
                             void *stream);
 
 /*
+ * slim_decode_override -- test and measurement control, process-wide: which of
+ * its launch geometries slim_linear_gemv (and slim_lowrank up to 16 tokens)
+ * takes from now on.  Not for production use: the automatic choice is the
+ * product path.
+ *   path    -1 automatic; 0 the two-launch kernels; 1 the one-launch kernel's two
+ *           roles as two launches (where that geometry fits, else as 0); 2 as -1;
+ *           3 a test of the kernel's bounded wait: where the one-launch geometry
+ *           fits, only the half of the kernel that waits for T is launched, with
+ *           the wait cut to 256 polls, so it gives up: every wavefront still ends
+ *           normally, Y is NaN and the workspace's error word is set
+ *           (slim_workspace_check then reports SLIM_ERR_WAIT);
+ *   lds_kb  0: plan with the device's LDS; 16..160: with at most this many KiB
+ *           (X then streams through the LDS in chunks on small layers too).
+ * Errors: SHAPE (a value outside these ranges).
+ */
+int slim_decode_override(int32_t path, int32_t lds_kb);
+
+/*
  * slim_decode_plan -- what slim_linear_gemv would launch for this layer (only
  * shape, rank_pad and adapter_bits are read) at m tokens; nothing is launched.
  * out: 12 ints (HOST pointer): [0] path (2: one launch, 1: its two roles as two
@@ -332,7 +365,11 @@ int slim_decode_plan(const slim_layer *layer, int32_t m, int32_t *out);
 
 /*
  * slim_linear_gemm -- prefill-shaped forward, any m >= 1 (meant for m >= 64):
- * matrix-core GEMM over the compressed weights with the adapter product
+ * Y = X W^C + (X L) R of Sec. 3.2 in this header's orientation; by the count of
+ * App. "Computation Reduction Analysis" (Eq. 13) the 2:4 mask halves the
+ * multiply-adds of the weight term, quantization saves none, and the adapters
+ * add 2 m r (n + k).
+ * Matrix-core GEMM over the compressed weights with the adapter product
  * T = X R^T (rounded once to fp16) folded in as extra k-steps, row scale
  * applied to the fp32 accumulators, Y rounded once to fp16.
  * Requires k % 128 == 0.  Errors as slim_linear_gemv.

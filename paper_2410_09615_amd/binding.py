@@ -34,10 +34,10 @@ class slim_layer(ctypes.Structure):
                 ("Ls", ctypes.c_void_p), ("Rq", ctypes.c_void_p), ("Rs", ctypes.c_void_p)]
 
 
-SLIM_OK, SLIM_ERR_NULL, SLIM_ERR_SHAPE, SLIM_ERR_ALIGN, SLIM_ERR_WORKSPACE, SLIM_ERR_HIP = 0, -1, -2, -3, -4, -5
+SLIM_OK, SLIM_ERR_NULL, SLIM_ERR_SHAPE, SLIM_ERR_ALIGN, SLIM_ERR_WORKSPACE, SLIM_ERR_HIP, SLIM_ERR_WAIT = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pack", "slim_pack_adapters",
-           "slim_unpack", "slim_workspace_bytes", "slim_decode_plan", "slim_linear_gemv", "slim_linear_gemv_static", "slim_linear_gemm",
+           "slim_unpack", "slim_workspace_bytes", "slim_workspace_check", "slim_decode_override", "slim_decode_plan", "slim_linear_gemv", "slim_linear_gemv_static", "slim_linear_gemm",
            "slim_lowrank",
            "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4", "slim_pack_ex",
            "slim_quant_workspace_bytes", "slim_quant_search", "slim_quant_search_rows", "slim_adapters_workspace_bytes",
@@ -64,6 +64,8 @@ def lib():
         L.slim_unpack.argtypes = [vp, vp, slim_shape, vp, vp, vp]
         L.slim_workspace_bytes.argtypes = [ctypes.POINTER(slim_layer), i32, psz]
         L.slim_decode_plan.argtypes = [ctypes.POINTER(slim_layer), i32, pi32]
+        L.slim_workspace_check.argtypes = [vp, vp]
+        L.slim_decode_override.argtypes = [i32, i32]
         L.slim_adapter_q4_sizes.argtypes = [i32, i32, psz, psz]
         L.slim_pack_ex.argtypes = [vp, slim_shape, vp, vp, vp, vp, vp, vp]
         L.slim_quant_workspace_bytes.argtypes = [slim_shape, psz]
@@ -402,6 +404,23 @@ def slim_workspace_bytes(layer: SlimLayer, m: int) -> int:
     cs = layer.c_struct()
     _check("slim_workspace_bytes", lib().slim_workspace_bytes(ctypes.byref(cs), m, out))
     return out.value
+
+
+def slim_workspace_check(workspace: torch.Tensor | None = None):
+    """Raise (status SLIM_ERR_WAIT) if a decode call on this workspace gave up waiting for its own T since the
+    last check; synchronizes the current stream.  None: the library's own scratch array."""
+    dev = workspace.device.index if workspace is not None else torch.cuda.current_device()
+    _check("slim_workspace_check", lib().slim_workspace_check(_ptr(workspace), ctypes.c_void_p(
+        torch._C._cuda_getCurrentRawStream(dev))))
+
+
+DECODE_PATHS = {"auto": -1, "parts": 0, "roles": 1, "fused": 2, "wait_test": 3}
+
+
+def slim_decode_override(path: str = "auto", lds_kb: int = 0):
+    """Test and measurement control: force a decode launch geometry ("parts", "roles", "fused"; "auto" = the
+    product path) and/or the LDS the one-launch geometry plans with (0 = the device's)."""
+    _check("slim_decode_override", lib().slim_decode_override(DECODE_PATHS[path], lds_kb))
 
 
 def slim_decode_plan(n: int, k: int, rank: int, m: int, adapter_bits: int = 16) -> dict:

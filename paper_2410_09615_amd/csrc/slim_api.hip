@@ -1,9 +1,48 @@
 // Host-only parts of the boundary: status text, size queries, workspace plan.
 #include "slim_internal.h"
 
+#include <atomic>
+#include <mutex>
+
 namespace slim {
 
 static size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+DeviceInfo device_info()
+{
+    constexpr int kSlots = 64;
+    static DeviceInfo table[kSlots];
+    static std::atomic<int> known[kSlots];
+    const DeviceInfo nominal{256, (size_t)160 * 1024};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kSlots) {
+        (void)hipGetLastError();         // no device: the error must not surface in a later call
+        return nominal;
+    }
+    if (known[dev].load(std::memory_order_acquire)) return table[dev];
+    static std::mutex mu;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!known[dev].load(std::memory_order_acquire)) {
+        DeviceInfo d = nominal;
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) == hipSuccess) {
+            if (prop.multiProcessorCount > 0) d.cus = prop.multiProcessorCount;
+            // the kernels are laid out for at most 160 KiB per workgroup
+            const size_t lds = prop.maxSharedMemoryPerMultiProcessor;
+            if (lds >= 64 * 1024 && lds < d.lds) d.lds = lds;
+        } else {
+            (void)hipGetLastError();
+        }
+        table[dev] = d;
+        known[dev].store(1, std::memory_order_release);
+    }
+    return table[dev];
+}
+
+static std::atomic<int> g_decode_path{-1};
+static std::atomic<int> g_decode_lds_kb{0};
+int decode_path_override() { return g_decode_path.load(std::memory_order_relaxed); }
+size_t decode_lds_limit() { return (size_t)g_decode_lds_kb.load(std::memory_order_relaxed) * 1024; }
 
 int gemm_t_splits(int32_t m, int32_t rank_pad, int32_t k);   // slim_gemm.hip
 
@@ -58,8 +97,38 @@ extern "C" const char *slim_status_string(int status)
         case SLIM_ERR_ALIGN: return "a pointer is not 16-byte aligned";
         case SLIM_ERR_WORKSPACE: return "workspace is NULL or too small";
         case SLIM_ERR_HIP: return "a HIP runtime call failed";
+        case SLIM_ERR_WAIT: return "a decode call gave up waiting for its own intermediate result";
         default: return "unknown status";
     }
+}
+
+extern "C" int slim_decode_override(int32_t path, int32_t lds_kb)
+{
+    if (path < -1 || path > 3) return SLIM_ERR_SHAPE;
+    if (lds_kb != 0 && (lds_kb < 16 || lds_kb > 160)) return SLIM_ERR_SHAPE;
+    g_decode_path.store(path, std::memory_order_relaxed);
+    g_decode_lds_kb.store(lds_kb, std::memory_order_relaxed);
+    return SLIM_OK;
+}
+
+extern "C" int slim_workspace_check(void *workspace, void *stream)
+{
+    char *ws = static_cast<char *>(workspace);
+    if (!ws) {
+        void *own = nullptr;
+        const int rc = scratch_of_current_device(&own);
+        if (rc != SLIM_OK) return rc;
+        ws = static_cast<char *>(own);
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned flag = 0;
+    if (hipMemcpyAsync(&flag, ws + 8, sizeof(flag), hipMemcpyDeviceToHost, st) != hipSuccess) return SLIM_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return SLIM_ERR_HIP;
+    if (!flag) return SLIM_OK;
+    flag = 0;
+    if (hipMemcpyAsync(ws + 8, &flag, sizeof(flag), hipMemcpyHostToDevice, st) != hipSuccess) return SLIM_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return SLIM_ERR_HIP;
+    return SLIM_ERR_WAIT;
 }
 
 extern "C" int32_t slim_rank_pad(int32_t rank) { return rank <= 0 ? 0 : (rank + 31) / 32 * 32; }

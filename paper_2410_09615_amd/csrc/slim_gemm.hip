@@ -255,10 +255,13 @@ extern "C" int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, c
     const half_t *Rh = reinterpret_cast<const half_t *>(R);
     const half_t *Lh = reinterpret_cast<const half_t *>(L);
     half_t *Yh = reinterpret_cast<half_t *>(Y);
-    if (m <= 16)
+    if (m <= 16) {
+        // the decode kernels use 2^31 as "past the end of every buffer"
+        if (tl_bytes(shape.n, rank_pad) >= 0x80000000ull || tl_bytes(rank_pad, shape.k) >= 0x80000000ull) return SLIM_ERR_SHAPE;
         return launch_lowrank_decode(Xh, m, Rh, Lh, shape.n, shape.k, shape.rank, rank_pad, Yh, accumulate,
                                      reinterpret_cast<float *>(ws + p.dec_off + 256), ws + p.t16_off,
                                      reinterpret_cast<unsigned *>(ws + p.dec_off), st);
+    }
 
     if ((uint64_t)shape.n * (uint64_t)rank_pad * 2 > 0xFFFFFFFFull) return SLIM_ERR_SHAPE;
     half_t *T = reinterpret_cast<half_t *>(ws + p.t_off);
@@ -278,9 +281,10 @@ extern "C" int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, c
         g.Y = Yh + (size_t)t0 * shape.n;
         // the tallest row tile that still gives every compute unit a workgroup
         const long tt = (g.m + 127) / 128;
-        if ((long)((shape.n + 511) / 512) * tt >= 256)
+        const long cus = device_info().cus;
+        if ((long)((shape.n + 511) / 512) * tt >= cus)
             launch_dense<4>(g, 1, st);
-        else if ((long)((shape.n + 255) / 256) * tt >= 256)
+        else if ((long)((shape.n + 255) / 256) * tt >= cus)
             launch_dense<2>(g, 1, st);
         else
             launch_dense<1>(g, 1, st);

@@ -306,7 +306,7 @@ int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *s
         a.X = X + (size_t)t0 * k;
         a.T = T ? T + (size_t)t0 * rank_pad : nullptr;
         a.Y = Y + (size_t)t0 * n;
-        plan_tiles(a, 256);
+        plan_tiles(a, device_info().cus);
         const int n_rem = a.rem_split * (a.tiles_total - a.n_full);
         if (a.n_full > 0) hipLaunchKernelGGL(gemm_sparse_kernel<4>, dim3((unsigned)a.n_full), dim3(256), lds, st, a);
         if (n_rem > 0 && a.rem_split == 2)

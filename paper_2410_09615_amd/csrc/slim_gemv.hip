@@ -502,16 +502,17 @@ static int launch_decode(const DecodeArgs &a, const DecodePlan &p, hipStream_t s
 {
     const size_t lds1 = (size_t)(p.mp + 1) * (p.kc + kLdsPad) * sizeof(half_t);
     const size_t lds2 = (size_t)2 * (p.mp + 1) * (a.rank_pad + kLdsPad) * sizeof(half_t) + kP2RedBytes;
-    if (lds1 > 160 * 1024 || lds2 > 160 * 1024) return SLIM_ERR_SHAPE;
+    const DeviceInfo dev = device_info();
+    if (lds1 > dev.lds || lds2 > dev.lds) return SLIM_ERR_SHAPE;
     const long units_r = (long)(a.rank_pad / 16) * ((p.kc + p.rsl - 1) / p.rsl);
     const long tasks_w = (long)((a.n_packed + 15) / 16) * p.wsl_full;
     // blocks per chunk: at most about four per CU, and such that every wave gets
     // the same number of tasks
     const long tasks = units_r + tasks_w;
-    long resident = (160 * 1024) / (long)(lds1 > 0 ? lds1 : 1);    // blocks of this LDS size a CU holds
+    long resident = (long)dev.lds / (long)(lds1 > 0 ? lds1 : 1);    // blocks of this LDS size a CU holds
     if (resident > 4) resident = 4;
     if (resident < 1) resident = 1;
-    const long cap = 256 * resident / p.nch > 0 ? 256 * resident / p.nch : 1;
+    const long cap = dev.cus * resident / p.nch > 0 ? dev.cus * resident / p.nch : 1;
     const long per_wave = (tasks + cap * kDecWaves - 1) / (cap * kDecWaves);
     long b1 = (tasks + per_wave * kDecWaves - 1) / (per_wave * kDecWaves);
     if (b1 < 1) b1 = 1;
@@ -546,15 +547,14 @@ static void fill_plan(DecodeArgs &a, const DecodePlan &p)
     a.slots = p.slots;
 }
 
-// The one-launch kernel without its packed items where the geometry allows it (SLIM_DECODE_PATH =
-// parts keeps the two-part kernels, as for slim_linear_gemv); T16: the one-launch path's pieces of T.
+// The one-launch kernel without its packed items where the geometry allows it (slim_decode_override with
+// path 0 keeps the two-part kernels, as for slim_linear_gemv); T16: the one-launch path's pieces of T.
 int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t *L, int n, int k, int rank, int rank_pad,
                           half_t *Y, int accumulate, float *T, void *T16, unsigned *ctrl, hipStream_t st)
 {
     {
         const FusedPlan f = plan_fused(n, k, rank_pad, m);
-        const char *env = getenv("SLIM_DECODE_PATH");
-        if (f.ok && f.n_r > 0 && !(env && !strcmp(env, "parts"))) {
+        if (f.ok && f.n_r > 0 && decode_path_override() != 0) {
             slim_layer lay{};
             lay.shape = slim_shape{n, k, rank};
             lay.L = reinterpret_cast<const slim_half *>(L);
@@ -599,7 +599,7 @@ constexpr int kMaxDevices = 64;
 static std::atomic<void *> g_scratch_ptr[kMaxDevices];
 
 // Address of `scratch` on the current device, looked up once per device.
-static int scratch_of_current_device(void **out)
+int scratch_of_current_device(void **out)
 {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SLIM_ERR_HIP;
@@ -610,6 +610,22 @@ static int scratch_of_current_device(void **out)
     }
     *out = p;
     return SLIM_OK;
+}
+
+// 2: one launch, 1: its roles as two launches, 3: the Y role alone (test of the bounded wait), -1: the two-launch kernels
+static int decode_mode(const FusedPlan &f)
+{
+    const int forced = decode_path_override();
+    if (!f.ok || forced == 0) return -1;
+    return forced == 1 ? 1 : (forced == 3 ? 3 : 2);
+}
+
+// The decode kernels address every buffer with 32-bit byte offsets and use 2^31 as "past the end".
+static bool decode_buffers_addressable(int n, int k, int rank_pad, int m)
+{
+    const uint64_t lim = 0x80000000ull;
+    return pk_qbytes(n, k) < lim && tl_bytes(n, rank_pad) < lim && tl_bytes(rank_pad, k) < lim &&
+           (uint64_t)m * (uint64_t)k * 2 < lim && (uint64_t)m * (uint64_t)n * 2 < lim;
 }
 
 // own_scratch: the workspace is the library's array; it has to hold what the chosen path uses
@@ -643,6 +659,7 @@ int slim::linear_gemv(const slim_layer *layer_in, const slim_half *X, int32_t m,
     if (!q4 && s.rank > 0 && (!layer->L || !layer->R)) return SLIM_ERR_NULL;
     if (s.n < 1 || s.k < 128 || s.k % 128 || s.rank < 0 || m < 1 || m > kMaxTokens) return SLIM_ERR_SHAPE;
     if (layer->rank_pad != slim_rank_pad(s.rank)) return SLIM_ERR_SHAPE;
+    if (!decode_buffers_addressable(s.n, s.k, layer->rank_pad, m)) return SLIM_ERR_SHAPE;
     if (!aligned16(layer->qvals) || !aligned16(layer->meta) || !aligned16(layer->scale) || !aligned16(X) ||
         !aligned16(Y) || (!q4 && (!aligned16(layer->L) || !aligned16(layer->R))) || !aligned16(workspace))
         return SLIM_ERR_ALIGN;
@@ -653,15 +670,10 @@ int slim::linear_gemv(const slim_layer *layer_in, const slim_half *X, int32_t m,
 
     char *ws = nullptr;
     // Path: one launch where X fits the LDS of a compute unit, else the two-part
-    // kernels.  SLIM_DECODE_PATH = parts | roles | fused overrides (measurement).
+    // kernels; slim_decode_override forces one (tests, measurement).
     {
         const FusedPlan f = plan_fused(s.n, s.k, layer->rank_pad, m);
-        int mode = f.ok ? 2 : -1;
-        if (const char *env = getenv("SLIM_DECODE_PATH")) {
-            if (!strcmp(env, "parts")) mode = -1;
-            if (!strcmp(env, "roles") && f.ok) mode = 1;
-            if (!strcmp(env, "fused") && f.ok) mode = 2;
-        }
+        const int mode = decode_mode(f);
         // the one-launch kernel uses the head of the workspace only (control words and T)
         if (own_scratch) {
             if (workspace_bytes < (mode > 0 ? w.dec_off + w.dec_bytes : w.total)) return SLIM_ERR_WORKSPACE;
@@ -712,14 +724,9 @@ extern "C" int slim_decode_plan(const slim_layer *layer, int32_t m, int32_t *out
     if (s.n < 1 || s.k < 128 || s.k % 128 || s.rank < 0 || m < 1 || m > kMaxTokens) return SLIM_ERR_SHAPE;
     if (layer->rank_pad != slim_rank_pad(s.rank)) return SLIM_ERR_SHAPE;
     const FusedPlan f = plan_fused(s.n, s.k, layer->rank_pad, m);
-    int mode = f.ok ? 2 : -1;
-    if (const char *env = getenv("SLIM_DECODE_PATH")) {
-        if (!strcmp(env, "parts")) mode = -1;
-        if (!strcmp(env, "roles") && f.ok) mode = 1;
-        if (!strcmp(env, "fused") && f.ok) mode = 2;
-    }
+    const int mode = decode_mode(f);
     for (int i = 0; i < 12; ++i) out[i] = 0;
-    out[0] = mode > 0 ? mode : 0;
+    out[0] = mode > 0 ? (mode == 3 ? 2 : mode) : 0;
     if (mode > 0) {
         out[1] = f.n_r + f.ygrid;
         out[2] = (f.waves + f.helpers) * kWave;

@@ -8,7 +8,7 @@
 //          take units of 16 ranks x 256 inputs (R and X straight from memory
 //          into registers, dense 16 x 16 x 32 matrix instruction), add their
 //          partial tiles in LDS, and wavefront 0 stores the tile as fp16 in
-//          16-byte pieces {epoch of this call, 0, four ranks of one token},
+//          16-byte pieces {epoch of this call, four ranks of one token, checksum},
 //          written through to memory.  These workgroups wait for nothing.
 //  Y role  (all others) S wavefronts per tile of 16 output rows.  Wavefront s
 //          of a tile takes the halves (512 inputs) s, s + S, ... of the packed
@@ -31,7 +31,8 @@
 // Progress: workgroups start in the order of their index, so every R-role
 // workgroup has started before any Y-role workgroup can wait for it, and the
 // wait is bounded anyway (a helper gives up after kSpinLimit reads and records
-// that in the control words; the call then returns wrong numbers, not a hang).
+// that in the control words and puts NaN in place of the T it did not get, so the
+// outputs of its workgroup are NaN: a failed call cannot pass for a result).
 //
 // The same kernel also runs the roles as two launches (mode 0, then mode 1).
 //
@@ -49,6 +50,7 @@ constexpr int kScopeDevice = 16;      // cache policy of a buffer access: device
 constexpr int kMaxShares = 4;         // R role: at most this many shares of the inputs (planes of T)
 constexpr int kFusedWavesPerSimd = 4;   // the kernel is compiled for 128 registers: 16 wavefronts per compute unit
 constexpr int kSpinLimit = 1 << 16;
+constexpr int kSpinLimitShort = 256;   // test of the bounded wait (mode bit 3)
 constexpr int kWaitVm0 = 0x0F70;       // s_waitcnt vmcnt(0) (expcnt, lgkmcnt left alone): all vector memory loads of the wavefront are back
 constexpr uint32_t kNowhere = 0x80000000u;       // byte offset past the end of every buffer here (all are < 2 GiB)
 
@@ -64,7 +66,7 @@ struct FusedArgs {
     const half_t *Ls;
     const half_t *X;
     half_t *Y;
-    uint4_t *T;          // pieces {epoch, 0, 4 ranks fp16} [kh][16][rank_pad / 4]: T is the sum of the planes
+    uint4_t *T;          // pieces {epoch, 4 ranks fp16, checksum} [kh][16][rank_pad / 4]: T is the sum of the planes
     unsigned *err;       // set to 1 when a wait gave up
     unsigned epoch;      // this call's number (top bit clear, never 0), or
     const unsigned *epoch_ptr;   // under stream capture: where a small kernel ahead of this one has put it (top bit set)
@@ -80,6 +82,7 @@ struct FusedArgs {
     int helpers;         // wavefronts of a workgroup that only fetch T (Y role)
     int mode;            // 0: R role only; 1: Y role only, T complete; 2: both roles in this grid;
                          // + 4 (low-rank term alone, both roles): add to what Y holds
+                         // + 8 (test of the bounded wait): the helpers give up after kSpinLimitShort polls
 };
 
 // The number that tags this call's pieces of T.  A launch argument normally; a launch that is
@@ -96,6 +99,18 @@ __global__ void decode_epoch_bump_kernel(unsigned *ctr)
     const unsigned v = (*ctr + 1u) & 0x7FFFFFFFu;
     *ctr = v ? v : 1u;
 }
+
+// A piece of T: {epoch, two dwords of four fp16 ranks, epoch ^ dword ^ dword}.  The reader accepts it only if
+// the first dword is this call's epoch and the last one is the checksum of the three before it, so a piece
+// whose dwords come from two different stores (should a 128-bit store ever become visible in parts) is
+// taken for "not there yet" and read again, unless the old and the new data have the same checksum --
+// which they do when they are the same data.  Only single dwords need to be atomic for that.
+__device__ __forceinline__ bool piece_valid(const uint4_t &pc, unsigned epoch)
+{
+    return pc[0] == epoch && pc[3] == (pc[0] ^ pc[1] ^ pc[2]);
+}
+constexpr unsigned short kHalfNaNBits = 0x7E00;
+#define kHalfNaN __builtin_bit_cast(half_t, kHalfNaNBits)
 
 // ---- R role ----
 template <bool Q4>
@@ -201,7 +216,8 @@ __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb
         const rsrc_t t_rs = make_rsrc(a.T, (uint32_t)a.kh * kMaxTokens * (rp / 4) * 16u);
         const uint32_t off = (((uint32_t)kh * kMaxTokens + lx) * (rp / 4) + 4 * rt + ly) * 16u;
         typedef unsigned int store4_t __attribute__((__vector_size__(16)));
-        const store4_t piece = {call_epoch(a), 0u, hb[0], hb[1]};
+        const unsigned ep = call_epoch(a);
+        const store4_t piece = {ep, hb[0], hb[1], ep ^ hb[0] ^ hb[1]};
         __builtin_amdgcn_raw_buffer_store_b128(piece, t_rs, (int)off, 0, kScopeDevice);
     }
 }
@@ -378,6 +394,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
         const int pairs = a.m * qpr;
         int spins = 0;
         bool gave_up = false;
+        const int spin_limit = (a.mode & 8) ? kSpinLimitShort : kSpinLimit;
         const unsigned epoch = call_epoch(a);
         auto piece_off = [&](int pair, int share) {
             const int row = pair / qpr, q = pair - row * qpr;
@@ -401,9 +418,9 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
                     for (int i = 0; i < PB; ++i)
 #pragma unroll
                         for (int h = 0; h < KH; ++h)
-                            all_there = all_there && (p0 + i * hn >= pairs || pc[i * KH + h][0] == epoch);
+                            all_there = all_there && (p0 + i * hn >= pairs || piece_valid(pc[i * KH + h], epoch));
                     if (!all_there) {
-                        if (++spins >= kSpinLimit) {
+                        if (++spins >= spin_limit) {
                             gave_up = true;
                             break;
                         }
@@ -415,7 +432,9 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
                     const int pair = p0 + i * hn;
                     half4_t sum = {0, 0, 0, 0};
 #pragma unroll
-                    for (int h = 0; h < KH; ++h) sum += __builtin_bit_cast(half4_t, uint2_t{pc[i * KH + h][2], pc[i * KH + h][3]});
+                    for (int h = 0; h < KH; ++h) sum += __builtin_bit_cast(half4_t, uint2_t{pc[i * KH + h][1], pc[i * KH + h][2]});
+                    // a wait that gave up must not pass for a result: NaN in T makes every output of this workgroup NaN
+                    if (gave_up) sum = half4_t{kHalfNaN, kHalfNaN, kHalfNaN, kHalfNaN};
                     if (pair < pairs) {
                         const int row = pair / qpr, q = pair - row * qpr;
                         *reinterpret_cast<half4_t *>(t_lds + row * ldt + 4 * q) = sum;
@@ -430,7 +449,7 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
                 fetch(std::integral_constant<int, 2>{});
             else
                 fetch(std::integral_constant<int, 4>{});
-            if ((gave_up || spins >= kSpinLimit) && a.err) __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((gave_up || spins >= spin_limit) && a.err) __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         // the barriers of the working wavefronts: T, then those of every round
         if (rp > 0) __syncthreads();
@@ -578,7 +597,7 @@ __global__ __launch_bounds__(kFusedMaxThreads, kFusedWavesPerSimd) void decode_f
     extern __shared__ __attribute__((aligned(16))) half_t lds[];
     if (a.mode == 0) {
         role_r<Q4>(a, lds, blockIdx.x);
-    } else if (a.mode == 1) {
+    } else if ((a.mode & 3) == 1) {
         role_y<Q4, LR>(a, lds, blockIdx.x, gridDim.x);
     } else if ((int)blockIdx.x < a.n_r) {
         role_r<Q4>(a, lds, blockIdx.x);
@@ -593,7 +612,7 @@ static int pad_tokens16(int m) { return m <= 1 ? 1 : (m <= 4 ? 4 : (m <= 8 ? 8 :
 // chunks of 4096, 2048 or 1024 inputs in two buffers; the shares of the R role;
 // the largest S (wavefronts per row tile) with which every workgroup is
 // resident at once.
-static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
+static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves, const DeviceInfo &dev, size_t lds_limit)
 {
     FusedPlan p{};
     p.mp = pad_tokens16(m);
@@ -601,12 +620,10 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
     p.waves = waves;
     const long wtiles = (n + 15) / 16;
     const int kcs[4] = {p.kpad, 4096, 2048, 1024};
-    // LDS of a compute unit; SLIM_DECODE_LDS_KB lowers it (tests: chunks on small layers)
-    size_t lds_cap = 160 * 1024;
-    if (const char *env = getenv("SLIM_DECODE_LDS_KB")) {
-        const long kb = atol(env);
-        if (kb >= 16 && kb <= 160) lds_cap = (size_t)kb * 1024;
-    }
+    // LDS of a compute unit; slim_decode_override can lower what the geometry plans with (tests: chunks on small layers)
+    const size_t lds_cu = dev.lds;
+    size_t lds_cap = lds_cu;
+    if (lds_limit >= 16 * 1024 && lds_limit < lds_cap) lds_cap = lds_limit;
     for (int ci = 0; ci < 4 && !p.ok; ++ci) {
         const int kc = kcs[ci];
         if (ci > 0 && kc >= p.kpad) continue;
@@ -642,12 +659,12 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
             if (lds > lds_cap) continue;
             // workgroups a compute unit holds
             long per_cu = 4 * kFusedWavesPerSimd / total;
-            if (per_cu > (long)(160 * 1024 / lds)) per_cu = (long)(160 * 1024 / lds);
+            if (per_cu > (long)(lds_cu / lds)) per_cu = (long)(lds_cu / lds);
             const long wgs = (wtiles + tpw - 1) / tpw;
             int kh = kh_max;
-            while (kh > 1 && wgs + (long)(rank_pad / 16) * kh > 256 * per_cu) kh /= 2;
+            while (kh > 1 && wgs + (long)(rank_pad / 16) * kh > dev.cus * per_cu) kh /= 2;
             const int n_r = (rank_pad / 16) * kh;
-            if (wgs + n_r <= 256 * per_cu) {
+            if (wgs + n_r <= dev.cus * per_cu) {
                 p.S = S;
                 p.ygrid = (int)wgs;
                 p.lds = lds;
@@ -671,8 +688,31 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves)
 // per compute unit where the LDS permits.
 FusedPlan plan_fused(int n, int k, int rank_pad, int m)
 {
-    const FusedPlan a = plan_fused_waves(n, k, rank_pad, m, 8);
-    return a.ok ? a : plan_fused_waves(n, k, rank_pad, m, 4);
+    // The plan is a pure function of these seven numbers; a decode loop asks for the same few over and
+    // over, so each thread keeps the last ones it computed.
+    struct Key {
+        int n, k, rank_pad, m, cus;
+        size_t lds, limit;
+        bool operator==(const Key &o) const
+        {
+            return n == o.n && k == o.k && rank_pad == o.rank_pad && m == o.m && cus == o.cus && lds == o.lds && limit == o.limit;
+        }
+    };
+    constexpr int kSlots = 16;
+    thread_local Key keys[kSlots];
+    thread_local FusedPlan plans[kSlots];
+    thread_local int used = 0, next = 0;
+    const DeviceInfo dev = device_info();
+    const Key key{n, k, rank_pad, m, dev.cus, dev.lds, decode_lds_limit()};
+    for (int i = 0; i < used; ++i)
+        if (keys[i] == key) return plans[i];
+    FusedPlan p = plan_fused_waves(n, k, rank_pad, m, 8, dev, key.limit);
+    if (!p.ok) p = plan_fused_waves(n, k, rank_pad, m, 4, dev, key.limit);
+    keys[next] = key;
+    plans[next] = p;
+    next = (next + 1) % kSlots;
+    if (used < kSlots) ++used;
+    return p;
 }
 
 static std::atomic<unsigned> g_epoch{0};
@@ -728,7 +768,12 @@ int launch_decode_fused(const slim_layer *layer, const half_t *X, int m, half_t 
         else
             hipLaunchKernelGGL(decode_fused_kernel<false>, dim3(grid), blk, p.lds, st, a);
     };
-    if (mode == 2 || p.n_r == 0) {
+    if (mode == 3 && p.n_r > 0) {
+        // test of the bounded wait: the Y role alone, so the pieces of T it waits for never come; the
+        // helpers give up after a few polls, the outputs are NaN and the error word is set
+        a.mode = 1 | 8;
+        launch((unsigned)p.ygrid);
+    } else if (mode == 2 || p.n_r == 0) {
         a.mode = p.n_r == 0 ? 1 : (lowrank == 2 ? 6 : 2);
         launch((unsigned)(p.n_r + p.ygrid));
     } else {

@@ -156,6 +156,22 @@ __device__ __forceinline__ uint2_t load8(rsrc_t r, uint32_t lane_off, uint32_t u
 
 #endif
 
+// What the planners need to know of the device that is current: compute units and LDS bytes per compute
+// unit, read once per device from its properties (the nominal MI355X figures, 256 and 160 KiB, where no
+// device can be asked: the planners are host logic and also run without one).
+struct DeviceInfo {
+    int cus;
+    size_t lds;
+};
+DeviceInfo device_info();
+
+// Process-wide test and measurement control of the decode geometry (slim_decode_override).
+int decode_path_override();      // -1: automatic, 0: two-launch kernels, 1: the roles as two launches, 2: one launch
+size_t decode_lds_limit();       // 0: the device's LDS; else bytes the one-launch geometry may plan with
+
+// Device address of the library's own scratch array on the current device (slim_gemv.hip).
+int scratch_of_current_device(void **out);
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? SLIM_OK : SLIM_ERR_HIP; }

@@ -31,3 +31,12 @@ def read_golden(name):
 @pytest.fixture(scope="session")
 def golden_dir():
     return GOLDEN
+
+
+@pytest.fixture
+def decode_override():
+    """slim_decode_override for the duration of a test (host-side control of the decode launch geometry);
+    the automatic choice is restored afterwards."""
+    from paper_2410_09615_amd import binding as B
+    yield B.slim_decode_override
+    B.slim_decode_override("auto", 0)

@@ -201,20 +201,16 @@ def _forward_case(shape, m, fn, seed=0, rows=None, bits=16):
     return _check_forward(layer, ref, Lr, Rr, X, fn, rows, c_t, f"{fn.__name__} {shape.name} m={m} bits={bits}")
 
 
-# slim_linear_gemv has a one-launch path (layers whose X fits the LDS of a compute
-# unit) and a two-part path (everything else); SLIM_DECODE_PATH forces one of
-# them, "roles" runs the one-launch kernel's two roles as two launches.
+# slim_linear_gemv has a one-launch path (wherever its geometry fits) and a two-part path (everything
+# else); slim_decode_override forces one of them, "roles" runs the one-launch kernel's two roles as two launches.
 @pytest.fixture(params=["auto", "parts", "roles", "fused"])
-def decode_path(request, monkeypatch):
-    if request.param == "auto":
-        monkeypatch.delenv("SLIM_DECODE_PATH", raising=False)
-    else:
-        monkeypatch.setenv("SLIM_DECODE_PATH", request.param)
+def decode_path(request, decode_override):
+    decode_override(request.param)
     return request.param
 
 
 @pytest.mark.parametrize("m", [1, 16])
-def test_gemv_launch_geometries_agree(m, monkeypatch):
+def test_gemv_launch_geometries_agree(m, decode_override):
     """The same call through the three decode geometries (one launch, its two roles as two
     launches, the two-launch kernels): the results differ only by reassociation of fp32 sums,
     by the fp16 rounding of T's shares on the one-launch path and by the final rounding of Y
@@ -227,7 +223,7 @@ def test_gemv_launch_geometries_agree(m, monkeypatch):
     Xd = X.to(DEV)
     out = {}
     for path in ("parts", "roles", "fused"):
-        monkeypatch.setenv("SLIM_DECODE_PATH", path)
+        decode_override(path)
         out[path] = B.slim_linear_gemv(layer, Xd).float().cpu().numpy().astype(np.float64)
     assert np.array_equal(out["roles"], out["fused"])
     assert _relerr(out["parts"], out["fused"]) <= 6e-4
@@ -266,11 +262,10 @@ def test_gemv_full_size_all_rows(shape, m, decode_path):
 
 @pytest.mark.parametrize("n,k,r,m,lds_kb", [(1000, 4096, 100, 16, 96), (1000, 4096, 100, 16, 72), (520, 11008, 410, 8, 64),
                                             (300, 2176, 37, 5, 24), (2049, 8192, 33, 16, 160), (64, 3072, 0, 16, 70)])
-def test_gemv_one_launch_with_x_in_chunks(n, k, r, m, lds_kb, monkeypatch):
+def test_gemv_one_launch_with_x_in_chunks(n, k, r, m, lds_kb, decode_override):
     """The one-launch kernel with X streamed through LDS in chunks (a smaller LDS
     budget forces the chunks on layers the oracle finishes quickly)."""
-    monkeypatch.setenv("SLIM_DECODE_PATH", "fused")
-    monkeypatch.setenv("SLIM_DECODE_LDS_KB", str(lds_kb))
+    decode_override("fused", lds_kb)
     plan = B.slim_decode_plan(n, k, r, m)
     assert plan["path"] == 2 and plan["chunks"] > 1            # the case really runs what it is meant to
     assert _forward_case(_shape(n, k, r), m, B.slim_linear_gemv, seed=13) <= TOL_Y
@@ -294,7 +289,34 @@ def test_gemv_never_gives_up_waiting():
     assert int(ws.view(torch.int32)[2]) == 0
 
 
-def test_gemv_repeated_calls_one_workspace(monkeypatch):
+def test_a_wait_that_gives_up_is_loud(decode_override):
+    """The bounded wait of the one-launch kernel, forced from the host to run out (only the waiting half of the
+    kernel is launched, with a short poll limit; every wavefront ends normally): the outputs are NaN, not
+    plausible numbers, the workspace's error word is set, slim_workspace_check reports it once and clears
+    it, and the next ordinary call on the same workspace is correct."""
+    shape = _shape(640, 1024, 51)
+    W, L, R, X = wl.make_layer(shape, 4, seed=17)
+    layer = _gpu_layer(W, L, R)
+    ref = O.compress(W.numpy())
+    ws = B.alloc_workspace(layer, 4)
+    B.slim_workspace_check(ws)                                  # a fresh workspace is clean
+    decode_override("wait_test")
+    Y = B.slim_linear_gemv(layer, X.to(DEV), workspace=ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(Y).all())
+    assert int(ws.view(torch.int32)[2]) == 1
+    with pytest.raises(B.SlimError) as e:
+        B.slim_workspace_check(ws)
+    assert e.value.status == B.SLIM_ERR_WAIT
+    B.slim_workspace_check(ws)                                  # reported once, then clear again
+    decode_override("auto")
+    Y = B.slim_linear_gemv(layer, X.to(DEV), workspace=ws)
+    torch.cuda.synchronize()
+    _assert_layer_close(Y, ref, L.numpy(), R.numpy(), X, what="the call after a wait that gave up")
+    B.slim_workspace_check(ws)
+
+
+def test_gemv_repeated_calls_one_workspace(decode_override):
     """One workspace, many calls: the paths alternate, the token count changes, and
     every call must give the result of a call on a fresh workspace (no state of an
     earlier call may leak: flags, epochs, the T buffers)."""
@@ -306,7 +328,7 @@ def test_gemv_repeated_calls_one_workspace(monkeypatch):
     Xd = X.to(DEV)
     for i, (path, m) in enumerate([("fused", 16), ("parts", 3), ("fused", 3), ("fused", 1), ("roles", 16), ("parts", 16),
                                    ("fused", 8), ("fused", 16), ("parts", 1), ("fused", 2)]):
-        monkeypatch.setenv("SLIM_DECODE_PATH", path)
+        decode_override(path)
         Y = B.slim_linear_gemv(layer, Xd[:m].contiguous(), workspace=ws)
         torch.cuda.synchronize()
         _assert_layer_close(Y, ref_layer, L.numpy(), R.numpy(), X[:m], what=f"call {i} ({path}, m={m})")
@@ -522,9 +544,8 @@ def test_gemm_q4_adapters_full_size_sampled_rows(shape, m):
 
 
 @pytest.mark.parametrize("n,k,r,m,lds_kb", [(1000, 4096, 100, 16, 96), (520, 11008, 410, 8, 64), (300, 2176, 37, 5, 24)])
-def test_gemv_q4_adapters_with_x_in_chunks(n, k, r, m, lds_kb, monkeypatch):
-    monkeypatch.setenv("SLIM_DECODE_PATH", "fused")
-    monkeypatch.setenv("SLIM_DECODE_LDS_KB", str(lds_kb))
+def test_gemv_q4_adapters_with_x_in_chunks(n, k, r, m, lds_kb, decode_override):
+    decode_override("fused", lds_kb)
     plan = B.slim_decode_plan(n, k, r, m, 4)
     assert plan["path"] == 2 and plan["chunks"] > 1
     assert _forward_case_q4(_shape(n, k, r), m, B.slim_linear_gemv, seed=17) <= TOL_Y
@@ -551,13 +572,13 @@ def test_q4_adapters_change_the_result_as_much_as_the_quantization_says():
 @pytest.mark.parametrize("m", [1, 16, 300])
 @pytest.mark.parametrize("accumulate", [False, True])
 @pytest.mark.parametrize("path", ["auto", "parts"])
-def test_lowrank(m, accumulate, path, monkeypatch):
+def test_lowrank(m, accumulate, path, decode_override):
     """Up to 16 tokens the call is the one-launch decode kernel without its packed items; "parts"
     keeps the two-part kernels that serve where that geometry does not fit."""
     if path == "parts":
         if m > 16:
             pytest.skip("the decode paths differ up to 16 tokens only")
-        monkeypatch.setenv("SLIM_DECODE_PATH", "parts")
+        decode_override("parts")
     n, k, r = 640, 1280, 51
     L, R = wl.make_adapters(n, k, r, 21, 22)
     X = wl.make_activations(m, k, True, 23, 24)
@@ -659,13 +680,10 @@ def test_quant_search_rows_on_a_row_whose_two_best_candidates_tie_exactly():
 # ---- one workspace, several layers ---------------------------------------------------
 
 @pytest.mark.parametrize("path", ["auto", "parts", "roles", "fused"])
-def test_gemv_one_workspace_shared_by_layers_of_different_rank(path, monkeypatch):
+def test_gemv_one_workspace_shared_by_layers_of_different_rank(path, decode_override):
     """Nothing is carried between calls: layers of different shape and rank, fp16 and 4-bit
     adapters, take turns on one workspace, on every decode geometry."""
-    if path == "auto":
-        monkeypatch.delenv("SLIM_DECODE_PATH", raising=False)
-    else:
-        monkeypatch.setenv("SLIM_DECODE_PATH", path)
+    decode_override(path)
     cases = []
     for i, (n, k, r) in enumerate([(640, 1024, 51), (300, 2176, 37), (1000, 4096, 100), (48, 4096, 1024)]):
         shape = _shape(n, k, r)

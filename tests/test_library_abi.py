@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_status_strings():
-    for code in (0, -1, -2, -3, -4, -5):
+    for code in (0, -1, -2, -3, -4, -5, -6):
         assert B.slim_status_string(code)
     assert B.slim_status_string(-99) == "unknown status"
 
@@ -113,13 +113,12 @@ def test_input_quant_validation():
     assert lib.slim_input_quant_fp8(None, 16, None, None, None, 0, None) == B.SLIM_ERR_NULL
 
 
-def test_decode_plan_of_the_configured_shapes(monkeypatch):
+def test_decode_plan_of_the_configured_shapes(decode_override):
     """Host logic of slim_linear_gemv: every configured layer takes the one-launch path at every token
     count, within what a compute unit holds (1024 threads, 160 KiB of LDS, 16 wavefronts), with all
     workgroups resident at once and every row tile covered."""
     from paper_2410_09615_amd import workloads as wl
-    monkeypatch.delenv("SLIM_DECODE_PATH", raising=False)
-    monkeypatch.delenv("SLIM_DECODE_LDS_KB", raising=False)
+    decode_override("auto", 0)
     for shp in (wl.TINY, wl.L7B_ATTN, wl.L7B_UP, wl.L7B_DOWN, wl.L13B_ATTN, wl.L13B_UP, wl.L70B_ATTN, wl.L70B_UP):
         for m in (1, 2, 4, 8, 16):
             p = B.slim_decode_plan(shp.n, shp.k, shp.r, m)
@@ -136,11 +135,13 @@ def test_decode_plan_of_the_configured_shapes(monkeypatch):
             if p["chunks"] > 1:
                 assert B.slim_rank_pad(shp.r) <= p["chunk_inputs"]        # T takes the place of an X buffer
     # forced paths and errors
-    monkeypatch.setenv("SLIM_DECODE_PATH", "parts")
+    decode_override("parts")
     assert B.slim_decode_plan(4096, 4096, 410, 1)["path"] == 0
-    monkeypatch.setenv("SLIM_DECODE_PATH", "roles")
+    decode_override("roles")
     assert B.slim_decode_plan(4096, 4096, 410, 1)["path"] == 1
-    monkeypatch.delenv("SLIM_DECODE_PATH")
+    decode_override("auto")
+    for bad in ((4, 0), (-2, 0), (0, 8), (0, 161)):
+        assert B.lib().slim_decode_override(*bad) == B.SLIM_ERR_SHAPE
     with pytest.raises(B.SlimError):
         B.slim_decode_plan(4096, 4096, 410, 17)
     with pytest.raises(B.SlimError):
@@ -148,7 +149,7 @@ def test_decode_plan_of_the_configured_shapes(monkeypatch):
     # a reduced LDS budget (what the chunk tests use) forces chunks
     for n, k, r, m, lds_kb in [(1000, 4096, 100, 16, 96), (1000, 4096, 100, 16, 72), (520, 11008, 410, 8, 64),
                                (300, 2176, 37, 5, 24), (2049, 8192, 33, 16, 160), (64, 3072, 0, 16, 70)]:
-        monkeypatch.setenv("SLIM_DECODE_LDS_KB", str(lds_kb))
+        decode_override("auto", lds_kb)
         p = B.slim_decode_plan(n, k, r, m)
         assert p["path"] == 2 and p["chunks"] > 1 and p["lds_bytes"] <= lds_kb * 1024, (n, k, r, m, lds_kb)
 
@@ -163,9 +164,58 @@ def test_static_scratch_call_validates_on_the_host():
     assert lib.slim_linear_gemv_static(ctypes.byref(layer), a, 0, a, None) == B.SLIM_ERR_SHAPE
     assert lib.slim_linear_gemv_static(ctypes.byref(layer), a, 17, a, None) == B.SLIM_ERR_SHAPE
     assert lib.slim_linear_gemv_static(ctypes.byref(layer), ctypes.c_void_p(0x1004), 1, a, None) == B.SLIM_ERR_ALIGN
-    # a layer whose decode call needs partial sums beyond the array: 16 tokens x 2^20 rows of floats per slot
-    huge = B.slim_layer(B.slim_shape(1 << 20, 8192, 0), 0x1000, 0x1000, 0x1000, None, None, 0)
+    # a layer whose decode call needs partial sums beyond the array: 16 tokens x 600000 rows of floats per slot
+    huge = B.slim_layer(B.slim_shape(600000, 8192, 0), 0x1000, 0x1000, 0x1000, None, None, 0)
     out = ctypes.c_size_t()
     assert lib.slim_workspace_bytes(ctypes.byref(huge), 16, out) == 0 and out.value > (8 << 20)
-    assert B.slim_decode_plan(1 << 20, 8192, 0, 16)["path"] == 0
+    assert B.slim_decode_plan(600000, 8192, 0, 16)["path"] == 0
     assert lib.slim_linear_gemv_static(ctypes.byref(huge), a, 16, a, None) == B.SLIM_ERR_WORKSPACE
+
+
+def test_decode_refuses_buffers_the_kernels_cannot_address():
+    """The decode kernels use 32-bit byte offsets with 2^31 as "past the end": a layer with a buffer of 2 GiB
+    or more is refused on the host (slim_linear_gemv and slim_lowrank alike), one just below is planned."""
+    lib = B.lib()
+    a = ctypes.c_void_p(0x1000)
+    big = B.slim_layer(B.slim_shape(1 << 20, 8192, 0), 0x1000, 0x1000, 0x1000, None, None, 0)      # 2 GiB of codes
+    assert lib.slim_linear_gemv(ctypes.byref(big), a, 1, a, a, 1 << 40, None) == B.SLIM_ERR_SHAPE
+    wide = B.slim_shape(1 << 20, 1024, 1024)                                                       # L: 2 GiB
+    assert lib.slim_lowrank(a, 4, a, a, wide, 1024, a, 0, a, 1 << 40, None) == B.SLIM_ERR_SHAPE
+    assert B.slim_decode_plan((1 << 20) - 32, 8192, 0, 1)["path"] in (0, 2)
+
+
+def test_decode_plan_invariants_over_random_shapes():
+    """Host logic only: for random layers and token counts the plan either declines (two-launch kernels) or
+    describes a launch that fits a compute unit and covers every row tile and every input; the workspace
+    and packed sizes are consistent with it."""
+    import random
+    rnd = random.Random(7)
+    for _ in range(400):
+        n = rnd.choice([rnd.randint(1, 300), rnd.randint(1, 40000)])
+        k = 128 * rnd.randint(1, 120)
+        r = rnd.choice([0, rnd.randint(1, min(n, k, 1100))])
+        m = rnd.randint(1, 16)
+        bits = rnd.choice([16, 4])
+        p = B.slim_decode_plan(n, k, r, m, bits)
+        rp = B.slim_rank_pad(r)
+        layer = B.slim_layer(B.slim_shape(n, k, r), None, None, None, None, None, rp, bits, None, None, None, None)
+        out = ctypes.c_size_t()
+        assert B.lib().slim_workspace_bytes(ctypes.byref(layer), m, out) == 0
+        assert out.value >= 256 + 3 * 16 * rp * 4 and out.value % 256 == 0
+        sz = B.slim_packed_sizes(n, k, r)
+        assert sz["qvals"] == 2 * sz["meta"] == ((n + 31) // 32) * ((k + 127) // 128) * 1024
+        assert sz["rank_pad"] == rp and sz["L"] == ((n + 31) // 32 * 32) * rp * 2 and sz["R"] == rp * k * 2
+        if p["path"] == 0:
+            continue
+        assert p["path"] == 2
+        assert p["threads"] == 64 * (p["working_wavefronts"] + p["helper_wavefronts"]) <= 1024
+        assert 0 < p["lds_bytes"] <= 160 * 1024
+        per_cu = min(16 // (p["threads"] // 64), (160 * 1024) // p["lds_bytes"])
+        assert per_cu >= 1 and p["workgroups"] == p["r_workgroups"] + p["y_workgroups"] <= 256 * per_cu
+        assert p["r_workgroups"] == (rp // 16) * p["r_shares"] <= 512 and (p["r_shares"] in (1, 2, 4) or rp == 0)
+        tpw = p["working_wavefronts"] // p["wavefronts_per_row_tile"]
+        assert tpw >= 1 and p["working_wavefronts"] % p["wavefronts_per_row_tile"] == 0
+        assert p["y_workgroups"] * tpw >= (n + 15) // 16
+        assert p["chunk_inputs"] % 1024 == 0 and p["chunk_inputs"] * p["chunks"] >= k
+        if p["chunks"] > 1:
+            assert rp <= p["chunk_inputs"] and (p["chunk_inputs"] // 512) % p["wavefronts_per_row_tile"] == 0

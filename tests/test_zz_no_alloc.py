@@ -59,12 +59,13 @@ def test_static_scratch_matches_the_workspace_call_on_calls_in_a_row():
         torch.cuda.synchronize()
         assert torch.equal(Y, Yw)
         assert _relerr(Y.cpu().numpy(), Yref) <= TOL_Y
+    B.slim_workspace_check(None)                          # no call on the library's array gave up waiting
 
 
-def test_static_scratch_on_the_two_launch_kernels(monkeypatch):
+def test_static_scratch_on_the_two_launch_kernels(decode_override):
     """The two-launch kernels keep partial sums and T (fp32, atomic adds: the last bits differ from call to
     call) in the array: a call, then a smaller one."""
-    monkeypatch.setenv("SLIM_DECODE_PATH", "parts")
+    decode_override("parts")
     for n, k, r, m, seed in ((1000, 4096, 100, 16, 31), (300, 1024, 37, 3, 32)):
         layer, X, Yref = _case(n, k, r, m, seed)
         assert B.slim_decode_plan(n, k, r, m)["path"] == 0
@@ -76,7 +77,7 @@ def test_static_scratch_on_the_two_launch_kernels(monkeypatch):
         assert _relerr(Y.cpu().numpy(), Yw.cpu().numpy().astype(np.float64)) <= 1e-3
 
 
-def test_static_scratch_refuses_what_does_not_fit(monkeypatch):
+def test_static_scratch_refuses_what_does_not_fit(decode_override):
     """A call that needs more than the array holds is refused on the host, with the workspace status, and Y
     is left alone: here the two-launch kernels on 28672 x 8192 with 4-bit adapters (their fp16 expansion
     alone is 60 MB); the same layer through the one-launch kernel fits and runs."""
@@ -91,13 +92,13 @@ def test_static_scratch_refuses_what_does_not_fit(monkeypatch):
     assert B.slim_workspace_bytes(layer, m) > 8 << 20
     X = torch.ones(m, k, dtype=torch.float16, device=DEV)
     Y = torch.full((m, n), 3.0, dtype=torch.float16, device=DEV)
-    monkeypatch.setenv("SLIM_DECODE_PATH", "parts")
+    decode_override("parts")
     with pytest.raises(B.SlimError) as e:
         B.slim_linear_gemv_static(layer, X, Y)
     assert e.value.status == B.SLIM_ERR_WORKSPACE
     torch.cuda.synchronize()
     assert float(Y.float().min()) == 3.0 and float(Y.float().max()) == 3.0
-    monkeypatch.delenv("SLIM_DECODE_PATH")
+    decode_override("auto")
     B.slim_linear_gemv_static(layer, X, Y)                # zero codes, zero adapters: Y = 0
     torch.cuda.synchronize()
     assert float(Y.float().abs().max()) == 0.0
