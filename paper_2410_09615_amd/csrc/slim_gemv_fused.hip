@@ -112,6 +112,33 @@ __device__ __forceinline__ bool piece_valid(const uint4_t &pc, unsigned epoch)
 constexpr unsigned short kHalfNaNBits = 0x7E00;
 #define kHalfNaN __builtin_bit_cast(half_t, kHalfNaNBits)
 
+// The loads of one item of the Y role: eight 128-bit loads.
+struct ItemRegs {
+    uint4_t r[8];
+};
+
+// One half (512 inputs) of a packed item: 8 sparse matrix instructions (V_SMFMAC_F32_16X16X64_F16) on
+// registers r[4 H], r[4 H + 1] (codes) and the low halves of r[4 H + 2], r[4 H + 3] (positions of the
+// lane's inputs 0-63 and 64-127).  xh and the B operand as in packed_half().
+template <int H>
+__device__ __forceinline__ void packed_half_item(const ItemRegs &b, const half_t *xh, float4_t &acc0, float4_t &acc1)
+{
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint32_t qd = t < 4 ? b.r[4 * H][t] : b.r[4 * H + 1][t - 4];
+        const half8_t av = codes_to_half8(qd);
+        const half8_t b1 = *reinterpret_cast<const half8_t *>(xh + 16 * t);
+        const half8_t b2 = *reinterpret_cast<const half8_t *>(xh + 256 + 16 * t);
+        const half16_t bv = __builtin_shufflevector(b1, b2, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+        const int idx = (int)(t < 4 ? b.r[4 * H + 2][t >> 1] : b.r[4 * H + 3][(t >> 1) - 2]);
+        // even t: index bits 15..0, odd t: bits 31..16 of the position dword
+        if (t & 1)
+            acc1 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(av, bv, acc1, idx, 0, 1);
+        else
+            acc0 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(av, bv, acc0, idx, 0, 0);
+    }
+}
+
 // ---- R role ----
 template <bool Q4>
 __device__ __forceinline__ void role_r(const FusedArgs &a, half_t *lds_h, int rb)
@@ -270,82 +297,105 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     const uint32_t kt = pk_ktiles(a.k);
     const uint4_t zero = {0u, 0u, 0u, 0u};
 
-    // Loads of item j of row tile ot, as buffer loads: one 32-bit offset per lane,
-    // no branches.  Rows past n inside the last tile of 32 are zero bytes in the
-    // tiled layouts, tiles past the last one lie past the end of the buffer, and
-    // what lies past the inputs or the ranks gets the offset kNowhere: all zeros.
+    auto tile_of = [&](int r) { return tile0 + r * tstride; };   // r >= rounds: past the last tile, loads read zeros
+    // Loads of item j of the row tile of round r: ALWAYS the same eight load instructions, whatever the
+    // item is (packed inputs, rank steps, or nothing), with the descriptors and offsets chosen by
+    // uniform selects.  The compiler keeps count of the loads in flight per register: with one
+    // instruction sequence per item it knows, at every use, how many younger loads there are, and
+    // waits for exactly the set it needs while the other set stays in flight (with loads under
+    // branches it waits for everything, every time).  Offsets: one 32-bit value per lane, no
+    // branches around loads; rows past n inside the last tile of 32 are zero bytes in the tiled
+    // layouts, tiles past the last one lie past the end of the buffer, and what lies past the
+    // inputs or the ranks gets the offset kNowhere: all zeros.
+    //   packed item (two halves x):  r[4x], r[4x+1] codes; r[4x+2], r[4x+3] positions (the low
+    //                                8 bytes of each 16-byte load are the lane's)
+    //   rank item, fp16:             r[i] = the lane's piece of L for step i
+    //   rank item, 4-bit (units x):  r[4x], r[4x+1] codes; r[4x+2] the 16 bytes that hold the scale
     const rsrc_t q_rs = make_rsrc(a.qvals, (uint32_t)pk_qbytes(a.n, a.k));
     const rsrc_t m_rs = make_rsrc(a.meta, (uint32_t)pk_mbytes(a.n, a.k));
     const rsrc_t l_rs = Q4 ? make_rsrc(a.Lq, (uint32_t)q4_code_bytes(a.n, rp)) : make_rsrc(a.L, (uint32_t)tl_bytes(a.n, rp));
     const rsrc_t ls_rs = make_rsrc(Q4 ? a.Ls : nullptr, Q4 ? (uint32_t)q4_scale_bytes(a.n, rp) : 0u);
-    auto issue_item = [&](int ot, int j, UnitRegs &b) {
+    const rsrc_t sc_rs = make_rsrc(LR ? nullptr : a.scale, LR ? 0u : (uint32_t)a.n * 4u);
+    auto issue_item = [&](int r, int j, ItemRegs &b) {
+        const int ot = tile_of(r);                   // r >= rounds: past the last tile
+        const bool tile_ok = ot < wtiles;
         const uint32_t o = 16u * ot + lx;
-        if (j < nP) {
+        const bool packed = j < nP;
+        uint32_t off[8];
+        if (packed) {
             const int c = j / ipd, jj = j - c * ipd;        // chunk, item within the chunk
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
                 const int hl = s + S * (2 * jj + x);        // half within the chunk
                 const int h = c * hc + hl;
                 const int kl = 512 * h + 128 * ly;          // the lane's 128 inputs: one tile column of the packed layout
-                const bool ok = hl < hc && h < H && kl < a.k && ot < wtiles;
+                const bool ok = hl < hc && h < H && kl < a.k && tile_ok;
                 const uint32_t qo = ok ? (uint32_t)pk_qoff(o, (uint32_t)kl / 4, kt) : kNowhere;
                 const uint32_t mo = ok ? (uint32_t)pk_moff(o, (uint32_t)kl / 8, kt) : kNowhere;
-                b.r[3 * x] = load16(q_rs, qo, 0);
-                b.r[3 * x + 1] = load16(q_rs, qo, 512);
-                const uint2_t lo = load8(m_rs, mo, 0), hi = load8(m_rs, mo, 256);
-                b.r[3 * x + 2] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
+                off[4 * x] = qo;
+                off[4 * x + 1] = qo + 512u;
+                off[4 * x + 2] = mo;
+                off[4 * x + 3] = mo + 256u;
             }
-            b.r[6] = zero;
-            b.r[7] = zero;
+        } else if constexpr (!Q4) {
+            // step t = s + S (8 jl + i) takes ranks 32 t + 8 ly .. + 7 of row o: piece (o, 4 t + ly)
+            const int t0 = s + S * 8 * (j - nP);
+            const uint32_t base = tl_piece(o, 4u * t0 + ly, (uint32_t)rp);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) off[i] = (j < nI && tile_ok && t0 + S * i < steps) ? base + 2048u * S * i : kNowhere;
         } else {
-            if constexpr (!Q4) {
-                // step t = s + S (8 jl + i) takes ranks 32 t + 8 ly .. + 7 of row o: piece (o, 4 t + ly)
-                const int t0 = s + S * 8 * (j - nP);
-                const uint32_t base = tl_piece(o, 4u * t0 + ly, (uint32_t)rp);
+            // two units of 256 ranks: 32 bytes of codes and a scale per lane and unit
+            const uint32_t ct = q4_ctiles(rp), gs = q4_groups(rp);
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    b.r[i] = load16(l_rs, (j < nI && ot < wtiles && t0 + S * i < steps) ? base + 2048u * S * i : kNowhere, 0);
-            } else {
-                // two units of 256 ranks: 32 bytes of codes and a scale per lane and unit
-                const uint32_t ct = q4_ctiles(rp), gs = q4_groups(rp);
-#pragma unroll
-                for (int x = 0; x < 2; ++x) {
-                    const int uu = s + S * (2 * (j - nP) + x);
-                    const bool ok = j < nI && ot < wtiles && uu < units_l && 256 * uu + 64 * ly < rp;
-                    const uint32_t qo = ok ? q4_piece(o, 4u * uu + ly, ct) : kNowhere;
-                    b.r[3 * x] = load16(l_rs, qo, 0);
-                    b.r[3 * x + 1] = load16(l_rs, qo, 16);
-                    const unsigned short sb = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(
-                        ls_rs, ok ? (int)((o * gs + 2u * uu + (ly >> 1)) * 2u) : (int)kNowhere, 0, 0);
-                    b.r[3 * x + 2] = uint4_t{sb, 0u, 0u, 0u};
-                }
-                b.r[6] = zero;
-                b.r[7] = zero;
+            for (int x = 0; x < 2; ++x) {
+                const int uu = s + S * (2 * (j - nP) + x);
+                const bool ok = j < nI && tile_ok && uu < units_l && 256 * uu + 64 * ly < rp;
+                const uint32_t qo = ok ? q4_piece(o, 4u * uu + ly, ct) : kNowhere;
+                off[4 * x] = qo;
+                off[4 * x + 1] = qo + 16u;
+                off[4 * x + 2] = ok ? ((o * gs + 2u * uu + (ly >> 1)) * 2u) & ~3u : kNowhere;    // the dword that holds the scale
+                off[4 * x + 3] = kNowhere;
             }
         }
+        // descriptors per slot: codes / positions of the packed rows, or the adapter buffers
+        const rsrc_t d0 = packed ? q_rs : l_rs;
+        const rsrc_t d1 = packed ? m_rs : (Q4 ? ls_rs : l_rs);
+        const rsrc_t d2 = packed ? m_rs : l_rs;                 // 4-bit rank items: offset kNowhere, any descriptor
+        b.r[0] = load16(d0, off[0], 0);
+        b.r[1] = load16(d0, off[1], 0);
+        b.r[2] = load16(d1, off[2], 0);
+        b.r[3] = load16(d2, off[3], 0);
+        b.r[4] = load16(d0, off[4], 0);
+        b.r[5] = load16(d0, off[5], 0);
+        b.r[6] = load16(d1, off[6], 0);
+        b.r[7] = load16(d2, off[7], 0);
     };
 
-    // A wavefront's work is a sequence of items (nIe per round; a wavefront without
-    // any still takes part in the barriers).  Two register sets alternate: the
-    // loads of the item after next go out as soon as an item is done.
+    // A wavefront's work is a sequence of items, nIe per round (a wavefront without any still takes
+    // part in the barriers), numbered through the rounds.  Two register sets alternate: the loads
+    // of the item after next go out as soon as an item is done.  Nothing may move across the
+    // boundaries between "use a set" and "load a set": the instruction scheduler would otherwise
+    // sink the loads to the end of the loop and wait for all of them at its top.
     const int nIe = nI > 0 ? nI : 1;
+    const int total = rounds * nIe;                  // items of this wavefront
     auto advance = [&](int &r, int &j) {
-        if (++j >= nIe) {
-            j = 0;
-            ++r;
-        }
+        const bool wrap = j + 1 >= nIe;
+        j = wrap ? 0 : j + 1;
+        r += wrap ? 1 : 0;
     };
-    auto tile_of = [&](int r) { return tile0 + r * tstride; };   // r >= rounds: past the last tile, loads read zeros
     int ir = 0, ij = 0;              // next item to load
-    UnitRegs bufA, bufB;
+    ItemRegs bufA, bufB;
 
     // the first two items' loads go out before anything else
+    __builtin_amdgcn_sched_barrier(0);
     if (wave < nwc) {
-        issue_item(tile_of(ir), ij, bufA);
+        issue_item(ir, ij, bufA);
         advance(ir, ij);
-        issue_item(tile_of(ir), ij, bufB);
+        __builtin_amdgcn_sched_barrier(0);
+        issue_item(ir, ij, bufB);
         advance(ir, ij);
     }
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- helpers: T -> LDS ----
     // A helper lane owns (token, four ranks) pairs hl, hl + 64 helpers, ...; a pair
@@ -471,41 +521,38 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
 
     float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0, sc4 = acc0;
     // item j of round r, its loads in cur
-    auto step = [&](int r, int j, const UnitRegs &cur) {
+    auto step = [&](int r, int j, const ItemRegs &cur) {
         const int ot = tile_of(r);
         const int ob = 16 * ot + 4 * ly;
         const bool vec = (ob + 3 < a.n) && (a.n & 3) == 0;
-        if (j == 0) {
-            acc0 = float4_t{0.f, 0.f, 0.f, 0.f};
-            acc1 = acc0;
-            // row scales of this lane's four outputs: needed when the packed items are done
-            sc4 = acc0;
-            if (!LR && ot < wtiles) {
-                if (vec) {
-                    sc4 = *reinterpret_cast<const float4_t *>(a.scale + ob);
-                } else {
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        if (ob + v < a.n) sc4[v] = a.scale[ob + v];
-                }
-            }
-        }
         if (j == nP) {
-            // the packed term is scaled once; the rank steps go on in the same registers
-            acc0 = (acc0 + acc1) * sc4;
-            acc1 = float4_t{0.f, 0.f, 0.f, 0.f};
+            // the packed term is scaled once; the rank steps go on in the same registers.  (This use of the
+            // scales stands ahead of their load in the code on purpose: what it waits for was loaded at
+            // least one item ago, and the compiler's count of loads in flight then lets the other register
+            // set stay in flight.  Without packed items there is nothing to scale.)
+            if (nP > 0) {
+                acc0 = (acc0 + acc1) * sc4;
+                acc1 = float4_t{0.f, 0.f, 0.f, 0.f};
+            }
             if (!t_ready) {
                 meet_for_t();
                 t_ready = true;
             }
+        }
+        if (j == 0) {
+            acc0 = float4_t{0.f, 0.f, 0.f, 0.f};
+            acc1 = acc0;
+            // row scales of this lane's four outputs (rows past n read as zero): needed when the packed
+            // items are done
+            sc4 = __builtin_bit_cast(float4_t, load16(sc_rs, (!LR && ot < wtiles) ? (uint32_t)ob * 4u : kNowhere, 0));
         }
         if (j < nP) {
             const int c = j / ipd, jj = j - c * ipd;
             if (c > 0 && jj == 0) __syncthreads();     // chunk c is in LDS; everybody has left chunk c - 1
             const half_t *xc = xrow_packed + (c & 1) * xbuf;
             const int h0 = min(s + S * (2 * jj), hc - 1), h1 = min(s + S * (2 * jj + 1), hc - 1);
-            packed_half<0>(cur, xc + 512 * h0, acc0, acc1);
-            packed_half<1>(cur, xc + 512 * h1, acc0, acc1);
+            packed_half_item<0>(cur, xc + 512 * h0, acc0, acc1);
+            packed_half_item<1>(cur, xc + 512 * h1, acc0, acc1);
         } else if (j < nI) {
             if constexpr (!Q4) {
                 const int t0 = s + S * 8 * (j - nP);
@@ -521,16 +568,20 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
                         acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);
                 }
             } else {
+                const uint32_t gs = q4_groups(rp);
 #pragma unroll
                 for (int x = 0; x < 2; ++x) {
                     const int uu = s + S * (2 * (j - nP) + x);
-                    const half_t sc = __builtin_bit_cast(half_t, (unsigned short)cur.r[3 * x + 2][0]);
+                    // the scale is one half of the dword that was loaded: which, by its byte address
+                    const uint32_t sa = ((16u * ot + lx) * gs + 2u * uu + (ly >> 1)) * 2u;
+                    const uint32_t sd = cur.r[4 * x + 2][0];
+                    const half_t sc = __builtin_bit_cast(half_t, (unsigned short)((sa & 2u) ? (sd >> 16) : (sd & 0xFFFFu)));
 #pragma unroll
                     for (int t = 0; t < 8; ++t) {
                         // ranks 256 uu + 64 ly + 8 t .. + 7; past the end the codes are zero and T is read inside the row
                         const int col = min(256 * uu + 64 * ly + 8 * t, rp - 8);
                         const half8_t bv = *reinterpret_cast<const half8_t *>(t_lds + trow * ldt + col);
-                        const half8_t av = codes_to_half8(cur.r[3 * x + (t >> 2)][t & 3]) * sc;
+                        const half8_t av = codes_to_half8(cur.r[4 * x + (t >> 2)][t & 3]) * sc;
                         if (t & 1)
                             acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0);
                         else
@@ -577,17 +628,25 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
         if (S > 1 && r + 1 < rounds) __syncthreads();      // the partial sums are read before the next round writes
     };
 
+    // Items in pairs: set A, then set B; an odd total ends with a pair whose second half is skipped
+    // (its loads were all past the end and brought zeros).
     int cr = 0, cj = 0;              // item being worked on
-    while (cr < rounds) {
+    for (int g = 0; g < total; g += 2) {
+        __builtin_amdgcn_sched_barrier(0);
         step(cr, cj, bufA);
         advance(cr, cj);
-        issue_item(tile_of(ir), ij, bufA);
+        __builtin_amdgcn_sched_barrier(0);
+        issue_item(ir, ij, bufA);
         advance(ir, ij);
-        if (cr >= rounds) break;
-        step(cr, cj, bufB);
-        advance(cr, cj);
-        issue_item(tile_of(ir), ij, bufB);
+        __builtin_amdgcn_sched_barrier(0);
+        if (g + 1 < total) {
+            step(cr, cj, bufB);
+            advance(cr, cj);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        issue_item(ir, ij, bufB);
         advance(ir, ij);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -595,15 +654,13 @@ template <bool Q4, bool LR = false>
 __global__ __launch_bounds__(kFusedMaxThreads, kFusedWavesPerSimd) void decode_fused_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) half_t lds[];
-    if (a.mode == 0) {
+    // mode & 3: 0 = every workgroup in the R role, 1 = every workgroup in the Y role, 2 = the first n_r in
+    // the R role and the others in the Y role (one copy of each role's code)
+    const int split = (a.mode & 3) == 2 ? a.n_r : ((a.mode & 3) == 0 ? (int)gridDim.x : 0);
+    if ((int)blockIdx.x < split)
         role_r<Q4>(a, lds, blockIdx.x);
-    } else if ((a.mode & 3) == 1) {
-        role_y<Q4, LR>(a, lds, blockIdx.x, gridDim.x);
-    } else if ((int)blockIdx.x < a.n_r) {
-        role_r<Q4>(a, lds, blockIdx.x);
-    } else {
-        role_y<Q4, LR>(a, lds, (int)blockIdx.x - a.n_r, (int)gridDim.x - a.n_r);
-    }
+    else
+        role_y<Q4, LR>(a, lds, (int)blockIdx.x - split, (int)gridDim.x - split);
 }
 
 static int pad_tokens16(int m) { return m <= 1 ? 1 : (m <= 4 ? 4 : (m <= 8 ? 8 : 16)); }
@@ -636,7 +693,9 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves, 
         // (with more than 8 tokens eight: T is then one batch per lane, and the workgroup has
         // the compute unit to itself anyway)
         int helpers = m > 8 ? 8 : 4;
-        if (waves < 8) {
+        if (waves == 7) {
+            helpers = 1;                               // up to 4 tokens: X and T are a few loads per lane
+        } else if (waves < 8) {
             const int by_t = m <= 4 ? 1 : (m <= 8 ? 2 : 4);
             const int by_x = (int)(((size_t)m * kc * 2 + 32767) / 32768);
             helpers = by_x > by_t ? by_x : by_t;
@@ -652,13 +711,18 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves, 
                                       : (size_t)2 * m * (kc + kLdsPad) * sizeof(half_t);
         const size_t red_r = (size_t)(total - 1) * kWave * 16;
         for (int S = waves; S >= 1; S /= 2) {
+            if (waves % S) continue;                         // whole row tiles per workgroup
             if (nch > 1 && (S > hc || hc % S)) continue;     // every wavefront has the same items in every chunk
             const int tpw = waves / S;
             const size_t red_y = S > 1 ? (size_t)tpw * (S - 1) * kWave * 16 : 0;
             const size_t lds = lds_x + red_y > red_r ? lds_x + red_y : red_r;
             if (lds > lds_cap) continue;
-            // workgroups a compute unit holds
-            long per_cu = 4 * kFusedWavesPerSimd / total;
+            // Workgroups a compute unit is sure to hold: the wavefronts of a workgroup are dealt to the
+            // four SIMDs in turn, so one SIMD gets ceil(total / 4) of them, and a SIMD holds
+            // kFusedWavesPerSimd.  (Counting wavefronts per compute unit alone admitted three
+            // workgroups of five, which the hardware does not always place: the last ones then
+            // started only when the R role had ended, 7 us late on the largest layer.)
+            long per_cu = kFusedWavesPerSimd / ((total + 3) / 4);
             if (per_cu > (long)(lds_cu / lds)) per_cu = (long)(lds_cu / lds);
             const long wgs = (wtiles + tpw - 1) / tpw;
             int kh = kh_max;
@@ -682,10 +746,12 @@ static FusedPlan plan_fused_waves(int n, int k, int rank_pad, int m, int waves, 
     return p;
 }
 
-// Which layers take this path, and with what geometry.  Workgroups of 8
-// wavefronts, one per compute unit, measured best wherever they fit; layers
-// with more row tiles than that allows run workgroups of 4 wavefronts, three
-// per compute unit where the LDS permits.
+// Which layers take this path, and with what geometry.  Workgroups of 8 working
+// wavefronts, one per compute unit, measured best wherever they fit; layers with
+// more row tiles than that allows run, up to 4 tokens, workgroups of 7 working
+// wavefronts and one helper (two per compute unit, every SIMD evenly loaded:
+// 28672 x 8192 is then 256 workgroups of 7 row tiles), else workgroups of 4
+// working wavefronts, two per compute unit.
 FusedPlan plan_fused(int n, int k, int rank_pad, int m)
 {
     // The plan is a pure function of these seven numbers; a decode loop asks for the same few over and
@@ -707,6 +773,7 @@ FusedPlan plan_fused(int n, int k, int rank_pad, int m)
     for (int i = 0; i < used; ++i)
         if (keys[i] == key) return plans[i];
     FusedPlan p = plan_fused_waves(n, k, rank_pad, m, 8, dev, key.limit);
+    if (!p.ok && m <= 4) p = plan_fused_waves(n, k, rank_pad, m, 7, dev, key.limit);
     if (!p.ok) p = plan_fused_waves(n, k, rank_pad, m, 4, dev, key.limit);
     keys[next] = key;
     plans[next] = p;
