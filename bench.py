@@ -44,7 +44,7 @@ BATCHES = 5
 # WRITE_SIZE), each scaled by what the same counter reads for the 256 MiB device copy this script
 # issues first.  Not measured by this run: the summary file holds the command and the readings.
 TRAFFIC_SOURCE = "profiles/decode_gemv_llama70b_up_hbm_traffic.md"
-TRAFFIC_BYTES_PER_LAUNCH = None
+TRAFFIC_BYTES_PER_LAUNCH = 155.12e6
 
 
 def parse_args():
@@ -58,6 +58,9 @@ def parse_args():
                     help="warm-up, the timed steps and the batches only (profiler runs: every launch of the "
                          "dominant kernel is then one of the headline step)")
     ap.add_argument("--tokens", default="1,16", help="token counts of one step (counter runs use one value)")
+    ap.add_argument("--layer", default="llama2_70b_up_28672x8192",
+                    help="profiler runs of another configured shape: the decode step on that layer instead of the "
+                         "headline one (the JSON line then names it in config.workload; not the benchmark)")
     return ap.parse_args()
 
 
@@ -192,7 +195,12 @@ def main():
         return rec
 
     # ---------------- headline: LLaMA-2-70B-shaped up projection, decode ----------------
-    shape = wl.L70B_UP
+    by_name = {c.name: c for c in (wl.L7B_ATTN, wl.L7B_UP, wl.L7B_DOWN, wl.L13B_ATTN, wl.L13B_UP, wl.L70B_ATTN, wl.L70B_UP)}
+    if args.layer not in by_name:
+        print("bench.py: --layer is one of " + ", ".join(by_name), file=sys.stderr)
+        return 2
+    shape = by_name[args.layer]
+    headline = shape is wl.L70B_UP
     tokens = tuple(int(t) for t in args.tokens.split(","))
     rot = Rotating(shape, tokens, with_dense=not args.headline_only)
 
@@ -231,7 +239,8 @@ def main():
                   + " + ".join(f"{m}" for m in tokens) + " tokens)",
         "achieved": round(launch_bytes / launch_us * 1e-3, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(launch_bytes / launch_us * 1e-3 / HBM_PEAK_GBPS, 4),
-        "traffic": TRAFFIC_BYTES_PER_LAUNCH, "traffic_source": TRAFFIC_SOURCE if TRAFFIC_BYTES_PER_LAUNCH else None,
+        "traffic": TRAFFIC_BYTES_PER_LAUNCH if headline and tokens == (1, 16) else None,
+        "traffic_source": TRAFFIC_SOURCE if TRAFFIC_BYTES_PER_LAUNCH and headline and tokens == (1, 16) else None,
         "algorithmic_bytes": launch_bytes, "avg_launch_us": round(launch_us, 3),
         "note": "bytes and duration per launch are means over the calls of a step; duration = event time of the "
                 "timed region / launches (launch gaps included)",
@@ -376,9 +385,9 @@ def main():
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_step, 6), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "LLaMA-2-70B-shaped up projection at one-GPU full size, decode: W 28672x8192 int4 2:4 + "
-                               "rank-820 fp16 adapters, X of " + " and ".join(str(m) for m in tokens) +
-                               " tokens (one step = these forwards), cold caches",
+        "config": {"workload": ("LLaMA-2-70B-shaped up projection at one-GPU full size" if headline else shape.name) +
+                               f", decode: W {shape.n}x{shape.k} int4 2:4 + rank-{shape.r} fp16 adapters, X of " +
+                               " and ".join(str(m) for m in tokens) + " tokens (one step = these forwards), cold caches",
                    "n": shape.n, "k": shape.k, "rank": shape.r, "tokens": list(tokens), "layer_copies": headline_copies},
         "batches": batches,
         "layer_us": {str(m): per_m[m]["us"] for m in per_m},
