@@ -228,6 +228,13 @@ def main():
     wall = time.perf_counter() - t_wall0
     step_b = batches_ms(step, args.steps)
     rot.check_workspaces()
+    # CPU time of one call through the binding (argument checks, ctypes, the launch), queue not full
+    torch.cuda.synchronize()
+    t_h0 = time.perf_counter()
+    for i in range(50):
+        step(i)
+    host_us = (time.perf_counter() - t_h0) / (50 * len(tokens)) * 1e6
+    torch.cuda.synchronize()
     step_bytes = sum(A.layer_bytes(shape.n, shape.k, shape.r, m) for m in tokens)
     step_flops = sum(A.flops_eff(shape.n, shape.k, shape.r, m) for m in tokens)
     value = step_bytes / ms_step * 1e-6            # GB/s
@@ -242,6 +249,7 @@ def main():
         "traffic": TRAFFIC_BYTES_PER_LAUNCH if headline and tokens == (1, 16) else None,
         "traffic_source": TRAFFIC_SOURCE if TRAFFIC_BYTES_PER_LAUNCH and headline and tokens == (1, 16) else None,
         "algorithmic_bytes": launch_bytes, "avg_launch_us": round(launch_us, 3),
+        "host_enqueue_us_per_call": round(host_us, 2),
         "note": "bytes and duration per launch are means over the calls of a step; duration = event time of the "
                 "timed region / launches (launch gaps included)",
     }
@@ -457,9 +465,10 @@ def offline_legs(rot, torch, B, A, wl, dev, event_time_ms):
     del wcopies
     # slim_pack_adapters_q4: the layer's fp16 adapters to 4-bit group-128 codes + fp16 scales (Sec. 3.3)
     Ld, Rd = rot.L_host.to(dev), rot.R_host.to(dev)
+    q4_out = B.slim_pack_adapters_q4(Ld, Rd)
     for _ in range(3):
-        B.slim_pack_adapters_q4(Ld, Rd)
-    ms_q4 = event_time_ms(lambda i: B.slim_pack_adapters_q4(Ld, Rd), 30)
+        B.slim_pack_adapters_q4(Ld, Rd, out=q4_out)
+    ms_q4 = event_time_ms(lambda i: B.slim_pack_adapters_q4(Ld, Rd, out=q4_out), 30)
     q4b = shape.r * (shape.n + shape.k) * (2 + 0.5) + 2 * (shape.n * ((shape.r + 127) // 128) + shape.r * (shape.k // 128))
     legs.append({"shape": shape.name, "entry": "slim_pack_adapters_q4", "us": round(ms_q4 * 1e3, 2),
                  "GBps": round(q4b / ms_q4 * 1e-6, 1), "bound": "hbm",

@@ -318,20 +318,30 @@ def slim_adapter_q4_sizes(rows: int, cols: int) -> dict:
     return {"codes": c.value, "scales": s.value}
 
 
-def slim_pack_adapters_q4(L: torch.Tensor, R: torch.Tensor):
+def slim_pack_adapters_q4(L: torch.Tensor, R: torch.Tensor, out=None):
     """L fp16 [n][rank], R fp16 [rank][k] -> (Lq, Ls, Rq, Rs): 4-bit group-128 codes in the kernels'
-    layout and fp16 group scales (flat tensors; sizes from slim_adapter_q4_sizes)."""
+    layout and fp16 group scales (flat tensors; sizes from slim_adapter_q4_sizes).  `out`: the four
+    tensors of an earlier call on the same shape, written in place (then nothing is allocated)."""
     _dev(L, torch.float16, "L")
     _dev(R, torch.float16, "R")
     n, rank = L.shape
     k = R.shape[1]
     if R.shape[0] != rank:
         raise ValueError("L and R disagree on the rank")
-    sl, sr = slim_adapter_q4_sizes(n, rank), slim_adapter_q4_sizes(rank, k)
-    Lq = torch.empty(sl["codes"], dtype=torch.uint8, device=L.device)
-    Ls = torch.empty(sl["scales"] // 2, dtype=torch.float16, device=L.device)
-    Rq = torch.empty(sr["codes"], dtype=torch.uint8, device=L.device)
-    Rs = torch.empty(sr["scales"] // 2, dtype=torch.float16, device=L.device)
+    if out is not None:
+        Lq, Ls, Rq, Rs = out
+        sl, sr = slim_adapter_q4_sizes(n, rank), slim_adapter_q4_sizes(rank, k)
+        for t, dt, cnt, name in ((Lq, torch.uint8, sl["codes"], "Lq"), (Ls, torch.float16, sl["scales"] // 2, "Ls"),
+                                 (Rq, torch.uint8, sr["codes"], "Rq"), (Rs, torch.float16, sr["scales"] // 2, "Rs")):
+            _dev(t, dt, name)
+            if t.numel() != cnt:
+                raise ValueError(f"{name}: {t.numel()} elements, this shape needs {cnt}")
+    else:
+        sl, sr = slim_adapter_q4_sizes(n, rank), slim_adapter_q4_sizes(rank, k)
+        Lq = torch.empty(sl["codes"], dtype=torch.uint8, device=L.device)
+        Ls = torch.empty(sl["scales"] // 2, dtype=torch.float16, device=L.device)
+        Rq = torch.empty(sr["codes"], dtype=torch.uint8, device=L.device)
+        Rs = torch.empty(sr["scales"] // 2, dtype=torch.float16, device=L.device)
     _check("slim_pack_adapters_q4", lib().slim_pack_adapters_q4(_ptr(L), _ptr(R), slim_shape(n, k, rank), _ptr(Lq),
                                                                 _ptr(Ls), _ptr(Rq), _ptr(Rs), _stream(L)))
     return Lq, Ls, Rq, Rs

@@ -17,13 +17,27 @@ namespace slim {
 
 constexpr int kGroup = 128;
 
-// One wavefront per (row, group): a lane owns two neighbouring columns = one byte.
-__global__ __launch_bounds__(256) void adapter_q4_pack_kernel(const half_t *A, int rows, int K, uint8_t *codes,
-                                                               half_t *scales)
+// One matrix to quantize: A fp16 [rows][K] row-major -> codes, scales in the device layout.
+struct Q4PackJob {
+    const half_t *A;
+    int rows, K;
+    uint8_t *codes;
+    half_t *scales;
+    unsigned blocks;                     // workgroups of this job
+};
+
+// One wavefront per (row, group): a lane owns two neighbouring columns = one byte.  Both adapters
+// of a layer in one launch: the first j0.blocks workgroups work on j0, the others on j1.
+__global__ __launch_bounds__(256) void adapter_q4_pack_kernel(Q4PackJob j0, Q4PackJob j1)
 {
+    const bool second = blockIdx.x >= j0.blocks;
+    const half_t *A = second ? j1.A : j0.A;
+    const int rows = second ? j1.rows : j0.rows, K = second ? j1.K : j0.K;
+    uint8_t *codes = second ? j1.codes : j0.codes;
+    half_t *scales = second ? j1.scales : j0.scales;
     const int lane = threadIdx.x & (kWave - 1);
     const int groups = (int)q4_groups(K);
-    const long pair = (long)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    const long pair = (long)(blockIdx.x - (second ? j0.blocks : 0u)) * (blockDim.x / kWave) + threadIdx.x / kWave;
     const int row = (int)(pair / groups), g = (int)(pair % groups);
     if (row >= (int)q4_rows(rows)) return;
     const int col = g * kGroup + 2 * lane;
@@ -101,12 +115,10 @@ extern "C" int slim_adapter_q4_sizes(int32_t rows, int32_t cols, size_t *codes_b
     return SLIM_OK;
 }
 
-static int pack_one(const slim_half *A, int rows, int K, uint8_t *codes, slim_half *scales, hipStream_t st)
+static Q4PackJob pack_job(const slim_half *A, int rows, int K, uint8_t *codes, slim_half *scales)
 {
     const long pairs = (long)q4_rows(rows) * q4_groups(K);
-    hipLaunchKernelGGL(adapter_q4_pack_kernel, dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, st,
-                       reinterpret_cast<const half_t *>(A), rows, K, codes, reinterpret_cast<half_t *>(scales));
-    return hip_status(hipGetLastError());
+    return Q4PackJob{reinterpret_cast<const half_t *>(A), rows, K, codes, reinterpret_cast<half_t *>(scales), (unsigned)((pairs + 3) / 4)};
 }
 
 extern "C" int slim_pack_adapters_q4(const slim_half *L, const slim_half *R, slim_shape shape, uint8_t *Lq,
@@ -117,9 +129,9 @@ extern "C" int slim_pack_adapters_q4(const slim_half *L, const slim_half *R, sli
     if (!aligned16(L) || !aligned16(R) || !aligned16(Lq) || !aligned16(Ls) || !aligned16(Rq) || !aligned16(Rs))
         return SLIM_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int rc = pack_one(L, shape.n, shape.rank, Lq, Ls, st);
-    if (rc != SLIM_OK) return rc;
-    return pack_one(R, shape.rank, shape.k, Rq, Rs, st);
+    const Q4PackJob jl = pack_job(L, shape.n, shape.rank, Lq, Ls), jr = pack_job(R, shape.rank, shape.k, Rq, Rs);
+    hipLaunchKernelGGL(adapter_q4_pack_kernel, dim3(jl.blocks + jr.blocks), dim3(256), 0, st, jl, jr);
+    return hip_status(hipGetLastError());
 }
 
 extern "C" int slim_unpack_adapters_q4(const uint8_t *codes, const slim_half *scales, int32_t rows, int32_t cols,

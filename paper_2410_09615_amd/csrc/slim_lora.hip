@@ -315,49 +315,94 @@ __global__ __launch_bounds__(1024) void lora_diagmax_kernel(const float *G, int 
 
 // Diagonal block at (j0, j0), width w <= 64: L11 replaces its lower triangle in G, and
 // X11 = L11^-1 (lower triangular, zeros above) goes to D[j0 .. j0 + w)[0 .. 64).
+// Column c of the factor and row c of the inverse are final after step c: the forward
+// substitution L X = I runs along with the factorisation (x starts as the identity).
+// The block lives in registers: 256 threads as a 16 x 16 grid, thread (ty, tx) owns the
+// elements (ty + 16 p, tx + 16 q) of a and of x.  A step needs column c of a and row c of x:
+// their owners publish them in LDS (two buffers in turn, one barrier per step), everybody
+// reads the four values of its rows and of its columns, and the update is 32 predicated
+// multiply-adds on registers.  Scaled column c and row c are final then and go to LDS
+// for the write-out at the end.
 __global__ __launch_bounds__(256) void lora_chol_diag_kernel(float *G, int l, int j0, int w, const float *gmax, float *D)
 {
-    __shared__ float a[kCb][kCb + 1];
-    __shared__ float x[kCb][kCb + 1];
-    __shared__ float piv;
-    const int tid = threadIdx.x, T = blockDim.x, ty = tid >> 4, tx = tid & 15;
-    for (int idx = tid; idx < w * w; idx += T) {
-        const int i = idx / w, c = idx % w;
-        a[i][c] = G[(size_t)(j0 + i) * l + j0 + c];
-        x[i][c] = i == c ? 1.0f : 0.f;
+    __shared__ float col[2][kCb];        // column c of a, as it stands at step c (unscaled)
+    __shared__ float xrow[2][kCb];       // row c of x (unscaled)
+    __shared__ float lout[kCb][kCb + 1];
+    __shared__ float xout[kCb][kCb + 1];
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    float av[4][4], xv[4][4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int i = ty + 16 * p, cc = tx + 16 * q;
+            av[p][q] = (i < w && cc < w) ? G[(size_t)(j0 + i) * l + j0 + cc] : 0.f;
+            xv[p][q] = i == cc ? 1.0f : 0.f;
+        }
+    for (int idx = tid; idx < kCb * kCb; idx += 256) {
+        lout[idx / kCb][idx % kCb] = 0.f;
+        xout[idx / kCb][idx % kCb] = 0.f;
     }
     const float floor_ = *gmax * 1e-9f;
-    // Column c of the factor and row c of the inverse are final after step c: the forward
-    // substitution L X = I runs along with the factorisation (x starts as the identity).
     for (int c = 0; c < w; ++c) {
-        __syncthreads();
-        if (tid == 0) {
-            const float d = a[c][c];
-            const float pv = d > floor_ ? sqrtf(d) : 0.f;
-            piv = pv;
-            a[c][c] = pv > 0.f ? pv : 1.0f;
+        const int b = c & 1, cq = c >> 4, cr = c & 15;
+        // publish: column c of a from the threads with tx == c mod 16, row c of x from those with ty == c mod 16
+        if (tx == cr) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (q == cq) {
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) col[b][ty + 16 * p] = av[p][q];
+                }
+        }
+        if (ty == cr) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+                if (p == cq) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) xrow[b][tx + 16 * q] = xv[p][q];
+                }
         }
         __syncthreads();
-        const float inv = piv > 0.f ? 1.0f / piv : 0.f;
-        const float dinv = 1.0f / a[c][c];
-        for (int i = c + 1 + tid; i < w; i += T) a[i][c] *= inv;
-        for (int cc = tid; cc <= c; cc += T) x[c][cc] *= dinv;
-        __syncthreads();
-        // threads as a 16 x 16 grid over (row, column): no divisions in the loops
-        for (int i = c + 1 + ty; i < w; i += 16) {
-            const float lic = a[i][c];
-            for (int cc = c + 1 + tx; cc <= i; cc += 16) a[i][cc] -= lic * a[cc][c];
-            for (int cc = tx; cc <= c; cc += 16) x[i][cc] -= lic * x[c][cc];
+        const float d = col[b][c];
+        const float pv = d > floor_ ? sqrtf(d) : 0.f;        // 0: a column in the span of the ones before it
+        const float inv = pv > 0.f ? 1.0f / pv : 0.f;
+        const float dinv = pv > 0.f ? 1.0f / pv : 1.0f;
+        float li[4], lc[4], xr[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) li[p] = col[b][ty + 16 * p] * inv;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            lc[q] = col[b][tx + 16 * q] * inv;
+            xr[q] = xrow[b][tx + 16 * q] * dinv;
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int i = ty + 16 * p, cc = tx + 16 * q;
+                if (i > c && cc > c && cc <= i) av[p][q] -= li[p] * lc[q];
+                if (i > c && cc <= c) xv[p][q] -= li[p] * xr[q];
+            }
+        // what is final now: column c of the factor (threads 0..63), row c of the inverse (64..127)
+        if (tid < kCb) {
+            if (tid > c)
+                lout[tid][c] = col[b][tid] * inv;
+            else if (tid == c)
+                lout[tid][c] = pv > 0.f ? pv : 1.0f;
+        } else if (tid < 2 * kCb) {
+            const int cc = tid - kCb;
+            if (cc <= c) xout[c][cc] = xrow[b][cc] * dinv;
         }
     }
     __syncthreads();
-    for (int idx = tid; idx < w * w; idx += T) {
+    for (int idx = tid; idx < w * w; idx += 256) {
         const int i = idx / w, c = idx % w;
-        if (c <= i) G[(size_t)(j0 + i) * l + j0 + c] = a[i][c];
+        if (c <= i) G[(size_t)(j0 + i) * l + j0 + c] = lout[i][c];
     }
-    for (int idx = tid; idx < w * kCb; idx += T) {
+    for (int idx = tid; idx < w * kCb; idx += 256) {
         const int i = idx / kCb, c = idx % kCb;
-        D[(size_t)(j0 + i) * kCb + c] = c < w ? x[i][c] : 0.f;
+        D[(size_t)(j0 + i) * kCb + c] = c < w ? xout[i][c] : 0.f;
     }
 }
 

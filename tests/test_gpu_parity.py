@@ -516,6 +516,20 @@ def test_pack_adapters_q4_bit_exact(n, k, r):
         assert np.array_equal(codes.cpu().numpy(), rc)
 
 
+def test_pack_adapters_q4_in_place_outputs():
+    """The form that allocates nothing writes the same bytes into tensors of an earlier call (first filled with junk)."""
+    L, R = wl.make_adapters(300, 640, 51, 5, 6)
+    ref = B.slim_pack_adapters_q4(L.to(DEV), R.to(DEV))
+    out = tuple(torch.full_like(t, 77) for t in ref)
+    again = B.slim_pack_adapters_q4(L.to(DEV), R.to(DEV), out=out)
+    torch.cuda.synchronize()
+    assert all(a.data_ptr() == o.data_ptr() for a, o in zip(again, out))
+    for a, b in zip(out, ref):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+    with pytest.raises(ValueError):
+        B.slim_pack_adapters_q4(L.to(DEV), R.to(DEV), out=(out[0][:-1].contiguous(),) + out[1:])
+
+
 def _forward_case_q4(shape, m, fn, seed=0, rows=None):
     return _forward_case(shape, m, fn, seed=seed, rows=rows, bits=4)
 
