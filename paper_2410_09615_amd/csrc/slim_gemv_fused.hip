@@ -1,5 +1,6 @@
-// slim_linear_gemv in one launch, for layers whose X (all inputs, the padded
-// token rows) fits the LDS of a compute unit.
+// slim_linear_gemv in one launch: X lives in the LDS of a compute unit, all of
+// it where the token rows of all inputs fit, else in chunks that stream through
+// two buffers while the accumulators stay in registers.
 //
 // Two kinds of workgroups share one grid:
 //
@@ -14,11 +15,13 @@
 //          of a tile takes the halves (512 inputs) s, s + S, ... of the packed
 //          row tile through the structured-sparse matrix instruction against X
 //          held in LDS, then the steps of 32 ranks s, s + S, ... of the L row
-//          tile against T held in LDS.  One to four more wavefronts of the
-//          workgroup (helpers) do nothing but fetch T: they re-read its pieces
-//          until every piece carries this call's epoch, add the shares and put
-//          the sum into LDS, while the others are busy with the packed term;
-//          the workgroup meets at one barrier before its first rank step.  The
+//          tile against T held in LDS.  One to eight more wavefronts of the
+//          workgroup (helpers) move what is not a plain stream: they stage X
+//          with loads that write LDS directly, and they fetch T: they re-read
+//          its pieces until every piece carries this call's epoch and its
+//          checksum, add the shares and put the sum into LDS, while the others
+//          are busy with the packed term; the workgroup meets at one barrier
+//          before its first rank step.  The
 //          S partial results, each already scale * packed + low-rank, meet in
 //          LDS and wavefront 0 of the tile stores Y.  Nothing goes through
 //          memory between the two terms but T itself: no partial sums, no
@@ -28,9 +31,10 @@
 // there are no flags to order against the data, nothing to reset between calls,
 // and a workspace may serve different layers in turn.
 //
-// Progress: workgroups start in the order of their index, so every R-role
-// workgroup has started before any Y-role workgroup can wait for it, and the
-// wait is bounded anyway (a helper gives up after kSpinLimit reads and records
+// Progress: the planner admits a geometry only if all workgroups of the grid are
+// resident at once, so none that is waited for can be queued behind one that
+// waits (workgroups also start in the order of their index, which lets the R
+// role start first), and the wait is bounded anyway (a helper gives up after kSpinLimit reads and records
 // that in the control words and puts NaN in place of the T it did not get, so the
 // outputs of its workgroup are NaN: a failed call cannot pass for a result).
 //
