@@ -364,6 +364,20 @@ int slim_decode_override(int32_t path, int32_t lds_kb);
 int slim_decode_plan(const slim_layer *layer, int32_t m, int32_t *out);
 
 /*
+ * slim_gemm_tile_order -- which output tile (512 rows x 128 tokens) each
+ * workgroup of slim_linear_gemm's main kernel works on, for a layer of n rows
+ * at m tokens (m below the chunk the call walks X in); host logic only, nothing
+ * is launched (inspection and tests).  out (HOST pointer, count ints):
+ * [0] tiles = ceil(n / 512) * ceil(m / 128), [1] how many of them the launch
+ * with whole tiles takes (the others are cut into halves or quarters by a
+ * second launch, in the same order), [2 + w] = row tile + ceil(n / 512) *
+ * token tile of workgroup w.  Every tile appears exactly once.  The order
+ * hands the workgroups that share a die's L2 a compact block of the layer.
+ * Errors: NULL, SHAPE (n or m < 1, count < tiles + 2).
+ */
+int slim_gemm_tile_order(int32_t n, int32_t m, int32_t *out, size_t count);
+
+/*
  * slim_linear_gemm -- prefill-shaped forward, any m >= 1 (meant for m >= 64):
  * Y = X W^C + (X L) R of Sec. 3.2 in this header's orientation; by the count of
  * App. "Computation Reduction Analysis" (Eq. 13) the 2:4 mask halves the

@@ -41,7 +41,7 @@ EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pac
            "slim_lowrank",
            "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4", "slim_pack_ex",
            "slim_quant_workspace_bytes", "slim_quant_search", "slim_quant_search_rows", "slim_adapters_workspace_bytes",
-           "slim_compute_adapters", "slim_input_quant_fp8", "slim_probe_read", "slim_probe_mfma"]
+           "slim_compute_adapters", "slim_input_quant_fp8", "slim_probe_read", "slim_probe_mfma", "slim_gemm_tile_order"]
 
 
 def lib():
@@ -82,6 +82,7 @@ def lib():
         L.slim_linear_gemm.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp, sz, vp]
         L.slim_linear_gemv_static.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp]
         L.slim_lowrank.argtypes = [vp, i32, vp, vp, slim_shape, i32, vp, ctypes.c_int, vp, sz, vp]
+        L.slim_gemm_tile_order.argtypes = [i32, i32, pi32, sz]
         for name in EXPORTS[2:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -345,6 +346,14 @@ def slim_pack_adapters_q4(L: torch.Tensor, R: torch.Tensor, out=None):
     _check("slim_pack_adapters_q4", lib().slim_pack_adapters_q4(_ptr(L), _ptr(R), slim_shape(n, k, rank), _ptr(Lq),
                                                                 _ptr(Ls), _ptr(Rq), _ptr(Rs), _stream(L)))
     return Lq, Ls, Rq, Rs
+
+
+def slim_gemm_tile_order(n: int, m: int):
+    """(tiles, tiles of the whole-tile launch, [tile of workgroup w]) of slim_linear_gemm's main kernel; host logic."""
+    tiles = ((n + 511) // 512) * ((m + 127) // 128)
+    out = (ctypes.c_int32 * (tiles + 2))()
+    _check("slim_gemm_tile_order", lib().slim_gemm_tile_order(n, m, out, tiles + 2))
+    return out[0], out[1], list(out[2:2 + out[0]])
 
 
 def slim_unpack_adapters_q4(codes: torch.Tensor, scales: torch.Tensor, rows: int, cols: int):

@@ -34,7 +34,10 @@ __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
     const int wave = tid / kWave;
     const int li = lane & 31;
     const int lb = lane >> 5;
-    const int w = blockIdx.x;
+    // the workgroups of a die (index mod 8) take neighbouring positions of the blocked order
+    const int gx = (int)gridDim.x;
+    const int q = gx % kDies == 0 ? ((int)blockIdx.x % kDies) * (gx / kDies) + (int)blockIdx.x / kDies : (int)blockIdx.x;
+    const int w = blocked_tile(q, a.tiles_o, gx / a.tiles_o);
     const int o0 = (w % a.tiles_o) * (4 * WROWS) + wave * WROWS;
     const int t0 = (w / a.tiles_o) * 128;
     const int t_end = min(a.m, t0 + 128);

@@ -39,7 +39,21 @@ struct SparseGemmArgs {
     int tiles_total;     // row tiles x token tiles
     int n_full;          // tiles [0, n_full) run whole (AT = 4), the rest as halves of 256 rows (AT = 2) or quarters (AT = 1)
     int rem_split;       // pieces per remaining tile: 1 (none remain), 2 or 4
+    int per_die;         // workgroup slots per die (slots / 8), 0: the number of compute units is not a multiple of 8
 };
+
+// Which tile a workgroup works on: position q of the blocked order (blocked_tile(), slim_mma.h).  In
+// whole rounds of `slots` workgroups die d takes positions d * per_die .. of the round, i.e. one
+// block of 4 row tiles x 8 token tiles where the layer has them (interleave); elsewhere q = w.
+__host__ __device__ __forceinline__ int tile_of_workgroup(const SparseGemmArgs &a, int w, bool interleave)
+{
+    int q = w;
+    if (interleave && a.per_die > 0) {
+        const int slots = a.per_die * kDies;
+        if (w < (a.n_full / slots) * slots) q = (w / slots) * slots + (w % kDies) * a.per_die + (w % slots) / kDies;
+    }
+    return blocked_tile(q, a.tiles_o, a.tiles_total / a.tiles_o);
+}
 
 // AT row tiles of 32 per wavefront; accumulator tile (i, it) is a[16 (i NT + it) ..].
 template <int AT>
@@ -59,7 +73,7 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
     // (quarter) b % split of tile n_full + b / split.
     const int b = blockIdx.x;
     constexpr int split = 4 / AT;
-    const int w = (split > 1 ? a.n_full : 0) + b / split;
+    const int w = tile_of_workgroup(a, (split > 1 ? a.n_full : 0) + b / split, split == 1);
     const int o0 = (w % a.tiles_o) * 512 + (b % split) * (4 * WROWS) + wave * WROWS;
     const int t0 = (w / a.tiles_o) * 128;
     const int t_end = min(a.m, t0 + 128);                    // tokens of this workgroup: [t0, t_end)
@@ -281,6 +295,7 @@ static void plan_tiles(SparseGemmArgs &a, int slots)
     else if (rem != 0 && 2 * rem <= slots)
         a.rem_split = 2;
     a.n_full = a.rem_split > 1 ? a.tiles_total - rem : a.tiles_total;
+    a.per_die = slots % kDies == 0 ? slots / kDies : 0;
 }
 
 // Buffer offsets are 32 bits wide: the caller has checked that the weight and
@@ -318,3 +333,21 @@ int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *s
 }
 
 }  // namespace slim
+
+using namespace slim;
+
+extern "C" int slim_gemm_tile_order(int32_t n, int32_t m, int32_t *out, size_t count)
+{
+    if (!out) return SLIM_ERR_NULL;
+    if (n < 1 || m < 1) return SLIM_ERR_SHAPE;
+    SparseGemmArgs a{};
+    a.n = n;
+    a.m = m;
+    plan_tiles(a, device_info().cus);
+    if (count < (size_t)a.tiles_total + 2) return SLIM_ERR_SHAPE;
+    out[0] = a.tiles_total;
+    out[1] = a.n_full;
+    for (int w = 0; w < a.tiles_total; ++w) out[2 + w] = tile_of_workgroup(a, w, w < a.n_full);
+    return SLIM_OK;
+}
+

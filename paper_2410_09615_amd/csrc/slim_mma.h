@@ -101,6 +101,30 @@ __device__ __forceinline__ void mfma_fixed(half8_t av, half8_t bv)
                  : "v"(av), "v"(bv), "n"(16 * T), "n"(16 * T + 15));
 }
 
+// The order in which the prefill kernels hand output tiles (row tile x token tile) to workgroups.
+// These kernels are bound by the bytes their workgroups request from L2, and a die's L2 serves the
+// workgroups whose index is congruent to the die's modulo 8 (the dispatcher deals workgroups to the
+// dies in turn).  With tiles handed out in index order the 32 workgroups a die holds at a time are
+// scattered over the layer (8192 x 8192: 2 row tiles x 16 token tiles, 42 MB of distinct operands for
+// 4 MB of L2); in blocks of 4 row tiles x 8 token tiles they share 4 weight tiles and 8 X tiles
+// (28 MB), and the main kernel is 13 % faster on that layer.
+//   q -> tile: blocks of kBlkR x kBlkT tiles, row blocks fastest within a band of kBlkT token tiles,
+//   the tiles of a block rows fastest; ragged blocks at the edges just have fewer tiles.  Returns
+//   row tile + tiles_o * token tile.
+constexpr int kDies = 8, kBlkR = 4, kBlkT = 8;
+__host__ __device__ __forceinline__ int blocked_tile(int q, int tiles_o, int tiles_t)
+{
+    const int band = tiles_o * kBlkT;                       // tiles per band
+    const int tb_last = (tiles_t - 1) / kBlkT, rb_last = (tiles_o - 1) / kBlkR;
+    const int tb = q / band < tb_last ? q / band : tb_last;
+    const int bt = tiles_t - tb * kBlkT < kBlkT ? tiles_t - tb * kBlkT : kBlkT;            // token tiles in this band
+    const int q2 = q - tb * band;
+    const int rb = q2 / (kBlkR * bt) < rb_last ? q2 / (kBlkR * bt) : rb_last;
+    const int br = tiles_o - rb * kBlkR < kBlkR ? tiles_o - rb * kBlkR : kBlkR;            // row tiles in this block
+    const int e = q2 - rb * kBlkR * bt;
+    return (tb * kBlkT + e / br) * tiles_o + rb * kBlkR + e % br;
+}
+
 // Dense continuation on the fixed accumulators: acc(i, it) += A_i B_it^T over K
 // inputs (K a multiple of 32), 16 per step of V_MFMA_F32_32X32X16_F16.
 //   A: rows from global memory, 16 bytes per lane, row tile and step (da, av:

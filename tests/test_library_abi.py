@@ -219,3 +219,44 @@ def test_decode_plan_invariants_over_random_shapes():
         assert p["chunk_inputs"] % 1024 == 0 and p["chunk_inputs"] * p["chunks"] >= k
         if p["chunks"] > 1:
             assert rp <= p["chunk_inputs"] and (p["chunk_inputs"] // 512) % p["wavefronts_per_row_tile"] == 0
+
+
+def test_prefill_tile_order_covers_every_tile_once():
+    """Host logic of slim_linear_gemm: the order in which workgroups take output tiles is a permutation of
+    the tiles for every layer and token count (ragged edges included).  The 32 workgroups that share a
+    die's L2 in a round (index mod 8) work on a block of 4 row tiles x 8 token tiles at the configured
+    shapes, and over random shapes they touch no more distinct operand tiles than in index order (up to
+    what a ragged last band costs)."""
+    import random
+    from paper_2410_09615_amd import workloads as wl
+
+    def operand_tiles(n, m):
+        tiles, n_full, order = B.slim_gemm_tile_order(n, m)
+        tiles_o, tiles_t = (n + 511) // 512, (m + 127) // 128
+        assert tiles == tiles_o * tiles_t and 0 <= n_full <= tiles, (n, m)
+        assert sorted(order) == list(range(tiles)), (n, m)
+        blocked, plain, worst = 0, 0, (0, 0)
+        for start in range(0, n_full // 256 * 256, 256):
+            for die in range(8):
+                ws = range(start + die, start + 256, 8)
+                rows, toks = {order[w] % tiles_o for w in ws}, {order[w] // tiles_o for w in ws}
+                blocked += len(rows) + len(toks)
+                plain += len({w % tiles_o for w in ws}) + len({w // tiles_o for w in ws})
+                worst = max(worst, (len(rows), len(toks)))
+        return blocked, plain, worst
+
+    for shp, m in ((wl.L7B_UP, 2048), (wl.L7B_DOWN, 2048), (wl.L13B_ATTN, 4096), (wl.L13B_UP, 4096), (wl.L70B_ATTN, 4096),
+                   (wl.L70B_UP, 4096)):
+        blocked, plain, worst = operand_tiles(shp.n, m)
+        assert worst[0] <= 8 and worst[1] <= 8 and blocked <= plain, (shp.name, worst, blocked, plain)
+    rnd = random.Random(11)
+    for n, m in [(1, 1), (513, 129), (512 * 9, 128 * 3), (40000, 300)] + [(rnd.randint(1, 40000), rnd.randint(1, 9000))
+                                                                      for _ in range(80)]:
+        blocked, plain, _ = operand_tiles(n, m)
+        assert blocked <= 1.1 * plain + 8, (n, m, blocked, plain)
+    for bad in ((0, 1), (1, 0)):
+        out = (ctypes.c_int32 * 8)()
+        assert B.lib().slim_gemm_tile_order(bad[0], bad[1], out, 8) == B.SLIM_ERR_SHAPE
+    out = (ctypes.c_int32 * 3)()
+    assert B.lib().slim_gemm_tile_order(1024, 256, out, 3) == B.SLIM_ERR_SHAPE
+    assert B.lib().slim_gemm_tile_order(1024, 256, None, 100) == B.SLIM_ERR_NULL
