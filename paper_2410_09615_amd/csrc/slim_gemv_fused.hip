@@ -299,7 +299,6 @@ __device__ __forceinline__ void role_y(const FusedArgs &a, half_t *lds, int yb, 
     const int tstride = ygrid * tpw;
     const int rounds = (wtiles - yb * tpw + tstride - 1) / tstride;      // same for the whole workgroup
     const uint32_t kt = pk_ktiles(a.k);
-    const uint4_t zero = {0u, 0u, 0u, 0u};
 
     auto tile_of = [&](int r) { return tile0 + r * tstride; };   // r >= rounds: past the last tile, loads read zeros
     // Loads of item j of the row tile of round r: ALWAYS the same eight load instructions, whatever the
