@@ -459,6 +459,32 @@ def fp8_round(v: np.ndarray, fmt: str) -> np.ndarray:
     return np.copysign(np.minimum(r, fmax), v)      # the formats have signed zeros: what rounds to zero keeps its sign
 
 
+def fp8_encode(v: np.ndarray, fmt: str) -> np.ndarray:
+    """8-bit codes (uint8) of values that lie on the format's grid, as fp8_round returns them: sign in
+    bit 7, then the exponent field (bias 1 - smallest normal exponent: 7 for E4M3, 15 for E5M2) and the
+    mantissa; below the smallest normal value the exponent field is 0 and the mantissa counts the
+    format's smallest spacing."""
+    p, emin, fmax = FP8_FORMATS[fmt]
+    v = np.asarray(v, np.float64)
+    a = np.abs(v)
+    assert np.all(a <= fmax)
+    e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    sub = a < 2.0 ** emin
+    field = np.where(sub, 0.0, e + (1 - emin))
+    mant = np.where(sub, a / 2.0 ** (emin - p), (a / np.exp2(e) - 1.0) * (1 << p))
+    assert np.array_equal(mant, np.rint(mant)), "a value off the format's grid"
+    return ((np.signbit(v).astype(np.int64) << 7) | (field.astype(np.int64) << p) | mant.astype(np.int64)).astype(np.uint8)
+
+
+def input_quant_fp8_codes(X: np.ndarray):
+    """(codes uint8, scale, format) of the same quantization as input_quant_fp8: the 8-bit codes of
+    fp8_round(x / scale), i.e. of the quantized values before they go back to the fp16 grid."""
+    X = np.asarray(X)
+    _, s, fmt = input_quant_fp8(X)
+    qv = fp8_round((X.astype(np.float32) / s).astype(np.float32), fmt)
+    return fp8_encode(qv, fmt), s, fmt
+
+
 def input_quant_fp8(X: np.ndarray):
     """X fp16 -> (X' fp16, scale float32, format name).  M = max|X|; the format is E4M3 unless
     M exceeds its largest value 448, then E5M2; scale = M / (largest value of the format) in

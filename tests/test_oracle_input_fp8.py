@@ -103,3 +103,42 @@ def test_signed_zero_is_kept():
     X = np.array([[1.0, -0.0, 0.0, -6e-8, 6e-8]], np.float16)        # 6e-8: the smallest fp16 subnormal
     Xq, _, _ = O.input_quant_fp8(X)
     assert Xq.view(np.uint16).tolist() == [[0x3C00, 0x8000, 0x0000, 0x8000, 0x0000]]
+
+
+def _decode(code, exp_bits, man_bits, bias):
+    """Value of one 8-bit code from its bit fields (finite codes only)."""
+    sign = -1.0 if code & 0x80 else 1.0
+    e, m = (code & 0x7F) >> man_bits, code & ((1 << man_bits) - 1)
+    return sign * (m * 2.0 ** (1 - bias - man_bits) if e == 0 else (1 + m / (1 << man_bits)) * 2.0 ** (e - bias))
+
+
+@pytest.mark.parametrize("fmt,exp_bits,man_bits,bias", [("e4m3", 4, 3, 7), ("e5m2", 5, 2, 15)])
+def test_codes_are_the_bit_fields_of_the_values(fmt, exp_bits, man_bits, bias):
+    """fp8_encode against a decoder written from the formats' bit definition: every finite code decodes to a
+    value whose code it is (both signs, both zeros), so encode is the inverse of the definition."""
+    finite = [c for c in range(256) if not ((fmt == "e4m3" and (c & 0x7F) == 0x7F) or
+                                             (fmt == "e5m2" and ((c & 0x7F) >> man_bits) == (1 << exp_bits) - 1))]
+    vals = np.array([_decode(c, exp_bits, man_bits, bias) for c in finite])
+    assert np.array_equal(O.fp8_encode(vals, fmt), np.array(finite, np.uint8))
+    # a few known codes: 1.0, the largest value, the smallest subnormal, -2.0
+    known = {"e4m3": {1.0: 0x38, 448.0: 0x7E, 2.0 ** -9: 0x01, -2.0: 0xC0},
+             "e5m2": {1.0: 0x3C, 57344.0: 0x7B, 2.0 ** -16: 0x01, -2.0: 0xC0}}[fmt]
+    for v, c in known.items():
+        assert int(O.fp8_encode(np.array([v]), fmt)[0]) == c
+    with pytest.raises(AssertionError):
+        O.fp8_encode(np.array([1.0 + 2.0 ** -(man_bits + 1)]), fmt)           # not on the grid
+
+
+def test_input_quant_codes_decode_to_the_quantized_values():
+    rng = np.random.default_rng(4)
+    for X in (rng.standard_normal((8, 200)).astype(np.float16), (rng.standard_normal((4, 64)) * 300).astype(np.float16),
+              np.zeros((2, 16), np.float16)):
+        codes, s, fmt = O.input_quant_fp8_codes(X)
+        Xq, s2, fmt2 = O.input_quant_fp8(X)
+        assert s == s2 and fmt == fmt2 and codes.dtype == np.uint8 and codes.shape == X.shape
+        eb, mb, bias = (4, 3, 7) if fmt == "e4m3" else (5, 2, 15)
+        vals = np.array([_decode(int(c), eb, mb, bias) for c in codes.ravel()]).reshape(X.shape)
+        # the values the codes stand for, times the scale and rounded to fp16, are the quantizer's fp16 output
+        assert np.array_equal((vals.astype(np.float32) * s).astype(np.float32).astype(np.float16).view(np.uint16) & 0x7FFF,
+                              Xq.view(np.uint16) & 0x7FFF)
+        assert np.array_equal(np.signbit(vals), np.signbit(Xq.astype(np.float32)))
