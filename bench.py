@@ -194,6 +194,38 @@ def main():
             rec["roofline_frac_alg"] = round(falg / ms * 1e-9 / MFMA_PEAK_TFLOPS, 4)
         return rec
 
+    def fp8_leg(rot, m, iters, warm):
+        """slim_linear_gemm_fp8 on the rotation's inputs quantized once (App. "Input Quantization"): codes, scale and
+        the fp16 copy resident before the timed region; the quantizer itself is timed beside it."""
+        shape = rot.shape
+        q = [B.slim_input_quant_fp8(x, codes=True) for x in rot.X[m]]
+        torch.cuda.synchronize()
+        fmt = int(q[0][1][1])
+
+        def call(i):
+            xq, info, codes = q[i % len(q)]
+            B.slim_linear_gemm_fp8(rot.layers[i % rot.copies], codes, info, fmt, xq, rot.Y[m][i % len(q)], rot.ws[m][i % len(rot.ws[m])])
+        for i in range(warm):
+            call(i)
+        ms_b = batches_ms(call, iters)
+        ms = statistics.median(ms_b)
+        ms16 = statistics.median(batches_ms(lambda i: rot.call(B.slim_linear_gemm, m, i), iters, 3))
+        x0 = rot.X[m][0]
+        ms_q = statistics.median(batches_ms(lambda i: B.slim_input_quant_fp8(x0, q[0][0], q[0][1], None, q[0][2]), iters, 3))
+        for i in range(3):
+            rot.dense_call(m, i)
+        ms_dense = statistics.median(batches_ms(lambda i: rot.dense_call(m, i), iters, 3))
+        feff = A.flops_eff(shape.n, shape.k, shape.r, m)
+        return {"shape": shape.name, "tokens": m, "entry": "slim_linear_gemm_fp8", "inputs": "E4M3" if fmt == 0 else "E5M2",
+                "us": round(ms * 1e3, 3), "us_min": round(min(ms_b) * 1e3, 3), "batches": len(ms_b), "launches_per_batch": iters,
+                "TFLOPs_eff": round(feff / ms * 1e-9, 2), "fp16_inputs_us": round(ms16 * 1e3, 3),
+                "input_quant_us": round(ms_q * 1e3, 3), "dense_fp16_us": round(ms_dense * 1e3, 3),
+                "speedup_vs_dense_fp16": round(ms_dense / ms, 3), "speedup_vs_fp16_inputs": round(ms16 / ms, 3),
+                "bound": "mfma", "roofline_frac": round(feff / ms * 1e-9 / 5000.0, 4),
+                "roofline_frac_counts": "dense-equivalent FLOPs (flops_eff) over the dense FP8 peak, 5.0 PFLOP/s: the weight term runs "
+                                        "on the 8-bit instruction, the adapters (a fifth of the FLOPs) on fp16",
+                "roofline_frac_fp16_peak": round(feff / ms * 1e-9 / MFMA_PEAK_TFLOPS, 4)}
+
     # ---------------- headline: LLaMA-2-70B-shaped up projection, decode ----------------
     by_name = {c.name: c for c in (wl.L7B_ATTN, wl.L7B_UP, wl.L7B_DOWN, wl.L13B_ATTN, wl.L13B_UP, wl.L70B_ATTN, wl.L70B_UP)}
     if args.layer not in by_name:
@@ -388,6 +420,12 @@ def main():
             legs.append(leg_record(r, 4096, B.slim_linear_gemm, 8, 3, "slim_linear_gemm"))
             del r
             torch.cuda.empty_cache()
+            # 8-bit inputs (App. "Input Quantization"): the weight term on the 8-bit sparse matrix instruction
+            for shp, m in ((wl.L7B_UP, 2048), (wl.L70B_ATTN, 4096), (wl.L70B_UP, 4096)):
+                r = Rotating(shp, (m,), min_copies=2, max_bytes=1 << 30)
+                legs.append(fp8_leg(r, m, 8, 3))
+                del r
+                torch.cuda.empty_cache()
 
     out = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,

@@ -41,7 +41,8 @@ EXPORTS = ["slim_status_string", "slim_rank_pad", "slim_packed_sizes", "slim_pac
            "slim_lowrank",
            "slim_adapter_q4_sizes", "slim_pack_adapters_q4", "slim_unpack_adapters_q4", "slim_pack_ex",
            "slim_quant_workspace_bytes", "slim_quant_search", "slim_quant_search_rows", "slim_adapters_workspace_bytes",
-           "slim_compute_adapters", "slim_input_quant_fp8", "slim_probe_read", "slim_probe_mfma", "slim_gemm_tile_order"]
+           "slim_compute_adapters", "slim_input_quant_fp8", "slim_probe_read", "slim_probe_mfma", "slim_gemm_tile_order", "slim_input_quant_fp8_codes",
+           "slim_linear_gemm_fp8"]
 
 
 def lib():
@@ -83,6 +84,8 @@ def lib():
         L.slim_linear_gemv_static.argtypes = [ctypes.POINTER(slim_layer), vp, i32, vp, vp]
         L.slim_lowrank.argtypes = [vp, i32, vp, vp, slim_shape, i32, vp, ctypes.c_int, vp, sz, vp]
         L.slim_gemm_tile_order.argtypes = [i32, i32, pi32, sz]
+        L.slim_input_quant_fp8_codes.argtypes = [vp, sz, vp, vp, vp, vp, sz, vp]
+        L.slim_linear_gemm_fp8.argtypes = [ctypes.POINTER(slim_layer), vp, vp, i32, vp, i32, vp, vp, sz, vp]
         for name in EXPORTS[2:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -246,11 +249,17 @@ def slim_compute_adapters(W: torch.Tensor, qvals, meta, scale, rank: int, x_tild
     return L, R, diag
 
 
-def slim_input_quant_fp8(X: torch.Tensor, Xq=None, info=None, workspace=None):
+def slim_input_quant_fp8(X: torch.Tensor, Xq=None, info=None, workspace=None, codes=None):
     """FP8 AbsMax quantization of an input tensor, values back on the fp16 grid:
     (Xq fp16 like X, info fp32 [2] = scale, format (0: E4M3, 1: E5M2)).  Xq, info and a
-    workspace of at least 1024 bytes may be passed in (a caller in a loop)."""
+    workspace of at least 1024 bytes may be passed in (a caller in a loop).  codes=True (or a uint8
+    tensor of X's size): also the 8-bit codes, for slim_linear_gemm_fp8; returns (Xq, info, codes)."""
     _dev(X, torch.float16, "X")
+    if codes is True:
+        codes = torch.empty(X.shape, dtype=torch.uint8, device=X.device)
+    if codes is not None and (codes.dtype != torch.uint8 or codes.numel() != X.numel() or codes.device != X.device
+                              or not codes.is_contiguous()):
+        raise ValueError("codes must be contiguous uint8 with X's size on X's device")
     if Xq is None:
         Xq = torch.empty_like(X)
     elif Xq.dtype != torch.float16 or Xq.numel() != X.numel() or Xq.device != X.device or not Xq.is_contiguous():
@@ -262,6 +271,10 @@ def slim_input_quant_fp8(X: torch.Tensor, Xq=None, info=None, workspace=None):
     ws = workspace if workspace is not None else torch.empty(1024, dtype=torch.uint8, device=X.device)
     if ws.device != X.device:
         raise ValueError("workspace must be on X's device")
+    if codes is not None:
+        _check("slim_input_quant_fp8_codes", lib().slim_input_quant_fp8_codes(_ptr(X), X.numel(), _ptr(Xq), _ptr(codes), _ptr(info),
+                                                                              _ptr(ws), ws.numel(), _stream(X)))
+        return Xq, info, codes
     _check("slim_input_quant_fp8", lib().slim_input_quant_fp8(_ptr(X), X.numel(), _ptr(Xq), _ptr(info), _ptr(ws), ws.numel(),
                                                               _stream(X)))
     return Xq, info
@@ -499,6 +512,25 @@ def slim_linear_gemv_static(layer: SlimLayer, X: torch.Tensor, Y: torch.Tensor) 
 def slim_linear_gemm(layer: SlimLayer, X: torch.Tensor, Y=None, workspace=None) -> torch.Tensor:
     """Prefill-shaped forward."""
     return _forward("slim_linear_gemm", layer, X, Y, workspace)
+
+
+def slim_linear_gemm_fp8(layer: SlimLayer, codes: torch.Tensor, info: torch.Tensor, fmt: int, Xq: torch.Tensor, Y=None,
+                         workspace=None) -> torch.Tensor:
+    """Prefill-shaped forward on 8-bit inputs: codes uint8 [m][k], info (scale, format) and Xq fp16 [m][k] as
+    slim_input_quant_fp8(..., codes=True) returns them; fmt = 0 (E4M3) or 1 (E5M2), the format in info[1]."""
+    _dev(Xq, torch.float16, "Xq")
+    _dev(codes, torch.uint8, "codes")
+    _dev(info, torch.float32, "info")
+    m, k = Xq.shape
+    if k != layer.k or codes.numel() != m * k or info.numel() < 2:
+        raise ValueError("codes and Xq must be [m][k], info [2]")
+    if Y is None:
+        Y = torch.empty(m, layer.n, dtype=torch.float16, device=Xq.device)
+    if workspace is None:
+        workspace = alloc_workspace(layer, m)
+    _check("slim_linear_gemm_fp8", lib().slim_linear_gemm_fp8(layer.c_ref(), _ptr(codes), _ptr(info), int(fmt), _ptr(Xq), m, _ptr(Y),
+                                                              _ptr(workspace), workspace.numel(), _stream(Xq)))
+    return Y
 
 
 def slim_lowrank(X: torch.Tensor, R_pad: torch.Tensor, L_pad: torch.Tensor, n: int, rank: int, Y=None,

@@ -185,8 +185,8 @@ static int launch_t(const half_t *X, int m, const half_t *R, int k, int rank_pad
 }
 
 int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *scale, const half_t *X, const half_t *L,
-                       const half_t *T, half_t *Y, int n, int k, int rank_pad, int m,
-                       hipStream_t st);   // slim_gemm_sparse.hip
+                       const half_t *T, half_t *Y, int n, int k, int rank_pad, int m, hipStream_t st, int xf,
+                       const float *x_scale);   // slim_gemm_sparse.hip
 
 int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t *L, int n, int k, int rank, int rank_pad,
                           half_t *Y, int accumulate, float *T, void *T16, unsigned *ctrl, hipStream_t st);   // slim_gemv.hip
@@ -195,10 +195,15 @@ int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t 
 
 using namespace slim;
 
-extern "C" int slim_linear_gemm(const slim_layer *layer_in, const slim_half *X, int32_t m, slim_half *Y,
-                                void *workspace, size_t workspace_bytes, void *stream)
+// X: fp16 [m][k].  X8 (with xf = 1 or 2, and x_info = {scale, format} in device memory): the same tensor as
+// 8-bit codes for the weight term; X then serves the adapter term only.
+static int linear_gemm(const slim_layer *layer_in, const slim_half *X, const uint8_t *X8, int xf, const float *x_info,
+                       int32_t m, slim_half *Y, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!layer_in || !X || !Y) return SLIM_ERR_NULL;
+    if (xf != 0 && (!X8 || !x_info)) return SLIM_ERR_NULL;
+    if (xf < 0 || xf > 2) return SLIM_ERR_SHAPE;
+    if (xf != 0 && !aligned16(X8)) return SLIM_ERR_ALIGN;
     const slim_layer *layer = layer_in;
     const slim_shape s = layer->shape;
     if (!layer->qvals || !layer->meta || !layer->scale) return SLIM_ERR_NULL;
@@ -236,8 +241,23 @@ extern "C" int slim_linear_gemm(const slim_layer *layer_in, const slim_half *X, 
         if (rc != SLIM_OK) return rc;
     }
 
-    return launch_gemm_sparse(layer->qvals, layer->meta, layer->scale, Xh, reinterpret_cast<const half_t *>(layer->L),
-                              T, reinterpret_cast<half_t *>(Y), s.n, s.k, rp, m, st);
+    return launch_gemm_sparse(layer->qvals, layer->meta, layer->scale, xf ? reinterpret_cast<const half_t *>(X8) : Xh,
+                              reinterpret_cast<const half_t *>(layer->L), T, reinterpret_cast<half_t *>(Y), s.n, s.k, rp, m, st,
+                              xf, x_info);
+}
+
+extern "C" int slim_linear_gemm(const slim_layer *layer, const slim_half *X, int32_t m, slim_half *Y, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    return linear_gemm(layer, X, nullptr, 0, nullptr, m, Y, workspace, workspace_bytes, stream);
+}
+
+extern "C" int slim_linear_gemm_fp8(const slim_layer *layer, const uint8_t *X8, const float *x_info, int32_t format,
+                                    const slim_half *Xq, int32_t m, slim_half *Y, void *workspace, size_t workspace_bytes,
+                                    void *stream)
+{
+    if (format != 0 && format != 1) return SLIM_ERR_SHAPE;
+    return linear_gemm(layer, Xq, X8, 1 + format, x_info, m, Y, workspace, workspace_bytes, stream);
 }
 
 extern "C" int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, const slim_half *L, slim_shape shape,

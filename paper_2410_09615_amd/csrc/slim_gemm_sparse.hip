@@ -26,11 +26,15 @@
 
 namespace slim {
 
+typedef int int4_t __attribute__((ext_vector_type(4)));
+typedef int int8v_t __attribute__((ext_vector_type(8)));
+
 struct SparseGemmArgs {
     const uint8_t *qvals;
     const uint8_t *meta;
     const float *scale;
-    const half_t *X;     // [m][k]
+    const half_t *X;     // [m][k] fp16, or (XF != 0) the same tensor as 8-bit codes, one byte per value
+    const float *x_scale; // XF != 0: the tensor's scale (device memory)
     const half_t *L;     // [n][rank_pad]
     const half_t *T;     // [m][rank_pad] fp16
     half_t *Y;           // [m][n]
@@ -55,8 +59,36 @@ __host__ __device__ __forceinline__ int tile_of_workgroup(const SparseGemmArgs &
     return blocked_tile(q, a.tiles_o, a.tiles_total / a.tiles_o);
 }
 
+// Sparse step with 8-bit operands on accumulator tile T: a[16 T ..] += A(sparse, 32 x 64, E5M2 codes of
+// the integer weights) B(64 x 32, FP8 inputs: E4M3, or E5M2 with E5).  The index operand is one
+// dword: 8 groups of four inputs per lane.
+template <int T, bool E5>
+__device__ __forceinline__ void smfmac8_fixed(int4_t av, int8v_t bv, int idx)
+{
+    if (E5)
+        asm volatile("v_smfmac_f32_32x32x64_bf8_bf8 a[%3:%4], %0, %1, %2"
+                     :
+                     : "v"(av), "v"(bv), "v"(idx), "n"(16 * T), "n"(16 * T + 15));
+    else
+        asm volatile("v_smfmac_f32_32x32x64_bf8_fp8 a[%3:%4], %0, %1, %2"
+                     :
+                     : "v"(av), "v"(bv), "v"(idx), "n"(16 * T), "n"(16 * T + 15));
+}
+
+// Eight codes (a dword) -> eight E5M2 bytes: the integers -8 .. 7 as fp16 have nothing below their two
+// top mantissa bits, so the E5M2 code of a value is the high byte of its fp16 code.
+__device__ __forceinline__ uint2_t codes_to_e5m2x8(uint32_t q)
+{
+    const uint4_t h = __builtin_bit_cast(uint4_t, codes_to_half8(q));
+    return uint2_t{__builtin_amdgcn_perm(h[1], h[0], 0x07050301u), __builtin_amdgcn_perm(h[3], h[2], 0x07050301u)};
+}
+
 // AT row tiles of 32 per wavefront; accumulator tile (i, it) is a[16 (i NT + it) ..].
-template <int AT>
+// XF: 0 = X in fp16; 1, 2 = X as 8-bit codes (E4M3, E5M2) with one scale for the tensor
+// (App. "Input Quantization"): the weight term then runs on the 8-bit sparse instruction, 64 inputs
+// per step, on half the bytes of X; the adapter term is unchanged (its T comes from the caller's
+// fp16 copy of the quantized X).
+template <int AT, int XF = 0>
 __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
 {
     constexpr int WROWS = 32 * AT;       // rows per wavefront
@@ -157,6 +189,109 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
         });
     };
 
+    if constexpr (XF != 0) {
+        // ---- 8-bit inputs ----
+        // A stage is 128 tokens x 128 inputs = 16 KiB in LDS, rows of 144 bytes.  Within a row the
+        // inputs are stored in the order in which the lanes of the 8-bit instruction want them: for
+        // step u (64 inputs of the stage) lane half h takes 32 contiguous bytes at 64 u + 32 h, the
+        // inputs 32 u + 16 h + [0, 16) and 64 + 32 u + 16 h + [0, 16) -- the packed layout gives lane
+        // half lb the inputs 16 t + 8 lb + [0, 8) and 64 + 16 t + 8 lb + [0, 8) of slice t, and a step is
+        // two slices.  (Checked on the GPU with one-hot inputs.)  A staging thread moves 16 contiguous
+        // bytes.
+        constexpr int F8_LD = 144, F8_STAGE = 128 * F8_LD;
+        unsigned char *const lds8 = reinterpret_cast<unsigned char *>(lds);
+        const rsrc_t dq = make_rsrc(a.qvals, (uint32_t)pk_qbytes(a.n, a.k));
+        const rsrc_t dm = make_rsrc(a.meta, (uint32_t)pk_mbytes(a.n, a.k));
+        const rsrc_t dx = make_rsrc(a.X, (uint32_t)a.m * k);
+        const int srow8 = tid >> 3, c16 = tid & 7;
+        const uint32_t xv8 = (uint32_t)(t0 + srow8) * k + 16u * (uint32_t)c16;
+        unsigned char *const lw8 = lds8 + srow8 * F8_LD + 64 * ((c16 & 3) >> 1) + 32 * (c16 & 1) + 16 * (c16 >> 2);
+        const unsigned char *const lr8 = lds8 + li * F8_LD + 32 * lb;
+        uint4_t x8[2][4];
+        auto fetch_x8 = [&](int p, int s, uint4_t (&reg)[4]) {
+            reg[p] = load16(dx, xv8, (uint32_t)s * 128u + (uint32_t)p * 32u * k);
+        };
+        auto stage_store8 = [&](int u, const uint4_t (&reg)[4]) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4_t *>(lw8 + u * F8_STAGE + p * 32 * F8_LD) = reg[p];
+        };
+        auto read_b8 = [&](int ub, int u, int it) {
+            const unsigned char *bp = lr8 + ub * F8_STAGE + it * 32 * F8_LD + 64 * u;
+            const uint4_t b1 = *reinterpret_cast<const uint4_t *>(bp);
+            const uint4_t b2 = *reinterpret_cast<const uint4_t *>(bp + 16);
+            return int8v_t{(int)b1[0], (int)b1[1], (int)b1[2], (int)b1[3], (int)b2[0], (int)b2[1], (int)b2[2], (int)b2[3]};
+        };
+        auto fetch_a = [&](int j, int s, uint4_t (&q)[AT], uint2_t (&mm)[AT]) {    // j < 2 AT
+            if (j < AT)
+                q[j] = load16(dq, qv, ((uint32_t)j * (k / 128) + (uint32_t)s) * 1024u);
+            else
+                mm[j - AT] = load8(dm, mv, ((uint32_t)(j - AT) * (k / 128) + (uint32_t)s) * 512u);
+        };
+        // One stage = 2 steps (u) x NT token tiles: 2 NT blocks of AT matrix instructions.  The codes of
+        // step 1 are converted while step 0's instructions run.
+        auto compute_stage8 = [&](int ub, const uint4_t (&q)[AT], const uint2_t (&mm)[AT], auto &&fetch) {
+            int4_t a8[2][AT];
+#pragma unroll
+            for (int i = 0; i < AT; ++i) {
+                const uint2_t c0 = codes_to_e5m2x8(q[i][0]), c1 = codes_to_e5m2x8(q[i][1]);
+                a8[0][i] = int4_t{(int)c0[0], (int)c0[1], (int)c1[0], (int)c1[1]};
+            }
+            int8v_t b_cur = read_b8(ub, 0, 0), b_nxt = b_cur;
+            asm volatile("s_nop 3");
+            static_for<2>([&](auto uc) {
+                constexpr int u = uc;
+                static_for<NT>([&](auto itc) {
+                    constexpr int it = itc;
+                    if (it + 1 < NT)
+                        b_nxt = read_b8(ub, u, it + 1);
+                    else if (u + 1 < 2)
+                        b_nxt = read_b8(ub, u + 1, 0);
+                    fetch(std::integral_constant<int, u * NT + it>{});
+                    __builtin_amdgcn_sched_barrier(0);
+                    static_for<AT>([&](auto ic) {
+                        constexpr int i = ic;
+                        smfmac8_fixed<i * NT + it, XF == 2>(a8[u][i], b_cur, (int)mm[i][u]);
+                        if constexpr (u == 0 && it < AT && i == 0) {
+                            // tile `it` of step 1
+                            const uint2_t c0 = codes_to_e5m2x8(q[it][2]), c1 = codes_to_e5m2x8(q[it][3]);
+                            a8[1][it] = int4_t{(int)c0[0], (int)c0[1], (int)c1[0], (int)c1[1]};
+                        }
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
+                    b_cur = b_nxt;
+                });
+                if constexpr (u == 0) asm volatile("s_nop 3");
+            });
+        };
+#pragma unroll
+        for (int p = 0; p < 4; ++p) fetch_x8(p, 0, x8[0]);
+#pragma unroll
+        for (int j = 0; j < 2 * AT; ++j) fetch_a(j, 0, qa[0], ma[0]);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) fetch_x8(p, 1, x8[1]);
+        stage_store8(0, x8[0]);
+        __syncthreads();
+        for (int s0 = 0; s0 < nsteps; s0 += 2) {
+            static_for<2>([&](auto uc) {
+                constexpr int u = uc;
+                const int s = s0 + u;
+                if (s >= nsteps) return;
+                compute_stage8(u, qa[u], ma[u], [&](auto bc) {
+                    constexpr int bi = bc;           // 0 .. 2 NT - 1
+                    if constexpr (bi < NT) {
+                        constexpr int per = (2 * AT + NT - 1) / NT;      // weights of stage s + 1
+#pragma unroll
+                        for (int j = bi * per; j < (bi + 1) * per && j < 2 * AT; ++j)
+                            fetch_a(j, s + 1, qa[u ^ 1], ma[u ^ 1]);
+                    } else {
+                        fetch_x8(bi - NT, s + 2, x8[u]);                 // X of stage s + 2: four loads
+                    }
+                });
+                stage_store8(u ^ 1, x8[u ^ 1]);
+                __syncthreads();
+            });
+        }
+    } else {
     // The global loads are spread over the stage, one or two per block, so the
     // four wavefronts do not all queue sixteen loads at the address unit right
     // after the barrier (that burst stalled the first slice of every stage).
@@ -210,8 +345,12 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
         }
     }
 
-    // row scale: accumulator element 4 blk + e of tile i is row 32 i + 8 blk + 4 lb + e
+    }
+
+    // row scale (times the scale of the 8-bit inputs): accumulator element 4 blk + e of tile i is row 32 i + 8 blk + 4 lb + e
     {
+        float xs = 1.0f;
+        if constexpr (XF != 0) xs = *a.x_scale;
         acc_settle();
         const rsrc_t rs = make_rsrc(a.scale, (uint32_t)a.n * 4u);
         static_for<AT>([&](auto ic) {
@@ -227,7 +366,7 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
                     // (bit-casting the vector element in place reads element 0 with this
                     // compiler; go through a scalar)
                     const uint32_t sbits = sv[e / 4][e % 4];
-                    const float sc = __builtin_bit_cast(float, sbits);
+                    const float sc = __builtin_bit_cast(float, sbits) * xs;
                     acc_write<16 * (i * NT + it) + e>(acc_read<16 * (i * NT + it) + e>() * sc);
                 });
             });
@@ -301,8 +440,10 @@ static void plan_tiles(SparseGemmArgs &a, int slots)
 // Buffer offsets are 32 bits wide: the caller has checked that the weight and
 // adapter matrices stay below 4 GiB each; X, T and Y are walked in token chunks
 // that do.
+// xf: 0 = X fp16; 1, 2 = X as E4M3 / E5M2 codes (one byte per value) with the tensor's scale at x_scale
 int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *scale, const half_t *X, const half_t *L,
-                       const half_t *T, half_t *Y, int n, int k, int rank_pad, int m, hipStream_t st)
+                       const half_t *T, half_t *Y, int n, int k, int rank_pad, int m, hipStream_t st, int xf,
+                       const float *x_scale)
 {
     SparseGemmArgs a{};
     a.qvals = qvals;
@@ -312,22 +453,31 @@ int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *s
     a.n = n;
     a.k = k;
     a.rank_pad = rank_pad;
+    a.x_scale = x_scale;
+    const size_t xbytes = xf ? 1 : 2;       // bytes per value of X
     const uint64_t row_bytes = 2ull * (uint64_t)(k > rank_pad ? k : rank_pad);
     const int chunk = (int)((0xFFFFFFFFull / row_bytes) / 128 * 128);
     if (chunk < 128) return SLIM_ERR_SHAPE;
     const size_t lds = (size_t)2 * SG_STAGE * sizeof(half_t);
     for (int t0 = 0; t0 < m; t0 += chunk) {
         a.m = m - t0 < chunk ? m - t0 : chunk;
-        a.X = X + (size_t)t0 * k;
+        a.X = reinterpret_cast<const half_t *>(reinterpret_cast<const char *>(X) + (size_t)t0 * k * xbytes);
         a.T = T ? T + (size_t)t0 * rank_pad : nullptr;
         a.Y = Y + (size_t)t0 * n;
         plan_tiles(a, device_info().cus);
         const int n_rem = a.rem_split * (a.tiles_total - a.n_full);
-        if (a.n_full > 0) hipLaunchKernelGGL(gemm_sparse_kernel<4>, dim3((unsigned)a.n_full), dim3(256), lds, st, a);
-        if (n_rem > 0 && a.rem_split == 2)
-            hipLaunchKernelGGL(gemm_sparse_kernel<2>, dim3((unsigned)n_rem), dim3(256), lds, st, a);
-        if (n_rem > 0 && a.rem_split == 4)
-            hipLaunchKernelGGL(gemm_sparse_kernel<1>, dim3((unsigned)n_rem), dim3(256), lds, st, a);
+        auto launch = [&](auto atc, unsigned grid) {
+            constexpr int AT = decltype(atc)::value;
+            if (xf == 0)
+                hipLaunchKernelGGL((gemm_sparse_kernel<AT, 0>), dim3(grid), dim3(256), lds, st, a);
+            else if (xf == 1)
+                hipLaunchKernelGGL((gemm_sparse_kernel<AT, 1>), dim3(grid), dim3(256), lds, st, a);
+            else
+                hipLaunchKernelGGL((gemm_sparse_kernel<AT, 2>), dim3(grid), dim3(256), lds, st, a);
+        };
+        if (a.n_full > 0) launch(std::integral_constant<int, 4>{}, (unsigned)a.n_full);
+        if (n_rem > 0 && a.rem_split == 2) launch(std::integral_constant<int, 2>{}, (unsigned)n_rem);
+        if (n_rem > 0 && a.rem_split == 4) launch(std::integral_constant<int, 1>{}, (unsigned)n_rem);
     }
     return hip_status(hipGetLastError());
 }

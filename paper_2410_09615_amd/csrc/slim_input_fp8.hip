@@ -52,8 +52,21 @@ __device__ __forceinline__ float fp8_round_abs(float v, float fmax)
     return fminf(rintf(a * qinv) * q, fmax);
 }
 
+// The 8-bit code of a value r >= 0 that lies on the format's grid (P mantissa bits, exponent bias BIAS,
+// smallest normal exponent EMIN): exponent field and mantissa from r's binary32 bits; subnormals count
+// in units of the format's smallest spacing.
+template <int P, int EMIN, int BIAS>
+__device__ __forceinline__ uint32_t fp8_bits_abs(float r)
+{
+    const uint32_t b = __float_as_uint(r);
+    const int e = (int)((b >> 23) & 0xFFu) - 127;
+    if (r == 0.f) return 0u;
+    if (e < EMIN) return (uint32_t)(r * __uint_as_float((uint32_t)(P - EMIN + 127) << 23));      // r / 2^(EMIN - P), an integer below 2^P
+    return ((uint32_t)(e + BIAS) << P) | ((b >> (23 - P)) & ((1u << P) - 1u));
+}
+
 __global__ __launch_bounds__(256) void input_fp8_kernel(const half_t *__restrict__ X, size_t count, const float *part, int nparts,
-                                                        half_t *Xq, float *info)
+                                                        half_t *Xq, uint8_t *Xb, float *info)
 {
     __shared__ float red[4];
     float a = (int)threadIdx.x < nparts ? part[threadIdx.x] : 0.f;
@@ -70,35 +83,56 @@ __global__ __launch_bounds__(256) void input_fp8_kernel(const half_t *__restrict
     }
     // The sign is carried over as a bit: the product's conversion to half may be contracted into a
     // fused multiply-add with a +0 addend, which would turn a result of -0 into +0.
-    auto one = [&](half_t x) {
+    // code: the 8-bit code of the same value (sign bit 7), for the kernels that take FP8 operands
+    auto one = [&](half_t x, uint32_t &code) {
         const float v = (float)x / s;
         const float r = e5 ? fp8_round_abs<2, -14>(v, fmax) : fp8_round_abs<3, -6>(v, fmax);
-        const half_t h = (half_t)(r * s);
-        const uint16_t bits = (uint16_t)(__builtin_bit_cast(uint16_t, h) | (__builtin_bit_cast(uint16_t, x) & 0x8000u));
+        // product rounded to binary32, then to binary16 (two roundings, as defined): the empty asm hides the
+        // product from the compiler, which would otherwise fuse the two into one mixed-precision
+        // multiply-add that rounds once
+        float prod = r * s;
+        asm volatile("" : "+v"(prod));
+        const half_t h = (half_t)prod;
+        const uint16_t sign = (uint16_t)(__builtin_bit_cast(uint16_t, x) & 0x8000u);
+        const uint16_t bits = (uint16_t)(__builtin_bit_cast(uint16_t, h) | sign);
+        code = (e5 ? fp8_bits_abs<2, -14, 15>(r) : fp8_bits_abs<3, -6, 7>(r)) | (uint32_t)(sign >> 8);
         return __builtin_bit_cast(half_t, bits);
     };
     const size_t n8 = count / 8;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (size_t)gridDim.x * blockDim.x) {
         const half8_t v = reinterpret_cast<const half8_t *>(X)[i];
         half8_t o;
+        uint32_t lo = 0, hi = 0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = one(v[e]);
+        for (int e = 0; e < 8; ++e) {
+            uint32_t c;
+            o[e] = one(v[e], c);
+            if (e < 4)
+                lo |= c << (8 * e);
+            else
+                hi |= c << (8 * (e - 4));
+        }
         reinterpret_cast<half8_t *>(Xq)[i] = o;
+        if (Xb) reinterpret_cast<uint2_t *>(Xb)[i] = uint2_t{lo, hi};
     }
     if (blockIdx.x == 0)
-        for (size_t i = n8 * 8 + threadIdx.x; i < count; i += blockDim.x) Xq[i] = one(X[i]);
+        for (size_t i = n8 * 8 + threadIdx.x; i < count; i += blockDim.x) {
+            uint32_t c;
+            Xq[i] = one(X[i], c);
+            if (Xb) Xb[i] = (uint8_t)c;
+        }
 }
 
 }  // namespace slim
 
 using namespace slim;
 
-extern "C" int slim_input_quant_fp8(const slim_half *X, size_t count, slim_half *Xq, float *info, void *workspace,
-                                    size_t workspace_bytes, void *stream)
+extern "C" int slim_input_quant_fp8_codes(const slim_half *X, size_t count, slim_half *Xq, uint8_t *Xb, float *info,
+                                          void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!X || !Xq || !info || !workspace) return SLIM_ERR_NULL;
     if (count < 1) return SLIM_ERR_SHAPE;
-    if (!aligned16(X) || !aligned16(Xq) || !aligned16(workspace)) return SLIM_ERR_ALIGN;
+    if (!aligned16(X) || !aligned16(Xq) || !aligned16(workspace) || (Xb && !aligned16(Xb))) return SLIM_ERR_ALIGN;
     if (workspace_bytes < kInMaxBlocks * sizeof(float)) return SLIM_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t g = (count / 8 + 255) / 256;
@@ -107,6 +141,12 @@ extern "C" int slim_input_quant_fp8(const slim_half *X, size_t count, slim_half 
     float *part = static_cast<float *>(workspace);
     hipLaunchKernelGGL(input_absmax_kernel, dim3(grid_a), dim3(256), 0, st, reinterpret_cast<const half_t *>(X), count, part);
     hipLaunchKernelGGL(input_fp8_kernel, dim3(grid_q), dim3(256), 0, st, reinterpret_cast<const half_t *>(X), count,
-                       (const float *)part, (int)grid_a, reinterpret_cast<half_t *>(Xq), info);
+                       (const float *)part, (int)grid_a, reinterpret_cast<half_t *>(Xq), Xb, info);
     return hip_status(hipGetLastError());
+}
+
+extern "C" int slim_input_quant_fp8(const slim_half *X, size_t count, slim_half *Xq, float *info, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    return slim_input_quant_fp8_codes(X, count, Xq, nullptr, info, workspace, workspace_bytes, stream);
 }

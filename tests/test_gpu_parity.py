@@ -654,6 +654,81 @@ def test_input_quant_fp8_bit_exact(case):
     assert np.array_equal(Xq.cpu().numpy().view(np.uint16), rq.view(np.uint16))
 
 
+@pytest.mark.parametrize("case", ["normal", "beyond_e4m3", "tiny", "ragged"])
+def test_input_quant_fp8_codes_bit_exact(case):
+    """The 8-bit codes equal the oracle's (the bit fields of its quantized values), and the fp16 output and the
+    scale are those of the call without codes."""
+    rng = np.random.default_rng(len(case) + 7)
+    if case == "normal":
+        X = wl.make_activations(16, 4096, seed=6).numpy()
+    elif case == "beyond_e4m3":
+        X = (rng.standard_normal((8, 1024)) * 40).astype(np.float16)
+        X[1, 5] = np.float16(2500.0)
+    elif case == "tiny":
+        X = (rng.standard_normal((4, 512)) * 1e-4).astype(np.float16)
+        X[0, :6] = np.array([-0.0, 0.0, -6e-8, 6e-8, -1e-7, 1e-7], np.float16)
+    else:
+        X = rng.standard_normal((3, 1001)).astype(np.float16)
+    Xq, info, codes = B.slim_input_quant_fp8(torch.from_numpy(X).to(DEV), codes=True)
+    Xq2, info2 = B.slim_input_quant_fp8(torch.from_numpy(X).to(DEV))
+    torch.cuda.synchronize()
+    rc, rs, rf = O.input_quant_fp8_codes(X)
+    assert info.cpu().numpy()[0].view(np.uint32) == np.float32(rs).view(np.uint32)
+    assert float(info[1]) == (1.0 if rf == "e5m2" else 0.0)
+    assert np.array_equal(codes.cpu().numpy(), rc)
+    assert torch.equal(Xq.view(torch.int16), Xq2.view(torch.int16)) and torch.equal(info, info2)
+
+
+def _fp8_forward_case(n, k, r, m, seed=0, x_gain=1.0, rows=None, shape=None):
+    """slim_linear_gemm_fp8 against the oracle: the weight term on the exact quantized values value(code) * scale,
+    the adapter term on the quantizer's fp16 output (what the entry point is defined to compute)."""
+    shape = shape or _shape(n, k, r)
+    W, L, R, X = wl.make_layer(shape, m, seed=seed)
+    X = (X.float() * x_gain).half()
+    layer = _gpu_layer(W, L if shape.r else None, R if shape.r else None)
+    Xq, info, codes = B.slim_input_quant_fp8(X.to(DEV), codes=True)
+    torch.cuda.synchronize()
+    fmt = int(info[1])
+    ws = B.alloc_workspace(layer, m)
+    Y = B.slim_linear_gemm_fp8(layer, codes, info, fmt, Xq, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws.view(torch.int32)[2]) == 0
+    ref = O.compress(W.numpy())
+    x16, s, fname = O.input_quant_fp8(X.numpy())
+    assert fmt == (1 if fname == "e5m2" else 0)
+    xe = O.fp8_round((X.numpy().astype(np.float32) / s).astype(np.float32), fname).astype(np.float64) * np.float64(s)
+    Yref = O.forward(ref, None, None, xe, rows=rows)
+    T, Lr = None, None
+    if shape.r:
+        Lr, Rr, x16d = L.numpy().astype(np.float64), R.numpy().astype(np.float64), x16.astype(np.float64)
+        Yl, T = O.forward(ref, Lr, Rr, x16d, rows=rows, return_t=True)
+        Yref = Yref + (Yl - O.forward(ref, None, None, x16d, rows=rows))
+    sel = slice(None) if rows is None else rows
+    tol = element_tolerance(Yref, T, None if Lr is None else Lr[sel], ref.scale[sel].astype(np.float64), xe, CT_PREFILL, mma8=True)
+    Yg = Y.cpu().numpy()
+    return assert_forward_close(Yg if rows is None else Yg[:, rows], Yref, tol, f"slim_linear_gemm_fp8 {shape.name} m={m} fmt={fmt}")["whole"], fmt
+
+
+@pytest.mark.parametrize("n,k,r,m", [(512, 128, 0, 128), (640, 1024, 0, 200), (1000, 2048, 64, 300), (33, 256, 1, 17),
+                                     (2100, 4096, 410, 700), (1537, 1152, 100, 129)])
+def test_gemm_fp8_inputs_small_and_ragged(n, k, r, m):
+    err, fmt = _fp8_forward_case(n, k, r, m, seed=n % 7)
+    assert err <= TOL_Y and fmt == 0
+
+
+def test_gemm_fp8_inputs_e5m2():
+    """Inputs beyond E4M3's range take the E5M2 form of the kernel."""
+    err, fmt = _fp8_forward_case(512, 512, 32, 128, seed=1, x_gain=300.0)
+    assert err <= TOL_Y and fmt == 1
+
+
+@pytest.mark.parametrize("shape,m", [(wl.L7B_UP, 2048), (wl.L70B_ATTN, 4096)])
+def test_gemm_fp8_inputs_full_size_sampled_rows(shape, m):
+    rows = prefill_row_sample(shape.n, 256, seed=3)
+    err, _ = _fp8_forward_case(shape.n, shape.k, shape.r, m, seed=2, rows=rows, shape=shape)
+    assert err <= TOL_Y
+
+
 def test_forward_on_fp8_quantized_input():
     shape = _shape(512, 1024, 51)
     W, L, R, X = wl.make_layer(shape, 8, seed=13)
