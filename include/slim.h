@@ -425,11 +425,12 @@ int slim_input_quant_fp8(const slim_half *X, size_t count, slim_half *Xq, float 
 
 /*
  * slim_input_quant_fp8_codes -- slim_input_quant_fp8 that also writes the 8-bit
- * codes of the quantized values (Xb: `count` bytes, may be NULL): sign in bit
- * 7, then the exponent field (4 bits, bias 7, for E4M3; 5 bits, bias 15, for
- * E5M2) and the mantissa (3 or 2 bits), subnormals with exponent field 0 -- the
- * OCP 8-bit formats.  value(Xb[i]) * scale is the quantized value before its
- * rounding to fp16 in Xq.  Errors as slim_input_quant_fp8; ALIGN also for Xb.
+ * codes of the quantized values (Xb: `count` bytes): sign in bit 7, then the
+ * exponent field (4 bits, bias 7, for E4M3; 5 bits, bias 15, for E5M2) and the
+ * mantissa (3 or 2 bits), subnormals with exponent field 0 -- the OCP 8-bit
+ * formats.  value(Xb[i]) * scale is the quantized value before its rounding to
+ * fp16 in Xq.  Either of Xq and Xb may be NULL (not both).  Errors as
+ * slim_input_quant_fp8; ALIGN also for Xb.
  */
 int slim_input_quant_fp8_codes(const slim_half *X, size_t count, slim_half *Xq, uint8_t *Xb, float *info,
                                void *workspace, size_t workspace_bytes, void *stream);
@@ -437,23 +438,22 @@ int slim_input_quant_fp8_codes(const slim_half *X, size_t count, slim_half *Xq, 
 /*
  * slim_linear_gemm_fp8 -- slim_linear_gemm on an input tensor quantized to 8 bits
  * (App. "Input Quantization": AbsMax FP8 quantization of the layer's input, one
- * scale per tensor):
- *   Y = scale_x * (value(X8) W^C) + (Xq L) R   in the orientation of Sec. 3.2,
- * the weight term on the 8-bit structured-sparse matrix instruction (the int4
- * weights are exact in E5M2, the products exact in fp32), the adapter term on
- * Xq as in slim_linear_gemm.
- *   X8      [m][k] 8-bit codes, Xq [m][k] fp16, x_info = {scale, format} (DEVICE
- *           pointers): the three outputs of slim_input_quant_fp8_codes for the
- *           tensor;
+ * scale per tensor):  with Xv = scale * value(X8), the exact quantized values,
+ *   Y = Xv W^C + (Xv L) R   in the orientation of Sec. 3.2.
+ * The weight term runs on the 8-bit structured-sparse matrix instruction (the
+ * int4 weights are exact in E5M2, the products exact in binary32); the adapter
+ * product T = Xv R^T reads the codes too (half the bytes), turns them into
+ * fp16 exactly and goes on as in slim_linear_gemm.
+ *   X8      [m][k] 8-bit codes, x_info = {scale, format} (DEVICE pointers): outputs
+ *           of slim_input_quant_fp8_codes for the tensor;
  *   format  0 = E4M3, 1 = E5M2: what x_info[1] holds (the caller reads it back
  *           once, or knows it from the range of its activations: E4M3 unless
  *           max|X| > 448).
  * Everything else, the workspace included, as slim_linear_gemm.  Errors as
  * slim_linear_gemm; SHAPE also for a format other than 0 or 1.
  */
-int slim_linear_gemm_fp8(const slim_layer *layer, const uint8_t *X8, const float *x_info, int32_t format,
-                         const slim_half *Xq, int32_t m, slim_half *Y, void *workspace, size_t workspace_bytes,
-                         void *stream);
+int slim_linear_gemm_fp8(const slim_layer *layer, const uint8_t *X8, const float *x_info, int32_t format, int32_t m,
+                         slim_half *Y, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Measurement aids (they compute nothing of the method): what this machine

@@ -85,7 +85,7 @@ def lib():
         L.slim_lowrank.argtypes = [vp, i32, vp, vp, slim_shape, i32, vp, ctypes.c_int, vp, sz, vp]
         L.slim_gemm_tile_order.argtypes = [i32, i32, pi32, sz]
         L.slim_input_quant_fp8_codes.argtypes = [vp, sz, vp, vp, vp, vp, sz, vp]
-        L.slim_linear_gemm_fp8.argtypes = [ctypes.POINTER(slim_layer), vp, vp, i32, vp, i32, vp, vp, sz, vp]
+        L.slim_linear_gemm_fp8.argtypes = [ctypes.POINTER(slim_layer), vp, vp, i32, i32, vp, vp, sz, vp]
         for name in EXPORTS[2:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -253,14 +253,20 @@ def slim_input_quant_fp8(X: torch.Tensor, Xq=None, info=None, workspace=None, co
     """FP8 AbsMax quantization of an input tensor, values back on the fp16 grid:
     (Xq fp16 like X, info fp32 [2] = scale, format (0: E4M3, 1: E5M2)).  Xq, info and a
     workspace of at least 1024 bytes may be passed in (a caller in a loop).  codes=True (or a uint8
-    tensor of X's size): also the 8-bit codes, for slim_linear_gemm_fp8; returns (Xq, info, codes)."""
+    tensor of X's size): also the 8-bit codes, for slim_linear_gemm_fp8; returns (Xq, info, codes);
+    Xq=False then skips the fp16 output (Xq is returned as None)."""
     _dev(X, torch.float16, "X")
+    skip_xq = Xq is False
+    if skip_xq and codes is None:
+        raise ValueError("nothing to compute: Xq=False needs codes")
     if codes is True:
         codes = torch.empty(X.shape, dtype=torch.uint8, device=X.device)
     if codes is not None and (codes.dtype != torch.uint8 or codes.numel() != X.numel() or codes.device != X.device
                               or not codes.is_contiguous()):
         raise ValueError("codes must be contiguous uint8 with X's size on X's device")
-    if Xq is None:
+    if skip_xq:
+        Xq = None
+    elif Xq is None:
         Xq = torch.empty_like(X)
     elif Xq.dtype != torch.float16 or Xq.numel() != X.numel() or Xq.device != X.device or not Xq.is_contiguous():
         raise ValueError("Xq must be contiguous float16 with X's size on X's device")
@@ -514,22 +520,20 @@ def slim_linear_gemm(layer: SlimLayer, X: torch.Tensor, Y=None, workspace=None) 
     return _forward("slim_linear_gemm", layer, X, Y, workspace)
 
 
-def slim_linear_gemm_fp8(layer: SlimLayer, codes: torch.Tensor, info: torch.Tensor, fmt: int, Xq: torch.Tensor, Y=None,
-                         workspace=None) -> torch.Tensor:
-    """Prefill-shaped forward on 8-bit inputs: codes uint8 [m][k], info (scale, format) and Xq fp16 [m][k] as
+def slim_linear_gemm_fp8(layer: SlimLayer, codes: torch.Tensor, info: torch.Tensor, fmt: int, Y=None, workspace=None) -> torch.Tensor:
+    """Prefill-shaped forward on 8-bit inputs: codes uint8 [m][k] and info (scale, format) as
     slim_input_quant_fp8(..., codes=True) returns them; fmt = 0 (E4M3) or 1 (E5M2), the format in info[1]."""
-    _dev(Xq, torch.float16, "Xq")
     _dev(codes, torch.uint8, "codes")
     _dev(info, torch.float32, "info")
-    m, k = Xq.shape
-    if k != layer.k or codes.numel() != m * k or info.numel() < 2:
-        raise ValueError("codes and Xq must be [m][k], info [2]")
+    if codes.dim() != 2 or codes.shape[1] != layer.k or info.numel() < 2:
+        raise ValueError("codes must be [m][k], info [2]")
+    m = codes.shape[0]
     if Y is None:
-        Y = torch.empty(m, layer.n, dtype=torch.float16, device=Xq.device)
+        Y = torch.empty(m, layer.n, dtype=torch.float16, device=codes.device)
     if workspace is None:
         workspace = alloc_workspace(layer, m)
-    _check("slim_linear_gemm_fp8", lib().slim_linear_gemm_fp8(layer.c_ref(), _ptr(codes), _ptr(info), int(fmt), _ptr(Xq), m, _ptr(Y),
-                                                              _ptr(workspace), workspace.numel(), _stream(Xq)))
+    _check("slim_linear_gemm_fp8", lib().slim_linear_gemm_fp8(layer.c_ref(), _ptr(codes), _ptr(info), int(fmt), m, _ptr(Y),
+                                                              _ptr(workspace), workspace.numel(), _stream(codes)))
     return Y
 
 

@@ -13,7 +13,8 @@ enum OutMode { OUT_STORE = 0, OUT_ACCUM = 1, OUT_PARTIAL = 2 };
 
 struct DenseGemmArgs {
     const half_t *A;     // [rows][kt] in the tiled adapter layout
-    const half_t *B;     // [m][kt]
+    const half_t *B;     // [m][kt] fp16, or (BF != 0) 8-bit codes, one byte per value
+    const float *b_scale; // BF != 0: the scale of B's tensor (device memory); the result is multiplied by it
     int rows, m, kt;     // kt: row length of A and B (the full k extent)
     int ks;              // inputs per split (multiple of 128); grid.y splits
     half_t *Y;           // fp16 [m][rows]   (OUT_STORE, OUT_ACCUM)
@@ -22,9 +23,30 @@ struct DenseGemmArgs {
     int tiles_o;         // row tiles of 128 AT
 };
 
+// Eight 8-bit codes (two dwords) -> eight fp16 values, exactly: E4M3 (BF 1) and E5M2 (BF 2) values all lie
+// on the fp16 grid.
+template <int BF>
+__device__ __forceinline__ uint4_t fp8x8_to_half8(uint32_t lo, uint32_t hi)
+{
+    uint4_t out;
+#pragma unroll
+    for (int d = 0; d < 2; ++d) {
+        const int src = (int)(d ? hi : lo);
+        typedef float f2_t __attribute__((ext_vector_type(2)));
+        const f2_t p0 = BF == 1 ? __builtin_amdgcn_cvt_pk_f32_fp8(src, false) : __builtin_amdgcn_cvt_pk_f32_bf8(src, false);
+        const f2_t p1 = BF == 1 ? __builtin_amdgcn_cvt_pk_f32_fp8(src, true) : __builtin_amdgcn_cvt_pk_f32_bf8(src, true);
+        out[2 * d] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(p0[0], p0[1]));       // exact: nothing to round
+        out[2 * d + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(p1[0], p1[1]));
+    }
+    return out;
+}
+
 // Workgroup: 4 wavefronts, tile (128 AT) rows x 128 tokens, each wavefront
 // (32 AT) rows x 128 tokens on fixed accumulators; the k-loop is dense_phase().
-template <int AT>
+// BF: 0 = B in fp16; 1, 2 = B as E4M3 / E5M2 codes with one scale for the tensor (App. "Input
+// Quantization"): half the bytes of B are requested, the codes become fp16 on their way into LDS,
+// and the result is multiplied by the scale.
+template <int AT, int BF = 0>
 __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
 {
     constexpr int WROWS = 32 * AT;
@@ -48,19 +70,41 @@ __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
     static_for<16 * AT * NT>([&](auto r) { acc_write<r>(0.0f); });
 
     const uint32_t kt = (uint32_t)a.kt;
-    const int srow = tid >> 4, scol = (tid & 15) * 8;
-    half_t *const lw = lds + srow * SG_LD + scol;
     const half_t *const lr = lds + li * SG_LD + 8 * lb;
-    uint4_t xs[XR];
-    auto stage_store = [&](int u, const uint4_t (&reg)[XR]) {
-#pragma unroll
-        for (int p = 0; p < XR; ++p) *reinterpret_cast<uint4_t *>(lw + u * SG_STAGE + p * 16 * SG_LD) = reg[p];
-    };
     const rsrc_t da = make_rsrc(a.A, (uint32_t)tl_bytes(a.rows, a.kt));
-    const rsrc_t db = make_rsrc(a.B, (uint32_t)a.m * kt * 2u);
     const uint32_t av = tl_piece((uint32_t)o0 + li, (uint32_t)k0 / 8 + lb, kt);      // k0 is a multiple of 128
-    const uint32_t bv = ((uint32_t)(t0 + srow) * kt + (uint32_t)k0 + (uint32_t)scol) * 2u;
-    dense_phase<AT>(da, av, (kt / 16) * 1024u, 1024u, db, bv, 32u * kt, klen, lr, xs, stage_store);
+    float b_scale = 1.0f;
+    if constexpr (BF == 0) {
+        // 16 lanes per token row (256 contiguous bytes), 16 rows per pass
+        const int srow = tid >> 4, scol = (tid & 15) * 8;
+        half_t *const lw = lds + srow * SG_LD + scol;
+        uint4_t xs[XR];
+        auto stage_store = [&](int u, const uint4_t (&reg)[XR]) {
+#pragma unroll
+            for (int p = 0; p < XR; ++p) *reinterpret_cast<uint4_t *>(lw + u * SG_STAGE + p * 16 * SG_LD) = reg[p];
+        };
+        const rsrc_t db = make_rsrc(a.B, (uint32_t)a.m * kt * 2u);
+        const uint32_t bv = ((uint32_t)(t0 + srow) * kt + (uint32_t)k0 + (uint32_t)scol) * 2u;
+        dense_phase<AT>(da, av, (kt / 16) * 1024u, 1024u, db, bv, 32u * kt, klen, lr, xs, stage_store);
+    } else {
+        // 8 lanes per token row (128 contiguous bytes = 128 codes), 32 rows per pass; a load of 16 codes
+        // becomes two pieces of 8 halves in LDS
+        b_scale = *a.b_scale;
+        const int srow = tid >> 3, scol = (tid & 7) * 16;
+        half_t *const lw = lds + srow * SG_LD + scol;
+        uint4_t xs[XR / 2];
+        auto stage_store = [&](int u, const uint4_t (&reg)[XR / 2]) {
+#pragma unroll
+            for (int p = 0; p < XR / 2; ++p) {
+                half_t *d = lw + u * SG_STAGE + p * 32 * SG_LD;
+                *reinterpret_cast<uint4_t *>(d) = fp8x8_to_half8<BF>(reg[p][0], reg[p][1]);
+                *reinterpret_cast<uint4_t *>(d + 8) = fp8x8_to_half8<BF>(reg[p][2], reg[p][3]);
+            }
+        };
+        const rsrc_t db = make_rsrc(a.B, (uint32_t)a.m * kt);
+        const uint32_t bv = (uint32_t)(t0 + srow) * kt + (uint32_t)k0 + (uint32_t)scol;
+        dense_phase<AT, 1>(da, av, (kt / 16) * 1024u, 1024u, db, bv, 32u * kt, klen, lr, xs, stage_store);
+    }
     acc_settle();
 
     // lane holds token t0 + 32 it + li, rows o .. o + 3 per (i, blk)
@@ -80,6 +124,10 @@ __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
                 v[1] = acc_read<16 * (i * NT + it) + 4 * blk + 1>();
                 v[2] = acc_read<16 * (i * NT + it) + 4 * blk + 2>();
                 v[3] = acc_read<16 * (i * NT + it) + 4 * blk + 3>();
+                if constexpr (BF != 0) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] *= b_scale;
+                }
                 if (a.mode == OUT_PARTIAL) {
                     float *pp = a.P + ((size_t)blockIdx.y * a.m + t) * a.rows + o;
                     if (vec_ok) {
@@ -129,13 +177,13 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
 }
 
 // One dense product on up to 2^32 - 1 bytes of B: C = A B^T over `splits` k ranges.
-template <int AT>
+template <int AT, int BF = 0>
 static void launch_dense(DenseGemmArgs a, int splits, hipStream_t st)
 {
     a.tiles_o = (a.rows + 128 * AT - 1) / (128 * AT);
     const int tiles_t = (a.m + 127) / 128;
     const size_t lds = (size_t)2 * SG_STAGE * sizeof(half_t);
-    hipLaunchKernelGGL(gemm_dense_kernel<AT>, dim3((unsigned)(a.tiles_o * tiles_t), (unsigned)splits), dim3(256), lds,
+    hipLaunchKernelGGL((gemm_dense_kernel<AT, BF>), dim3((unsigned)(a.tiles_o * tiles_t), (unsigned)splits), dim3(256), lds,
                        st, a);
 }
 
@@ -156,9 +204,10 @@ int gemm_t_splits(int32_t m, int32_t rank_pad, int32_t k)
     return s;
 }
 
-// T fp16 [m][rank_pad] = X R^T.
+// T fp16 [m][rank_pad] = X R^T.  xf: 0 = X fp16; 1, 2 = X as E4M3 / E5M2 codes (one byte per value) with the
+// tensor's scale at x_scale: T = scale * (value(X) R^T).
 static int launch_t(const half_t *X, int m, const half_t *R, int k, int rank_pad, half_t *T, float *P, int splits,
-                    hipStream_t st)
+                    hipStream_t st, int xf = 0, const float *x_scale = nullptr)
 {
     if ((uint64_t)rank_pad * (uint64_t)k * 2 > 0xFFFFFFFFull) return SLIM_ERR_SHAPE;
     const int chunk = token_chunk(k);
@@ -171,10 +220,16 @@ static int launch_t(const half_t *X, int m, const half_t *R, int k, int rank_pad
     g.mode = splits > 1 ? OUT_PARTIAL : OUT_STORE;
     for (int t0 = 0; t0 < m; t0 += chunk) {
         g.m = m - t0 < chunk ? m - t0 : chunk;
-        g.B = X + (size_t)t0 * k;
+        g.B = reinterpret_cast<const half_t *>(reinterpret_cast<const char *>(X) + (size_t)t0 * k * (xf ? 1 : 2));
+        g.b_scale = x_scale;
         g.Y = T + (size_t)t0 * rank_pad;
         g.P = P;
-        launch_dense<2>(g, splits, st);
+        if (xf == 0)
+            launch_dense<2>(g, splits, st);
+        else if (xf == 1)
+            launch_dense<2, 1>(g, splits, st);
+        else
+            launch_dense<2, 2>(g, splits, st);
         if (splits > 1) {
             const size_t count = (size_t)g.m * rank_pad;
             const int blocks = (int)((count + 255) / 256 < 4096 ? (count + 255) / 256 : 4096);
@@ -195,15 +250,14 @@ int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t 
 
 using namespace slim;
 
-// X: fp16 [m][k].  X8 (with xf = 1 or 2, and x_info = {scale, format} in device memory): the same tensor as
-// 8-bit codes for the weight term; X then serves the adapter term only.
-static int linear_gemm(const slim_layer *layer_in, const slim_half *X, const uint8_t *X8, int xf, const float *x_info,
-                       int32_t m, slim_half *Y, void *workspace, size_t workspace_bytes, void *stream)
+// X: fp16 [m][k] (xf = 0), or 8-bit codes [m][k] with x_info = {scale, format} in device memory (xf = 1: E4M3,
+// 2: E5M2).
+static int linear_gemm(const slim_layer *layer_in, const void *X, int xf, const float *x_info, int32_t m, slim_half *Y,
+                       void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!layer_in || !X || !Y) return SLIM_ERR_NULL;
-    if (xf != 0 && (!X8 || !x_info)) return SLIM_ERR_NULL;
+    if (xf != 0 && !x_info) return SLIM_ERR_NULL;
     if (xf < 0 || xf > 2) return SLIM_ERR_SHAPE;
-    if (xf != 0 && !aligned16(X8)) return SLIM_ERR_ALIGN;
     const slim_layer *layer = layer_in;
     const slim_shape s = layer->shape;
     if (!layer->qvals || !layer->meta || !layer->scale) return SLIM_ERR_NULL;
@@ -237,27 +291,25 @@ static int linear_gemm(const slim_layer *layer_in, const slim_half *X, const uin
     const int rp = layer->rank_pad;
     const half_t *Xh = reinterpret_cast<const half_t *>(X);
     if (rp > 0) {
-        const int rc = launch_t(Xh, m, reinterpret_cast<const half_t *>(layer->R), s.k, rp, T, P, p.splits, st);
+        const int rc = launch_t(Xh, m, reinterpret_cast<const half_t *>(layer->R), s.k, rp, T, P, p.splits, st, xf, x_info);
         if (rc != SLIM_OK) return rc;
     }
 
-    return launch_gemm_sparse(layer->qvals, layer->meta, layer->scale, xf ? reinterpret_cast<const half_t *>(X8) : Xh,
-                              reinterpret_cast<const half_t *>(layer->L), T, reinterpret_cast<half_t *>(Y), s.n, s.k, rp, m, st,
-                              xf, x_info);
+    return launch_gemm_sparse(layer->qvals, layer->meta, layer->scale, Xh, reinterpret_cast<const half_t *>(layer->L), T,
+                              reinterpret_cast<half_t *>(Y), s.n, s.k, rp, m, st, xf, x_info);
 }
 
 extern "C" int slim_linear_gemm(const slim_layer *layer, const slim_half *X, int32_t m, slim_half *Y, void *workspace,
                                 size_t workspace_bytes, void *stream)
 {
-    return linear_gemm(layer, X, nullptr, 0, nullptr, m, Y, workspace, workspace_bytes, stream);
+    return linear_gemm(layer, X, 0, nullptr, m, Y, workspace, workspace_bytes, stream);
 }
 
-extern "C" int slim_linear_gemm_fp8(const slim_layer *layer, const uint8_t *X8, const float *x_info, int32_t format,
-                                    const slim_half *Xq, int32_t m, slim_half *Y, void *workspace, size_t workspace_bytes,
-                                    void *stream)
+extern "C" int slim_linear_gemm_fp8(const slim_layer *layer, const uint8_t *X8, const float *x_info, int32_t format, int32_t m,
+                                    slim_half *Y, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (format != 0 && format != 1) return SLIM_ERR_SHAPE;
-    return linear_gemm(layer, Xq, X8, 1 + format, x_info, m, Y, workspace, workspace_bytes, stream);
+    return linear_gemm(layer, X8, 1 + format, x_info, m, Y, workspace, workspace_bytes, stream);
 }
 
 extern "C" int slim_lowrank(const slim_half *X, int32_t m, const slim_half *R, const slim_half *L, slim_shape shape,

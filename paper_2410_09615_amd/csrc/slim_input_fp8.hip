@@ -112,13 +112,14 @@ __global__ __launch_bounds__(256) void input_fp8_kernel(const half_t *__restrict
             else
                 hi |= c << (8 * (e - 4));
         }
-        reinterpret_cast<half8_t *>(Xq)[i] = o;
+        if (Xq) reinterpret_cast<half8_t *>(Xq)[i] = o;
         if (Xb) reinterpret_cast<uint2_t *>(Xb)[i] = uint2_t{lo, hi};
     }
     if (blockIdx.x == 0)
         for (size_t i = n8 * 8 + threadIdx.x; i < count; i += blockDim.x) {
             uint32_t c;
-            Xq[i] = one(X[i], c);
+            const half_t h = one(X[i], c);
+            if (Xq) Xq[i] = h;
             if (Xb) Xb[i] = (uint8_t)c;
         }
 }
@@ -130,9 +131,9 @@ using namespace slim;
 extern "C" int slim_input_quant_fp8_codes(const slim_half *X, size_t count, slim_half *Xq, uint8_t *Xb, float *info,
                                           void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!X || !Xq || !info || !workspace) return SLIM_ERR_NULL;
+    if (!X || (!Xq && !Xb) || !info || !workspace) return SLIM_ERR_NULL;
     if (count < 1) return SLIM_ERR_SHAPE;
-    if (!aligned16(X) || !aligned16(Xq) || !aligned16(workspace) || (Xb && !aligned16(Xb))) return SLIM_ERR_ALIGN;
+    if (!aligned16(X) || (Xq && !aligned16(Xq)) || !aligned16(workspace) || (Xb && !aligned16(Xb))) return SLIM_ERR_ALIGN;
     if (workspace_bytes < kInMaxBlocks * sizeof(float)) return SLIM_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t g = (count / 8 + 255) / 256;
@@ -148,5 +149,6 @@ extern "C" int slim_input_quant_fp8_codes(const slim_half *X, size_t count, slim
 extern "C" int slim_input_quant_fp8(const slim_half *X, size_t count, slim_half *Xq, float *info, void *workspace,
                                     size_t workspace_bytes, void *stream)
 {
+    if (!Xq) return SLIM_ERR_NULL;
     return slim_input_quant_fp8_codes(X, count, Xq, nullptr, info, workspace, workspace_bytes, stream);
 }

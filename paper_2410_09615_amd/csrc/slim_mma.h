@@ -132,22 +132,25 @@ __host__ __device__ __forceinline__ int blocked_tile(int q, int tiles_o, int til
 //      a_step: bytes between steps), fetched three steps ahead into four rotating sets;
 //   B: 128 tokens x 128 inputs per stage staged through the LDS buffers like X
 //      (db, bv: this lane's staging offset for stage 0; b_pass: bytes between
-//      the 16-row passes; a stage is 256 bytes further), next stage's loads
-//      issued during steps 0-3 of the current one.
+//      the passes of 16-byte loads; a stage is 128 BB bytes further), next stage's
+//      loads issued during steps 0-3 of the current one.  BB = 2: B is fp16, eight
+//      loads per lane and stage; BB = 1: B is 8-bit codes, four loads, which
+//      stage_store() expands to fp16 on their way into LDS.
 // Loads past the end stay inside the descriptors or read as zero and are not
 // used; issuing them anyway keeps one path through the loop body.
 // Starts and ends with every wavefront past a barrier.
-template <int AT, class Store>
+template <int AT, int BB = 2, class Store>
 __device__ __forceinline__ void dense_phase(rsrc_t da, uint32_t av, uint32_t a_tile, uint32_t a_step, rsrc_t db,
                                             uint32_t bv,
-                                            uint32_t b_pass, int K, const half_t *lr, uint4_t (&xs)[XR],
+                                            uint32_t b_pass, int K, const half_t *lr, uint4_t (&xs)[XR * BB / 2],
                                             Store &&stage_store)
 {
+    constexpr int XRN = XR * BB / 2;              // 16-byte loads of a stage per lane
     const int nst = K / 16;                       // steps
     const int stages = (K + SG_BK - 1) / SG_BK;
     uint4_t la[4][AT];
 #pragma unroll
-    for (int p = 0; p < XR; ++p) xs[p] = load16(db, bv, (uint32_t)p * b_pass);
+    for (int p = 0; p < XRN; ++p) xs[p] = load16(db, bv, (uint32_t)p * b_pass);
 #pragma unroll
     for (int g = 0; g < 3; ++g)
 #pragma unroll
@@ -169,9 +172,9 @@ __device__ __forceinline__ void dense_phase(rsrc_t da, uint32_t av, uint32_t a_t
                 constexpr int it = itc;
                 if constexpr (it < AT)
                     la[(j + 3) & 3][it] = load16(da, av, (uint32_t)it * a_tile + (uint32_t)(g + 3) * a_step);
-                if constexpr (j < 4 && it < 2)
-                    xs[2 * j + it] =
-                        load16(db, bv, (uint32_t)(s + 1) * (SG_BK * 2) + (uint32_t)(2 * j + it) * b_pass);
+                if constexpr (j < 4 && it < XRN / 4)
+                    xs[(XRN / 4) * j + it] =
+                        load16(db, bv, (uint32_t)(s + 1) * (SG_BK * BB) + (uint32_t)((XRN / 4) * j + it) * b_pass);
                 if constexpr (j + 1 < 8)
                     b_nxt[it] = *reinterpret_cast<const half8_t *>(lr + u * SG_STAGE + it * 32 * SG_LD + 16 * (j + 1));
                 __builtin_amdgcn_sched_barrier(0);

@@ -677,32 +677,32 @@ def test_input_quant_fp8_codes_bit_exact(case):
     assert float(info[1]) == (1.0 if rf == "e5m2" else 0.0)
     assert np.array_equal(codes.cpu().numpy(), rc)
     assert torch.equal(Xq.view(torch.int16), Xq2.view(torch.int16)) and torch.equal(info, info2)
+    none, info3, codes3 = B.slim_input_quant_fp8(torch.from_numpy(X).to(DEV), Xq=False, codes=True)      # codes alone
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(codes3, codes) and torch.equal(info3, info)
 
 
 def _fp8_forward_case(n, k, r, m, seed=0, x_gain=1.0, rows=None, shape=None):
-    """slim_linear_gemm_fp8 against the oracle: the weight term on the exact quantized values value(code) * scale,
-    the adapter term on the quantizer's fp16 output (what the entry point is defined to compute)."""
+    """slim_linear_gemm_fp8 against the oracle's forward on the exact quantized values value(code) * scale (both terms;
+    the codes themselves are checked bit for bit in test_input_quant_fp8_codes_bit_exact)."""
     shape = shape or _shape(n, k, r)
     W, L, R, X = wl.make_layer(shape, m, seed=seed)
     X = (X.float() * x_gain).half()
     layer = _gpu_layer(W, L if shape.r else None, R if shape.r else None)
-    Xq, info, codes = B.slim_input_quant_fp8(X.to(DEV), codes=True)
+    _, info, codes = B.slim_input_quant_fp8(X.to(DEV), Xq=False, codes=True)
     torch.cuda.synchronize()
     fmt = int(info[1])
     ws = B.alloc_workspace(layer, m)
-    Y = B.slim_linear_gemm_fp8(layer, codes, info, fmt, Xq, workspace=ws)
+    Y = B.slim_linear_gemm_fp8(layer, codes, info, fmt, workspace=ws)
     torch.cuda.synchronize()
     assert int(ws.view(torch.int32)[2]) == 0
     ref = O.compress(W.numpy())
-    x16, s, fname = O.input_quant_fp8(X.numpy())
+    _, s, fname = O.input_quant_fp8(X.numpy())
     assert fmt == (1 if fname == "e5m2" else 0)
     xe = O.fp8_round((X.numpy().astype(np.float32) / s).astype(np.float32), fname).astype(np.float64) * np.float64(s)
-    Yref = O.forward(ref, None, None, xe, rows=rows)
-    T, Lr = None, None
-    if shape.r:
-        Lr, Rr, x16d = L.numpy().astype(np.float64), R.numpy().astype(np.float64), x16.astype(np.float64)
-        Yl, T = O.forward(ref, Lr, Rr, x16d, rows=rows, return_t=True)
-        Yref = Yref + (Yl - O.forward(ref, None, None, x16d, rows=rows))
+    Lr = L.numpy().astype(np.float64) if shape.r else None
+    Rr = R.numpy().astype(np.float64) if shape.r else None
+    Yref, T = O.forward(ref, Lr, Rr, xe, rows=rows, return_t=True)
     sel = slice(None) if rows is None else rows
     tol = element_tolerance(Yref, T, None if Lr is None else Lr[sel], ref.scale[sel].astype(np.float64), xe, CT_PREFILL, mma8=True)
     Yg = Y.cpu().numpy()
