@@ -79,6 +79,20 @@ def test_argument_validation_returns_codes_before_any_launch():
     assert lib.slim_linear_gemm(ctypes.byref(withrank), a, 4, a, a, 1 << 20, None) == B.SLIM_ERR_NULL
     assert lib.slim_lowrank(a, 4, a, a, B.slim_shape(128, 256, 0), 0, a, 0, a, 1 << 20, None) == B.SLIM_ERR_SHAPE
     assert lib.slim_lowrank(a, 4, a, a, B.slim_shape(128, 256, 8), 8, a, 0, a, 1 << 20, None) == B.SLIM_ERR_SHAPE
+    # the 8-bit-input forms
+    gf = lib.slim_linear_gemm_fp8
+    assert gf(None, a, a, 0, 4, a, a, 1 << 20, None) == B.SLIM_ERR_NULL
+    assert gf(ctypes.byref(layer), a, None, 0, 4, a, a, 1 << 20, None) == B.SLIM_ERR_NULL          # no scale
+    assert gf(ctypes.byref(layer), a, a, 2, 4, a, a, 1 << 20, None) == B.SLIM_ERR_SHAPE            # format is 0 or 1
+    assert gf(ctypes.byref(layer), a, a, 0, 0, a, a, 1 << 20, None) == B.SLIM_ERR_SHAPE
+    assert gf(ctypes.byref(layer), ctypes.c_void_p(0x1004), a, 0, 4, a, a, 1 << 20, None) == B.SLIM_ERR_ALIGN
+    assert gf(ctypes.byref(layer), a, a, 1, 4, a, a, 16, None) == B.SLIM_ERR_WORKSPACE
+    qc = lib.slim_input_quant_fp8_codes
+    assert qc(a, 16, None, None, a, a, 1024, None) == B.SLIM_ERR_NULL                              # nothing to write
+    assert qc(a, 0, a, a, a, a, 1024, None) == B.SLIM_ERR_SHAPE
+    assert qc(a, 16, a, ctypes.c_void_p(0x1001), a, a, 1024, None) == B.SLIM_ERR_ALIGN
+    assert qc(a, 16, None, a, a, a, 8, None) == B.SLIM_ERR_WORKSPACE
+    assert lib.slim_input_quant_fp8(a, 16, None, a, a, 1024, None) == B.SLIM_ERR_NULL
 
 
 def test_missing_library_fails_loudly(monkeypatch):
