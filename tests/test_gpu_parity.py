@@ -250,13 +250,11 @@ def test_gemv_without_adapters(decode_path):
 
 
 # every configured decode shape and token count (the 7B attention projection has its own test above),
-# a few more, all output rows against the oracle; the forced paths on one 13B and one 70B layer
+# a few more, all output rows against the oracle, on the automatic path and on each forced one
 @pytest.mark.parametrize("shape,m", [(wl.L13B_ATTN, 1), (wl.L13B_UP, 1), (wl.L70B_ATTN, 1), (wl.L70B_ATTN, 16), (wl.L70B_UP, 1),
                                      (wl.L70B_UP, 16), (wl.L70B_UP, 4), (wl.L7B_DOWN, 4), (wl.L7B_UP, 16)],
                          ids=lambda v: str(getattr(v, "name", v)))
 def test_gemv_full_size_all_rows(shape, m, decode_path):
-    if decode_path in ("roles", "parts") and not (shape is wl.L13B_UP or (shape is wl.L70B_UP and m == 16)):
-        pytest.skip("the forced paths run at full size on one 13B and one 70B layer")
     assert _forward_case(shape, m, B.slim_linear_gemv) <= TOL_Y
 
 
