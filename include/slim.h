@@ -238,9 +238,10 @@ int slim_pack_adapters(const slim_half *L, const slim_half *R, slim_shape shape,
  * rows padded to 16, columns to 256 with zero codes.  Scales: fp16
  * [rows16][2 * ceil(cols / 256)], row-major, entry g = group g of the row.
  * Sizes from slim_adapter_q4_sizes (HOST out-pointers).  A value is used as
- * fp16(code * scale).  slim_linear_gemv reads the codes directly (a quarter of
- * the adapter bytes); slim_linear_gemm expands them to fp16 in the workspace
- * first.  slim_unpack_adapters_q4 returns codes int8 [rows][cols] and scales
+ * fp16(code * scale).  The forward calls read the codes directly (a quarter of
+ * the adapter bytes) and turn them into fp16 in registers; only the two-launch
+ * decode kernels (layers whose one-launch geometry does not fit) expand them to
+ * fp16 in the workspace first.  slim_unpack_adapters_q4 returns codes int8 [rows][cols] and scales
  * fp16 [rows][ceil(cols / 128)], row-major (tests, inspection).
  * slim_pack_adapters_q4 requires k % 128 == 0, as the forward calls do (SHAPE
  * otherwise); n and rank are free.

@@ -60,7 +60,8 @@ WorkspacePlan plan_workspace(int32_t n, int32_t k, int32_t rank_pad, int32_t m, 
     p.splits = rank_pad > 0 ? gemm_t_splits(m, rank_pad, k) : 1;
     p.part_bytes = p.splits > 1 ? round256((size_t)p.splits * m * rank_pad * sizeof(float)) : 0;
     p.exp_off = p.part_off + p.part_bytes;
-    p.exp_bytes = q4 && rank_pad > 0 ? round256(tl_bytes(n, rank_pad)) + round256(tl_bytes(rank_pad, k)) : 0;
+    // (the prefill kernels read the 4-bit codes themselves; the two-launch decode kernels read fp16)
+    p.exp_bytes = q4 && rank_pad > 0 && m <= 16 ? round256(tl_bytes(n, rank_pad)) + round256(tl_bytes(rank_pad, k)) : 0;
     p.total = p.exp_off + p.exp_bytes;
     if (p.total < 256) p.total = 256;
     return p;

@@ -12,7 +12,10 @@ namespace slim {
 enum OutMode { OUT_STORE = 0, OUT_ACCUM = 1, OUT_PARTIAL = 2 };
 
 struct DenseGemmArgs {
-    const half_t *A;     // [rows][kt] in the tiled adapter layout
+    const half_t *A;     // [rows][kt] in the tiled adapter layout, or (AQ) null and
+    const uint8_t *Aq;   //   the 4-bit codes of A [aq_rows][kt] (4-bit adapter layout)
+    const half_t *As;    //   with their group scales
+    int aq_rows;
     const half_t *B;     // [m][kt] fp16, or (BF != 0) 8-bit codes, one byte per value
     const float *b_scale; // BF != 0: the scale of B's tensor (device memory); the result is multiplied by it
     int rows, m, kt;     // kt: row length of A and B (the full k extent)
@@ -46,7 +49,8 @@ __device__ __forceinline__ uint4_t fp8x8_to_half8(uint32_t lo, uint32_t hi)
 // BF: 0 = B in fp16; 1, 2 = B as E4M3 / E5M2 codes with one scale for the tensor (App. "Input
 // Quantization"): half the bytes of B are requested, the codes become fp16 on their way into LDS,
 // and the result is multiplied by the scale.
-template <int AT, int BF = 0>
+// AQ: A as 4-bit codes (Sec. 3.3), turned into fp16 in registers (dense_phase_q4()).
+template <int AT, int BF = 0, bool AQ = false>
 __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
 {
     constexpr int WROWS = 32 * AT;
@@ -71,8 +75,11 @@ __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
 
     const uint32_t kt = (uint32_t)a.kt;
     const half_t *const lr = lds + li * SG_LD + 8 * lb;
-    const rsrc_t da = make_rsrc(a.A, (uint32_t)tl_bytes(a.rows, a.kt));
+    const rsrc_t da = make_rsrc(a.A, AQ ? 0u : (uint32_t)tl_bytes(a.rows, a.kt));
     const uint32_t av = tl_piece((uint32_t)o0 + li, (uint32_t)k0 / 8 + lb, kt);      // k0 is a multiple of 128
+    const half_t *const lrq = lds + li * SG_LD + 32 * lb;
+    Q4Rows aq{};
+    if constexpr (AQ) aq = q4_rows_operand(a.Aq, a.As, a.aq_rows, a.kt, o0, li, lb, k0);
     float b_scale = 1.0f;
     if constexpr (BF == 0) {
         // 16 lanes per token row (256 contiguous bytes), 16 rows per pass
@@ -85,7 +92,10 @@ __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
         };
         const rsrc_t db = make_rsrc(a.B, (uint32_t)a.m * kt * 2u);
         const uint32_t bv = ((uint32_t)(t0 + srow) * kt + (uint32_t)k0 + (uint32_t)scol) * 2u;
-        dense_phase<AT>(da, av, (kt / 16) * 1024u, 1024u, db, bv, 32u * kt, klen, lr, xs, stage_store);
+        if constexpr (AQ)
+            dense_phase_q4<AT>(aq, db, bv, 32u * kt, scol, klen, lrq, xs, stage_store);
+        else
+            dense_phase<AT>(da, av, (kt / 16) * 1024u, 1024u, db, bv, 32u * kt, klen, lr, xs, stage_store);
     } else {
         // 8 lanes per token row (128 contiguous bytes = 128 codes), 32 rows per pass; a load of 16 codes
         // becomes two pieces of 8 halves in LDS
@@ -103,7 +113,10 @@ __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
         };
         const rsrc_t db = make_rsrc(a.B, (uint32_t)a.m * kt);
         const uint32_t bv = (uint32_t)(t0 + srow) * kt + (uint32_t)k0 + (uint32_t)scol;
-        dense_phase<AT, 1>(da, av, (kt / 16) * 1024u, 1024u, db, bv, 32u * kt, klen, lr, xs, stage_store);
+        if constexpr (AQ)
+            dense_phase_q4<AT, 1>(aq, db, bv, 32u * kt, scol, klen, lrq, xs, stage_store);
+        else
+            dense_phase<AT, 1>(da, av, (kt / 16) * 1024u, 1024u, db, bv, 32u * kt, klen, lr, xs, stage_store);
     }
     acc_settle();
 
@@ -177,14 +190,14 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
 }
 
 // One dense product on up to 2^32 - 1 bytes of B: C = A B^T over `splits` k ranges.
-template <int AT, int BF = 0>
+template <int AT, int BF = 0, bool AQ = false>
 static void launch_dense(DenseGemmArgs a, int splits, hipStream_t st)
 {
     a.tiles_o = (a.rows + 128 * AT - 1) / (128 * AT);
     const int tiles_t = (a.m + 127) / 128;
     const size_t lds = (size_t)2 * SG_STAGE * sizeof(half_t);
-    hipLaunchKernelGGL((gemm_dense_kernel<AT, BF>), dim3((unsigned)(a.tiles_o * tiles_t), (unsigned)splits), dim3(256), lds,
-                       st, a);
+    hipLaunchKernelGGL((gemm_dense_kernel<AT, BF, AQ>), dim3((unsigned)(a.tiles_o * tiles_t), (unsigned)splits), dim3(256),
+                       lds, st, a);
 }
 
 // Largest token count whose rows of `row_halves` halves stay below 4 GiB
@@ -206,14 +219,19 @@ int gemm_t_splits(int32_t m, int32_t rank_pad, int32_t k)
 
 // T fp16 [m][rank_pad] = X R^T.  xf: 0 = X fp16; 1, 2 = X as E4M3 / E5M2 codes (one byte per value) with the
 // tensor's scale at x_scale: T = scale * (value(X) R^T).
+// R: fp16 [rank_pad][k] in the adapter layout, or null with Rq / Rs: the 4-bit codes and scales of R [rank][k].
 static int launch_t(const half_t *X, int m, const half_t *R, int k, int rank_pad, half_t *T, float *P, int splits,
-                    hipStream_t st, int xf = 0, const float *x_scale = nullptr)
+                    hipStream_t st, int xf = 0, const float *x_scale = nullptr, const uint8_t *Rq = nullptr,
+                    const half_t *Rs = nullptr, int rank = 0)
 {
     if ((uint64_t)rank_pad * (uint64_t)k * 2 > 0xFFFFFFFFull) return SLIM_ERR_SHAPE;
     const int chunk = token_chunk(k);
     if (chunk < 128) return SLIM_ERR_SHAPE;
     DenseGemmArgs g{};
     g.A = R;
+    g.Aq = Rq;
+    g.As = Rs;
+    g.aq_rows = rank;
     g.rows = rank_pad;
     g.kt = k;
     g.ks = ((k / 128 + splits - 1) / splits) * 128;
@@ -224,7 +242,14 @@ static int launch_t(const half_t *X, int m, const half_t *R, int k, int rank_pad
         g.b_scale = x_scale;
         g.Y = T + (size_t)t0 * rank_pad;
         g.P = P;
-        if (xf == 0)
+        if (!R) {
+            if (xf == 0)
+                launch_dense<2, 0, true>(g, splits, st);
+            else if (xf == 1)
+                launch_dense<2, 1, true>(g, splits, st);
+            else
+                launch_dense<2, 2, true>(g, splits, st);
+        } else if (xf == 0)
             launch_dense<2>(g, splits, st);
         else if (xf == 1)
             launch_dense<2, 1>(g, splits, st);
@@ -241,7 +266,7 @@ static int launch_t(const half_t *X, int m, const half_t *R, int k, int rank_pad
 
 int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *scale, const half_t *X, const half_t *L,
                        const half_t *T, half_t *Y, int n, int k, int rank_pad, int m, hipStream_t st, int xf,
-                       const float *x_scale);   // slim_gemm_sparse.hip
+                       const float *x_scale, const uint8_t *Lq, const half_t *Ls, int rank);   // slim_gemm_sparse.hip
 
 int launch_lowrank_decode(const half_t *X, int m, const half_t *R, const half_t *L, int n, int k, int rank, int rank_pad,
                           half_t *Y, int accumulate, float *T, void *T16, unsigned *ctrl, hipStream_t st);   // slim_gemv.hip
@@ -279,24 +304,23 @@ static int linear_gemm(const slim_layer *layer_in, const void *X, int xf, const 
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
-    // 4-bit adapters: this compute-bound path reads them as fp16, expanded once per call
-    slim_layer expanded;
-    if (q4) {
-        const int rc = expand_q4_adapters(layer, p, ws, &expanded, st);
-        if (rc != SLIM_OK) return rc;
-        layer = &expanded;
-    }
+    // 4-bit adapters: both products read the codes themselves (dense_phase_q4())
+    if (q4 && ((uint64_t)q4_code_bytes(s.n, s.rank) > 0xFFFFFFFFull || (uint64_t)q4_code_bytes(s.rank, s.k) > 0xFFFFFFFFull))
+        return SLIM_ERR_SHAPE;
     half_t *T = reinterpret_cast<half_t *>(ws + p.t_off);
     float *P = reinterpret_cast<float *>(ws + p.part_off);
     const int rp = layer->rank_pad;
     const half_t *Xh = reinterpret_cast<const half_t *>(X);
+    const half_t *Lh = q4 ? nullptr : reinterpret_cast<const half_t *>(layer->L);
+    const half_t *Rh = q4 ? nullptr : reinterpret_cast<const half_t *>(layer->R);
+    const half_t *Ls = reinterpret_cast<const half_t *>(layer->Ls), *Rs = reinterpret_cast<const half_t *>(layer->Rs);
     if (rp > 0) {
-        const int rc = launch_t(Xh, m, reinterpret_cast<const half_t *>(layer->R), s.k, rp, T, P, p.splits, st, xf, x_info);
+        const int rc = launch_t(Xh, m, Rh, s.k, rp, T, P, p.splits, st, xf, x_info, layer->Rq, Rs, s.rank);
         if (rc != SLIM_OK) return rc;
     }
 
-    return launch_gemm_sparse(layer->qvals, layer->meta, layer->scale, Xh, reinterpret_cast<const half_t *>(layer->L), T,
-                              reinterpret_cast<half_t *>(Y), s.n, s.k, rp, m, st, xf, x_info);
+    return launch_gemm_sparse(layer->qvals, layer->meta, layer->scale, Xh, Lh, T, reinterpret_cast<half_t *>(Y), s.n, s.k, rp,
+                              m, st, xf, x_info, layer->Lq, Ls, s.rank);
 }
 
 extern "C" int slim_linear_gemm(const slim_layer *layer, const slim_half *X, int32_t m, slim_half *Y, void *workspace,

@@ -18,8 +18,9 @@
 //     read from LDS feeds AT matrix instructions.
 //   Then the accumulators are multiplied by the row scale and the adapter
 //   term continues on them with the dense instruction: A = L rows from global
-//   memory, B = T (fp16, from the workspace) staged through the same LDS
-//   buffers.  One rounding to fp16 at the store.
+//   memory (fp16, or 4-bit codes turned into fp16 in registers), B = T (fp16,
+//   from the workspace) staged through the same LDS buffers.  One rounding to
+//   fp16 at the store.
 // All global reads are buffer loads: a uniform descriptor and a 32-bit offset,
 // and rows past the end of a matrix read as zero.
 #include "slim_mma.h"
@@ -35,7 +36,10 @@ struct SparseGemmArgs {
     const float *scale;
     const half_t *X;     // [m][k] fp16, or (XF != 0) the same tensor as 8-bit codes, one byte per value
     const float *x_scale; // XF != 0: the tensor's scale (device memory)
-    const half_t *L;     // [n][rank_pad]
+    const half_t *L;     // [n][rank_pad], or null with the 4-bit form:
+    const uint8_t *Lq;   // codes of L [n][rank] (4-bit adapter layout)
+    const half_t *Ls;    // their group scales
+    int rank;
     const half_t *T;     // [m][rank_pad] fp16
     half_t *Y;           // [m][n]
     int n, k, rank_pad, m;
@@ -378,11 +382,16 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
     // tiled layout: one contiguous KiB per row tile and step
     if (a.rank_pad > 0) {
         const uint32_t rp = (uint32_t)a.rank_pad;
-        const rsrc_t dl = make_rsrc(a.L, (uint32_t)tl_bytes(a.n, a.rank_pad));
+        const rsrc_t dl = make_rsrc(a.L, a.L ? (uint32_t)tl_bytes(a.n, a.rank_pad) : 0u);
         const rsrc_t dt = make_rsrc(a.T, (uint32_t)a.m * rp * 2u);
         const uint32_t lv = tl_piece((uint32_t)o0 + li, lb, rp);
         const uint32_t tv = ((uint32_t)(t0 + srow) * rp + (uint32_t)scol) * 2u;
-        dense_phase<AT>(dl, lv, (rp / 16) * 1024u, 1024u, dt, tv, 32u * rp, (int)rp, lr, xr[0], stage_store);
+        if (a.Lq) {
+            const Q4Rows lq = q4_rows_operand(a.Lq, a.Ls, a.n, a.rank, o0, li, lb, 0);
+            dense_phase_q4<AT>(lq, dt, tv, 32u * rp, scol, (int)rp, lds + li * SG_LD + 32 * lb, xr[0], stage_store);
+        } else {
+            dense_phase<AT>(dl, lv, (rp / 16) * 1024u, 1024u, dt, tv, 32u * rp, (int)rp, lr, xr[0], stage_store);
+        }
         acc_settle();
     }
 
@@ -441,15 +450,19 @@ static void plan_tiles(SparseGemmArgs &a, int slots)
 // adapter matrices stay below 4 GiB each; X, T and Y are walked in token chunks
 // that do.
 // xf: 0 = X fp16; 1, 2 = X as E4M3 / E5M2 codes (one byte per value) with the tensor's scale at x_scale
+// L: fp16 [n][rank_pad] in the adapter layout, or null with Lq / Ls: the 4-bit codes and scales of L [n][rank]
 int launch_gemm_sparse(const uint8_t *qvals, const uint8_t *meta, const float *scale, const half_t *X, const half_t *L,
                        const half_t *T, half_t *Y, int n, int k, int rank_pad, int m, hipStream_t st, int xf,
-                       const float *x_scale)
+                       const float *x_scale, const uint8_t *Lq, const half_t *Ls, int rank)
 {
     SparseGemmArgs a{};
     a.qvals = qvals;
     a.meta = meta;
     a.scale = scale;
     a.L = L;
+    a.Lq = L ? nullptr : Lq;
+    a.Ls = Ls;
+    a.rank = rank;
     a.n = n;
     a.k = k;
     a.rank_pad = rank_pad;

@@ -154,6 +154,11 @@ __device__ __forceinline__ uint2_t load8(rsrc_t r, uint32_t lane_off, uint32_t u
     return __builtin_bit_cast(uint2_t, __builtin_amdgcn_raw_buffer_load_b64(r, (int)(lane_off + uniform_off), 0, 0));
 }
 
+__device__ __forceinline__ half_t load_half(rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_bit_cast(half_t, __builtin_amdgcn_raw_buffer_load_b16(r, (int)(lane_off + uniform_off), 0, 0));
+}
+
 #endif
 
 // What the planners need to know of the device that is current: compute units and LDS bytes per compute

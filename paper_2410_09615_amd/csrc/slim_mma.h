@@ -192,6 +192,137 @@ __device__ __forceinline__ void dense_phase(rsrc_t da, uint32_t av, uint32_t a_t
     }
 }
 
+// The A operand of dense_phase_q4(): the rows of a matrix [rows][K] stored as 4-bit codes with one
+// fp16 scale per group of 128 columns (slim_internal.h: tiles of 16 rows x 256 columns, a row's 256
+// columns in 128 contiguous bytes).
+struct Q4Rows {
+    rsrc_t codes, scales;
+    uint32_t cv, c_tile;     // code bytes: this lane's offset for row tile 0, columns 0-255; bytes between row tiles of 32
+    uint32_t sv, s_tile;     // scale bytes: this lane's offset for row tile 0, group 0; bytes between row tiles of 32
+    uint32_t g0;             // group of 128 columns at which the k range starts
+};
+
+// Lane (li, lb) of a wavefront whose row tile 0 starts at row o0 (a multiple of 32), k range from k0 (a
+// multiple of 128).  Rows past the last tile of 16 lie past the end of both descriptors and read as zero.
+__device__ __forceinline__ Q4Rows q4_rows_operand(const uint8_t *codes, const half_t *scales, int rows, int K, int o0,
+                                                  int li, int lb, int k0)
+{
+    const uint32_t ct = q4_ctiles(K);
+    Q4Rows q;
+    q.codes = make_rsrc(codes, (uint32_t)q4_code_bytes(rows, K));
+    q.scales = make_rsrc(scales, (uint32_t)q4_scale_bytes(rows, K));
+    q.cv = ((uint32_t)(o0 / 16 + (li >> 4)) * ct) * 2048u + (uint32_t)(li & 15) * 128u + (uint32_t)lb * 16u;
+    q.c_tile = 2u * ct * 2048u;
+    q.sv = (uint32_t)(o0 + li) * (2u * ct) * 2u;
+    q.s_tile = 32u * (2u * ct) * 2u;
+    q.g0 = (uint32_t)k0 / 128u;
+    return q;
+}
+
+// dense_phase() with the A operand read as 4-bit codes: acc(i, it) += A_i B_it^T over K inputs (K a
+// multiple of 32), B staged through LDS exactly as there.
+//   A: per stage of 128 inputs (one scale group) a lane loads 2 x 16 bytes of codes and one scale per row
+//      tile: 3 AT loads per stage where fp16 rows take 8 AT.  One register set: the half of a stage that
+//      steps 0-3 use is refilled for the next stage at step 3, the other half at step 7, four steps
+//      before the first use either way.  A dword of codes becomes eight fp16 values (the 13-instruction
+//      conversion of the weights) times the scale (four packed multiplies: the value is
+//      fp16(code * scale), what the expansion to fp16 stores), one step ahead, in pieces of two values
+//      pinned behind the matrix instructions.
+//   Order of the inputs inside a stage: the 16 bytes a lane loads are 32 consecutive columns of its row,
+//      so that a load instruction asks for 32 contiguous bytes of each of 32 rows and the two loads of
+//      a stage use up half a line of every row.  Step 4 q + j therefore multiplies columns
+//      64 q + 32 lb + 8 j + [0, 8) on lane half lb, and the B fragments are read from LDS in that order
+//      (lrq: this lane's token row at column 32 lb), one step ahead; a sum over the inputs does
+//      not care.  A partly valid stage runs whole groups of four steps: bcol = first column of the
+//      lane's share of a B stage, whose columns past K are replaced by zeros on their way into LDS.
+// Starts and ends with every wavefront past a barrier.
+template <int AT, int BB = 2, class Store>
+__device__ __forceinline__ void dense_phase_q4(const Q4Rows &qa, rsrc_t db, uint32_t bv, uint32_t b_pass, int bcol,
+                                               int K, const half_t *lrq, uint4_t (&xs)[XR * BB / 2],
+                                               Store &&stage_store)
+{
+    constexpr int XRN = XR * BB / 2;
+    static_assert(AT <= NT, "one load per block refills a half stage");
+    const int stages = (K + SG_BK - 1) / SG_BK;
+    uint4_t cq[2][AT];             // [half of the stage][row tile]
+    half_t sc[AT], sc_nxt[AT];
+    auto fetch_codes = [&](int h, int i, int s) {
+        const uint32_t sg = qa.g0 + (uint32_t)s;
+        cq[h][i] = load16(qa.codes, qa.cv, (uint32_t)i * qa.c_tile + (sg >> 1) * 2048u + (sg & 1u) * 64u + (uint32_t)h * 32u);
+    };
+    auto fetch_scale = [&](int i, int s, half_t (&dst)[AT]) {
+        dst[i] = load_half(qa.scales, qa.sv, (uint32_t)i * qa.s_tile + (qa.g0 + (uint32_t)s) * 2u);
+    };
+    auto zero_tail = [&](int s) {
+        if (SG_BK * s + bcol >= K) {
+#pragma unroll
+            for (int p = 0; p < XRN; ++p) xs[p] = uint4_t{0u, 0u, 0u, 0u};
+        }
+    };
+    auto read_b = [&](int u, int it, int jj) {
+        return *reinterpret_cast<const half8_t *>(lrq + u * SG_STAGE + it * 32 * SG_LD + 64 * (jj >> 2) + 8 * (jj & 3));
+    };
+#pragma unroll
+    for (int p = 0; p < XRN; ++p) xs[p] = load16(db, bv, (uint32_t)p * b_pass);
+#pragma unroll
+    for (int i = 0; i < AT; ++i) {
+        fetch_codes(0, i, 0);
+        fetch_codes(1, i, 0);
+        fetch_scale(i, 0, sc);
+    }
+    zero_tail(0);
+    stage_store(0, xs);
+    __syncthreads();
+    half8_t a_cur[AT], a_nxt[AT];
+#pragma unroll
+    for (int i = 0; i < AT; ++i) a_cur[i] = codes_to_half8(cq[0][i][0]) * sc[i];
+    for (int s = 0; s < stages; ++s) {
+        const int u = s & 1;
+        const int jn = min(8, 4 * ((K - SG_BK * s + 63) / 64));       // steps in this stage
+        half8_t b_cur[NT], b_nxt[NT];
+#pragma unroll
+        for (int it = 0; it < NT; ++it) b_cur[it] = read_b(u, it, 0);
+        static_for<8>([&](auto jc) {
+            constexpr int jj = jc;
+            if (jj >= jn) return;
+            constexpr int nq = ((jj + 1) & 7) >> 2, nd = (jj + 1) & 3;      // where the codes of the next step are
+            static_for<NT>([&](auto itc) {
+                constexpr int it = itc;
+                if constexpr (jj == 2 && it < AT) fetch_scale(it, s + 1, sc_nxt);
+                if constexpr (jj == 3 && it < AT) fetch_codes(0, it, s + 1);
+                if constexpr (jj == 7 && it < AT) fetch_codes(1, it, s + 1);
+                if constexpr (jj < 4 && it < XRN / 4)
+                    xs[(XRN / 4) * jj + it] =
+                        load16(db, bv, (uint32_t)(s + 1) * (SG_BK * BB) + (uint32_t)((XRN / 4) * jj + it) * b_pass);
+                if constexpr (jj + 1 < 8) b_nxt[it] = read_b(u, it, jj + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<AT>([&](auto ic) {
+                    constexpr int i = ic;
+                    mfma_fixed<i * NT + it>(a_cur[i], b_cur[it]);
+                    // 4 AT pieces of two values over AT NT matrix instructions
+                    constexpr int pc = it * AT + i, tile = pc / 4, g = pc % 4;
+                    if constexpr (tile < AT) {
+                        const half_t sv = jj == 7 ? sc_nxt[tile] : sc[tile];
+                        const half2_t h = code_pair(codes_bias(cq[nq][tile][nd]), g) * sv;
+                        a_nxt[tile][2 * g] = h[0];
+                        a_nxt[tile][2 * g + 1] = h[1];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            });
+#pragma unroll
+            for (int it = 0; it < NT; ++it) b_cur[it] = b_nxt[it];
+#pragma unroll
+            for (int i = 0; i < AT; ++i) a_cur[i] = a_nxt[i];
+        });
+#pragma unroll
+        for (int i = 0; i < AT; ++i) sc[i] = sc_nxt[i];
+        zero_tail(s + 1);
+        if (s + 1 < stages) stage_store(u ^ 1, xs);
+        __syncthreads();
+    }
+}
+
 }  // namespace slim
 
 #endif  // SLIM_MMA_H

@@ -563,9 +563,32 @@ def test_gemv_q4_adapters_with_x_in_chunks(n, k, r, m, lds_kb, decode_override):
     assert _forward_case_q4(_shape(n, k, r), m, B.slim_linear_gemv, seed=17) <= TOL_Y
 
 
-@pytest.mark.parametrize("n,k,r,m", [(512, 512, 51, 200), (1000, 1280, 37, 129)])
+@pytest.mark.parametrize("n,k,r,m", [(512, 512, 51, 200), (1000, 1280, 37, 129), (384, 640, 90, 129), (1200, 1024, 160, 300),
+                                     (2100, 4096, 410, 700), (130, 256, 5, 77), (700, 2048, 300, 40)])
 def test_gemm_q4_adapters(n, k, r, m):
+    """Prefill reads the 4-bit codes itself, in stages of 128 ranks or inputs taken in groups of 64:
+    ranks that end 32 past such a group (90, 160, 410), below one group (5, 37, 51), several stages,
+    ragged rows and tokens, the remainder-tile kernels (few tiles)."""
     assert _forward_case_q4(_shape(n, k, r), m, B.slim_linear_gemm, seed=5) <= TOL_Y
+
+
+def test_gemm_q4_adapters_tokens_do_not_leak_into_each_other():
+    """The adapter term runs whole groups of 64 ranks; where the padded rank ends inside a group the
+    kernel must multiply zeros, not whatever follows the row of T -- the next token's T.  Tokens whose
+    inputs are infinite make that visible: every other token still matches the oracle."""
+    shape, m = _shape(384, 640, 90), 260
+    layer, ref, Lr, Rr = _compressed(shape, 9, 4)
+    X = wl.make_activations(m, shape.k, shape.outliers, 12, 13)
+    bad = [1, 127, 128, 259]
+    Xg = X.clone()
+    Xg[bad] = float("inf")
+    Y = B.slim_linear_gemm(layer, Xg.to(DEV)).cpu().numpy()
+    keep = np.setdiff1d(np.arange(m), bad)
+    Xn = X.numpy().astype(np.float64)[keep]
+    Yref, T = O.forward(ref, Lr, Rr, Xn, return_t=True)
+    tol = element_tolerance(Yref, T, Lr, ref.scale.astype(np.float64), Xn, CT_PREFILL + CT_Q4)
+    assert np.isfinite(Y[keep]).all()
+    assert assert_forward_close(Y[keep], Yref, tol, "q4 prefill beside infinite tokens")["whole"] <= TOL_Y
 
 
 def test_q4_adapters_change_the_result_as_much_as_the_quantization_says():
@@ -680,13 +703,19 @@ def test_input_quant_fp8_codes_bit_exact(case):
     assert none is None and torch.equal(codes3, codes) and torch.equal(info3, info)
 
 
-def _fp8_forward_case(n, k, r, m, seed=0, x_gain=1.0, rows=None, shape=None):
+def _fp8_forward_case(n, k, r, m, seed=0, x_gain=1.0, rows=None, shape=None, bits=16):
     """slim_linear_gemm_fp8 against the oracle's forward on the exact quantized values value(code) * scale (both terms;
-    the codes themselves are checked bit for bit in test_input_quant_fp8_codes_bit_exact)."""
+    the codes themselves are checked bit for bit in test_input_quant_fp8_codes_bit_exact).  bits = 4: on 4-bit
+    adapters, the oracle's forward on their dequantized values."""
     shape = shape or _shape(n, k, r)
     W, L, R, X = wl.make_layer(shape, m, seed=seed)
     X = (X.float() * x_gain).half()
-    layer = _gpu_layer(W, L if shape.r else None, R if shape.r else None)
+    if bits == 4:
+        layer = _q4_layer(W, L, R)
+        L = torch.from_numpy(O.dequantize_adapter(*O.quantize_adapter(L.numpy())))
+        R = torch.from_numpy(O.dequantize_adapter(*O.quantize_adapter(R.numpy())))
+    else:
+        layer = _gpu_layer(W, L if shape.r else None, R if shape.r else None)
     _, info, codes = B.slim_input_quant_fp8(X.to(DEV), Xq=False, codes=True)
     torch.cuda.synchronize()
     fmt = int(info[1])
@@ -702,9 +731,11 @@ def _fp8_forward_case(n, k, r, m, seed=0, x_gain=1.0, rows=None, shape=None):
     Rr = R.numpy().astype(np.float64) if shape.r else None
     Yref, T = O.forward(ref, Lr, Rr, xe, rows=rows, return_t=True)
     sel = slice(None) if rows is None else rows
-    tol = element_tolerance(Yref, T, None if Lr is None else Lr[sel], ref.scale[sel].astype(np.float64), xe, CT_PREFILL, mma8=True)
+    tol = element_tolerance(Yref, T, None if Lr is None else Lr[sel], ref.scale[sel].astype(np.float64), xe,
+                            CT_PREFILL + (CT_Q4 if bits == 4 else 0), mma8=True)
     Yg = Y.cpu().numpy()
-    return assert_forward_close(Yg if rows is None else Yg[:, rows], Yref, tol, f"slim_linear_gemm_fp8 {shape.name} m={m} fmt={fmt}")["whole"], fmt
+    return assert_forward_close(Yg if rows is None else Yg[:, rows], Yref, tol,
+                                f"slim_linear_gemm_fp8 {shape.name} m={m} fmt={fmt} bits={bits}")["whole"], fmt
 
 
 @pytest.mark.parametrize("n,k,r,m", [(512, 128, 0, 128), (640, 1024, 0, 200), (1000, 2048, 64, 300), (33, 256, 1, 17),
@@ -718,6 +749,21 @@ def test_gemm_fp8_inputs_e5m2():
     """Inputs beyond E4M3's range take the E5M2 form of the kernel."""
     err, fmt = _fp8_forward_case(512, 512, 32, 128, seed=1, x_gain=300.0)
     assert err <= TOL_Y and fmt == 1
+
+
+@pytest.mark.parametrize("n,k,r,m,gain", [(1000, 2048, 64, 300, 1.0), (2100, 4096, 410, 700, 1.0), (384, 640, 90, 129, 1.0),
+                                          (512, 512, 32, 128, 300.0)])
+def test_gemm_fp8_inputs_with_q4_adapters(n, k, r, m, gain):
+    """8-bit inputs and 4-bit adapters together: both operands of T = X R^T are codes (the last case in E5M2)."""
+    err, fmt = _fp8_forward_case(n, k, r, m, seed=3, x_gain=gain, bits=4)
+    assert err <= TOL_Y and fmt == (1 if gain > 1 else 0)
+
+
+def test_gemm_fp8_inputs_with_q4_adapters_full_size_sampled_rows():
+    shape = wl.L70B_ATTN
+    rows = prefill_row_sample(shape.n, 256, seed=5)
+    err, _ = _fp8_forward_case(shape.n, shape.k, shape.r, 4096, seed=4, rows=rows, shape=shape, bits=4)
+    assert err <= TOL_Y
 
 
 @pytest.mark.parametrize("shape,m", [(wl.L7B_UP, 2048), (wl.L70B_ATTN, 4096)])
