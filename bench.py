@@ -217,6 +217,7 @@ def main():
         ms_dense = statistics.median(batches_ms(lambda i: rot.dense_call(m, i), iters, 3))
         feff = A.flops_eff(shape.n, shape.k, shape.r, m)
         return {"shape": shape.name, "tokens": m, "entry": "slim_linear_gemm_fp8", "inputs": "E4M3" if fmt == 0 else "E5M2",
+                "adapters": "4-bit group-128 (Sec. 3.3)" if rot.adapter_bits == 4 else "fp16",
                 "us": round(ms * 1e3, 3), "us_min": round(min(ms_b) * 1e3, 3), "batches": len(ms_b), "launches_per_batch": iters,
                 "TFLOPs_eff": round(feff / ms * 1e-9, 2), "fp16_inputs_us": round(ms16 * 1e3, 3),
                 "input_quant_us": round(ms_q * 1e3, 3), "dense_fp16_us": round(ms_dense * 1e3, 3),
@@ -421,8 +422,8 @@ def main():
             del r
             torch.cuda.empty_cache()
             # 8-bit inputs (App. "Input Quantization"): the weight term on the 8-bit sparse matrix instruction
-            for shp, m in ((wl.L7B_UP, 2048), (wl.L70B_ATTN, 4096), (wl.L70B_UP, 4096)):
-                r = Rotating(shp, (m,), min_copies=2, max_bytes=1 << 30)
+            for shp, m, bits in ((wl.L7B_UP, 2048, 16), (wl.L70B_ATTN, 4096, 16), (wl.L70B_UP, 4096, 16), (wl.L70B_ATTN, 4096, 4)):
+                r = Rotating(shp, (m,), min_copies=2, max_bytes=1 << 30, adapter_bits=bits)
                 legs.append(fp8_leg(r, m, 8, 3))
                 del r
                 torch.cuda.empty_cache()
