@@ -549,8 +549,11 @@ def test_gemv_q4_adapters_full_size_all_rows(shape, m):
     assert _forward_case_q4(shape, m, B.slim_linear_gemv) <= TOL_Y
 
 
-@pytest.mark.parametrize("shape,m", [(wl.L7B_UP, 2048), (wl.L70B_ATTN, 4096)], ids=lambda v: str(getattr(v, "name", v)))
+@pytest.mark.parametrize("shape,m", [(wl.L7B_UP, 2048), (wl.L7B_DOWN, 2048), (wl.L13B_ATTN, 4096), (wl.L13B_UP, 4096),
+                                     (wl.L70B_ATTN, 4096), (wl.L70B_UP, 4096)], ids=lambda v: str(getattr(v, "name", v)))
 def test_gemm_q4_adapters_full_size_sampled_rows(shape, m):
+    """Every configured prefill shape on 4-bit adapters read directly by both adapter products (whole
+    tiles and the remainder-tile kernels, k = 11008 with its odd number of 256-column code tiles)."""
     rows = prefill_row_sample(shape.n, 256, seed=3)
     assert _forward_case_q4(shape, m, B.slim_linear_gemm, rows=rows) <= TOL_Y
 
