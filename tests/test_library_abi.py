@@ -52,6 +52,13 @@ def test_workspace_query():
     big = ctypes.c_size_t()
     assert B.lib().slim_workspace_bytes(ctypes.byref(layer), 2048, big) == 0
     assert big.value >= 2048 * 416 * 2
+    # 4-bit adapters: prefill reads the codes itself and needs no room for an fp16 copy of them; a decode call
+    # may fall back on the two-launch kernels, which read fp16: room for both adapters then
+    q4 = B.slim_layer(B.slim_shape(4096, 4096, 410), None, None, None, None, None, 416, 4, None, None, None, None)
+    q4_big, q4_dec = ctypes.c_size_t(), ctypes.c_size_t()
+    assert B.lib().slim_workspace_bytes(ctypes.byref(q4), 2048, q4_big) == 0 and q4_big.value == big.value
+    assert B.lib().slim_workspace_bytes(ctypes.byref(q4), 16, q4_dec) == 0
+    assert q4_dec.value >= out.value + 2 * 4096 * 416 * 2
     layer.rank_pad = 410                                # not slim_rank_pad(rank)
     assert B.lib().slim_workspace_bytes(ctypes.byref(layer), 16, out) == B.SLIM_ERR_SHAPE
     assert B.lib().slim_workspace_bytes(None, 16, out) == B.SLIM_ERR_NULL
