@@ -567,11 +567,12 @@ def test_gemv_q4_adapters_with_x_in_chunks(n, k, r, m, lds_kb, decode_override):
 
 
 @pytest.mark.parametrize("n,k,r,m", [(512, 512, 51, 200), (1000, 1280, 37, 129), (384, 640, 90, 129), (1200, 1024, 160, 300),
-                                     (2100, 4096, 410, 700), (130, 256, 5, 77), (700, 2048, 300, 40)])
+                                     (2100, 4096, 410, 700), (130, 256, 5, 77), (700, 2048, 300, 40), (2000, 2048, 1100, 260)])
 def test_gemm_q4_adapters(n, k, r, m):
     """Prefill reads the 4-bit codes itself, in stages of 128 ranks or inputs taken in groups of 64:
-    ranks that end 32 past such a group (90, 160, 410), below one group (5, 37, 51), several stages,
-    ragged rows and tokens, the remainder-tile kernels (few tiles)."""
+    ranks that end 32 past such a group (90, 160, 410, 1100), below one group (5, 37, 51), several stages,
+    more than 1024 ranks (five tiles of 256 code columns), ragged rows and tokens, the remainder-tile kernels
+    (few tiles)."""
     assert _forward_case_q4(_shape(n, k, r), m, B.slim_linear_gemm, seed=5) <= TOL_Y
 
 
