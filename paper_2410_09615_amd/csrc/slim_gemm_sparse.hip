@@ -86,6 +86,13 @@ __device__ __forceinline__ uint2_t codes_to_e5m2x8(uint32_t q)
     const uint4_t h = __builtin_bit_cast(uint4_t, codes_to_half8(q));
     return uint2_t{__builtin_amdgcn_perm(h[1], h[0], 0x07050301u), __builtin_amdgcn_perm(h[3], h[2], 0x07050301u)};
 }
+// Half of that: codes 4 h .. 4 h + 3 of a dword already in offset-by-8 form (codes_bias()).
+__device__ __forceinline__ uint32_t codes_to_e5m2x4(uint32_t biased, int h)
+{
+    const uint32_t p0 = __builtin_bit_cast(uint32_t, code_pair(biased, 2 * h));
+    const uint32_t p1 = __builtin_bit_cast(uint32_t, code_pair(biased, 2 * h + 1));
+    return __builtin_amdgcn_perm(p1, p0, 0x07050301u);
+}
 
 // AT row tiles of 32 per wavefront; accumulator tile (i, it) is a[16 (i NT + it) ..].
 // XF: 0 = X in fp16; 1, 2 = X as 8-bit codes (E4M3, E5M2) with one scale for the tensor
@@ -231,17 +238,15 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
             else
                 mm[j - AT] = load8(dm, mv, ((uint32_t)(j - AT) * (k / 128) + (uint32_t)s) * 512u);
         };
-        // One stage = 2 steps (u) x NT token tiles: 2 NT blocks of AT matrix instructions.  The codes of
-        // step 1 are converted while step 0's instructions run.
-        auto compute_stage8 = [&](int ub, const uint4_t (&q)[AT], const uint2_t (&mm)[AT], auto &&fetch) {
-            int4_t a8[2][AT];
-#pragma unroll
-            for (int i = 0; i < AT; ++i) {
-                const uint2_t c0 = codes_to_e5m2x8(q[i][0]), c1 = codes_to_e5m2x8(q[i][1]);
-                a8[0][i] = int4_t{(int)c0[0], (int)c0[1], (int)c1[0], (int)c1[1]};
-            }
+        // One stage = 2 steps (u) x NT token tiles: 2 NT blocks of AT matrix instructions.  Every matrix
+        // instruction is followed by one piece of conversion (four codes -> four E5M2 bytes, 7 instructions):
+        // during step 0 the pieces of this stage's step 1, during step 1 those of the next stage's step 0
+        // (a0: this stage's step-0 operands on entry, the next stage's on exit), so that no conversion stands
+        // between two stages.  qn: the codes of the next stage, loaded a stage ago.
+        auto compute_stage8 = [&](int ub, const uint4_t (&q)[AT], const uint4_t (&qn)[AT], const uint2_t (&mm)[AT],
+                                  int4_t (&a0)[AT], auto &&fetch) {
+            int4_t a1[AT], an[AT];
             int8v_t b_cur = read_b8(ub, 0, 0), b_nxt = b_cur;
-            asm volatile("s_nop 3");
             static_for<2>([&](auto uc) {
                 constexpr int u = uc;
                 static_for<NT>([&](auto itc) {
@@ -254,39 +259,57 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
                     __builtin_amdgcn_sched_barrier(0);
                     static_for<AT>([&](auto ic) {
                         constexpr int i = ic;
-                        smfmac8_fixed<i * NT + it, XF == 2>(a8[u][i], b_cur, (int)mm[i][u]);
-                        if constexpr (u == 0 && it < AT && i == 0) {
-                            // tile `it` of step 1
-                            const uint2_t c0 = codes_to_e5m2x8(q[it][2]), c1 = codes_to_e5m2x8(q[it][3]);
-                            a8[1][it] = int4_t{(int)c0[0], (int)c0[1], (int)c1[0], (int)c1[1]};
+                        smfmac8_fixed<i * NT + it, XF == 2>(u == 0 ? a0[i] : a1[i], b_cur, (int)mm[i][u]);
+                        // 4 AT pieces over AT NT matrix instructions: piece `part` of a tile is half
+                        // (part & 1) of code dword (part >> 1) of the step
+                        constexpr int pc = it * AT + i, tile = pc / 4, part = pc % 4;
+                        if constexpr (tile < AT) {
+                            if constexpr (u == 0)
+                                a1[tile][part] = (int)codes_to_e5m2x4(codes_bias(q[tile][2 + (part >> 1)]), part & 1);
+                            else
+                                an[tile][part] = (int)codes_to_e5m2x4(codes_bias(qn[tile][part >> 1]), part & 1);
                         }
+                        __builtin_amdgcn_sched_barrier(0);
                     });
-                    __builtin_amdgcn_sched_barrier(0);
                     b_cur = b_nxt;
                 });
-                if constexpr (u == 0) asm volatile("s_nop 3");
+                asm volatile("s_nop 3");       // the last piece is written right before the next step reads it
             });
+#pragma unroll
+            for (int i = 0; i < AT; ++i) a0[i] = an[i];
         };
+        uint4_t qa8[3][AT];
+        uint2_t ma8[3][AT];
 #pragma unroll
         for (int p = 0; p < 4; ++p) fetch_x8(p, 0, x8[0]);
 #pragma unroll
-        for (int j = 0; j < 2 * AT; ++j) fetch_a(j, 0, qa[0], ma[0]);
+        for (int j = 0; j < 2 * AT; ++j) fetch_a(j, 0, qa8[0], ma8[0]);
 #pragma unroll
         for (int p = 0; p < 4; ++p) fetch_x8(p, 1, x8[1]);
+#pragma unroll
+        for (int j = 0; j < 2 * AT; ++j) fetch_a(j, 1, qa8[1], ma8[1]);
         stage_store8(0, x8[0]);
+        int4_t a0[AT];
+#pragma unroll
+        for (int i = 0; i < AT; ++i) {
+            const uint2_t c0 = codes_to_e5m2x8(qa8[0][i][0]), c1 = codes_to_e5m2x8(qa8[0][i][1]);
+            a0[i] = int4_t{(int)c0[0], (int)c0[1], (int)c1[0], (int)c1[1]};
+        }
         __syncthreads();
-        for (int s0 = 0; s0 < nsteps; s0 += 2) {
-            static_for<2>([&](auto uc) {
-                constexpr int u = uc;
-                const int s = s0 + u;
+        // weights two stages ahead in three register sets (stage s uses set s mod 3), X two stages ahead in two
+        // sets and two LDS buffers (s mod 2): the loop body is written out for six stages
+        for (int s0 = 0; s0 < nsteps; s0 += 6) {
+            static_for<6>([&](auto vc) {
+                constexpr int u = vc % 2, w = vc % 3, w1 = (vc + 1) % 3, w2 = (vc + 2) % 3;
+                const int s = s0 + vc;
                 if (s >= nsteps) return;
-                compute_stage8(u, qa[u], ma[u], [&](auto bc) {
+                compute_stage8(u, qa8[w], qa8[w1], ma8[w], a0, [&](auto bc) {
                     constexpr int bi = bc;           // 0 .. 2 NT - 1
                     if constexpr (bi < NT) {
-                        constexpr int per = (2 * AT + NT - 1) / NT;      // weights of stage s + 1
+                        constexpr int per = (2 * AT + NT - 1) / NT;      // weights of stage s + 2
 #pragma unroll
                         for (int j = bi * per; j < (bi + 1) * per && j < 2 * AT; ++j)
-                            fetch_a(j, s + 1, qa[u ^ 1], ma[u ^ 1]);
+                            fetch_a(j, s + 2, qa8[w2], ma8[w2]);
                     } else {
                         fetch_x8(bi - NT, s + 2, x8[u]);                 // X of stage s + 2: four loads
                     }
