@@ -8,7 +8,7 @@
 // round of workgroups.
 //   A (weights): never touches LDS.  Per 128 inputs a lane loads 16 bytes of
 //     codes and 8 bytes of positions of each of its rows straight from global
-//     memory (one stage ahead; the packed layout makes each load instruction one
+//     memory (two stages ahead; the packed layout makes each load instruction one
 //     contiguous KiB or half KiB), turns 4 code bytes into 8 fp16 values in
 //     registers, and passes the 16 position bits of those 4 groups as the index
 //     operand (the canonical metadata is that operand's format).  Each wavefront
@@ -132,8 +132,8 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
     // uniform terms; row tiles past the end read as zero
     const uint32_t qv = (uint32_t)(o0 / 32) * (k / 128) * 1024u + (uint32_t)(lb * 32 + li) * 16u;
     const uint32_t mv = (uint32_t)(o0 / 32) * (k / 128) * 512u + (uint32_t)(lb * 32 + li) * 8u;
-    uint4_t qa[2][AT];
-    uint2_t ma[2][AT];
+    uint4_t qa[3][AT];
+    uint2_t ma[3][AT];
 
     // X / T staging: 16 lanes per token row (256 contiguous bytes), 16 rows per pass
     const int srow = tid >> 4, scol = (tid & 15) * 8;
@@ -160,13 +160,15 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
     // instructions of the current one.  With one wavefront per SIMD nothing else
     // fills the matrix pipe's shadow, so the conversion of the next slice's codes
     // is cut into pieces of one group (3-4 instructions) and one piece follows
-    // each matrix instruction, pinned there by scheduling barriers.
+    // each matrix instruction, pinned there by scheduling barriers; the pieces
+    // behind the last slice convert the first slice of the next stage (qn: its
+    // codes, loaded a stage ago), so that no stage begins with a conversion.
+    // a_cur: the first slice of this stage on entry, of the next stage on exit.
     // `fetch(bi)` is called once per block, bi = t NT + it, right after the
     // block's LDS reads: the place to issue a share of the next stages' loads.
-    auto compute_stage = [&](int u, const uint4_t (&q)[AT], const uint2_t (&mm)[AT], auto &&fetch) {
-        half8_t a_cur[AT], a_nxt[AT];
-#pragma unroll
-        for (int i = 0; i < AT; ++i) a_cur[i] = codes_to_half8(q[i][0]);
+    auto compute_stage = [&](int u, const uint4_t (&q)[AT], const uint4_t (&qn)[AT], const uint2_t (&mm)[AT],
+                             half8_t (&a_cur)[AT], auto &&fetch) {
+        half8_t a_nxt[AT];
         half16_t b_cur = read_b(u, 0, 0), b_nxt = b_cur;
         static_for<4>([&](auto tc) {
             constexpr int t = tc;
@@ -182,11 +184,12 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
                     constexpr int i = ic;
                     // even slice: index bits 15..0, odd slice: bits 31..16 of the position dword
                     smfmac_fixed<i * NT + it, (t & 1) != 0>(a_cur[i], b_cur, (int)mm[i][t >> 1]);
-                    if constexpr (t + 1 < 4) {
-                        // 4 AT pieces per slice over AT NT matrix instructions
+                    {
+                        // 4 AT pieces per slice over AT NT matrix instructions; the last slice converts the
+                        // first one of the next stage
                         constexpr int pc = it * AT + i, tile = pc / 4, g = pc % 4;
                         if constexpr (tile < AT) {
-                            const half2_t h = code_pair(codes_bias(q[tile][t + 1]), g);
+                            const half2_t h = code_pair(codes_bias(t + 1 < 4 ? q[tile][(t + 1) & 3] : qn[tile][0]), g);
                             a_nxt[tile][2 * g] = h[0];
                             a_nxt[tile][2 * g + 1] = h[1];
                         }
@@ -322,7 +325,7 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
     // The global loads are spread over the stage, one or two per block, so the
     // four wavefronts do not all queue sixteen loads at the address unit right
     // after the barrier (that burst stalled the first slice of every stage).
-    // Weights of stage s + 1 go out in the first half of stage s; X of stage
+    // Weights of stage s + 2 go out in the first half of stage s; X of stage
     // s + 2 in the second half, to be written to LDS at the end of stage s + 1.
     // Fetches past the last stage stay inside the descriptors or read as zero and
     // are never used.
@@ -345,20 +348,27 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
         for (int j = 0; j < 2 * AT; ++j) fetch_a(j, 0, qa[0], ma[0]);
 #pragma unroll
         for (int p = 0; p < XR; ++p) fetch_x(p, 1, xr[1]);
+#pragma unroll
+        for (int j = 0; j < 2 * AT; ++j) fetch_a(j, 1, qa[1], ma[1]);
         stage_store(0, xr[0]);
+        half8_t a_first[AT];
+#pragma unroll
+        for (int i = 0; i < AT; ++i) a_first[i] = codes_to_half8(qa[0][i][0]);
         __syncthreads();
-        for (int s0 = 0; s0 < nsteps; s0 += 2) {
-            static_for<2>([&](auto uc) {
-                constexpr int u = uc;
-                const int s = s0 + u;
+        // weights two stages ahead in three register sets (stage s uses set s mod 3), X two stages ahead in
+        // two sets and two LDS buffers (s mod 2): the loop body is written out for six stages
+        for (int s0 = 0; s0 < nsteps; s0 += 6) {
+            static_for<6>([&](auto vc) {
+                constexpr int u = vc % 2, w = vc % 3, w1 = (vc + 1) % 3, w2 = (vc + 2) % 3;
+                const int s = s0 + vc;
                 if (s >= nsteps) return;
-                compute_stage(u, qa[u], ma[u], [&](auto bc) {
+                compute_stage(u, qa[w], qa[w1], ma[w], a_first, [&](auto bc) {
                     constexpr int bi = bc;
                     if constexpr (bi < HB) {
-                        constexpr int per = (2 * AT + HB - 1) / HB;      // weights of stage s + 1
+                        constexpr int per = (2 * AT + HB - 1) / HB;      // weights of stage s + 2
 #pragma unroll
                         for (int j = bi * per; j < (bi + 1) * per && j < 2 * AT; ++j)
-                            fetch_a(j, s + 1, qa[u ^ 1], ma[u ^ 1]);
+                            fetch_a(j, s + 2, qa[w2], ma[w2]);
                     } else {
                         constexpr int per = (XR + HB - 1) / HB;          // X of stage s + 2
 #pragma unroll
