@@ -372,11 +372,14 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
                     } else {
                         constexpr int per = (XR + HB - 1) / HB;          // X of stage s + 2
 #pragma unroll
-                        for (int p = (bi - HB) * per; p < (bi - HB + 1) * per && p < XR; ++p)
+                        for (int p = (bi - HB) * per; p < (bi - HB + 1) * per && p < XR; ++p) {
                             fetch_x(p, s + 2, xr[u]);
+                            // X of stage s + 1 (loaded a stage ago) goes into the other LDS buffer, which nobody
+                            // reads during this stage, piece by piece instead of in the stage's tail
+                            *reinterpret_cast<uint4_t *>(lw + (u ^ 1) * SG_STAGE + p * 16 * SG_LD) = xr[u ^ 1][p];
+                        }
                     }
                 });
-                stage_store(u ^ 1, xr[u ^ 1]);
                 __syncthreads();
             });
         }
