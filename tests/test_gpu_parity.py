@@ -345,6 +345,19 @@ def test_gemm_ragged_shapes(n, k, r, m):
     assert _forward_case(_shape(n, k, r), m, B.slim_linear_gemm, seed=11) <= TOL_Y
 
 
+@pytest.mark.parametrize("stages", [1, 2, 3, 4, 5, 6, 7, 9, 12, 13])
+@pytest.mark.parametrize("fp8", [False, True])
+def test_gemm_every_stage_count_modulo_six(stages, fp8):
+    """The main loops are written out for six stages of 128 inputs (three register sets of weights, two of X):
+    every residue of the stage count, below and above one pass of the loop, on fp16 and on 8-bit inputs."""
+    n, k, r, m = 200, 128 * stages, 20, 130
+    if fp8:
+        err, _ = _fp8_forward_case(n, k, r, m, seed=stages)
+    else:
+        err = _forward_case(_shape(n, k, r), m, B.slim_linear_gemm, seed=stages)
+    assert err <= TOL_Y
+
+
 def test_gemm_without_adapters():
     assert _forward_case(_shape(512, 1024, 0), 256, B.slim_linear_gemm, seed=4) <= TOL_Y
 
