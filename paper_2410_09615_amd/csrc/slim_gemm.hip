@@ -86,9 +86,10 @@ __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
         const int srow = tid >> 4, scol = (tid & 15) * 8;
         half_t *const lw = lds + srow * SG_LD + scol;
         uint4_t xs[XR];
-        auto stage_store = [&](int u, const uint4_t (&reg)[XR]) {
+        auto stage_store = [&](int u, const uint4_t (&reg)[XR], int only = -1) {
 #pragma unroll
-            for (int p = 0; p < XR; ++p) *reinterpret_cast<uint4_t *>(lw + u * SG_STAGE + p * 16 * SG_LD) = reg[p];
+            for (int p = 0; p < XR; ++p)
+                if (only < 0 || only == p) *reinterpret_cast<uint4_t *>(lw + u * SG_STAGE + p * 16 * SG_LD) = reg[p];
         };
         const rsrc_t db = make_rsrc(a.B, (uint32_t)a.m * kt * 2u);
         const uint32_t bv = ((uint32_t)(t0 + srow) * kt + (uint32_t)k0 + (uint32_t)scol) * 2u;
@@ -103,9 +104,10 @@ __global__ __launch_bounds__(256, 1) void gemm_dense_kernel(DenseGemmArgs a)
         const int srow = tid >> 3, scol = (tid & 7) * 16;
         half_t *const lw = lds + srow * SG_LD + scol;
         uint4_t xs[XR / 2];
-        auto stage_store = [&](int u, const uint4_t (&reg)[XR / 2]) {
+        auto stage_store = [&](int u, const uint4_t (&reg)[XR / 2], int only = -1) {
 #pragma unroll
             for (int p = 0; p < XR / 2; ++p) {
+                if (only >= 0 && only != p) continue;
                 half_t *d = lw + u * SG_STAGE + p * 32 * SG_LD;
                 *reinterpret_cast<uint4_t *>(d) = fp8x8_to_half8<BF>(reg[p][0], reg[p][1]);
                 *reinterpret_cast<uint4_t *>(d + 8) = fp8x8_to_half8<BF>(reg[p][2], reg[p][3]);

@@ -140,9 +140,10 @@ __global__ __launch_bounds__(256, 1) void gemm_sparse_kernel(SparseGemmArgs a)
     const uint32_t xv = ((uint32_t)(t0 + srow) * k + (uint32_t)scol) * 2u;
     half_t *const lw = lds + srow * SG_LD + scol;
     uint4_t xr[2][XR];
-    auto stage_store = [&](int u, const uint4_t (&reg)[XR]) {
+    auto stage_store = [&](int u, const uint4_t (&reg)[XR], int only = -1) {
 #pragma unroll
-        for (int p = 0; p < XR; ++p) *reinterpret_cast<uint4_t *>(lw + u * SG_STAGE + p * 16 * SG_LD) = reg[p];
+        for (int p = 0; p < XR; ++p)
+            if (only < 0 || only == p) *reinterpret_cast<uint4_t *>(lw + u * SG_STAGE + p * 16 * SG_LD) = reg[p];
     };
 
     // B fragment address of this lane inside a stage buffer: token li of tile

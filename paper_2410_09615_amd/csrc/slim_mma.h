@@ -135,7 +135,7 @@ __host__ __device__ __forceinline__ int blocked_tile(int q, int tiles_o, int til
 //      the passes of 16-byte loads; a stage is 128 BB bytes further), next stage's
 //      loads issued during steps 0-3 of the current one.  BB = 2: B is fp16, eight
 //      loads per lane and stage; BB = 1: B is 8-bit codes, four loads, which
-//      stage_store() expands to fp16 on their way into LDS.
+//      stage_store(buffer, registers, piece: one of them, or all with -1) expands to fp16 on their way into LDS.
 // Loads past the end stay inside the descriptors or read as zero and are not
 // used; issuing them anyway keeps one path through the loop body.
 // Starts and ends with every wavefront past a barrier.
@@ -177,6 +177,10 @@ __device__ __forceinline__ void dense_phase(rsrc_t da, uint32_t av, uint32_t a_t
                         load16(db, bv, (uint32_t)(s + 1) * (SG_BK * BB) + (uint32_t)((XRN / 4) * j + it) * b_pass);
                 if constexpr (j + 1 < 8)
                     b_nxt[it] = *reinterpret_cast<const half8_t *>(lr + u * SG_STAGE + it * 32 * SG_LD + 16 * (j + 1));
+                // the next stage's B, loaded four steps ago, goes into the other buffer (nobody reads it during
+                // this stage) piece by piece, not in the stage's tail
+                if constexpr (j >= 4 && it < XRN / 4)
+                    if (s + 1 < stages) stage_store(u ^ 1, xs, (XRN / 4) * (j - 4) + it);
                 __builtin_amdgcn_sched_barrier(0);
                 static_for<AT>([&](auto ic) {
                     constexpr int i = ic;
@@ -187,7 +191,6 @@ __device__ __forceinline__ void dense_phase(rsrc_t da, uint32_t av, uint32_t a_t
 #pragma unroll
             for (int it = 0; it < NT; ++it) b_cur[it] = b_nxt[it];
         });
-        if (s + 1 < stages) stage_store(u ^ 1, xs);
         __syncthreads();
     }
 }
@@ -295,6 +298,13 @@ __device__ __forceinline__ void dense_phase_q4(const Q4Rows &qa, rsrc_t db, uint
                     xs[(XRN / 4) * jj + it] =
                         load16(db, bv, (uint32_t)(s + 1) * (SG_BK * BB) + (uint32_t)((XRN / 4) * jj + it) * b_pass);
                 if constexpr (jj + 1 < 8) b_nxt[it] = read_b(u, it, jj + 1);
+                if constexpr (jj >= 4 && it < XRN / 4) {
+                    constexpr int p = (XRN / 4) * (jj - 4) + it;
+                    if (s + 1 < stages) {
+                        if (SG_BK * (s + 1) + bcol >= K) xs[p] = uint4_t{0u, 0u, 0u, 0u};
+                        stage_store(u ^ 1, xs, p);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 static_for<AT>([&](auto ic) {
                     constexpr int i = ic;
@@ -317,8 +327,6 @@ __device__ __forceinline__ void dense_phase_q4(const Q4Rows &qa, rsrc_t db, uint
         });
 #pragma unroll
         for (int i = 0; i < AT; ++i) sc[i] = sc_nxt[i];
-        zero_tail(s + 1);
-        if (s + 1 < stages) stage_store(u ^ 1, xs);
         __syncthreads();
     }
 }
